@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the EXEC hot path on one MI355X.
+
+A step is one EXEC of ResNet-50 (224x224, fp16 storage, fp32 accumulation) at
+batch 16 over a synthetic batch that is already resident in HBM (INPUT done once
+before the timed region): input cast, stem, max pool, 52 convolutions, global
+average pool, FC and softmax, all through the C ABI.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+BATCHES = (1, 2, 4, 8, 16)
+
+
+def cpu_baseline(seed, log):
+    """The oracle as it stands, one image per host thread, on a bounded sample."""
+    from oracle import network as N
+    from oracle import topology as T
+    from workload import gen
+    cores = len(os.sched_getaffinity(0))
+    threads = min(cores, 16)
+    ops = T.resnet(50)
+    w, b = gen.model_tensors(T.weight_shapes(ops), seed)
+    x = gen.images(seed, 0, threads, 3, 224, 224, "normal")
+    t0 = time.perf_counter()
+    N.forward(ops, w, b, x, threads=threads)
+    dt = time.perf_counter() - t0
+    log("cpu_baseline: %d images on %d threads in %.1f s" % (threads, threads, dt))
+    return {"value": threads / dt, "unit": "inferences/s", "cores": threads, "kind": "oracle",
+            "sample": "ResNet-50 224x224 fp32 nested-loop oracle, %d images of the same seeded workload, "
+                      "one image per thread, %.1f s wall" % (threads, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--profile-repeats", type=int, default=1000)
+    ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers-out", default="", help="write the per-launch table here (text)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (an 8-GPU node is 8 independent workers); "
+                 "run with --gpus 1")
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+
+    from paper_2006_02464_amd.runner import Worker, pinned_like
+    from workload import gen
+
+    seed = 0
+    wk = Worker(workspace_bytes=512 << 20, io_bytes=512 << 20, weight_pool_bytes=1 << 30,
+                load_staging_bytes=256 << 20)
+    ctx, stream = wk.ctx, wk.stream
+    mid = ctx.model_define_resnet(50, 224, 224, "fp16")
+    ops = ctx.model_get_ops(mid)
+    shapes = [(o[2], o[1], o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
+    w, b = gen.model_tensors(shapes, seed, "fp16")
+    wk.load(mid, gen.pack_blob(w, b, "fp16"))
+    del w, b
+    B = args.batch
+    x = pinned_like(gen.images(seed, 0, B, 3, 224, 224, "normal", "fp16"))
+    slot = ctx.input(mid, B, x, stream)
+    stream.synchronize()
+    log("model loaded, input resident")
+
+    # ---- timed region: K EXECs back to back on one stream
+    for _ in range(args.warmup):
+        ctx.exec(mid, B, slot, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.exec(mid, B, slot, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = B * args.steps / dt
+    log("batch %d: %.1f us/step wall, %.0f inferences/s" % (B, ms_per_step * 1e3, value))
+
+    # ---- per-launch durations by HIP events on the EXEC stream (separate pass: an event pair
+    # around every launch would perturb the timed region above)
+    plan = ctx.plan(mid, B)
+    reps = 20
+    per = np.zeros(len(plan))
+    for _ in range(3):
+        ctx.exec_timed_launches(mid, B, slot, stream)
+    for _ in range(reps):
+        per += ctx.exec_timed_launches(mid, B, slot, stream)
+    per /= reps
+    conv = [i for i, l in enumerate(plan) if l["kind"] == 1]
+    conv_us = float(sum(per[i] for i in conv))
+    conv_flops = float(sum(plan[i]["flops"] for i in conv))
+    conv_bytes = float(sum(plan[i]["bytes"] for i in conv))
+    achieved = conv_flops / (conv_us * 1e-6) / 1e12
+    lines = ["%-22s %4s %9s %6s %5s %7s %10s %9s %8s %8s %7s" % (
+        "launch", "op", "M", "N", "K", "grid", "GFLOP", "MB", "us", "TFLOP/s", "GB/s")]
+    for l, us in zip(plan, per):
+        lines.append("%-22s %4d %9d %6d %5d %7d %10.3f %9.2f %8.2f %8.1f %7.0f" % (
+            l["name"], l["op_index"], l["gemm_m"], l["gemm_n"], l["gemm_k"], l["grid_x"] * l["grid_y"],
+            l["flops"] / 1e9, l["bytes"] / 1e6, us, l["flops"] / (us * 1e-6) / 1e12, l["bytes"] / (us * 1e-6) / 1e9))
+    lines.append("sum of launches %.1f us; conv launches %d, %.1f us" % (per.sum(), len(conv), conv_us))
+    if args.layers_out:
+        with open(args.layers_out, "w") as f:
+            f.write("\n".join(lines) + "\n")
+    log("conv kernel: %d launches, %.1f us, %.1f TFLOP/s, %.0f GB/s algorithmic" % (
+        len(conv), conv_us, achieved, conv_bytes / (conv_us * 1e-6) / 1e9))
+
+    # ---- EXEC latency profile per batch size (on-device durations)
+    latency = {}
+    for bs in BATCHES:
+        ctx.profile_measure(mid, bs, 100)
+        p = ctx.profile_measure(mid, bs, args.profile_repeats)
+        latency[str(bs)] = {"p50_us": round(p["p50_us"], 2), "p99_us": round(p["p99_us"], 2),
+                            "p999_us": round(p["p999_us"], 2), "min_us": round(p["min_us"], 2),
+                            "max_us": round(p["max_us"], 2), "n": p["n"],
+                            "inferences_per_s": round(bs / (p["p50_us"] * 1e-6), 1),
+                            "p999_over_p50": round(p["p999_us"] / p["p50_us"], 4)}
+        log("batch %2d: p50 %.1f us p99 %.1f us p99.9 %.1f us" % (bs, p["p50_us"], p["p99_us"], p["p999_us"]))
+    ctx.release(slot)
+    wk.close()
+
+    out = {
+        "metric": "ResNet-50 inferences/s and exec p50/p99.9 latency at batch 1-16",
+        "value": round(value, 1), "unit": "inferences/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "ResNet-50 224x224x3, fp16 He-normal weights, folded-BN bias, N(0,1) inputs, "
+                               "EXEC at batch %d, input resident in HBM" % B,
+                   "batch": B, "global_batch": B, "parallelism": "single GPU"},
+        "exec_latency_us": latency,
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_F16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
+                     "kernel": "conv_igemm_kernel (all %d conv launches of one EXEC)" % len(conv),
+                     "avg_launch_us": round(conv_us / len(conv), 3),
+                     "algorithmic_GBps": round(conv_bytes / (conv_us * 1e-6) / 1e9, 1)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(seed, log)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

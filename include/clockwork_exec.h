@@ -1,0 +1,213 @@
+/*
+ * clockwork_exec.h -- C ABI of the MI355X worker hot path: the steps of an INFER
+ * action on one GPU (INPUT -> EXEC -> OUTPUT) plus LOAD / UNLOAD of weights and a
+ * measured EXEC-latency profile per (model, batch size).
+ *
+ * The call set follows the action model of the paper (section 4.4 "Predictable DNN
+ * Worker", section 5.1 "Models", section 5.2 "DNN Workers"):
+ *   - a model is weights + kernels per batch size + static memory metadata + a
+ *     seed latency profile (section 5.1);
+ *   - all device memory is allocated once and split into a workspace for
+ *     intermediates, an IO cache for inputs/outputs and a pool for weights
+ *     (section 5.2, "Managing model weights in memory");
+ *   - INFER = INPUT, EXEC, OUTPUT; EXEC checks that weights and input are present
+ *     and runs the kernels; one EXEC at a time per GPU (sections 4.4, 5.2);
+ *   - every action reports a status and its on-device duration (section 5.2,
+ *     "Results").
+ *
+ * Conventions
+ *   - Every call returns an int32_t status: CW_OK (0) or a negative CW_ERR_*.
+ *     No exception crosses this boundary.  cw_strerror() names a status;
+ *     cw_last_error() gives detail for the last failing call on a context.
+ *   - Pointers marked [host] are host memory owned by the caller; the library owns
+ *     all device memory.  No call allocates device memory after cw_create().
+ *   - `stream` is a raw hipStream_t (passed as void*; NULL = the default stream).
+ *     Calls that take a stream only enqueue work; the caller must keep [host]
+ *     buffers alive and unmodified until that stream has been synchronised.  Host
+ *     buffers should be pinned for the copies to be asynchronous.
+ *   - A context is bound to one GPU and is not thread safe: serialise calls on
+ *     one context (the paper's executors are one thread per action type; here the
+ *     caller provides that discipline).
+ *   - Storage type of weights and activations: fp16 or bf16 (per model);
+ *     accumulation is always fp32; biases, logits and probabilities are fp32.
+ */
+#ifndef CLOCKWORK_EXEC_H
+#define CLOCKWORK_EXEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cw_ctx cw_ctx; /* one per GPU: the paper's "worker-GPU" */
+
+enum {
+    CW_OK = 0,
+    CW_ERR_INVALID = -1,        /* bad argument (null pointer, unknown id, bad size) */
+    CW_ERR_HIP = -2,            /* a HIP runtime call failed; see cw_last_error() */
+    CW_ERR_NO_MEMORY = -3,      /* a pre-allocated pool cannot hold the request */
+    CW_ERR_NOT_LOADED = -4,     /* EXEC on a model whose weights are not resident */
+    CW_ERR_ALREADY_LOADED = -5, /* LOAD of a model that is resident */
+    CW_ERR_NO_INPUT = -6,       /* EXEC/OUTPUT on a slot that holds no input / no result */
+    CW_ERR_BAD_BATCH = -7,      /* batch size the model has no plan for */
+    CW_ERR_BUSY = -8,           /* an EXEC is still in flight on another stream */
+    CW_ERR_UNSUPPORTED = -9,    /* topology the kernels cannot run (see cw_model_define) */
+    CW_ERR_NO_SLOT = -10        /* every IO slot is in use */
+};
+
+enum { CW_OP_CONV = 0, CW_OP_MAXPOOL = 1, CW_OP_GAVGPOOL = 2, CW_OP_FC = 3, CW_OP_SOFTMAX = 4 };
+enum { CW_DTYPE_FP16 = 0, CW_DTYPE_BF16 = 1 };
+
+/* One operator of a model.  Ops form a DAG over earlier ops' outputs.
+ * CONV:     cross-correlation, kh x kw, `stride`, zero padding `pad`, + bias[cout],
+ *           then (if residual_from >= 0) + output of that op, then ReLU if relu != 0.
+ * MAXPOOL:  kh x kw window, `stride`, `pad`; padded taps are ignored.
+ * GAVGPOOL: mean over all spatial positions.
+ * FC:       cin -> cout, + bias; its fp32 output is the model's logits.
+ * SOFTMAX:  over the cout values of each sample; its output is the probabilities. */
+typedef struct {
+    int32_t op;            /* CW_OP_* */
+    int32_t cin, cout;     /* channels in / out (MAXPOOL, GAVGPOOL, SOFTMAX: cin == cout) */
+    int32_t kh, kw;        /* filter or window size (0 where unused) */
+    int32_t stride, pad;
+    int32_t relu;          /* CONV only */
+    int32_t residual_from; /* CONV only: -1 or index of an earlier op */
+    int32_t input_from;    /* -1 = the network input, else index of an earlier op */
+} cw_op;
+
+typedef struct {
+    int32_t device;             /* HIP device ordinal */
+    size_t workspace_bytes;     /* intermediates of the one EXEC in flight (paper: 512 MB) */
+    size_t io_bytes;            /* IO cache: inputs and outputs of in-flight INFERs (paper: 512 MB) */
+    size_t weight_pool_bytes;   /* packed weights of all resident models */
+    size_t load_staging_bytes;  /* device landing zone of one canonical blob during LOAD;
+                                   must be >= the largest blob that will be loaded */
+} cw_config;
+
+/* Allocates every device buffer the context will ever use.  [host] cfg. */
+int32_t cw_create(cw_ctx **out, const cw_config *cfg);
+/* Waits for all work the context enqueued, then frees everything. */
+int32_t cw_destroy(cw_ctx *ctx);
+
+/* ---- models (section 5.1: kernels per batch size + memory metadata) ----------
+ * Defines a topology and compiles one fixed launch plan per batch size: kernel
+ * variant, grid, split-K factor and workspace offsets are functions of (ops, input
+ * size, batch) only.  Nothing is tuned or chosen at run time.
+ * ops, batch_sizes: [host], copied.  The first op must read the network input
+ * (in_c x in_h x in_w, NCHW fp32 at the boundary); the list must end FC, SOFTMAX.
+ * Supported: CONV with cin % 32 == 0 and cout % 32 == 0 anywhere, plus a first
+ * CONV with cin <= 4; kh == kw.  Returns CW_ERR_UNSUPPORTED otherwise,
+ * CW_ERR_NO_MEMORY if a plan's workspace exceeds workspace_bytes. */
+int32_t cw_model_define(cw_ctx *ctx, const cw_op *ops, int32_t n_ops,
+                        int32_t in_c, int32_t in_h, int32_t in_w,
+                        const int32_t *batch_sizes, int32_t n_batch,
+                        int32_t dtype, int32_t *model_id);
+/* ResNet-18 / 50 / 152 (depth) with batch sizes 1,2,4,8,16 (section 5.1 default). */
+int32_t cw_model_define_resnet(cw_ctx *ctx, int32_t depth, int32_t in_h, int32_t in_w,
+                               int32_t dtype, int32_t *model_id);
+/* Copies the model's op list to ops_out[0..cap) [host]; *n_ops = its length. */
+int32_t cw_model_get_ops(cw_ctx *ctx, int32_t model_id, cw_op *ops_out, int32_t cap,
+                         int32_t *n_ops);
+/* Size in bytes of the canonical weight blob LOAD expects (0 for a bad id). */
+size_t cw_model_weight_bytes(cw_ctx *ctx, int32_t model_id);
+/* Workspace bytes the plan for (model, batch) uses (0 for a bad id / batch). */
+size_t cw_model_workspace_bytes(cw_ctx *ctx, int32_t model_id, int32_t batch);
+
+/* ---- LOAD / UNLOAD (section 5.2) ----------------------------------------------
+ * Canonical blob [host]: for every op that owns weights (CONV, FC), in op order,
+ * W[cout][cin][kh][kw] in the model's storage type, back to back; zero padding to
+ * a multiple of 4 bytes; then every bias[cout] as fp32 in the same op order.
+ * LOAD reserves room in the weight pool (CW_ERR_NO_MEMORY if it does not fit: the
+ * paper's LOAD aborts when no pages are free), copies the blob to the device on
+ * `stream` and re-lays it out there for the MFMA kernels.  The same packed
+ * weights serve every batch size.  `bytes` must equal cw_model_weight_bytes(). */
+int32_t cw_load_weights(cw_ctx *ctx, int32_t model_id, const void *host_blob,
+                        size_t bytes, void *stream);
+/* Metadata only; succeeds whether or not the model is resident (section 5.2). */
+int32_t cw_unload_weights(cw_ctx *ctx, int32_t model_id);
+/* Bytes currently free in the weight pool (the controller-visible memory state). */
+size_t cw_weight_pool_free(cw_ctx *ctx);
+
+/* ---- INFER = INPUT, EXEC, OUTPUT (section 5.2) --------------------------------
+ * INPUT: takes an IO slot and copies host_nchw [host], fp32 [batch][in_c][in_h][in_w],
+ * to it on `stream`.  *slot receives the slot id.  CW_ERR_NO_SLOT / CW_ERR_NO_MEMORY
+ * when the IO cache is full, CW_ERR_BAD_BATCH for a batch without a plan. */
+int32_t cw_input(cw_ctx *ctx, int32_t model_id, int32_t batch, const float *host_nchw,
+                 int32_t *slot, void *stream);
+/* EXEC: checks that the model's weights are resident (else CW_ERR_NOT_LOADED) and
+ * that `slot` holds an input of this (model, batch) (else CW_ERR_NO_INPUT /
+ * CW_ERR_BAD_BATCH), then enqueues the plan's kernels on `stream`, bracketed by
+ * two events.  The stream is made to wait for the slot's INPUT copy and the
+ * model's LOAD, so they may have been issued on other streams.  A second EXEC
+ * issued on a different stream while one is in flight returns CW_ERR_BUSY; on
+ * the same stream EXECs simply run back to back.  EXEC may be repeated on a slot. */
+int32_t cw_exec(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot, void *stream);
+/* OUTPUT: enqueues the copies of the slot's results to host_probs [host]
+ * [batch][classes] and, if not NULL, host_logits [host] [batch][classes] on
+ * `stream` (after the slot's EXEC), then releases the slot; its memory is reused
+ * only after these copies have completed.  CW_ERR_NO_INPUT if no EXEC ran. */
+int32_t cw_output(cw_ctx *ctx, int32_t slot, float *host_probs, float *host_logits,
+                  void *stream);
+/* Releases a slot without copying anything out. */
+int32_t cw_release(cw_ctx *ctx, int32_t slot);
+/* On-device duration of the slot's last EXEC (the "timing" field of a result).
+ * Blocks until that EXEC has finished. */
+int32_t cw_exec_duration_ns(cw_ctx *ctx, int32_t slot, uint64_t *on_device_ns);
+
+/* ---- measured latency profile per (model, batch) (section 5.1 "Profiling data") */
+typedef struct {
+    uint32_t n;
+    float p50_us, p99_us, p999_us, min_us, max_us, mean_us;
+} cw_profile;
+/* Runs `repeats` EXECs of (model, batch) back to back on an internal stream over a
+ * zero input, each timed on the device, and stores and returns nearest-rank
+ * percentiles.  Synchronous.  samples_us [host] may be NULL, else receives the
+ * `repeats` individual durations in microseconds. */
+int32_t cw_profile_measure(cw_ctx *ctx, int32_t model_id, int32_t batch, uint32_t repeats,
+                           cw_profile *out, float *samples_us);
+/* Last measured profile; n == 0 if none was measured. */
+int32_t cw_profile_get(cw_ctx *ctx, int32_t model_id, int32_t batch, cw_profile *out);
+
+/* ---- introspection for parity tests and per-layer measurement ----------------
+ * Number of kernel launches in the plan of (model, batch); negative on error. */
+int32_t cw_plan_num_launches(cw_ctx *ctx, int32_t model_id, int32_t batch);
+typedef struct {
+    int32_t op_index;      /* which op of the model this launch belongs to */
+    int32_t kind;          /* internal kernel family id */
+    int32_t grid_x, grid_y, grid_z, block;
+    int32_t tile_m, tile_n, split_k;
+    int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
+    int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
+    int64_t flops;         /* 2 * MACs */
+    char name[48];
+} cw_launch_info;
+int32_t cw_plan_launch_info(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t index,
+                            cw_launch_info *out);
+/* Runs EXEC like cw_exec but times every launch of the plan with its own pair of
+ * events; launch_us [host] receives cw_plan_num_launches() values.  Synchronous. */
+int32_t cw_exec_timed_launches(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot,
+                               float *launch_us, void *stream);
+/* Copies the output of op `op_index` from the slot's last EXEC to host_out [host]
+ * as fp32 NCHW [batch][cout][h][w].  Needs the context to have been created with
+ * debug retention (cw_set_debug_keep) before the plan was built; otherwise the
+ * workspace region may have been reused: returns CW_ERR_UNSUPPORTED. */
+int32_t cw_debug_read_op(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t op_index,
+                         float *host_out, size_t capacity_floats);
+/* When keep != 0, plans built afterwards give every op output its own workspace
+ * region (no reuse) so cw_debug_read_op can read them.  Costs workspace only. */
+int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..5 =
+ * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32; -1 = the plan compiler's own choice)
+ * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
+ * tests can reach every kernel instantiation.  Still fixed at plan time. */
+int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
+
+const char *cw_strerror(int32_t status);
+const char *cw_last_error(cw_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLOCKWORK_EXEC_H */

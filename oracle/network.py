@@ -114,7 +114,25 @@ def argmax(z, prec="f32"):
     return idx
 
 
-def _forward_one(ops, weights, biases, x, prec, keep):
+def _round_storage(y, storage):
+    """Round every element once (nearest even) to a 16-bit storage type and return
+    to the working precision.  Models a path that keeps activations in that type
+    between operators; the arithmetic inside an operator is unchanged."""
+    if storage is None:
+        return y
+    y32 = y.astype(np.float32)
+    if storage == "fp16":
+        q = y32.astype(np.float16).astype(np.float32)
+    elif storage == "bf16":
+        b = y32.view(np.uint32)
+        r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+        q = r.view(np.float32)
+    else:
+        raise ValueError(storage)
+    return q.astype(y.dtype)
+
+
+def _forward_one(ops, weights, biases, x, prec, keep, storage=None):
     """Forward pass of a batch held in one array; returns dict of kept outputs."""
     outs = []
     wi = 0
@@ -127,6 +145,7 @@ def _forward_one(ops, weights, biases, x, prec, keep):
                 y = add(y, outs[o.residual_from], prec)
             if o.relu:
                 y = relu(y, prec)
+            y = _round_storage(y, storage)
         elif o.op == MAXPOOL:
             y = maxpool2d(src, o.kh, o.stride, o.pad, prec)
         elif o.op == GAVGPOOL:
@@ -151,9 +170,14 @@ def _forward_one(ops, weights, biases, x, prec, keep):
     return res
 
 
-def forward(ops, weights, biases, x, prec="f32", threads=None, keep="final"):
+def forward(ops, weights, biases, x, prec="f32", threads=None, keep="final", storage=None):
     """EXEC of one batch.  ``weights[i]``/``biases[i]`` belong to the i-th op that
     owns weights (conv or FC, in op order); ``x`` is [N][C][H][W].
+
+    storage=None is the definition itself.  storage="fp16"/"bf16" is a second mode
+    that rounds each convolution's final output (after bias, shortcut and ReLU) once
+    to that type, as a path storing its feature maps in 16 bits does; pooled
+    features, logits and probabilities stay in the working precision.
 
     keep="final": returns {"logits": [N][classes], "probs": [N][classes]}.
     keep="all":   returns the list of every op's output (NCHW), whole batch,
@@ -161,13 +185,13 @@ def forward(ops, weights, biases, x, prec="f32", threads=None, keep="final"):
     """
     x = _arr(x, prec)
     if keep == "all":
-        return _forward_one(ops, weights, biases, x, prec, "all")
+        return _forward_one(ops, weights, biases, x, prec, "all", storage)
     n = x.shape[0]
     threads = threads or min(n, len(os.sched_getaffinity(0)))
     if threads <= 1 or n == 1:
-        return _forward_one(ops, weights, biases, x, prec, "final")
+        return _forward_one(ops, weights, biases, x, prec, "final", storage)
     with ThreadPoolExecutor(max_workers=threads) as ex:
         parts = list(ex.map(
-            lambda i: _forward_one(ops, weights, biases, x[i:i + 1], prec, "final"),
+            lambda i: _forward_one(ops, weights, biases, x[i:i + 1], prec, "final", storage),
             range(n)))
     return {k: np.concatenate([p[k] for p in parts], axis=0) for k in parts[0]}

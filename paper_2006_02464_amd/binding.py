@@ -1,0 +1,262 @@
+"""ctypes binding of include/clockwork_exec.h: same names, argument marshalling
+only.  Every step of the path runs in the library's HIP kernels."""
+import ctypes
+import os
+from ctypes import (POINTER, Structure, byref, c_char, c_char_p, c_float, c_int32,
+                    c_int64, c_size_t, c_uint32, c_uint64, c_void_p)
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libclockwork_exec.so")
+
+CW_OK = 0
+CW_ERR_INVALID, CW_ERR_HIP, CW_ERR_NO_MEMORY, CW_ERR_NOT_LOADED = -1, -2, -3, -4
+CW_ERR_ALREADY_LOADED, CW_ERR_NO_INPUT, CW_ERR_BAD_BATCH, CW_ERR_BUSY = -5, -6, -7, -8
+CW_ERR_UNSUPPORTED, CW_ERR_NO_SLOT = -9, -10
+CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX = 0, 1, 2, 3, 4
+CW_DTYPE_FP16, CW_DTYPE_BF16 = 0, 1
+DTYPES = {"fp16": CW_DTYPE_FP16, "bf16": CW_DTYPE_BF16}
+CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32x32": 5}
+
+
+class cw_op(Structure):
+    _fields_ = [(n, c_int32) for n in ("op", "cin", "cout", "kh", "kw", "stride", "pad",
+                                        "relu", "residual_from", "input_from")]
+
+
+class cw_config(Structure):
+    _fields_ = [("device", c_int32), ("workspace_bytes", c_size_t), ("io_bytes", c_size_t),
+                ("weight_pool_bytes", c_size_t), ("load_staging_bytes", c_size_t)]
+
+
+class cw_profile(Structure):
+    _fields_ = [("n", c_uint32), ("p50_us", c_float), ("p99_us", c_float), ("p999_us", c_float),
+                ("min_us", c_float), ("max_us", c_float), ("mean_us", c_float)]
+
+
+class cw_launch_info(Structure):
+    _fields_ = [("op_index", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
+                ("grid_z", c_int32), ("block", c_int32), ("tile_m", c_int32), ("tile_n", c_int32),
+                ("split_k", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
+                ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
+
+
+# name -> (restype, argtypes); every symbol the header declares
+SIGNATURES = {
+    "cw_create": (c_int32, [POINTER(c_void_p), POINTER(cw_config)]),
+    "cw_destroy": (c_int32, [c_void_p]),
+    "cw_model_define": (c_int32, [c_void_p, POINTER(cw_op), c_int32, c_int32, c_int32, c_int32,
+                                  POINTER(c_int32), c_int32, c_int32, POINTER(c_int32)]),
+    "cw_model_define_resnet": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, POINTER(c_int32)]),
+    "cw_model_get_ops": (c_int32, [c_void_p, c_int32, POINTER(cw_op), c_int32, POINTER(c_int32)]),
+    "cw_model_weight_bytes": (c_size_t, [c_void_p, c_int32]),
+    "cw_model_workspace_bytes": (c_size_t, [c_void_p, c_int32, c_int32]),
+    "cw_load_weights": (c_int32, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
+    "cw_unload_weights": (c_int32, [c_void_p, c_int32]),
+    "cw_weight_pool_free": (c_size_t, [c_void_p]),
+    "cw_input": (c_int32, [c_void_p, c_int32, c_int32, c_void_p, POINTER(c_int32), c_void_p]),
+    "cw_exec": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p]),
+    "cw_output": (c_int32, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]),
+    "cw_release": (c_int32, [c_void_p, c_int32]),
+    "cw_exec_duration_ns": (c_int32, [c_void_p, c_int32, POINTER(c_uint64)]),
+    "cw_profile_measure": (c_int32, [c_void_p, c_int32, c_int32, c_uint32, POINTER(cw_profile), c_void_p]),
+    "cw_profile_get": (c_int32, [c_void_p, c_int32, c_int32, POINTER(cw_profile)]),
+    "cw_plan_num_launches": (c_int32, [c_void_p, c_int32, c_int32]),
+    "cw_plan_launch_info": (c_int32, [c_void_p, c_int32, c_int32, c_int32, POINTER(cw_launch_info)]),
+    "cw_exec_timed_launches": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]),
+    "cw_debug_read_op": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_size_t]),
+    "cw_set_debug_keep": (c_int32, [c_void_p, c_int32]),
+    "cw_set_plan_override": (c_int32, [c_void_p, c_int32, c_int32]),
+    "cw_strerror": (c_char_p, [c_int32]),
+    "cw_last_error": (c_char_p, [c_void_p]),
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Builds it only if no built library exists; fails
+    loudly if it cannot be had (there is no other implementation to fall to)."""
+    global _lib
+    if _lib is None:
+        # PyTorch ships its own HIP runtime under the same soname.  Importing it first makes the
+        # dynamic loader hand that one copy to this library too; loaded the other way round the
+        # process would hold two HIP runtimes, and the second one fails to initialise.
+        import torch  # noqa: F401
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+class CwError(RuntimeError):
+    def __init__(self, status, detail=""):
+        self.status = status
+        name = lib().cw_strerror(status).decode()
+        super().__init__("%s (%d)%s" % (name, status, (": " + detail) if detail else ""))
+
+
+def _ptr(x):
+    """Host address of a numpy array / torch CPU tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return c_void_p(x)
+    if isinstance(x, np.ndarray):
+        assert x.flags["C_CONTIGUOUS"]
+        return c_void_p(x.ctypes.data)
+    if hasattr(x, "data_ptr"):
+        assert x.is_contiguous()
+        return c_void_p(x.data_ptr())
+    raise TypeError(type(x))
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return c_void_p(s)
+    return c_void_p(s.cuda_stream)  # torch.cuda.Stream
+
+
+class Context:
+    """One worker-GPU.  Methods carry the C names without the ``cw_`` prefix and
+    raise :class:`CwError` on a negative status."""
+
+    def __init__(self, device=0, workspace_bytes=512 << 20, io_bytes=512 << 20,
+                 weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20):
+        self._h = c_void_p()
+        cfg = cw_config(device, workspace_bytes, io_bytes, weight_pool_bytes, load_staging_bytes)
+        st = lib().cw_create(byref(self._h), byref(cfg))
+        if st != CW_OK:
+            self._h = c_void_p()
+            raise CwError(st, "cw_create: " + lib().cw_last_error(None).decode())
+
+    def _check(self, st):
+        if st < 0:
+            raise CwError(st, lib().cw_last_error(self._h).decode())
+        return st
+
+    def destroy(self):
+        if self._h:
+            lib().cw_destroy(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # -- models
+    def model_define(self, ops, in_c, in_h, in_w, batch_sizes=(1, 2, 4, 8, 16), dtype="fp16"):
+        arr = (cw_op * len(ops))(*[cw_op(*[int(v) for v in o]) for o in ops])
+        bs = (c_int32 * len(batch_sizes))(*batch_sizes)
+        mid = c_int32(-1)
+        self._check(lib().cw_model_define(self._h, arr, len(ops), in_c, in_h, in_w, bs,
+                                          len(batch_sizes), DTYPES[dtype], byref(mid)))
+        return mid.value
+
+    def model_define_resnet(self, depth, in_h, in_w, dtype="fp16"):
+        mid = c_int32(-1)
+        self._check(lib().cw_model_define_resnet(self._h, depth, in_h, in_w, DTYPES[dtype], byref(mid)))
+        return mid.value
+
+    def model_get_ops(self, model_id):
+        n = c_int32(0)
+        self._check(lib().cw_model_get_ops(self._h, model_id, None, 0, byref(n)))
+        arr = (cw_op * n.value)()
+        self._check(lib().cw_model_get_ops(self._h, model_id, arr, n.value, byref(n)))
+        return [tuple(getattr(o, f) for f, _ in cw_op._fields_) for o in arr]
+
+    def model_weight_bytes(self, model_id):
+        return lib().cw_model_weight_bytes(self._h, model_id)
+
+    def model_workspace_bytes(self, model_id, batch):
+        return lib().cw_model_workspace_bytes(self._h, model_id, batch)
+
+    # -- LOAD / UNLOAD
+    def load_weights(self, model_id, host_blob, stream=None):
+        nbytes = host_blob.nbytes if isinstance(host_blob, np.ndarray) else host_blob.numel() * host_blob.element_size()
+        self._check(lib().cw_load_weights(self._h, model_id, _ptr(host_blob), nbytes, _stream(stream)))
+
+    def unload_weights(self, model_id):
+        self._check(lib().cw_unload_weights(self._h, model_id))
+
+    def weight_pool_free(self):
+        return lib().cw_weight_pool_free(self._h)
+
+    # -- INFER
+    def input(self, model_id, batch, host_nchw, stream=None):
+        slot = c_int32(-1)
+        self._check(lib().cw_input(self._h, model_id, batch, _ptr(host_nchw), byref(slot), _stream(stream)))
+        return slot.value
+
+    def exec(self, model_id, batch, slot, stream=None):
+        self._check(lib().cw_exec(self._h, model_id, batch, slot, _stream(stream)))
+
+    def output(self, slot, host_probs, host_logits=None, stream=None):
+        self._check(lib().cw_output(self._h, slot, _ptr(host_probs), _ptr(host_logits), _stream(stream)))
+
+    def release(self, slot):
+        self._check(lib().cw_release(self._h, slot))
+
+    def exec_duration_ns(self, slot):
+        ns = c_uint64(0)
+        self._check(lib().cw_exec_duration_ns(self._h, slot, byref(ns)))
+        return ns.value
+
+    # -- profile
+    def profile_measure(self, model_id, batch, repeats, want_samples=False):
+        prof = cw_profile()
+        samples = np.empty(repeats, np.float32) if want_samples else None
+        self._check(lib().cw_profile_measure(self._h, model_id, batch, repeats, byref(prof), _ptr(samples)))
+        d = {f: getattr(prof, f) for f, _ in cw_profile._fields_}
+        return (d, samples) if want_samples else d
+
+    def profile_get(self, model_id, batch):
+        prof = cw_profile()
+        self._check(lib().cw_profile_get(self._h, model_id, batch, byref(prof)))
+        return {f: getattr(prof, f) for f, _ in cw_profile._fields_}
+
+    # -- introspection
+    def plan_num_launches(self, model_id, batch):
+        return self._check(lib().cw_plan_num_launches(self._h, model_id, batch))
+
+    def plan_launch_info(self, model_id, batch, index):
+        info = cw_launch_info()
+        self._check(lib().cw_plan_launch_info(self._h, model_id, batch, index, byref(info)))
+        d = {f: getattr(info, f) for f, _ in cw_launch_info._fields_}
+        d["name"] = d["name"].decode()
+        return d
+
+    def plan(self, model_id, batch):
+        return [self.plan_launch_info(model_id, batch, i) for i in range(self.plan_num_launches(model_id, batch))]
+
+    def exec_timed_launches(self, model_id, batch, slot, stream=None):
+        us = np.empty(self.plan_num_launches(model_id, batch), np.float32)
+        self._check(lib().cw_exec_timed_launches(self._h, model_id, batch, slot, _ptr(us), _stream(stream)))
+        return us
+
+    def debug_read_op(self, model_id, batch, op_index, shape):
+        out = np.empty(shape, np.float32)
+        self._check(lib().cw_debug_read_op(self._h, model_id, batch, op_index, _ptr(out), out.size))
+        return out
+
+    def set_debug_keep(self, keep):
+        self._check(lib().cw_set_debug_keep(self._h, int(keep)))
+
+    def set_plan_override(self, conv_tile=-1, split_k=0):
+        if isinstance(conv_tile, str):
+            conv_tile = CONV_TILES[conv_tile]
+        self._check(lib().cw_set_plan_override(self._h, conv_tile, split_k))
+
+
+__all__ = [n for n in dir() if n.startswith("CW_") or n.startswith("cw_")] + [
+    "Context", "CwError", "lib", "LIB_PATH", "SIGNATURES", "DTYPES", "CONV_TILES"]

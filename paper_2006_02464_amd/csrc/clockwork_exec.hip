@@ -1,0 +1,710 @@
+// C ABI of the worker hot path (see include/clockwork_exec.h for the contract).
+#include "../../include/clockwork_exec.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "plan.h"
+
+using namespace cw;
+
+namespace {
+
+constexpr int kMaxSlots = 64;
+constexpr int kProfileEvents = 128;  // EXECs timed back to back between two host syncs
+
+enum SlotState { SLOT_FREE = 0, SLOT_INPUT, SLOT_EXECUTED };
+
+struct Slot {
+    SlotState state = SLOT_FREE;
+    int32_t model = -1, batch = 0;
+    size_t off = 0, bytes = 0;               // region in the IO cache
+    size_t in_off = 0, logits_off = 0, probs_off = 0;
+    hipEvent_t input_done = nullptr, exec_start = nullptr, exec_end = nullptr, released = nullptr;
+    bool release_pending = false;            // `released` guards reuse of the region
+};
+
+struct ModelRt {
+    Model m;
+    bool loaded = false;
+    size_t pool_off = 0;
+    hipEvent_t load_done = nullptr;
+};
+
+}  // namespace
+
+struct cw_ctx {
+    int device = -1;       // -1: planning-only context without a GPU
+    cw_config cfg{};
+    char *workspace = nullptr, *io = nullptr, *pool = nullptr, *staging = nullptr;
+    RangeAllocator io_alloc, pool_alloc;
+    Slot slots[kMaxSlots];
+    std::vector<std::unique_ptr<ModelRt>> models;
+    PlanOverride ov;
+    hipStream_t internal_stream = nullptr;
+    hipEvent_t staging_free = nullptr;  // last LOAD's pack kernels are done with the staging area
+    bool staging_used = false;
+    hipEvent_t prof_ev[2 * kProfileEvents] = {};
+    // one EXEC at a time: remember where the last one went
+    hipStream_t last_exec_stream = nullptr;
+    hipEvent_t last_exec_end = nullptr;
+    std::string err;
+};
+
+namespace {
+
+int32_t set_err(cw_ctx *c, int32_t code, const std::string &msg) {
+    if (c) c->err = msg;
+    return code;
+}
+
+int32_t hip_fail(cw_ctx *c, hipError_t e, const char *what) {
+    char buf[256];
+    snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    return set_err(c, CW_ERR_HIP, buf);
+}
+
+#define CW_HIP(ctx, call)                                   \
+    do {                                                    \
+        hipError_t e__ = (call);                            \
+        if (e__ != hipSuccess) return hip_fail(ctx, e__, #call); \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
+    }
+    ~DeviceGuard() {
+        if (ok && prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+ModelRt *get_model(cw_ctx *c, int32_t id) {
+    if (!c || id < 0 || id >= (int32_t)c->models.size()) return nullptr;
+    return c->models[id].get();
+}
+
+Plan *get_plan(ModelRt *m, int32_t batch) {
+    for (Plan &p : m->m.plans)
+        if (p.batch == batch) return &p;
+    return nullptr;
+}
+
+char *resolve(cw_ctx *c, const ModelRt *m, const Slot *s, const Ref &r) {
+    switch (r.space) {
+        case SP_WORKSPACE: return c->workspace + r.offset;
+        case SP_WEIGHTS: return c->pool + m->pool_off + r.offset;
+        case SP_SLOT_INPUT: return c->io + s->in_off;
+        case SP_SLOT_LOGITS: return c->io + s->logits_off;
+        case SP_SLOT_PROBS: return c->io + s->probs_off;
+        default: return nullptr;
+    }
+}
+
+hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hipStream_t st) {
+    const DType dt = m->m.dtype;
+    switch (l.kind) {
+        case K_CAST_INPUT: {
+            CastArgs a = l.cast;
+            a.x = reinterpret_cast<const float *>(resolve(c, m, s, l.x));
+            a.y = resolve(c, m, s, l.y);
+            return launch_cast_input(dt, a, st);
+        }
+        case K_CONV: {
+            ConvArgs a = l.conv;
+            a.x = resolve(c, m, s, l.x);
+            a.w = resolve(c, m, s, l.w);
+            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            a.res = resolve(c, m, s, l.res);
+            a.y = resolve(c, m, s, l.y);
+            a.partial = reinterpret_cast<float *>(resolve(c, m, s, l.partial));
+            return launch_conv(dt, l.tile, l.stem, a, st);
+        }
+        case K_SPLITK_REDUCE: {
+            ReduceArgs a = l.red;
+            a.partial = reinterpret_cast<const float *>(resolve(c, m, s, l.partial));
+            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            a.res = resolve(c, m, s, l.res);
+            a.y = resolve(c, m, s, l.y);
+            return launch_splitk_reduce(dt, a, st);
+        }
+        case K_MAXPOOL:
+        case K_GAVGPOOL: {
+            PoolArgs a = l.pool;
+            a.x = resolve(c, m, s, l.x);
+            a.y = resolve(c, m, s, l.y);
+            return l.kind == K_MAXPOOL ? launch_maxpool(dt, a, st) : launch_gavgpool(dt, a, st);
+        }
+        case K_FC: {
+            FcArgs a = l.fc;
+            a.f = reinterpret_cast<const float *>(resolve(c, m, s, l.x));
+            a.w = resolve(c, m, s, l.w);
+            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            a.z = reinterpret_cast<float *>(resolve(c, m, s, l.y));
+            return launch_fc(dt, a, st);
+        }
+        case K_SOFTMAX: {
+            SoftmaxArgs a = l.sm;
+            a.z = reinterpret_cast<const float *>(resolve(c, m, s, l.x));
+            a.p = reinterpret_cast<float *>(resolve(c, m, s, l.y));
+            return launch_softmax(a, st);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+// Checks shared by cw_exec and its instrumented twin.
+int32_t exec_checks(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, ModelRt **mo, Plan **po, Slot **so) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    if (!m->loaded) return set_err(c, CW_ERR_NOT_LOADED, "weights are not resident");
+    if (slot < 0 || slot >= kMaxSlots || c->slots[slot].state == SLOT_FREE)
+        return set_err(c, CW_ERR_NO_INPUT, "slot holds no input");
+    Slot *s = &c->slots[slot];
+    if (s->model != model_id) return set_err(c, CW_ERR_NO_INPUT, "slot holds an input for another model");
+    if (s->batch != batch) return set_err(c, CW_ERR_BAD_BATCH, "slot holds an input of another batch size");
+    *mo = m; *po = p; *so = s;
+    return CW_OK;
+}
+
+int32_t exec_gate(cw_ctx *c, ModelRt *m, Slot *s, hipStream_t st) {
+    if (c->last_exec_end && c->last_exec_stream != st) {
+        hipError_t q = hipEventQuery(c->last_exec_end);
+        if (q == hipErrorNotReady) return set_err(c, CW_ERR_BUSY, "an EXEC is in flight on another stream");
+        if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
+    }
+    CW_HIP(c, hipStreamWaitEvent(st, s->input_done, 0));
+    CW_HIP(c, hipStreamWaitEvent(st, m->load_done, 0));
+    return CW_OK;
+}
+
+void percentile_profile(std::vector<float> v, cw_profile *out) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    auto rank = [&](double q) {  // nearest rank
+        size_t k = (size_t)std::ceil(q * (double)n);
+        if (k < 1) k = 1;
+        if (k > n) k = n;
+        return v[k - 1];
+    };
+    out->n = (uint32_t)n;
+    out->p50_us = rank(0.50);
+    out->p99_us = rank(0.99);
+    out->p999_us = rank(0.999);
+    out->min_us = v.front();
+    out->max_us = v.back();
+    double s = 0;
+    for (float x : v) s += x;
+    out->mean_us = (float)(s / (double)n);
+}
+
+int32_t acquire_slot(cw_ctx *c, ModelRt *m, int32_t model_id, int32_t batch, hipStream_t st, int32_t *slot_out) {
+    int idx = -1;
+    for (int i = 0; i < kMaxSlots; ++i)
+        if (c->slots[i].state == SLOT_FREE) { idx = i; break; }
+    if (idx < 0) return set_err(c, CW_ERR_NO_SLOT, "every IO slot is in use");
+    Slot &s = c->slots[idx];
+    const size_t in_b = (size_t)batch * m->m.in_c * m->m.in_h * m->m.in_w * 4;
+    const size_t out_b = (size_t)batch * m->m.classes * 4;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t total = up(in_b) + 2 * up(out_b);
+    size_t off = 0;
+    if (!c->io_alloc.alloc(total, &off)) return set_err(c, CW_ERR_NO_MEMORY, "IO cache is full");
+    // The region may have belonged to a slot whose OUTPUT copies are still in flight: every
+    // pending release is waited for by the stream that is about to overwrite IO memory.
+    for (int i = 0; i < kMaxSlots; ++i) {
+        Slot &o = c->slots[i];
+        if (o.release_pending) {
+            hipError_t q = hipEventQuery(o.released);
+            if (q == hipErrorNotReady) {
+                hipError_t e = hipStreamWaitEvent(st, o.released, 0);
+                if (e != hipSuccess) { c->io_alloc.free(off, total); return hip_fail(c, e, "hipStreamWaitEvent"); }
+            } else {
+                o.release_pending = false;
+            }
+        }
+    }
+    s.state = SLOT_INPUT;
+    s.model = model_id; s.batch = batch;
+    s.off = off; s.bytes = total;
+    s.in_off = off;
+    s.logits_off = off + up(in_b);
+    s.probs_off = s.logits_off + up(out_b);
+    *slot_out = idx;
+    return CW_OK;
+}
+
+void free_slot(cw_ctx *c, Slot *s) {
+    if (s->state == SLOT_FREE) return;
+    c->io_alloc.free(s->off, s->bytes);
+    s->state = SLOT_FREE;
+    s->model = -1;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *cw_strerror(int32_t st) {
+    switch (st) {
+        case CW_OK: return "ok";
+        case CW_ERR_INVALID: return "invalid argument";
+        case CW_ERR_HIP: return "HIP runtime error";
+        case CW_ERR_NO_MEMORY: return "pre-allocated pool exhausted";
+        case CW_ERR_NOT_LOADED: return "weights not loaded";
+        case CW_ERR_ALREADY_LOADED: return "weights already loaded";
+        case CW_ERR_NO_INPUT: return "slot holds no input or result";
+        case CW_ERR_BAD_BATCH: return "no plan for this batch size";
+        case CW_ERR_BUSY: return "an EXEC is already in flight";
+        case CW_ERR_UNSUPPORTED: return "unsupported topology or request";
+        case CW_ERR_NO_SLOT: return "no free IO slot";
+        default: return "unknown status";
+    }
+}
+
+static thread_local std::string g_create_err;  // detail of a failed cw_create (no context yet)
+const char *cw_last_error(cw_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
+    if (!out || !cfg) return CW_ERR_INVALID;
+    *out = nullptr;
+    std::unique_ptr<cw_ctx> c(new cw_ctx);
+    c->cfg = *cfg;
+    c->device = cfg->device;
+    c->io_alloc.reset(cfg->io_bytes);
+    c->pool_alloc.reset(cfg->weight_pool_bytes);
+    if (cfg->device < 0) {  // planning-only: models and plans can be defined and inspected
+        *out = c.release();
+        return CW_OK;
+    }
+    auto create_fail = [&](int32_t code, const char *what, hipError_t e) {
+        g_create_err = std::string(what) + ": " + hipGetErrorString(e);
+        return code;
+    };
+    int ndev = 0;
+    hipError_t ce = hipGetDeviceCount(&ndev);
+    if (ce != hipSuccess) return create_fail(CW_ERR_HIP, "hipGetDeviceCount", ce);
+    if (cfg->device >= ndev) return create_fail(CW_ERR_INVALID, "device ordinal out of range", hipErrorInvalidDevice);
+    DeviceGuard g(cfg->device);
+    if (!g.ok) return create_fail(CW_ERR_HIP, "hipSetDevice", hipGetLastError());
+    hipDeviceProp_t prop;
+    if ((ce = hipGetDeviceProperties(&prop, cfg->device)) != hipSuccess) return create_fail(CW_ERR_HIP, "hipGetDeviceProperties", ce);
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)  // kernels exist for gfx950 only
+        return create_fail(CW_ERR_UNSUPPORTED, prop.gcnArchName, hipErrorNoBinaryForGpu);
+    cw_ctx *p = c.get();
+    auto cleanup = [&]() { cw_destroy(c.release()); };
+    auto dmalloc = [&](char **ptr, size_t bytes) {
+        return bytes == 0 ? hipSuccess : hipMalloc(reinterpret_cast<void **>(ptr), bytes);
+    };
+    if (dmalloc(&p->workspace, cfg->workspace_bytes) != hipSuccess || dmalloc(&p->io, cfg->io_bytes) != hipSuccess ||
+        dmalloc(&p->pool, cfg->weight_pool_bytes) != hipSuccess ||
+        dmalloc(&p->staging, cfg->load_staging_bytes) != hipSuccess) {
+        g_create_err = std::string("hipMalloc of the pools: ") + hipGetErrorString(hipGetLastError());
+        cleanup();
+        return CW_ERR_NO_MEMORY;
+    }
+    bool ok = hipStreamCreateWithFlags(&p->internal_stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&p->staging_free, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; ok && i < kMaxSlots; ++i) {
+        Slot &s = p->slots[i];
+        ok = hipEventCreateWithFlags(&s.input_done, hipEventDisableTiming) == hipSuccess &&
+             hipEventCreate(&s.exec_start) == hipSuccess && hipEventCreate(&s.exec_end) == hipSuccess &&
+             hipEventCreateWithFlags(&s.released, hipEventDisableTiming) == hipSuccess;
+    }
+    for (int i = 0; ok && i < 2 * kProfileEvents; ++i) ok = hipEventCreate(&p->prof_ev[i]) == hipSuccess;
+    if (!ok) {
+        g_create_err = std::string("stream/event creation: ") + hipGetErrorString(hipGetLastError());
+        cleanup();
+        return CW_ERR_HIP;
+    }
+    *out = c.release();
+    return CW_OK;
+}
+
+int32_t cw_destroy(cw_ctx *c) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device >= 0) {
+        DeviceGuard g(c->device);
+        (void)hipDeviceSynchronize();
+        for (auto &m : c->models)
+            if (m && m->load_done) (void)hipEventDestroy(m->load_done);
+        for (Slot &s : c->slots) {
+            if (s.input_done) (void)hipEventDestroy(s.input_done);
+            if (s.exec_start) (void)hipEventDestroy(s.exec_start);
+            if (s.exec_end) (void)hipEventDestroy(s.exec_end);
+            if (s.released) (void)hipEventDestroy(s.released);
+        }
+        for (hipEvent_t e : c->prof_ev)
+            if (e) (void)hipEventDestroy(e);
+        if (c->staging_free) (void)hipEventDestroy(c->staging_free);
+        if (c->internal_stream) (void)hipStreamDestroy(c->internal_stream);
+        if (c->workspace) (void)hipFree(c->workspace);
+        if (c->io) (void)hipFree(c->io);
+        if (c->pool) (void)hipFree(c->pool);
+        if (c->staging) (void)hipFree(c->staging);
+    }
+    delete c;
+    return CW_OK;
+}
+
+int32_t cw_set_debug_keep(cw_ctx *c, int32_t keep) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.keep_all = keep != 0;
+    return CW_OK;
+}
+
+int32_t cw_set_plan_override(cw_ctx *c, int32_t conv_tile, int32_t split_k) {
+    if (!c) return CW_ERR_INVALID;
+    if (conv_tile >= (int32_t)N_CONV_TILES || split_k < 0) return set_err(c, CW_ERR_INVALID, "bad override");
+    c->ov.tile = conv_tile < 0 ? -1 : conv_tile;
+    c->ov.split_k = split_k;
+    return CW_OK;
+}
+
+int32_t cw_model_define(cw_ctx *c, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
+                        const int32_t *batch_sizes, int32_t n_batch, int32_t dtype, int32_t *model_id) {
+    if (!c || !ops || !batch_sizes || n_batch < 1 || !model_id) return set_err(c, CW_ERR_INVALID, "null or empty argument");
+    std::unique_ptr<ModelRt> m(new ModelRt);
+    std::string err;
+    int32_t rc = model_init(&m->m, ops, n_ops, in_c, in_h, in_w, dtype, &err);
+    if (rc != CW_OK) return set_err(c, rc, err);
+    m->m.keep_all = c->ov.keep_all;
+    for (int i = 0; i < n_batch; ++i) {
+        if (get_plan(m.get(), batch_sizes[i])) continue;  // duplicate batch size
+        Plan p;
+        rc = plan_build(m->m, batch_sizes[i], c->ov, &p, &err);
+        if (rc != CW_OK) return set_err(c, rc, err);
+        if (p.workspace_bytes > c->cfg.workspace_bytes && c->device >= 0)
+            return set_err(c, CW_ERR_NO_MEMORY, "plan needs more workspace than the context has");
+        m->m.plans.push_back(std::move(p));
+    }
+    if (c->device >= 0) {
+        DeviceGuard g(c->device);
+        CW_HIP(c, hipEventCreateWithFlags(&m->load_done, hipEventDisableTiming));
+    }
+    c->models.push_back(std::move(m));
+    *model_id = (int32_t)c->models.size() - 1;
+    return CW_OK;
+}
+
+int32_t cw_model_define_resnet(cw_ctx *c, int32_t depth, int32_t in_h, int32_t in_w, int32_t dtype, int32_t *model_id) {
+    if (!c) return CW_ERR_INVALID;
+    std::vector<cw_op> ops;
+    if (!resnet_ops(depth, &ops)) return set_err(c, CW_ERR_UNSUPPORTED, "depth must be 18, 50 or 152");
+    static const int32_t batches[5] = {1, 2, 4, 8, 16};
+    return cw_model_define(c, ops.data(), (int32_t)ops.size(), 3, in_h, in_w, batches, 5, dtype, model_id);
+}
+
+int32_t cw_model_get_ops(cw_ctx *c, int32_t model_id, cw_op *ops_out, int32_t cap, int32_t *n_ops) {
+    ModelRt *m = get_model(c, model_id);
+    if (!m || !n_ops) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    *n_ops = (int32_t)m->m.ops.size();
+    if (ops_out)
+        for (int i = 0; i < std::min(cap, *n_ops); ++i) ops_out[i] = m->m.ops[i];
+    return CW_OK;
+}
+
+size_t cw_model_weight_bytes(cw_ctx *c, int32_t model_id) {
+    ModelRt *m = get_model(c, model_id);
+    return m ? m->m.blob_bytes : 0;
+}
+
+size_t cw_model_workspace_bytes(cw_ctx *c, int32_t model_id, int32_t batch) {
+    ModelRt *m = get_model(c, model_id);
+    Plan *p = m ? get_plan(m, batch) : nullptr;
+    return p ? p->workspace_bytes : 0;
+}
+
+size_t cw_weight_pool_free(cw_ctx *c) { return c ? c->pool_alloc.free_bytes() : 0; }
+
+int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size_t bytes, void *stream) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m || !host_blob) return set_err(c, CW_ERR_INVALID, "unknown model id or null blob");
+    if (bytes != m->m.blob_bytes) return set_err(c, CW_ERR_INVALID, "blob size does not match the model");
+    if (m->loaded) return set_err(c, CW_ERR_ALREADY_LOADED, "model is resident");
+    if (bytes > c->cfg.load_staging_bytes) return set_err(c, CW_ERR_NO_MEMORY, "blob larger than the LOAD staging area");
+    size_t off = 0;
+    if (!c->pool_alloc.alloc(m->m.packed_bytes, &off)) return set_err(c, CW_ERR_NO_MEMORY, "weight pool is full");
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto bail = [&](hipError_t e, const char *what) {
+        c->pool_alloc.free(off, m->m.packed_bytes);
+        return hip_fail(c, e, what);
+    };
+    hipError_t e;
+    // One staging area: a LOAD waits for the previous LOAD's pack kernels.
+    if (c->staging_used && (e = hipStreamWaitEvent(st, c->staging_free, 0)) != hipSuccess) return bail(e, "hipStreamWaitEvent");
+    if ((e = hipMemcpyAsync(c->staging, host_blob, bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "hipMemcpyAsync");
+    char *base = c->pool + off;
+    for (const WeightSlot &ws : m->m.wslots) {
+        e = launch_pack_weights(c->staging + ws.blob_w_off, base + ws.packed_w_off, ws.cout, ws.cin, ws.kh, ws.kw, ws.kwp,
+                                ws.cinp, st);
+        if (e != hipSuccess) return bail(e, "pack_weights");
+        e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
+                            reinterpret_cast<float *>(base + ws.packed_b_off), ws.cout, st);
+        if (e != hipSuccess) return bail(e, "copy bias");
+    }
+    if ((e = hipEventRecord(c->staging_free, st)) != hipSuccess) return bail(e, "hipEventRecord");
+    c->staging_used = true;
+    if ((e = hipEventRecord(m->load_done, st)) != hipSuccess) return bail(e, "hipEventRecord");
+    m->pool_off = off;
+    m->loaded = true;
+    return CW_OK;
+}
+
+int32_t cw_unload_weights(cw_ctx *c, int32_t model_id) {
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    if (m->loaded) {
+        c->pool_alloc.free(m->pool_off, m->m.packed_bytes);
+        m->loaded = false;
+    }
+    return CW_OK;
+}
+
+int32_t cw_input(cw_ctx *c, int32_t model_id, int32_t batch, const float *host_nchw, int32_t *slot, void *stream) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m || !host_nchw || !slot) return set_err(c, CW_ERR_INVALID, "unknown model id or null pointer");
+    if (!get_plan(m, batch)) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t idx = -1;
+    int32_t rc = acquire_slot(c, m, model_id, batch, st, &idx);
+    if (rc != CW_OK) return rc;
+    Slot &s = c->slots[idx];
+    const size_t in_b = (size_t)batch * m->m.in_c * m->m.in_h * m->m.in_w * 4;
+    hipError_t e = hipMemcpyAsync(c->io + s.in_off, host_nchw, in_b, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipEventRecord(s.input_done, st);
+    if (e != hipSuccess) {
+        free_slot(c, &s);
+        return hip_fail(c, e, "input copy");
+    }
+    *slot = idx;
+    return CW_OK;
+}
+
+int32_t cw_exec(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, void *stream) {
+    ModelRt *m; Plan *p; Slot *s;
+    int32_t rc = exec_checks(c, model_id, batch, slot, &m, &p, &s);
+    if (rc != CW_OK) return rc;
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = exec_gate(c, m, s, st);
+    if (rc != CW_OK) return rc;
+    CW_HIP(c, hipEventRecord(s->exec_start, st));
+    for (const Launch &l : p->launches) {
+        hipError_t e = issue(c, m, s, l, st);
+        if (e != hipSuccess) return hip_fail(c, e, l.info.name);
+    }
+    CW_HIP(c, hipEventRecord(s->exec_end, st));
+    s->state = SLOT_EXECUTED;
+    c->last_exec_stream = st;
+    c->last_exec_end = s->exec_end;
+    return CW_OK;
+}
+
+int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, float *launch_us, void *stream) {
+    ModelRt *m; Plan *p; Slot *s;
+    int32_t rc = exec_checks(c, model_id, batch, slot, &m, &p, &s);
+    if (rc != CW_OK) return rc;
+    if (!launch_us) return set_err(c, CW_ERR_INVALID, "null output");
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = exec_gate(c, m, s, st);
+    if (rc != CW_OK) return rc;
+    const size_t n = p->launches.size();
+    CW_HIP(c, hipEventRecord(s->exec_start, st));
+    for (size_t base = 0; base < n; base += kProfileEvents) {
+        const size_t cnt = std::min<size_t>(kProfileEvents, n - base);
+        for (size_t i = 0; i < cnt; ++i) {
+            CW_HIP(c, hipEventRecord(c->prof_ev[2 * i], st));
+            hipError_t e = issue(c, m, s, p->launches[base + i], st);
+            if (e != hipSuccess) return hip_fail(c, e, p->launches[base + i].info.name);
+            CW_HIP(c, hipEventRecord(c->prof_ev[2 * i + 1], st));
+        }
+        CW_HIP(c, hipStreamSynchronize(st));
+        for (size_t i = 0; i < cnt; ++i) {
+            float ms = 0.f;
+            CW_HIP(c, hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+            launch_us[base + i] = ms * 1000.f;
+        }
+    }
+    CW_HIP(c, hipEventRecord(s->exec_end, st));
+    CW_HIP(c, hipStreamSynchronize(st));
+    s->state = SLOT_EXECUTED;
+    c->last_exec_stream = st;
+    c->last_exec_end = s->exec_end;
+    return CW_OK;
+}
+
+int32_t cw_output(cw_ctx *c, int32_t slot, float *host_probs, float *host_logits, void *stream) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    if (slot < 0 || slot >= kMaxSlots || c->slots[slot].state != SLOT_EXECUTED)
+        return set_err(c, CW_ERR_NO_INPUT, "slot holds no result");
+    if (!host_probs) return set_err(c, CW_ERR_INVALID, "null output buffer");
+    Slot &s = c->slots[slot];
+    ModelRt *m = get_model(c, s.model);
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t out_b = (size_t)s.batch * m->m.classes * 4;
+    CW_HIP(c, hipStreamWaitEvent(st, s.exec_end, 0));
+    CW_HIP(c, hipMemcpyAsync(host_probs, c->io + s.probs_off, out_b, hipMemcpyDeviceToHost, st));
+    if (host_logits) CW_HIP(c, hipMemcpyAsync(host_logits, c->io + s.logits_off, out_b, hipMemcpyDeviceToHost, st));
+    CW_HIP(c, hipEventRecord(s.released, st));
+    s.release_pending = true;
+    free_slot(c, &s);
+    return CW_OK;
+}
+
+int32_t cw_release(cw_ctx *c, int32_t slot) {
+    if (!c || slot < 0 || slot >= kMaxSlots) return set_err(c, CW_ERR_INVALID, "bad slot");
+    Slot &s = c->slots[slot];
+    if (s.state == SLOT_FREE) return CW_OK;
+    if (c->device >= 0) {
+        // Work that reads or writes the slot may still be queued: whoever reuses the memory waits
+        // for the last EXEC that touched it.
+        DeviceGuard g(c->device);
+        if (s.state == SLOT_EXECUTED) {
+            CW_HIP(c, hipStreamWaitEvent(c->internal_stream, s.exec_end, 0));
+            CW_HIP(c, hipEventRecord(s.released, c->internal_stream));
+            s.release_pending = true;
+        }
+    }
+    free_slot(c, &s);
+    return CW_OK;
+}
+
+int32_t cw_exec_duration_ns(cw_ctx *c, int32_t slot, uint64_t *ns) {
+    if (!c || !ns) return CW_ERR_INVALID;
+    if (slot < 0 || slot >= kMaxSlots || c->slots[slot].state != SLOT_EXECUTED)
+        return set_err(c, CW_ERR_NO_INPUT, "slot holds no result");
+    Slot &s = c->slots[slot];
+    DeviceGuard g(c->device);
+    CW_HIP(c, hipEventSynchronize(s.exec_end));
+    float ms = 0.f;
+    CW_HIP(c, hipEventElapsedTime(&ms, s.exec_start, s.exec_end));
+    *ns = (uint64_t)((double)ms * 1e6 + 0.5);
+    return CW_OK;
+}
+
+int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t repeats, cw_profile *out, float *samples_us) {
+    if (!c || !out || repeats == 0) return set_err(c, CW_ERR_INVALID, "null output or zero repeats");
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    if (!m->loaded) return set_err(c, CW_ERR_NOT_LOADED, "weights are not resident");
+    DeviceGuard g(c->device);
+    hipStream_t st = c->internal_stream;
+    if (c->last_exec_end) CW_HIP(c, hipEventSynchronize(c->last_exec_end));  // one EXEC at a time
+    int32_t slot = -1;
+    int32_t rc = acquire_slot(c, m, model_id, batch, st, &slot);
+    if (rc != CW_OK) return rc;
+    Slot &s = c->slots[slot];
+    const size_t in_b = ((size_t)batch * m->m.in_c * m->m.in_h * m->m.in_w * 4 + 255) / 256 * 256;
+    hipError_t e = launch_fill_zero(c->io + s.in_off, in_b, st);
+    if (e == hipSuccess) e = hipEventRecord(s.input_done, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(st, m->load_done, 0);
+    if (e != hipSuccess) { free_slot(c, &s); return hip_fail(c, e, "profile setup"); }
+    std::vector<float> samples;
+    samples.reserve(repeats);
+    rc = CW_OK;
+    for (uint32_t done = 0; done < repeats && rc == CW_OK;) {
+        const uint32_t cnt = std::min<uint32_t>(kProfileEvents, repeats - done);
+        for (uint32_t i = 0; i < cnt && rc == CW_OK; ++i) {
+            if ((e = hipEventRecord(c->prof_ev[2 * i], st)) != hipSuccess) { rc = hip_fail(c, e, "hipEventRecord"); break; }
+            for (const Launch &l : p->launches)
+                if ((e = issue(c, m, &s, l, st)) != hipSuccess) { rc = hip_fail(c, e, l.info.name); break; }
+            if (rc == CW_OK && (e = hipEventRecord(c->prof_ev[2 * i + 1], st)) != hipSuccess) rc = hip_fail(c, e, "hipEventRecord");
+        }
+        if ((e = hipStreamSynchronize(st)) != hipSuccess && rc == CW_OK) rc = hip_fail(c, e, "hipStreamSynchronize");
+        for (uint32_t i = 0; i < cnt && rc == CW_OK; ++i) {
+            float ms = 0.f;
+            if ((e = hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1])) != hipSuccess) { rc = hip_fail(c, e, "hipEventElapsedTime"); break; }
+            samples.push_back(ms * 1000.f);
+        }
+        done += cnt;
+    }
+    free_slot(c, &s);
+    if (rc != CW_OK) return rc;
+    percentile_profile(samples, &p->profile);
+    *out = p->profile;
+    if (samples_us) std::copy(samples.begin(), samples.end(), samples_us);
+    return CW_OK;
+}
+
+int32_t cw_profile_get(cw_ctx *c, int32_t model_id, int32_t batch, cw_profile *out) {
+    ModelRt *m = get_model(c, model_id);
+    if (!m || !out) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    *out = p->profile;
+    return CW_OK;
+}
+
+int32_t cw_plan_num_launches(cw_ctx *c, int32_t model_id, int32_t batch) {
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    return (int32_t)p->launches.size();
+}
+
+int32_t cw_plan_launch_info(cw_ctx *c, int32_t model_id, int32_t batch, int32_t index, cw_launch_info *out) {
+    ModelRt *m = get_model(c, model_id);
+    if (!m || !out) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    if (index < 0 || index >= (int32_t)p->launches.size()) return set_err(c, CW_ERR_INVALID, "launch index out of range");
+    *out = p->launches[index].info;
+    return CW_OK;
+}
+
+int32_t cw_debug_read_op(cw_ctx *c, int32_t model_id, int32_t batch, int32_t op_index, float *host_out, size_t cap) {
+    if (!c || !host_out) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    if (!m->m.keep_all) return set_err(c, CW_ERR_UNSUPPORTED, "model was not defined with debug retention");
+    if (op_index < 0 || op_index >= (int32_t)m->m.ops.size()) return set_err(c, CW_ERR_INVALID, "bad op index");
+    const Ref &r = p->op_out[op_index];
+    if (r.space != SP_WORKSPACE) return set_err(c, CW_ERR_UNSUPPORTED, "op output lives in the IO slot; use cw_output");
+    const OpShape &sh = m->m.shapes[op_index];
+    const size_t count = (size_t)batch * sh.c * sh.h * sh.w;
+    if (cap < count) return set_err(c, CW_ERR_INVALID, "host buffer too small");
+    DeviceGuard g(c->device);
+    CW_HIP(c, hipDeviceSynchronize());
+    if (m->m.ops[op_index].op == CW_OP_GAVGPOOL) {  // already fp32 [B][C]
+        CW_HIP(c, hipMemcpy(host_out, c->workspace + r.offset, count * 4, hipMemcpyDeviceToHost));
+        return CW_OK;
+    }
+    // The conversion needs count*4 bytes of scratch: the LOAD staging area is idle after the sync.
+    if (count * 4 > c->cfg.load_staging_bytes) return set_err(c, CW_ERR_NO_MEMORY, "staging area too small for read-back");
+    hipError_t e = launch_nhwc_to_nchw_f32(m->m.dtype, c->workspace + r.offset, reinterpret_cast<float *>(c->staging), batch,
+                                           sh.c, sh.h, sh.w, c->internal_stream);
+    if (e != hipSuccess) return hip_fail(c, e, "nhwc_to_nchw");
+    CW_HIP(c, hipStreamSynchronize(c->internal_stream));
+    CW_HIP(c, hipMemcpy(host_out, c->staging, count * 4, hipMemcpyDeviceToHost));
+    return CW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+// Internal types shared by the plan compiler, the kernels and the C ABI.
+// gfx950 (CDNA4) only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace cw {
+
+typedef _Float16 f16;
+typedef __bf16 bf16;
+
+enum DType : int32_t { DT_F16 = 0, DT_BF16 = 1 };
+
+// Kernel families (cw_launch_info.kind).
+enum Kind : int32_t {
+    K_CAST_INPUT = 0,  // fp32 NCHW -> storage-type NHWC4
+    K_CONV = 1,        // implicit-GEMM convolution on MFMA (fused epilogue or split-K partials)
+    K_SPLITK_REDUCE = 2,
+    K_MAXPOOL = 3,
+    K_GAVGPOOL = 4,
+    K_FC = 5,
+    K_SOFTMAX = 6,
+};
+
+// Implicit GEMM view of a convolution (also used for the stem with Cin padded to 4 and
+// the filter row padded to 8 taps): M = B*Ho*Wo output pixels, N = Cout, K = kh*kwp*Cin.
+struct ConvArgs {
+    const void *x;      // NHWC [B][H][W][Cin]
+    const void *w;      // packed [Cout][K], k = (r*kwp + s)*Cin + c
+    const float *bias;  // [Cout]
+    const void *res;    // NHWC like y, or nullptr
+    void *y;            // NHWC [B][Ho][Wo][Cout]
+    float *partial;     // split-K: [split][M][Cout] fp32, else nullptr
+    int32_t B, H, W, Cin, Ho, Wo, Cout;
+    int32_t kh, kw, kwp, stride, pad;
+    int32_t M, K;
+    int32_t relu;
+    int32_t split_k, ktiles_per_split;
+};
+
+struct ReduceArgs {
+    const float *partial;  // [split][M][Cout]
+    const float *bias;
+    const void *res;
+    void *y;
+    int32_t M, Cout, split_k, relu;
+};
+
+struct CastArgs {
+    const float *x;  // NCHW fp32 [B][C][H][W]
+    void *y;         // NHWC4 [B][H][W][4]
+    int32_t B, C, H, W;
+};
+
+struct PoolArgs {
+    const void *x;  // NHWC
+    void *y;        // NHWC (maxpool) / fp32 [B][C] (global average)
+    int32_t B, H, W, C, Ho, Wo, k, stride, pad;
+};
+
+struct FcArgs {
+    const float *f;  // [B][In] fp32
+    const void *w;   // [Out][In]
+    const float *bias;
+    float *z;        // [B][Out]
+    int32_t B, In, Out;
+};
+
+struct SoftmaxArgs {
+    const float *z;
+    float *p;
+    int32_t B, D;
+};
+
+// Tile shapes the conv kernel is instantiated for (fixed at plan time per layer).
+enum ConvTile : int32_t { T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, N_CONV_TILES };
+struct TileDim {
+    int bm, bn, threads;
+};
+TileDim conv_tile_dim(ConvTile t);
+
+// Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
+hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);
+hipError_t launch_splitk_reduce(DType dt, const ReduceArgs &a, hipStream_t s);
+hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
+hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
+hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
+hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
+hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
+// LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout][kh][kwp][cinp] (zero padded).
+hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw,
+                               int kwp, int cinp, hipStream_t s);
+hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t s);
+// debug read-back: NHWC storage type -> fp32 NCHW
+hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H,
+                                   int W, hipStream_t s);
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+
+// Grid and block of a conv launch (pure function of tile and shape).
+void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block);
+void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block);
+
+}  // namespace cw

@@ -1,0 +1,464 @@
+// Model validation, weight-slot layout and the launch-plan compiler (host only).
+#include "plan.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+namespace cw {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- RangeAllocator
+void RangeAllocator::reset(size_t size) {
+    free_.clear();
+    if (size) free_.push_back({0, size});
+    high_ = 0;
+}
+
+bool RangeAllocator::alloc(size_t bytes, size_t *offset) {
+    bytes = align_up(bytes ? bytes : 1, 256);
+    for (size_t i = 0; i < free_.size(); ++i) {
+        if (free_[i].len >= bytes) {
+            *offset = free_[i].off;
+            free_[i].off += bytes;
+            free_[i].len -= bytes;
+            if (free_[i].len == 0) free_.erase(free_.begin() + i);
+            high_ = std::max(high_, *offset + bytes);
+            return true;
+        }
+    }
+    return false;
+}
+
+void RangeAllocator::free(size_t offset, size_t bytes) {
+    bytes = align_up(bytes ? bytes : 1, 256);
+    size_t i = 0;
+    while (i < free_.size() && free_[i].off < offset) ++i;
+    free_.insert(free_.begin() + i, {offset, bytes});
+    if (i + 1 < free_.size() && free_[i].off + free_[i].len == free_[i + 1].off) {
+        free_[i].len += free_[i + 1].len;
+        free_.erase(free_.begin() + i + 1);
+    }
+    if (i > 0 && free_[i - 1].off + free_[i - 1].len == free_[i].off) {
+        free_[i - 1].len += free_[i].len;
+        free_.erase(free_.begin() + i);
+    }
+}
+
+size_t RangeAllocator::free_bytes() const {
+    size_t s = 0;
+    for (const Seg &g : free_) s += g.len;
+    return s;
+}
+
+// ---------------------------------------------------------------- ResNet op lists
+// Post-activation ResNets with BatchNorm folded into each convolution's weights and bias; the
+// stride of a down-sampling bottleneck sits on its 3x3 convolution.  A block's last conv adds
+// the shortcut (the block input, or its 1x1 projection when the shape changes) before ReLU.
+bool resnet_ops(int32_t depth, std::vector<cw_op> *ops) {
+    int nblk[4];
+    bool bottleneck;
+    switch (depth) {
+        case 18: nblk[0] = 2; nblk[1] = 2; nblk[2] = 2; nblk[3] = 2; bottleneck = false; break;
+        case 50: nblk[0] = 3; nblk[1] = 4; nblk[2] = 6; nblk[3] = 3; bottleneck = true; break;
+        case 152: nblk[0] = 3; nblk[1] = 8; nblk[2] = 36; nblk[3] = 3; bottleneck = true; break;
+        default: return false;
+    }
+    ops->clear();
+    auto add_conv = [&](int cin, int cout, int k, int stride, int pad, int relu, int src, int res) {
+        cw_op o{CW_OP_CONV, cin, cout, k, k, stride, pad, relu, res, src};
+        ops->push_back(o);
+        return (int)ops->size() - 1;
+    };
+    int cur = add_conv(3, 64, 7, 2, 3, 1, -1, -1);
+    ops->push_back(cw_op{CW_OP_MAXPOOL, 64, 64, 3, 3, 2, 1, 0, -1, cur});
+    cur = (int)ops->size() - 1;
+    int cin = 64;
+    for (int stage = 0; stage < 4; ++stage) {
+        const int width = 64 << stage;
+        const int cout = bottleneck ? 4 * width : width;
+        for (int b = 0; b < nblk[stage]; ++b) {
+            const int stride = (b == 0 && stage > 0) ? 2 : 1;
+            const int block_in = cur;
+            int t;
+            if (bottleneck) {
+                t = add_conv(cin, width, 1, 1, 0, 1, block_in, -1);
+                t = add_conv(width, width, 3, stride, 1, 1, t, -1);
+            } else {
+                t = add_conv(cin, width, 3, stride, 1, 1, block_in, -1);
+            }
+            int shortcut = block_in;
+            if (stride != 1 || cin != cout) shortcut = add_conv(cin, cout, 1, stride, 0, 0, block_in, -1);
+            cur = bottleneck ? add_conv(width, cout, 1, 1, 0, 1, t, shortcut)
+                             : add_conv(width, cout, 3, 1, 1, 1, t, shortcut);
+            cin = cout;
+        }
+    }
+    ops->push_back(cw_op{CW_OP_GAVGPOOL, cin, cin, 0, 0, 1, 0, 0, -1, cur});
+    ops->push_back(cw_op{CW_OP_FC, cin, 1000, 1, 1, 1, 0, 0, -1, (int)ops->size() - 1});
+    ops->push_back(cw_op{CW_OP_SOFTMAX, 1000, 1000, 0, 0, 1, 0, 0, -1, (int)ops->size() - 1});
+    return true;
+}
+
+// ---------------------------------------------------------------- model_init
+static int32_t fail(std::string *err, int32_t code, const char *fmt, int a = 0, int b = 0) {
+    char buf[256];
+    snprintf(buf, sizeof buf, fmt, a, b);
+    if (err) *err = buf;
+    return code;
+}
+
+int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
+                   int32_t dtype, std::string *err) {
+    if (!ops || n_ops < 3) return fail(err, CW_ERR_INVALID, "need at least 3 ops");
+    if (dtype != CW_DTYPE_FP16 && dtype != CW_DTYPE_BF16) return fail(err, CW_ERR_INVALID, "bad dtype %d", dtype);
+    if (in_c < 1 || in_h < 1 || in_w < 1) return fail(err, CW_ERR_INVALID, "bad input size");
+    m->ops.assign(ops, ops + n_ops);
+    m->shapes.assign(n_ops, OpShape{0, 0, 0});
+    m->in_c = in_c; m->in_h = in_h; m->in_w = in_w;
+    m->dtype = (DType)dtype;
+    m->wslots.clear();
+    m->op_wslot.assign(n_ops, -1);
+    if (ops[n_ops - 2].op != CW_OP_FC || ops[n_ops - 1].op != CW_OP_SOFTMAX)
+        return fail(err, CW_ERR_UNSUPPORTED, "op list must end with FC, SOFTMAX");
+
+    size_t blob_w = 0;
+    for (int i = 0; i < n_ops; ++i) {
+        const cw_op &o = ops[i];
+        if (o.input_from >= i || o.input_from < -1) return fail(err, CW_ERR_INVALID, "op %d: bad input_from", i);
+        if ((o.input_from == -1) != (i == 0))
+            return fail(err, CW_ERR_UNSUPPORTED, "op %d: only the first op may read the network input", i);
+        int sc, sh, sw;
+        if (o.input_from < 0) { sc = in_c; sh = in_h; sw = in_w; }
+        else { sc = m->shapes[o.input_from].c; sh = m->shapes[o.input_from].h; sw = m->shapes[o.input_from].w; }
+        if (o.cin != sc) return fail(err, CW_ERR_INVALID, "op %d: cin does not match its input (%d)", i, sc);
+        OpShape out{o.cout, 1, 1};
+        switch (o.op) {
+            case CW_OP_CONV: {
+                if (o.kh < 1 || o.kh != o.kw || o.stride < 1 || o.pad < 0)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs square filter, stride>=1", i);
+                if (sh + 2 * o.pad < o.kh || sw + 2 * o.pad < o.kw)
+                    return fail(err, CW_ERR_INVALID, "op %d: filter larger than padded input", i);
+                if (i == 0) {
+                    if (o.cin > 4 || o.kw > 8)
+                        return fail(err, CW_ERR_UNSUPPORTED, "first conv needs cin<=4 and kw<=8");
+                } else if (o.cin % 32 != 0) {
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cin must be a multiple of 32", i);
+                }
+                if (o.cout % 32 != 0) return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cout must be a multiple of 32", i);
+                out.h = (sh + 2 * o.pad - o.kh) / o.stride + 1;
+                out.w = (sw + 2 * o.pad - o.kw) / o.stride + 1;
+                if (o.residual_from >= 0) {
+                    if (o.residual_from >= i) return fail(err, CW_ERR_INVALID, "op %d: bad residual_from", i);
+                    const OpShape &r = m->shapes[o.residual_from];
+                    const int rop = ops[o.residual_from].op;
+                    if ((rop != CW_OP_CONV && rop != CW_OP_MAXPOOL) || r.c != out.c || r.h != out.h || r.w != out.w)
+                        return fail(err, CW_ERR_INVALID, "op %d: residual shape mismatch", i);
+                } else if (o.residual_from != -1) {
+                    return fail(err, CW_ERR_INVALID, "op %d: bad residual_from", i);
+                }
+                break;
+            }
+            case CW_OP_MAXPOOL:
+                if (i == 0) return fail(err, CW_ERR_UNSUPPORTED, "first op must be a conv");
+                if (o.cout != o.cin || o.cin % 8 != 0 || o.kh < 1 || o.kh != o.kw || o.stride < 1 || o.pad < 0 ||
+                    o.pad >= o.kh || sh + 2 * o.pad < o.kh || sw + 2 * o.pad < o.kw)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: unsupported max pool", i);
+                out.h = (sh + 2 * o.pad - o.kh) / o.stride + 1;
+                out.w = (sw + 2 * o.pad - o.kw) / o.stride + 1;
+                break;
+            case CW_OP_GAVGPOOL:
+                if (i == 0 || o.cout != o.cin || o.cin % 8 != 0)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: unsupported average pool", i);
+                break;
+            case CW_OP_FC:
+                if (i != n_ops - 2 || ops[o.input_from].op != CW_OP_GAVGPOOL || o.cin % 512 != 0 || o.cout < 1)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: FC must follow the global average pool, cin %% 512 == 0", i);
+                break;
+            case CW_OP_SOFTMAX:
+                if (i != n_ops - 1 || o.input_from != n_ops - 2 || o.cout != o.cin)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: SOFTMAX must be last and read the FC", i);
+                break;
+            default: return fail(err, CW_ERR_INVALID, "op %d: unknown op code", i);
+        }
+        if (o.op != CW_OP_FC && o.op != CW_OP_SOFTMAX && o.op != CW_OP_GAVGPOOL && i > 0) {
+            const int src = ops[o.input_from].op;
+            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL)
+                return fail(err, CW_ERR_UNSUPPORTED, "op %d: spatial op needs a spatial input", i);
+        }
+        if (o.op == CW_OP_GAVGPOOL) {
+            const int src = ops[o.input_from].op;
+            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL)
+                return fail(err, CW_ERR_UNSUPPORTED, "op %d: average pool needs a spatial input", i);
+        }
+        m->shapes[i] = out;
+        if (o.op == CW_OP_CONV || o.op == CW_OP_FC) {
+            WeightSlot ws{};
+            ws.op_index = i;
+            ws.cout = o.cout; ws.cin = o.cin;
+            ws.kh = o.op == CW_OP_FC ? 1 : o.kh;
+            ws.kw = o.op == CW_OP_FC ? 1 : o.kw;
+            ws.kwp = (i == 0) ? 8 : ws.kw;
+            ws.cinp = (i == 0) ? 4 : ws.cin;
+            ws.blob_w_off = blob_w;
+            blob_w += (size_t)ws.cout * ws.cin * ws.kh * ws.kw * 2;
+            m->op_wslot[i] = (int)m->wslots.size();
+            m->wslots.push_back(ws);
+        }
+    }
+    m->classes = ops[n_ops - 2].cout;
+    size_t blob_b = align_up(blob_w, 4), packed = 0;
+    for (WeightSlot &ws : m->wslots) {
+        ws.blob_b_off = blob_b;
+        blob_b += (size_t)ws.cout * 4;
+        ws.packed_w_off = packed;
+        ws.packed_w_bytes = (size_t)ws.cout * ws.kh * ws.kwp * ws.cinp * 2;
+        packed = align_up(packed + ws.packed_w_bytes, 256);
+    }
+    for (WeightSlot &ws : m->wslots) {
+        ws.packed_b_off = packed;
+        packed = align_up(packed + (size_t)ws.cout * 4, 256);
+    }
+    m->blob_bytes = blob_b;
+    m->packed_bytes = packed;
+    return CW_OK;
+}
+
+// ---------------------------------------------------------------- tile choice
+// Largest tile that still gives every CU at least one workgroup; below that, a 64x64 (or
+// narrower) tile with K split over up to 16 workgroups.  Pure function of the GEMM shape.
+static void pick_conv_tile(int64_t M, int64_t N, int64_t ktiles, const PlanOverride &ov, ConvTile *tile,
+                           int32_t *split) {
+    static const ConvTile order[] = {T128x128, T128x64, T64x64, T32x64, T64x32, T32x32};
+    auto blocks = [&](ConvTile t) {
+        const TileDim d = conv_tile_dim(t);
+        return ((M + d.bm - 1) / d.bm) * ((N + d.bn - 1) / d.bn);
+    };
+    const int64_t target = 256;
+    ConvTile chosen = T32x32;
+    bool found = false;
+    for (ConvTile t : order) {
+        const TileDim d = conv_tile_dim(t);
+        if (d.bn > N && t != T32x32) continue;
+        if (blocks(t) >= target) { chosen = t; found = true; break; }
+    }
+    int32_t s = 1;
+    if (!found) {
+        chosen = (N >= 64 && M > 32) ? T64x64 : (N >= 64 ? T32x64 : T32x32);
+        const int64_t b = blocks(chosen);
+        const int64_t want = (target + b - 1) / b;
+        const int64_t cap = std::max<int64_t>(1, ktiles / 8);
+        s = (int32_t)std::min<int64_t>(std::min(want, cap), 16);
+    }
+    if (ov.tile >= 0 && ov.tile < N_CONV_TILES) { chosen = (ConvTile)ov.tile; if (ov.split_k <= 0) s = 1; }
+    if (ov.split_k > 0) s = (int32_t)std::min<int64_t>(ov.split_k, ktiles);
+    *tile = chosen;
+    *split = std::max(1, s);
+}
+
+// ---------------------------------------------------------------- plan_build
+int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err) {
+    if (batch < 1 || batch > 4096) return fail(err, CW_ERR_BAD_BATCH, "batch %d out of range", batch);
+    const int n_ops = (int)m.ops.size();
+    const size_t esz = 2;
+    Plan p;
+    p.batch = batch;
+    p.op_out.assign(n_ops, Ref{});
+
+    // Guard the 32-bit element indexing of the conv kernel.
+    {
+        int64_t biggest = (int64_t)batch * m.in_h * m.in_w * 4;
+        for (const OpShape &s : m.shapes) biggest = std::max<int64_t>(biggest, (int64_t)batch * s.c * s.h * s.w);
+        if (biggest >= (int64_t)1 << 31) return fail(err, CW_ERR_BAD_BATCH, "batch %d: tensor exceeds 2^31 elements", batch);
+    }
+
+    std::vector<int> last_use(n_ops, -1);
+    for (int i = 0; i < n_ops; ++i) {
+        if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = i;
+        if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) last_use[m.ops[i].residual_from] = i;
+    }
+    std::vector<size_t> out_bytes(n_ops, 0);
+    RangeAllocator arena((size_t)1 << 46);
+    auto ws_alloc = [&](size_t bytes) {
+        size_t off = 0;
+        arena.alloc(bytes, &off);
+        return off;
+    };
+
+    // input cast: fp32 NCHW in the IO slot -> NHWC4 in the workspace
+    const size_t cast_bytes = (size_t)batch * m.in_h * m.in_w * 4 * esz;
+    const size_t cast_off = ws_alloc(cast_bytes);
+    {
+        Launch l{};
+        l.kind = K_CAST_INPUT;
+        l.op_index = 0;
+        l.cast.B = batch; l.cast.C = m.in_c; l.cast.H = m.in_h; l.cast.W = m.in_w;
+        l.x = Ref{SP_SLOT_INPUT, 0};
+        l.y = Ref{SP_WORKSPACE, cast_off};
+        l.info.bytes = (int64_t)batch * m.in_c * m.in_h * m.in_w * 4 + (int64_t)cast_bytes;
+        snprintf(l.info.name, sizeof l.info.name, "cast_input");
+        p.launches.push_back(l);
+    }
+
+    for (int i = 0; i < n_ops; ++i) {
+        const cw_op &o = m.ops[i];
+        const OpShape &os = m.shapes[i];
+        int sc, sh, sw;
+        Ref src;
+        if (o.input_from < 0) { sc = 4; sh = m.in_h; sw = m.in_w; src = Ref{SP_WORKSPACE, cast_off}; }
+        else { sc = m.shapes[o.input_from].c; sh = m.shapes[o.input_from].h; sw = m.shapes[o.input_from].w; src = p.op_out[o.input_from]; }
+        size_t partial_off = 0, partial_bytes = 0;
+
+        switch (o.op) {
+            case CW_OP_CONV: {
+                const WeightSlot &ws = m.wslots[m.op_wslot[i]];
+                out_bytes[i] = (size_t)batch * os.h * os.w * os.c * esz;
+                p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
+                Launch l{};
+                l.kind = K_CONV;
+                l.op_index = i;
+                l.stem = (i == 0);
+                ConvArgs &a = l.conv;
+                a.B = batch; a.H = sh; a.W = sw; a.Cin = ws.cinp; a.Ho = os.h; a.Wo = os.w; a.Cout = o.cout;
+                a.kh = o.kh; a.kw = o.kw; a.kwp = ws.kwp; a.stride = o.stride; a.pad = o.pad;
+                a.M = batch * os.h * os.w;
+                a.K = o.kh * ws.kwp * ws.cinp;
+                a.relu = o.relu;
+                const int ktiles = a.K / 32;
+                pick_conv_tile(a.M, a.Cout, ktiles, ov, &l.tile, &a.split_k);
+                a.ktiles_per_split = (ktiles + a.split_k - 1) / a.split_k;
+                a.split_k = (ktiles + a.ktiles_per_split - 1) / a.ktiles_per_split;  // no empty splits
+                l.x = src;
+                l.w = Ref{SP_WEIGHTS, ws.packed_w_off};
+                l.bias = Ref{SP_WEIGHTS, ws.packed_b_off};
+                l.y = p.op_out[i];
+                if (o.residual_from >= 0) l.res = p.op_out[o.residual_from];
+                const int64_t in_pixels = (o.kh == 1 && o.stride > 1) ? (int64_t)a.M : (int64_t)batch * sh * sw;
+                const int64_t real_k = (int64_t)o.kh * o.kw * o.cin;
+                const int64_t in_b = in_pixels * (i == 0 ? 4 : o.cin) * esz;
+                const int64_t w_b = (int64_t)o.cout * real_k * esz + o.cout * 4;
+                const int64_t out_b = (int64_t)out_bytes[i];
+                const int64_t res_b = o.residual_from >= 0 ? out_b : 0;
+                l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = real_k;
+                l.info.flops = 2 * (int64_t)a.M * a.Cout * real_k;
+                const TileDim td = conv_tile_dim(l.tile);
+                l.info.tile_m = td.bm; l.info.tile_n = td.bn; l.info.split_k = a.split_k;
+                if (a.split_k > 1) {
+                    partial_bytes = (size_t)a.split_k * a.M * a.Cout * 4;
+                    partial_off = ws_alloc(partial_bytes);
+                    l.partial = Ref{SP_WORKSPACE, partial_off};
+                    l.info.bytes = in_b + w_b + (int64_t)partial_bytes;
+                    snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d_splitk", o.kh, o.kw, o.stride);
+                    p.launches.push_back(l);
+                    Launch r{};
+                    r.kind = K_SPLITK_REDUCE;
+                    r.op_index = i;
+                    r.red.M = a.M; r.red.Cout = a.Cout; r.red.split_k = a.split_k; r.red.relu = o.relu;
+                    r.partial = l.partial; r.bias = l.bias; r.res = l.res; r.y = l.y;
+                    r.info.bytes = (int64_t)partial_bytes + out_b + res_b;
+                    r.info.split_k = a.split_k;
+                    snprintf(r.info.name, sizeof r.info.name, "splitk_reduce");
+                    p.launches.push_back(r);
+                } else {
+                    l.info.bytes = in_b + w_b + out_b + res_b;
+                    snprintf(l.info.name, sizeof l.info.name, i == 0 ? "stem%dx%d_s%d" : "conv%dx%d_s%d", o.kh, o.kw, o.stride);
+                    p.launches.push_back(l);
+                }
+                break;
+            }
+            case CW_OP_MAXPOOL: {
+                out_bytes[i] = (size_t)batch * os.h * os.w * os.c * esz;
+                p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
+                Launch l{};
+                l.kind = K_MAXPOOL;
+                l.op_index = i;
+                l.pool = PoolArgs{nullptr, nullptr, batch, sh, sw, sc, os.h, os.w, o.kh, o.stride, o.pad};
+                l.x = src; l.y = p.op_out[i];
+                l.info.bytes = (int64_t)batch * sh * sw * sc * esz + (int64_t)out_bytes[i];
+                snprintf(l.info.name, sizeof l.info.name, "maxpool%dx%d_s%d", o.kh, o.kw, o.stride);
+                p.launches.push_back(l);
+                break;
+            }
+            case CW_OP_GAVGPOOL: {
+                out_bytes[i] = (size_t)batch * os.c * 4;
+                p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
+                Launch l{};
+                l.kind = K_GAVGPOOL;
+                l.op_index = i;
+                l.pool = PoolArgs{nullptr, nullptr, batch, sh, sw, sc, 1, 1, 0, 1, 0};
+                l.x = src; l.y = p.op_out[i];
+                l.info.bytes = (int64_t)batch * sh * sw * sc * esz + (int64_t)out_bytes[i];
+                snprintf(l.info.name, sizeof l.info.name, "global_avgpool");
+                p.launches.push_back(l);
+                break;
+            }
+            case CW_OP_FC: {
+                const WeightSlot &ws = m.wslots[m.op_wslot[i]];
+                p.op_out[i] = Ref{SP_SLOT_LOGITS, 0};
+                Launch l{};
+                l.kind = K_FC;
+                l.op_index = i;
+                l.fc.B = batch; l.fc.In = o.cin; l.fc.Out = o.cout;
+                l.x = src;
+                l.w = Ref{SP_WEIGHTS, ws.packed_w_off};
+                l.bias = Ref{SP_WEIGHTS, ws.packed_b_off};
+                l.y = p.op_out[i];
+                l.info.gemm_m = batch; l.info.gemm_n = o.cout; l.info.gemm_k = o.cin;
+                l.info.flops = 2 * (int64_t)batch * o.cout * o.cin;
+                l.info.bytes = (int64_t)batch * o.cin * 4 + (int64_t)o.cout * o.cin * esz + o.cout * 4 + (int64_t)batch * o.cout * 4;
+                snprintf(l.info.name, sizeof l.info.name, "fc");
+                p.launches.push_back(l);
+                break;
+            }
+            case CW_OP_SOFTMAX: {
+                p.op_out[i] = Ref{SP_SLOT_PROBS, 0};
+                Launch l{};
+                l.kind = K_SOFTMAX;
+                l.op_index = i;
+                l.sm.B = batch; l.sm.D = o.cout;
+                l.x = src; l.y = p.op_out[i];
+                l.info.bytes = 2 * (int64_t)batch * o.cout * 4;
+                snprintf(l.info.name, sizeof l.info.name, "softmax");
+                p.launches.push_back(l);
+                break;
+            }
+        }
+
+        if (partial_bytes) arena.free(partial_off, partial_bytes);
+        if (!ov.keep_all) {
+            if (i == 0) arena.free(cast_off, cast_bytes);
+            for (int j = 0; j <= i; ++j) {
+                const bool dead_now = (last_use[j] == i) || (j == i && last_use[j] < 0);
+                if (dead_now && p.op_out[j].space == SP_WORKSPACE && out_bytes[j]) {
+                    arena.free(p.op_out[j].offset, out_bytes[j]);
+                    out_bytes[j] = 0;
+                }
+            }
+        }
+    }
+
+    // grid/block of every launch, for introspection
+    for (Launch &l : p.launches) {
+        dim3 g(1, 1, 1);
+        int b = 0;
+        switch (l.kind) {
+            case K_CONV: conv_grid(l.tile, l.conv, &g, &b); break;
+            case K_SPLITK_REDUCE: reduce_grid(l.red, &g, &b); break;
+            case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.H * l.cast.W + 255) / 256)); b = 256; break;
+            case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
+            case K_GAVGPOOL: g = dim3((unsigned)((l.pool.B * (l.pool.C / 8) + 63) / 64)); b = 64; break;
+            case K_FC: g = dim3((l.fc.Out + 3) / 4, (l.fc.B + 15) / 16); b = 256; break;
+            case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
+        }
+        l.info.op_index = l.op_index;
+        l.info.kind = l.kind;
+        l.info.grid_x = g.x; l.info.grid_y = g.y; l.info.grid_z = g.z; l.info.block = b;
+        if (l.info.split_k == 0) l.info.split_k = 1;
+    }
+    p.workspace_bytes = arena.high_water();
+    *out = std::move(p);
+    return CW_OK;
+}
+
+}  // namespace cw

@@ -1,0 +1,107 @@
+// Host-side model description and launch-plan compiler.
+//
+// A plan is the paper's "kernels per batch size" + "memory metadata" (section 5.1) for one
+// (model, batch): the ordered list of kernel launches with their variant, grid, split-K factor
+// and workspace offsets.  It is a pure function of (op list, input size, batch, storage type):
+// nothing is measured, tuned or chosen when EXEC runs.
+#pragma once
+#include <string>
+#include <vector>
+
+#include "../../include/clockwork_exec.h"
+#include "common.h"
+
+namespace cw {
+
+// Where a launch argument points; resolved to an address when EXEC is issued.
+enum Space : int32_t { SP_NONE = 0, SP_WORKSPACE, SP_WEIGHTS, SP_SLOT_INPUT, SP_SLOT_LOGITS, SP_SLOT_PROBS };
+struct Ref {
+    Space space = SP_NONE;
+    size_t offset = 0;
+};
+
+struct Launch {
+    Kind kind;
+    int32_t op_index;
+    ConvTile tile = T64x64;
+    bool stem = false;
+    // Shape fields are final; pointer fields are filled from the Refs at EXEC time.
+    ConvArgs conv{};
+    ReduceArgs red{};
+    CastArgs cast{};
+    PoolArgs pool{};
+    FcArgs fc{};
+    SoftmaxArgs sm{};
+    Ref x, w, bias, res, y, partial;
+    cw_launch_info info{};
+};
+
+struct OpShape {
+    int32_t c, h, w;  // output channels and spatial size
+};
+
+struct WeightSlot {        // one op that owns weights
+    int32_t op_index;
+    size_t blob_w_off;     // byte offset of W in the canonical blob
+    size_t blob_b_off;     // byte offset of bias in the canonical blob
+    size_t packed_w_off;   // byte offset of packed W inside the model's weight-pool region
+    size_t packed_b_off;   // byte offset of the fp32 bias there
+    size_t packed_w_bytes;
+    int32_t cout, cin, kh, kw, kwp, cinp;
+};
+
+struct Plan {
+    int32_t batch = 0;
+    std::vector<Launch> launches;
+    std::vector<Ref> op_out;  // workspace (or slot) location of every op's output
+    size_t workspace_bytes = 0;
+    cw_profile profile{};
+};
+
+struct PlanOverride {
+    int32_t tile = -1;     // ConvTile or -1 = automatic
+    int32_t split_k = 0;   // 0 = automatic
+    bool keep_all = false; // no workspace reuse (debug read-back)
+};
+
+struct Model {
+    std::vector<cw_op> ops;
+    std::vector<OpShape> shapes;
+    int32_t in_c = 0, in_h = 0, in_w = 0;
+    DType dtype = DT_F16;
+    int32_t classes = 0;
+    std::vector<WeightSlot> wslots;
+    std::vector<int32_t> op_wslot;  // op index -> index in wslots or -1
+    size_t blob_bytes = 0;
+    size_t packed_bytes = 0;
+    std::vector<Plan> plans;
+    bool keep_all = false;
+};
+
+// Validates the op list and fills shapes, weight slots and sizes.  Returns CW_OK or an error
+// with a message in *err.
+int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
+                   int32_t dtype, std::string *err);
+// Compiles the plan of one batch size.
+int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err);
+// Operator list of ResNet-18/50/152.
+bool resnet_ops(int32_t depth, std::vector<cw_op> *ops);
+
+// First-fit allocator over a fixed range (host metadata only; used for the weight pool, the
+// IO cache and, at plan time, the workspace arena).
+class RangeAllocator {
+   public:
+    explicit RangeAllocator(size_t size = 0) { reset(size); }
+    void reset(size_t size);
+    bool alloc(size_t bytes, size_t *offset);  // 256-byte granularity
+    void free(size_t offset, size_t bytes);
+    size_t free_bytes() const;
+    size_t high_water() const { return high_; }
+
+   private:
+    struct Seg { size_t off, len; };
+    std::vector<Seg> free_;
+    size_t high_ = 0;
+};
+
+}  // namespace cw

@@ -1,0 +1,139 @@
+"""GPU tests of the boundary's action semantics: residency, slots, errors, timing."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_02464_amd as cw
+from gpu_common import Case
+from oracle import topology as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def setup():
+    from paper_2006_02464_amd.runner import Worker
+    w = Worker(workspace_bytes=64 << 20, io_bytes=32 << 20, weight_pool_bytes=60 << 20,
+               load_staging_bytes=32 << 20)
+    case = Case(T.resnet(18), 64, seed=0, dist="uniform")
+    yield w, case
+    w.close()
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(cw.CwError) as e:
+        fn(*a, **k)
+    return e.value.status
+
+
+def test_exec_checks_weights_and_input(setup):
+    w, case = setup
+    ctx = w.ctx
+    mid = ctx.model_define_resnet(18, 64, 64)
+    x = torch.zeros((1, 3, 64, 64), dtype=torch.float32).pin_memory()
+    slot = ctx.input(mid, 1, x, w.stream)
+    assert _status(ctx.exec, mid, 1, slot, w.stream) == cw.CW_ERR_NOT_LOADED
+    w.load(mid, case.blob)
+    assert _status(ctx.exec, mid, 2, slot, w.stream) == cw.CW_ERR_BAD_BATCH     # slot holds batch 1
+    assert _status(ctx.exec, mid, 3, slot, w.stream) == cw.CW_ERR_BAD_BATCH     # no plan
+    assert _status(ctx.exec, mid, 1, 63, w.stream) == cw.CW_ERR_NO_INPUT
+    probs = torch.empty((1, 1000), dtype=torch.float32).pin_memory()
+    assert _status(ctx.output, slot, probs, None, w.stream) == cw.CW_ERR_NO_INPUT  # no EXEC yet
+    ctx.exec(mid, 1, slot, w.stream)
+    ctx.exec(mid, 1, slot, w.stream)       # EXEC may be repeated on a slot
+    assert ctx.exec_duration_ns(slot) > 0
+    ctx.output(slot, probs, None, w.stream)
+    w.stream.synchronize()
+    assert abs(float(probs.sum()) - 1) < 1e-5
+    assert _status(ctx.exec, mid, 1, slot, w.stream) == cw.CW_ERR_NO_INPUT      # slot was released
+    assert _status(ctx.load_weights, mid, np.zeros(5, np.uint8)) == cw.CW_ERR_INVALID
+    assert _status(w.load, mid, case.blob) == cw.CW_ERR_ALREADY_LOADED
+    ctx.unload_weights(mid)
+    ctx.unload_weights(mid)                # always succeeds
+
+
+def test_load_aborts_when_pool_is_full_and_unload_frees(setup):
+    w, case = setup
+    ctx = w.ctx
+    free0 = ctx.weight_pool_free()
+    a = ctx.model_define_resnet(18, 64, 64)
+    b = ctx.model_define_resnet(18, 64, 64)
+    c = ctx.model_define_resnet(18, 64, 64)
+    w.load(a, case.blob)
+    w.load(b, case.blob)                   # 2 x 23.4 MB fit in 60 MB
+    assert ctx.weight_pool_free() < free0 - 2 * 23_000_000
+    assert _status(w.load, c, case.blob) == cw.CW_ERR_NO_MEMORY
+    ctx.unload_weights(a)
+    w.load(c, case.blob)                   # room again
+    x = case.images(0, 2)
+    za = w.infer(b, x)[1]
+    zc = w.infer(c, x)[1]
+    assert np.array_equal(za, zc)          # same weights, different pool regions
+    for m in (b, c):
+        ctx.unload_weights(m)
+    assert ctx.weight_pool_free() == free0
+
+
+def test_io_cache_exhaustion_and_reuse(setup):
+    w, case = setup
+    ctx = w.ctx
+    mid = ctx.model_define_resnet(18, 64, 64)
+    x = torch.zeros((16, 3, 64, 64), dtype=torch.float32).pin_memory()
+    slots = []
+    with pytest.raises(cw.CwError) as e:
+        for _ in range(100):
+            slots.append(ctx.input(mid, 16, x, w.stream))
+    assert e.value.status in (cw.CW_ERR_NO_MEMORY, cw.CW_ERR_NO_SLOT)
+    assert len(slots) >= 4
+    for s in slots:
+        ctx.release(s)
+    s = ctx.input(mid, 16, x, w.stream)
+    ctx.release(s)
+    w.stream.synchronize()
+
+
+def test_second_exec_on_another_stream_is_busy(setup):
+    w, case = setup
+    ctx = w.ctx
+    mid = ctx.model_define_resnet(18, 224, 224)     # ~1 ms per EXEC at batch 16
+    w.load(mid, case.blob)
+    x = torch.zeros((16, 3, 224, 224), dtype=torch.float32).pin_memory()
+    slot = ctx.input(mid, 16, x, w.stream)
+    other = torch.cuda.Stream()
+    for _ in range(20):                     # keep the EXEC stream busy
+        ctx.exec(mid, 16, slot, w.stream)
+    st = None
+    try:
+        ctx.exec(mid, 16, slot, other)
+    except cw.CwError as e:
+        st = e.status
+    assert st == cw.CW_ERR_BUSY
+    w.stream.synchronize()
+    ctx.exec(mid, 16, slot, other)          # idle now: allowed
+    other.synchronize()
+    ctx.release(slot)
+    ctx.unload_weights(mid)
+
+
+def test_profile_measure(setup):
+    w, case = setup
+    ctx = w.ctx
+    mid = ctx.model_define_resnet(18, 64, 64)
+    w.load(mid, case.blob)
+    assert ctx.profile_get(mid, 4)["n"] == 0
+    prof, samples = ctx.profile_measure(mid, 4, 300, want_samples=True)
+    assert prof["n"] == 300 and len(samples) == 300
+    assert 0 < prof["min_us"] <= prof["p50_us"] <= prof["p99_us"] <= prof["p999_us"] <= prof["max_us"]
+    s = np.sort(samples)
+    rank = lambda q: s[min(300, max(1, math.ceil(q * 300))) - 1]     # nearest rank
+    assert prof["p50_us"] == rank(0.50) and prof["p99_us"] == rank(0.99) and prof["p999_us"] == rank(0.999)
+    assert ctx.profile_get(mid, 4) == prof
+    per_launch = None
+    x = torch.zeros((4, 3, 64, 64), dtype=torch.float32).pin_memory()
+    slot = ctx.input(mid, 4, x, w.stream)
+    per_launch = ctx.exec_timed_launches(mid, 4, slot, w.stream)
+    assert len(per_launch) == ctx.plan_num_launches(mid, 4) and (per_launch > 0).all()
+    ctx.release(slot)
+    ctx.unload_weights(mid)

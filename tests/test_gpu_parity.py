@@ -1,0 +1,293 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Tolerance: per sample, max_j |z_gpu - z_ref| <= 2e-2 *
+max_j |z_ref| on the fp32 logits; top-1 is the lowest index attaining the maximum
+on both sides."""
+import numpy as np
+import pytest
+
+from gpu_common import TOL, Case, rel_err_per_sample, top2_gap
+from workload import gen
+from oracle import network as N
+from oracle import topology as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def worker():
+    from paper_2006_02464_amd.runner import Worker
+    w = Worker(workspace_bytes=512 << 20, io_bytes=256 << 20, weight_pool_bytes=1 << 30,
+               load_staging_bytes=256 << 20)
+    yield w
+    w.close()
+
+
+def _layer_tol(dtype):
+    # one rounding per stored activation: 2^-11 (fp16) / 2^-8 (bf16) relative to the layer's
+    # magnitude, times a few layers of accumulated drift
+    return 6e-3 if dtype == "fp16" else 4e-2
+
+
+def check_all_ops(worker, case, mid, batch, x, teacher=True):
+    """Every op's output against the oracle, two ways:
+
+    * free running: the oracle's own same-index tensor, within a per-layer tolerance;
+    * teacher forced: the oracle applies op i to the inputs the GPU actually produced for it
+      (read back), then rounds once to the storage type.  The two can then differ only by
+      summation order, i.e. by at most one unit in the last place of the storage type on the
+      few elements that sit on a rounding boundary."""
+    outs = case.oracle(x, keep="all")
+    shapes = T.shapes(case.ops, case.hw, case.hw)
+    ulp = 2.0 ** -10 if case.dtype == "fp16" else 2.0 ** -7
+    worst = 0.0
+    gpu = []
+    wi = 0
+    for i, (o, (c, h, w)) in enumerate(zip(case.ops, shapes)):
+        if o.op in (T.FC, T.SOFTMAX):
+            break
+        shape = (batch, c) if o.op == T.GAVGPOOL else (batch, c, h, w)
+        got = worker.ctx.debug_read_op(mid, batch, i, shape)
+        gpu.append(got)
+        ref = outs[i].reshape(shape)
+        scale = np.abs(ref).max()
+        err = np.abs(got - ref).max() / scale
+        worst = max(worst, err)
+        assert err <= _layer_tol(case.dtype), "op %d (%s): rel err %.3e" % (i, o, err)
+        if not teacher:
+            if o.op == T.CONV:
+                wi += 1
+            continue
+        src = x if o.input_from < 0 else gpu[o.input_from]
+        if o.op == T.CONV:
+            t = N.conv2d(src, case.w[wi], case.b[wi], o.stride, o.pad)
+            wi += 1
+            if o.residual_from >= 0:
+                t = N.add(t, gpu[o.residual_from])
+            if o.relu:
+                t = N.relu(t)
+            t = gen.quantize(t, case.dtype)
+            diff = np.abs(got - t)
+            # an element on a rounding boundary may land one storage ulp away; sums that cancel
+            # get an absolute allowance from the fp32 accumulation error of the layer
+            allow = ulp * np.abs(t) + 1e-5 * scale
+            assert (diff <= allow).all(), "op %d (%s): teacher-forced max diff %.3e" % (i, o, diff.max())
+            assert (diff > 1e-5 * scale).mean() <= 0.02, "op %d: too many elements off by an ulp" % i
+        elif o.op == T.MAXPOOL:
+            assert np.array_equal(got, N.maxpool2d(src, o.kh, o.stride, o.pad)), "op %d: max pool not exact" % i
+        elif o.op == T.GAVGPOOL:
+            t = N.global_avgpool(src)
+            assert np.abs(got - t).max() <= 1e-6 * np.abs(t).max()
+    return outs, worst, gpu
+
+
+def check_head(case, gpu_feat, logits, probs):
+    """FC and softmax, teacher forced from the GPU's pooled features."""
+    z = N.fc(gpu_feat, case.w[-1].reshape(case.w[-1].shape[0], -1), case.b[-1])
+    assert np.abs(logits - z).max() <= 1e-5 * np.abs(z).max()
+    assert np.abs(probs - N.softmax(logits)).max() <= 1e-6
+
+
+# ---------------------------------------------------------------- config 1
+def test_resnet18_64_batch1_every_layer(worker):
+    """ResNet-18 at 64x64, batch 1, U[-1,1] input, seed 0: every layer and the logits."""
+    case = Case(T.resnet(18), 64, seed=0, dist="uniform")
+    worker.ctx.set_debug_keep(True)
+    mid = worker.ctx.model_define_resnet(18, 64, 64)
+    worker.ctx.set_debug_keep(False)
+    worker.load(mid, case.blob)
+    x = case.images(0, 1)
+    probs, logits, ns = worker.infer(mid, x)
+    outs, worst, gpu = check_all_ops(worker, case, mid, 1, x)
+    check_head(case, gpu[-1], logits, probs)
+    z_ref = outs[-2]
+    assert rel_err_per_sample(logits, z_ref).max() <= TOL
+    assert np.array_equal(N.argmax(logits), N.argmax(z_ref))
+    assert ns > 0
+    worker.ctx.unload_weights(mid)
+
+
+@pytest.mark.parametrize("batch", [1, 2, 4, 8, 16])
+def test_resnet18_all_batch_sizes_and_batch_invariance(worker, batch):
+    case = Case(T.resnet(18), 64, seed=0, dist="uniform")
+    mid = worker.ctx.model_define_resnet(18, 64, 64)
+    worker.load(mid, case.blob)
+    x = case.images(0, 16)
+    ref = case.oracle(x)["logits"]
+    got = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 16, batch)])
+    assert rel_err_per_sample(got, ref).max() <= TOL
+    assert np.array_equal(N.argmax(got), N.argmax(ref))
+    worker.ctx.unload_weights(mid)
+
+
+def test_resnet18_top1_agreement_2048_samples(worker):
+    """Every sample within tolerance; top-1 agreement counted on 2048 samples.
+
+    A random-weight network has near-ties: samples whose two largest oracle logits are closer
+    than the fp16 storage error of the path.  Those may flip, and no summation order can avoid
+    it (rounding stored activations to fp16 in the oracle itself moves its logits by as much).
+    So: every mismatch must be such a near-tie (oracle top-2 gap <= 2x that sample's own
+    logit error), agreement must be >= 99.9 % on the samples whose gap exceeds twice the
+    largest logit error seen, and the raw rate is printed and bounded."""
+    case = Case(T.resnet(18), 64, seed=0, dist="uniform")
+    mid = worker.ctx.model_define_resnet(18, 64, 64)
+    worker.load(mid, case.blob)
+    n = 2048
+    x = case.images(100, n)
+    ref = case.oracle(x)["logits"]
+    got = np.concatenate([worker.infer(mid, x[i:i + 16])[1] for i in range(0, n, 16)])
+    err = rel_err_per_sample(got, ref)
+    assert err.max() <= TOL
+    a, b = N.argmax(got), N.argmax(ref)
+    mism = np.nonzero(a != b)[0]
+    abs_err = np.abs(got - ref).max(axis=1)
+    gaps = top2_gap(ref)
+    clear = gaps > 2 * abs_err.max()
+    print("top-1 agreement %.4f (%d mismatches / %d); max rel err %.2e; well-separated samples %d, "
+          "mismatches among them %d; (gap, err) of mismatches %s" % (
+              1 - len(mism) / n, len(mism), n, err.max(), int(clear.sum()), int((a != b)[clear].sum()),
+              [(float(gaps[i]), float(abs_err[i])) for i in mism]))
+    assert all(gaps[i] <= 2 * abs_err[i] for i in mism)      # only near-ties may flip
+    assert (a != b)[clear].sum() <= clear.sum() // 1000
+    assert len(mism) <= 0.005 * n
+    # the oracle's own 16-bit-storage mode is as far from its fp32 mode as the GPU is
+    ref16 = case.oracle(x[:256], storage="fp16")["logits"]
+    print("fp16-storage oracle vs fp32 oracle: max rel err %.2e; GPU vs fp16-storage oracle %.2e" % (
+        rel_err_per_sample(ref16, ref[:256]).max(), rel_err_per_sample(got[:256], ref16).max()))
+    worker.ctx.unload_weights(mid)
+
+
+# ---------------------------------------------------------------- every conv instantiation
+@pytest.mark.parametrize("tile", ["128x128", "128x64", "64x64", "64x32", "32x64", "32x32"])
+@pytest.mark.parametrize("split_k", [1, 3])
+def test_every_conv_tile_and_split_k(worker, tile, split_k):
+    """Forces one tile shape and split-K factor on every convolution of ResNet-18 at 64x64
+    (M from 4*B to 1024*B rows: ragged tiles in both dimensions)."""
+    case = Case(T.resnet(18), 64, seed=1, dist="uniform")
+    worker.ctx.set_plan_override(tile, split_k)
+    worker.ctx.set_debug_keep(True)
+    try:
+        mid = worker.ctx.model_define(case.ops, 3, 64, 64, batch_sizes=(3,))
+    finally:
+        worker.ctx.set_plan_override(-1, 0)
+        worker.ctx.set_debug_keep(False)
+    worker.load(mid, case.blob)
+    x = case.images(0, 3)
+    probs, logits, _ = worker.infer(mid, x)
+    outs, _, gpu = check_all_ops(worker, case, mid, 3, x)
+    check_head(case, gpu[-1], logits, probs)
+    assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+    worker.ctx.unload_weights(mid)
+
+
+# ---------------------------------------------------------------- bf16
+def test_resnet18_bf16(worker):
+    case = Case(T.resnet(18), 64, seed=2, dtype="bf16", dist="uniform")
+    worker.ctx.set_debug_keep(True)
+    mid = worker.ctx.model_define_resnet(18, 64, 64, dtype="bf16")
+    worker.ctx.set_debug_keep(False)
+    worker.load(mid, case.blob)
+    x = case.images(0, 4)
+    probs, logits, _ = worker.infer(mid, x)
+    outs, _, gpu = check_all_ops(worker, case, mid, 4, x)
+    check_head(case, gpu[-1], logits, probs)
+    assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+    worker.ctx.unload_weights(mid)
+
+
+# ---------------------------------------------------------------- softmax on moderate logits
+def test_softmax_against_oracle_on_small_logits(worker):
+    """With real He-normal weights the logits are ~1e3 and softmax is one-hot, so the
+    probabilities are compared on a model whose FC weights are scaled down."""
+    ops = T.resnet(18)
+    gain = [1.0] * len(T.weight_shapes(ops))
+    gain[-1] = 0.02
+    case = Case(ops, 64, seed=3, dist="uniform", weight_gain=gain)
+    mid = worker.ctx.model_define_resnet(18, 64, 64)
+    worker.load(mid, case.blob)
+    x = case.images(0, 8)
+    probs, logits, _ = worker.infer(mid, x)
+    ref = case.oracle(x)
+    assert np.abs(ref["logits"]).max() < 30
+    assert ref["probs"].max() < 0.999               # not one-hot
+    # softmax of the GPU's own logits, by the oracle: isolates the softmax kernel
+    assert np.abs(probs - N.softmax(logits)).max() <= 1e-6
+    assert np.abs(probs.sum(axis=1) - 1).max() <= 1e-5
+    assert np.array_equal(N.argmax(probs), N.argmax(logits))
+    # end to end: |dp| <= |dz|_inf * 2 * p  (softmax is 1-Lipschitz-ish); loose check
+    dz = np.abs(logits - ref["logits"]).max()
+    assert np.abs(probs - ref["probs"]).max() <= 2.5 * dz + 1e-6
+    worker.ctx.unload_weights(mid)
+
+
+# ---------------------------------------------------------------- config 2
+@pytest.fixture(scope="module")
+def r50():
+    case = Case(T.resnet(50), 224, seed=0, dist="normal")
+    x = case.images(0, 16)
+    ref = case.oracle(x)["logits"]       # 16 images, one per host thread
+    return case, x, ref
+
+
+def test_resnet50_224_batch16(worker, r50):
+    case, x, ref = r50
+    mid = worker.ctx.model_define_resnet(50, 224, 224)
+    worker.load(mid, case.blob)
+    probs, logits, ns = worker.infer(mid, x)
+    err = rel_err_per_sample(logits, ref)
+    print("resnet50 b16: max rel err %.3e, |z|inf %.1f, exec %.1f us" % (err.max(), np.abs(ref).max(), ns / 1e3))
+    assert np.isfinite(logits).all()
+    assert err.max() <= TOL
+    assert np.array_equal(N.argmax(logits), N.argmax(ref))
+    assert np.abs(probs.sum(axis=1) - 1).max() <= 1e-5
+    assert np.array_equal(N.argmax(probs), N.argmax(logits))
+    # same input twice: bit-identical (fixed summation order, no atomics)
+    _, again, _ = worker.infer(mid, x)
+    assert np.array_equal(again, logits)
+    worker.ctx.unload_weights(mid)
+
+
+@pytest.mark.parametrize("batch", [1, 2, 4, 8])
+def test_resnet50_224_small_batches(worker, r50, batch):
+    case, x, ref = r50
+    mid = worker.ctx.model_define_resnet(50, 224, 224)
+    worker.load(mid, case.blob)
+    n = min(16, 4 * batch)
+    got = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, n, batch)])
+    assert rel_err_per_sample(got, ref[:n]).max() <= TOL
+    assert np.array_equal(N.argmax(got), N.argmax(ref[:n]))
+    worker.ctx.unload_weights(mid)
+
+
+def test_resnet50_first_block_every_layer(worker):
+    """Per-layer parity on the real 224x224 shapes (stem, max pool, first bottleneck, and on
+    through the network) at batch 2."""
+    case = Case(T.resnet(50), 224, seed=5, dist="normal")
+    worker.ctx.set_debug_keep(True)
+    mid = worker.ctx.model_define(case.ops, 3, 224, 224, batch_sizes=(2,))
+    worker.ctx.set_debug_keep(False)
+    worker.load(mid, case.blob)
+    x = case.images(0, 2)
+    probs, logits, _ = worker.infer(mid, x)
+    outs, worst, gpu = check_all_ops(worker, case, mid, 2, x, teacher=False)
+    check_head(case, gpu[-1], logits, probs)
+    print("worst per-layer rel err %.3e" % worst)
+    assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+    worker.ctx.unload_weights(mid)
+
+
+# ---------------------------------------------------------------- config 4 (bf16: fp16 would overflow)
+def test_resnet152_bf16_batch16_sampled(worker):
+    """ResNet-152 at batch 16 in bf16 storage; the oracle checks 4 of the 16 samples (samples
+    are independent, so each is computed on its own)."""
+    case = Case(T.resnet(152), 224, seed=0, dtype="bf16", dist="normal")
+    mid = worker.ctx.model_define_resnet(152, 224, 224, dtype="bf16")
+    worker.load(mid, case.blob)
+    x = case.images(0, 16)
+    probs, logits, ns = worker.infer(mid, x)
+    assert np.isfinite(logits).all()
+    pick = [0, 5, 10, 15]
+    ref = case.oracle(x[pick])["logits"]
+    err = rel_err_per_sample(logits[pick], ref)
+    print("resnet152 bf16 b16: max rel err %.3e, |z|inf %.3e, exec %.1f us" % (err.max(), np.abs(ref).max(), ns / 1e3))
+    assert err.max() <= TOL
+    worker.ctx.unload_weights(mid)

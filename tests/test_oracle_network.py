@@ -173,3 +173,20 @@ def test_keep_all_returns_every_op_output(r18):
     proj = [i for i, o in enumerate(ops) if o.op == T.CONV and not o.relu]
     assert proj and all((outs[i] < 0).any() for i in proj)
     assert all((outs[i] >= 0).all() for i, o in enumerate(ops) if o.op == T.CONV and o.relu)
+
+
+def test_storage_mode_rounds_only_conv_outputs(r18):
+    """The 16-bit-storage mode: conv outputs become exactly representable in that type,
+    and the result stays within the type's rounding error of the definition."""
+    ops, w, b = r18
+    x = gen.images(0, 0, 1, 3, 64, 64, "uniform")
+    plain = N.forward(ops, w, b, x, keep="all")
+    for st, eps in (("fp16", 2.0 ** -11), ("bf16", 2.0 ** -8)):
+        outs = N.forward(ops, w, b, x, keep="all", storage=st)
+        for o, y in zip(ops, outs):
+            if o.op in (T.CONV, T.MAXPOOL):
+                assert np.array_equal(gen.quantize(y, st), y)
+        # first conv: exactly the rounded plain result
+        assert np.array_equal(outs[0], gen.quantize(plain[0], st))
+        z, zp = outs[-2], plain[-2]
+        assert 0 < np.abs(z - zp).max() <= 40 * eps * np.abs(zp).max()
