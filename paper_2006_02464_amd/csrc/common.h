@@ -97,6 +97,8 @@ hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B,
                                    int W, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 
+// K-slice width the conv kernel uses for a shape (64, or 32 for the stem / Cin % 64 != 0).
+int conv_bk(const ConvArgs &a, bool stem);
 // Grid and block of a conv launch (pure function of tile and shape).
 void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block);
 void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block);

@@ -1,22 +1,43 @@
 // Implicit-GEMM convolution on gfx950 MFMA (v_mfma_f32_32x32x16_{f16,bf16}), fp32 accumulate.
 //
-// GEMM view: M = B*Ho*Wo output pixels (rows, NHWC so a row of y is Cout contiguous values),
-// N = Cout, K = kh*kwp*Cin ordered (r, s, c) so that for one filter tap the K slice is the
+// GEMM view: M = B*Ho*Wo output pixels (rows; NHWC, so a row of y is Cout contiguous values),
+// N = Cout, K = kh*kwp*Cin ordered (r, s, c), so that for one filter tap the K slice is the
 // Cin-contiguous run of one input pixel.  A (activations) is gathered on the fly with zero
 // fill for padded taps; B (weights) was re-laid out at LOAD as [Cout][K].
 //
-// Per workgroup: a BM x BN output tile; K is walked in slices of 32 through two LDS stages
-// (global -> registers -> LDS, one barrier per slice).  Each wave owns a (BM/WARPS_M) x
-// (BN/WARPS_N) sub-tile made of 32x32 MFMA tiles.
+// Per workgroup: a BM x BN output tile.  K is walked in slices of BK (64, or 32 for the stem and
+// for Cin not divisible by 64).  Slices travel global -> registers -> LDS: PF register sets
+// hold the next PF slices in flight while the MFMAs consume the current one out of one of two
+// LDS stages (one barrier per slice).  All global reads are raw buffer loads: a padded tap, a
+// row beyond M, a channel beyond Cout or a slice beyond the K range is given an offset outside
+// the buffer, for which the hardware returns zeros.  That keeps the steady-state loop free of
+// branches, so the compiler can wait for exactly the oldest register set (s_waitcnt vmcnt(n))
+// instead of draining every load in flight.  LDS rows are BK elements with the 16-byte chunk index
+// XOR-swizzled by the row, so both the 16-byte writes and the MFMA operand reads (lane = row,
+// 8 consecutive k) are free of bank conflicts without padding.
 //
-// Epilogue (fused): + bias, + residual, ReLU, one round-to-nearest-even to the storage type.
-// With split-K (gridDim.y > 1) the raw fp32 partial sums go to a [split][M][Cout] buffer and
-// a second kernel reduces them in fixed order and applies the same epilogue.
+// Each wave owns a (BM/WARPS_M) x (BN/WARPS_N) sub-tile made of 32x32 MFMA tiles.
+//
+// Epilogue (fused): accumulators (+ bias) are transposed through LDS, 32 rows at a time per
+// wave, so that every lane then owns 8 consecutive output channels of one pixel: the residual
+// is read and the result written as 16-byte vectors (a row of a wave's sub-tile is one
+// contiguous run).  + residual, ReLU, one round-to-nearest-even to the storage type.
+// With split-K (gridDim.y > 1) the raw fp32 partial sums go to a [split][M][Cout] buffer and a
+// second kernel reduces them in fixed order and applies the same epilogue.
 #include "common.h"
 
 namespace cw {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (tensors are < 2 GiB)
+
+static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes) {
+    // raw buffer (stride 0), 32-bit data format word as on every CDNA part
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
 
 template <typename T>
 struct Mfma;
@@ -35,21 +56,31 @@ struct Mfma<bf16> {
     }
 };
 
-constexpr int BK = 32;   // K slice per LDS stage
-constexpr int BKP = 40;  // LDS row pitch in elements (80 B): conflict-free ds_read_b128
+// Element offset of 16-byte chunk c of `row` inside a [rows][BK] LDS stage.
+template <int BK>
+static __device__ __forceinline__ int swz(int row, int c) {
+    if (BK == 64) return row * 64 + ((c ^ (row & 7)) << 3);
+    return row * 32 + ((c ^ ((row >> 1) & 3)) << 3);
+}
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, bool STEM>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, bool STEM>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int NT = 64 * WARPS_M * WARPS_N;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_CHUNKS = BM * (BK / 8), B_CHUNKS = BN * (BK / 8);  // 16-byte chunks
+    constexpr int CPR = BK / 8;  // 16-byte chunks per LDS row
+    constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BN * CPR;
     static_assert(A_CHUNKS % NT == 0 && B_CHUNKS % NT == 0, "tile/threads mismatch");
+    static_assert(!STEM || BK == 32, "the stem walks one filter row (8 taps x 4 channels) per slice");
     constexpr int A_PER = A_CHUNKS / NT, B_PER = B_CHUNKS / NT;
+    constexpr int STAGE = (BM + BN) * BK;  // elements per LDS stage
+    constexpr int EPI_PITCH = WN + 8;      // floats; (4*pitch) % 64 == 32 keeps half-waves on disjoint banks
+    constexpr int EPI_BYTES = WARPS_M * WARPS_N * 32 * EPI_PITCH * 4;
+    constexpr int LDS_BYTES = 2 * STAGE * 2 > EPI_BYTES ? 2 * STAGE * 2 : EPI_BYTES;
     typedef typename Mfma<T>::v8 v8;
 
-    __shared__ __attribute__((aligned(16))) T sA[2][BM * BKP];
-    __shared__ __attribute__((aligned(16))) T sB[2][BN * BKP];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+    T *const lds = reinterpret_cast<T *>(smem);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -57,25 +88,33 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     const int wm0 = (wave / WARPS_N) * WM;
     const int wn0 = (wave % WARPS_N) * WN;
 
+    // Workgroups go to the 8 XCDs round-robin; give each XCD a contiguous run of tiles so that
+    // tiles sharing activation rows (same tile_m) meet in one XCD's L2.
+    int tile_id;
+    {
+        const int nb = gridDim.x, bid = blockIdx.x;
+        const int xcd = bid & 7, idx = bid >> 3;
+        const int per = nb >> 3, rem = nb & 7;
+        tile_id = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    }
     const int tiles_n = (a.Cout + BN - 1) / BN;
-    const int tile_m = blockIdx.x / tiles_n;
-    const int tile_n = blockIdx.x - tile_m * tiles_n;
+    const int tile_m = tile_id / tiles_n;
+    const int tile_n = tile_id - tile_m * tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int ktiles = a.K / BK;
     const int kt0 = blockIdx.y * a.ktiles_per_split;
     const int kt1 = min(ktiles, kt0 + a.ktiles_per_split);
 
-    const T *__restrict__ xg = static_cast<const T *>(a.x);
-    const T *__restrict__ wg = static_cast<const T *>(a.w);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.B * a.H * a.W * a.Cin * 2u);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (unsigned)a.Cout * a.K * 2u);
 
     // Per-thread gather coordinates of its A chunks (fixed for the whole K walk).
     int a_pix[A_PER];  // element offset of x[n][0][0][0], or -1 if the row is beyond M
     int a_ih0[A_PER], a_iw0[A_PER];
 #pragma unroll
     for (int j = 0; j < A_PER; ++j) {
-        const int cid = tid + j * NT;
-        const int m = m0 + (cid >> 2);
+        const int m = m0 + (tid + j * NT) / CPR;
         if (m < a.M) {
             const int q = m % a.Wo;
             const int t = m / a.Wo;
@@ -90,10 +129,16 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
             a_iw0[j] = 0;
         }
     }
+    // Byte offset of this thread's B chunks at slice 0, or out of bounds beyond Cout.
+    unsigned b_off[B_PER];
+#pragma unroll
+    for (int j = 0; j < B_PER; ++j) {
+        const int cid = tid + j * NT;
+        const int n = n0 + cid / CPR;
+        b_off[j] = n < a.Cout ? ((unsigned)n * a.K + (cid % CPR) * 8) * 2u : kOob;
+    }
 
-    uint4 ra[A_PER], rb[B_PER];
-
-    // (r, s, c0) of K slice kt: k0 = kt*32 = ((r*kwp + s)*Cin + c0).
+    // (r, s, c0) of the next K slice to load: k0 = kt*BK = (r*kwp + s)*Cin + c0.
     int fr, fs, fc0;
     if (STEM) {
         fr = kt0; fs = 0; fc0 = 0;
@@ -105,44 +150,37 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         fs = rs - fr * a.kwp;
     }
 
-    auto load_global = [&](int kt) {
+    u32x4 ra[PF][A_PER], rb[PF][B_PER];
+
+    // Issues the loads of slice kt (all zeros if kt >= kt1).  No branches.
+    auto load_global = [&](int kt, u32x4(&qa)[A_PER], u32x4(&qb)[B_PER]) {
+        const bool live = kt < kt1;
 #pragma unroll
         for (int j = 0; j < A_PER; ++j) {
-            const int cid = tid + j * NT;
-            const int kc = cid & 3;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            const int c = (tid + j * NT) % CPR;
             if (STEM) {
-                // Cin == 4, kwp == 8: slice kt is filter row r = kt; chunk kc holds taps 2kc, 2kc+1.
+                // Cin == 4, kwp == 8: slice kt is filter row r = kt; chunk c holds taps 2c, 2c+1.
                 const int ih = a_ih0[j] + fr;
-                if (a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H) {
-                    const int iw = a_iw0[j] + 2 * kc;
-                    const T *row = xg + a_pix[j] + (ih * a.W) * 4;
-                    if ((unsigned)iw < (unsigned)a.W) {
-                        const uint2 t = *reinterpret_cast<const uint2 *>(row + iw * 4);
-                        v.x = t.x; v.y = t.y;
-                    }
-                    if ((unsigned)(iw + 1) < (unsigned)a.W) {
-                        const uint2 t = *reinterpret_cast<const uint2 *>(row + (iw + 1) * 4);
-                        v.z = t.x; v.w = t.y;
-                    }
-                }
+                const int iw = a_iw0[j] + 2 * c;
+                const bool row_ok = live && a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H;
+                const unsigned base = (unsigned)(a_pix[j] + (ih * a.W + iw) * 4) * 2u;
+                const unsigned o0 = (row_ok && (unsigned)iw < (unsigned)a.W) ? base : kOob;
+                const unsigned o1 = (row_ok && (unsigned)(iw + 1) < (unsigned)a.W) ? base + 8u : kOob;
+                const u32x2 t0 = __builtin_amdgcn_raw_buffer_load_b64(rx, o0, 0, 0);
+                const u32x2 t1 = __builtin_amdgcn_raw_buffer_load_b64(rx, o1, 0, 0);
+                qa[j] = u32x4{t0.x, t0.y, t1.x, t1.y};
             } else {
                 const int ih = a_ih0[j] + fr, iw = a_iw0[j] + fs;
-                if (a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-                    v = *reinterpret_cast<const uint4 *>(xg + a_pix[j] + (ih * a.W + iw) * a.Cin + fc0 + kc * 8);
+                const bool ok = live && a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+                const unsigned o = ok ? (unsigned)(a_pix[j] + (ih * a.W + iw) * a.Cin + fc0 + c * 8) * 2u : kOob;
+                qa[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, o, 0, 0);
             }
-            ra[j] = v;
         }
+        // b_off is a real offset or kOob; adding the slice offset (< 2 GiB) keeps kOob out of bounds
+        const unsigned kb = (unsigned)kt * (BK * 2u);
 #pragma unroll
-        for (int j = 0; j < B_PER; ++j) {
-            const int cid = tid + j * NT;
-            const int n = n0 + (cid >> 2);
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (n < a.Cout)
-                v = *reinterpret_cast<const uint4 *>(wg + (size_t)n * a.K + kt * BK + (cid & 3) * 8);
-            rb[j] = v;
-        }
-        // advance (r, s, c0) to the next slice
+        for (int j = 0; j < B_PER; ++j)
+            qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, live ? b_off[j] + kb : kOob, 0, 0);
         if (STEM) {
             fr += 1;
         } else {
@@ -153,18 +191,23 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
             }
         }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf, const u32x4(&qa)[A_PER], const u32x4(&qb)[B_PER]) {
+        T *sA = lds + buf * STAGE;
+        T *sB = sA + BM * BK;
 #pragma unroll
         for (int j = 0; j < A_PER; ++j) {
             const int cid = tid + j * NT;
-            *reinterpret_cast<uint4 *>(&sA[buf][(cid >> 2) * BKP + (cid & 3) * 8]) = ra[j];
+            *reinterpret_cast<u32x4 *>(sA + swz<BK>(cid / CPR, cid % CPR)) = qa[j];
         }
 #pragma unroll
         for (int j = 0; j < B_PER; ++j) {
             const int cid = tid + j * NT;
-            *reinterpret_cast<uint4 *>(&sB[buf][(cid >> 2) * BKP + (cid & 3) * 8]) = rb[j];
+            *reinterpret_cast<u32x4 *>(sB + swz<BK>(cid / CPR, cid % CPR)) = qb[j];
         }
     };
+
+    const int lrow = lane & 31;
+    const int lhalf = lane >> 5;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -174,87 +217,139 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (kt0 < kt1) {
-        load_global(kt0);
-        store_lds(0);
-    }
-    __syncthreads();
-
-    const int lrow = lane & 31;
-    const int lk = (lane >> 5) * 8;
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int cur = (kt - kt0) & 1;
-        const bool more = kt + 1 < kt1;
-        if (more) load_global(kt + 1);
+    auto compute = [&](int cur) {
+        const T *sA = lds + cur * STAGE;
+        const T *sB = sA + BM * BK;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             v8 fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const v8 *>(&sA[cur][(wm0 + i * 32 + lrow) * BKP + kk * 16 + lk]);
+                fa[i] = *reinterpret_cast<const v8 *>(sA + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const v8 *>(&sB[cur][(wn0 + j * 32 + lrow) * BKP + kk * 16 + lk]);
+                fb[j] = *reinterpret_cast<const v8 *>(sB + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fa[i], fb[j], acc[i][j]);
         }
-        if (more) store_lds(cur ^ 1);
-        __syncthreads();
+    };
+
+    // Prologue: slices kt0 .. kt0+PF-1 into the register sets, the first one on into LDS.
+#pragma unroll
+    for (int u = 0; u < PF; ++u) load_global(kt0 + u, ra[u], rb[u]);
+    store_lds(0, ra[0], rb[0]);
+    __syncthreads();
+
+    // Steady state, PF slices per trip, no branches inside: register set u held slice kt and
+    // is in LDS by now, so it is refilled with slice kt+PF; the MFMAs run on slice kt; then
+    // set u+1 (slice kt+1, the oldest load in flight) goes to the other LDS stage.
+    int kt = kt0;
+    int cur = 0;
+    for (; kt + PF <= kt1; kt += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            load_global(kt + u + PF, ra[u], rb[u]);
+            compute(cur);
+            store_lds(cur ^ 1, ra[(u + 1) % PF], rb[(u + 1) % PF]);
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+    // Tail: fewer than PF slices left, nothing more to load.
+#pragma unroll
+    for (int u = 0; u < PF - 1; ++u) {
+        if (kt + u < kt1) {  // uniform across the workgroup
+            compute(cur);
+            if (kt + u + 1 < kt1) store_lds(cur ^ 1, ra[(u + 1) % PF], rb[(u + 1) % PF]);
+            __syncthreads();
+            cur ^= 1;
+        }
     }
 
-    // Epilogue.  Lane holds column n = lane%32 and rows 8*(e/4) + 4*(lane/32) + e%4 of each tile.
-    const int rhalf = (lane >> 5) * 4;
+    // Epilogue.  In an MFMA tile the lane holds column lane%32 and rows 8*(e/4) + 4*(lane/32) + e%4.
+    constexpr int LPR = WN / 8;    // lanes per output row when each lane takes 8 channels
+    constexpr int RPP = 64 / LPR;  // rows per pass
+    float *stage = reinterpret_cast<float *>(smem) + wave * 32 * EPI_PITCH;
+    const int rr0 = lane / LPR, cc = lane % LPR;
+    const int n_out = n0 + wn0 + cc * 8;
+    float bias[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn0 + j * 32 + lrow;
-        if (n >= a.Cout) continue;
-        const float bias = a.partial ? 0.f : a.bias[n];
+        bias[j] = (a.partial || n >= a.Cout) ? 0.f : a.bias[n];
+    }
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm0 + i * 32 + 8 * (e >> 2) + rhalf + (e & 3);
-                if (m >= a.M) continue;
-                const size_t o = (size_t)m * a.Cout + n;
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stage[(8 * (e >> 2) + 4 * lhalf + (e & 3)) * EPI_PITCH + j * 32 + lrow] = acc[i][j][e] + bias[j];
+        __syncthreads();
+#pragma unroll
+        for (int ps = 0; ps < 32 / RPP; ++ps) {
+            const int rr = ps * RPP + rr0;
+            const int m = m0 + wm0 + i * 32 + rr;
+            const float4 v0 = *reinterpret_cast<const float4 *>(stage + rr * EPI_PITCH + cc * 8);
+            const float4 v1 = *reinterpret_cast<const float4 *>(stage + rr * EPI_PITCH + cc * 8 + 4);
+            if (m < a.M && n_out < a.Cout) {
+                const size_t o = (size_t)m * a.Cout + n_out;
                 if (a.partial) {
-                    a.partial[(size_t)blockIdx.y * a.M * a.Cout + o] = acc[i][j][e];
+                    float *dst = a.partial + (size_t)blockIdx.y * a.M * a.Cout + o;
+                    *reinterpret_cast<float4 *>(dst) = v0;
+                    *reinterpret_cast<float4 *>(dst + 4) = v1;
                 } else {
-                    float v = acc[i][j][e] + bias;
-                    if (a.res) v += (float)static_cast<const T *>(a.res)[o];
-                    if (a.relu) v = fmaxf(v, 0.f);
-                    static_cast<T *>(a.y)[o] = (T)v;
+                    float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                    if (a.res) {
+                        const uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const T *>(a.res) + o);
+                        const T *r = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] += (float)r[e];
+                    }
+                    T out[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) out[e] = (T)(a.relu ? fmaxf(v[e], 0.f) : v[e]);
+                    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + o) = *reinterpret_cast<const uint4 *>(out);
                 }
             }
         }
+        if (i + 1 < TM) __syncthreads();
     }
 }
 
-// Fixed-order reduction of split-K partials + the fused epilogue. One thread = 4 columns.
+// Fixed-order reduction of split-K partials + the fused epilogue.  One thread = 8 columns.
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const ReduceArgs a) {
-    const size_t total4 = (size_t)a.M * a.Cout / 4;
+    const size_t total8 = (size_t)a.M * a.Cout / 8;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total4) return;
-    const size_t o = idx * 4;
+    if (idx >= total8) return;
+    const size_t o = idx * 8;
     const int n = (int)(o % a.Cout);
-    float4 s = *reinterpret_cast<const float4 *>(a.partial + o);
+    const size_t plane = (size_t)a.M * a.Cout;
+    float4 s0 = *reinterpret_cast<const float4 *>(a.partial + o);
+    float4 s1 = *reinterpret_cast<const float4 *>(a.partial + o + 4);
     for (int z = 1; z < a.split_k; ++z) {
-        const float4 t = *reinterpret_cast<const float4 *>(a.partial + (size_t)z * a.M * a.Cout + o);
-        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        const float4 t0 = *reinterpret_cast<const float4 *>(a.partial + z * plane + o);
+        const float4 t1 = *reinterpret_cast<const float4 *>(a.partial + z * plane + o + 4);
+        s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
+        s1.x += t1.x; s1.y += t1.y; s1.z += t1.z; s1.w += t1.w;
     }
-    const float4 b = *reinterpret_cast<const float4 *>(a.bias + n);
-    float v[4] = {s.x + b.x, s.y + b.y, s.z + b.z, s.w + b.w};
+    const float4 b0 = *reinterpret_cast<const float4 *>(a.bias + n);
+    const float4 b1 = *reinterpret_cast<const float4 *>(a.bias + n + 4);
+    float v[8] = {s0.x + b0.x, s0.y + b0.y, s0.z + b0.z, s0.w + b0.w,
+                  s1.x + b1.x, s1.y + b1.y, s1.z + b1.z, s1.w + b1.w};
     if (a.res) {
-        const T *r = static_cast<const T *>(a.res) + o;
+        const uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const T *>(a.res) + o);
+        const T *r = reinterpret_cast<const T *>(&raw);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] += (float)r[i];
+        for (int i = 0; i < 8; ++i) v[i] += (float)r[i];
     }
-    T out[4];
+    T out[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) out[i] = (T)(a.relu ? fmaxf(v[i], 0.f) : v[i]);
-    *reinterpret_cast<uint2 *>(static_cast<T *>(a.y) + o) = *reinterpret_cast<const uint2 *>(out);
+    for (int i = 0; i < 8; ++i) out[i] = (T)(a.relu ? fmaxf(v[i], 0.f) : v[i]);
+    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + o) = *reinterpret_cast<const uint4 *>(out);
 }
 
 TileDim conv_tile_dim(ConvTile t) {
@@ -268,6 +363,8 @@ TileDim conv_tile_dim(ConvTile t) {
     }
 }
 
+int conv_bk(const ConvArgs &a, bool stem) { return (!stem && a.Cin % 64 == 0) ? 64 : 32; }
+
 void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block) {
     const TileDim d = conv_tile_dim(tile);
     const unsigned tm = (a.M + d.bm - 1) / d.bm, tn = (a.Cout + d.bn - 1) / d.bn;
@@ -276,44 +373,52 @@ void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block) {
 }
 
 void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block) {
-    const size_t total4 = (size_t)a.M * a.Cout / 4;
-    *grid = dim3((unsigned)((total4 + 255) / 256), 1, 1);
+    const size_t total8 = (size_t)a.M * a.Cout / 8;
+    *grid = dim3((unsigned)((total8 + 255) / 256), 1, 1);
     *block = 256;
 }
 
-template <typename T, bool STEM>
+constexpr int kPrefetch = 3;  // K slices in flight in registers
+
+template <typename T, int BK, bool STEM>
 static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s) {
     dim3 grid;
     int block;
     conv_grid(tile, a, &grid, &block);
     switch (tile) {
-        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, STEM><<<grid, block, 0, s>>>(a); break;
-        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, STEM><<<grid, block, 0, s>>>(a); break;
-        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, STEM><<<grid, block, 0, s>>>(a); break;
-        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, STEM><<<grid, block, 0, s>>>(a); break;
-        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, STEM><<<grid, block, 0, s>>>(a); break;
-        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, STEM><<<grid, block, 0, s>>>(a); break;
+        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
+template <typename T>
+static hipError_t launch_conv_dt(ConvTile tile, bool stem, int bk, const ConvArgs &a, hipStream_t s) {
+    if (stem) return launch_conv_t<T, 32, true>(tile, a, s);
+    if (bk == 64) return launch_conv_t<T, 64, false>(tile, a, s);
+    return launch_conv_t<T, 32, false>(tile, a, s);
+}
+
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
     // Shapes the kernel's indexing relies on; the plan compiler guarantees them, checked again
     // here so that a bad launch is an error instead of an out-of-bounds access.
-    if (a.K % BK != 0 || a.M <= 0 || a.Cout <= 0 || a.split_k < 1 || a.ktiles_per_split < 1)
+    const int bk = conv_bk(a, stem);
+    if (a.K % bk != 0 || a.M <= 0 || a.Cout <= 0 || a.Cout % 8 != 0 || a.split_k < 1 || a.ktiles_per_split < 1)
         return hipErrorInvalidValue;
-    if (stem ? (a.Cin != 4 || a.kwp != 8 || a.K != a.kh * 32) : (a.Cin % BK != 0 || a.kwp != a.kw))
+    if (stem ? (a.Cin != 4 || a.kwp != 8 || a.K != a.kh * 32) : (a.Cin % 32 != 0 || a.kwp != a.kw || a.K != a.kh * a.kw * a.Cin))
         return hipErrorInvalidValue;
-    if ((long long)a.split_k * a.ktiles_per_split < a.K / BK) return hipErrorInvalidValue;
+    if ((long long)a.split_k * a.ktiles_per_split < a.K / bk) return hipErrorInvalidValue;
     if (a.split_k > 1 && !a.partial) return hipErrorInvalidValue;
-    if (dt == DT_F16)
-        return stem ? launch_conv_t<f16, true>(tile, a, s) : launch_conv_t<f16, false>(tile, a, s);
-    return stem ? launch_conv_t<bf16, true>(tile, a, s) : launch_conv_t<bf16, false>(tile, a, s);
+    return dt == DT_F16 ? launch_conv_dt<f16>(tile, stem, bk, a, s) : launch_conv_dt<bf16>(tile, stem, bk, a, s);
 }
 
 hipError_t launch_splitk_reduce(DType dt, const ReduceArgs &a, hipStream_t s) {
-    if (a.Cout % 4 != 0 || a.split_k < 1) return hipErrorInvalidValue;
+    if (a.Cout % 8 != 0 || a.split_k < 1) return hipErrorInvalidValue;
     dim3 grid;
     int block;
     reduce_grid(a, &grid, &block);

@@ -266,11 +266,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     p.batch = batch;
     p.op_out.assign(n_ops, Ref{});
 
-    // Guard the 32-bit element indexing of the conv kernel.
+    // Guard the 32-bit byte offsets of the conv kernel's buffer loads (tensors stay below 2 GiB).
     {
         int64_t biggest = (int64_t)batch * m.in_h * m.in_w * 4;
         for (const OpShape &s : m.shapes) biggest = std::max<int64_t>(biggest, (int64_t)batch * s.c * s.h * s.w);
-        if (biggest >= (int64_t)1 << 31) return fail(err, CW_ERR_BAD_BATCH, "batch %d: tensor exceeds 2^31 elements", batch);
+        if (biggest >= (int64_t)1 << 30) return fail(err, CW_ERR_BAD_BATCH, "batch %d: a tensor exceeds 2^30 elements", batch);
     }
 
     std::vector<int> last_use(n_ops, -1);
@@ -325,7 +325,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 a.M = batch * os.h * os.w;
                 a.K = o.kh * ws.kwp * ws.cinp;
                 a.relu = o.relu;
-                const int ktiles = a.K / 32;
+                const int ktiles = a.K / conv_bk(a, l.stem);
                 pick_conv_tile(a.M, a.Cout, ktiles, ov, &l.tile, &a.split_k);
                 a.ktiles_per_split = (ktiles + a.split_k - 1) / a.split_k;
                 a.split_k = (ktiles + a.ktiles_per_split - 1) / a.ktiles_per_split;  // no empty splits

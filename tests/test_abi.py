@@ -89,7 +89,7 @@ def test_plan_override_reaches_every_tile(ctx):
         bm, bn = (int(v) for v in name.split("x"))
         convs = [l for l in ctx.plan(m, 4) if l["name"].startswith(("conv", "stem"))]
         assert convs and all((l["tile_m"], l["tile_n"]) == (bm, bn) for l in convs)
-        assert all(l["split_k"] == 2 for l in convs)
+        assert all(l["split_k"] == 2 or l["gemm_k"] <= 64 for l in convs)   # one K slice cannot be split
     ctx.set_plan_override(-1, 0)
 
 
