@@ -97,12 +97,11 @@ def main():
     # ---- per-launch durations by HIP events on the EXEC stream (separate pass: an event pair
     # around every launch would perturb the timed region above)
     plan = ctx.plan(mid, B)
-    reps = 20
+    reps = 5
     per = np.zeros(len(plan))
-    for _ in range(3):
-        ctx.exec_timed_launches(mid, B, slot, stream)
+    ctx.exec_timed_launches(mid, B, slot, stream, inner=5)
     for _ in range(reps):
-        per += ctx.exec_timed_launches(mid, B, slot, stream)
+        per += ctx.exec_timed_launches(mid, B, slot, stream, inner=20)
     per /= reps
     conv = [i for i, l in enumerate(plan) if l["kind"] == 1]
     conv_us = float(sum(per[i] for i in conv))

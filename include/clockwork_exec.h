@@ -97,8 +97,8 @@ int32_t cw_destroy(cw_ctx *ctx);
  * size, batch) only.  Nothing is tuned or chosen at run time.
  * ops, batch_sizes: [host], copied.  The first op must read the network input
  * (in_c x in_h x in_w, NCHW fp32 at the boundary); the list must end FC, SOFTMAX.
- * Supported: CONV with cin % 32 == 0 and cout % 32 == 0 anywhere, plus a first
- * CONV with cin <= 4; kh == kw.  Returns CW_ERR_UNSUPPORTED otherwise,
+ * Supported: CONV with cin % 32 == 0, cout % 32 == 0 and kh == kw <= 5 anywhere,
+ * plus a first CONV with cin <= 4 and kh == kw <= 8.  Returns CW_ERR_UNSUPPORTED otherwise,
  * CW_ERR_NO_MEMORY if a plan's workspace exceeds workspace_bytes. */
 int32_t cw_model_define(cw_ctx *ctx, const cw_op *ops, int32_t n_ops,
                         int32_t in_c, int32_t in_h, int32_t in_w,
@@ -186,9 +186,11 @@ typedef struct {
 int32_t cw_plan_launch_info(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t index,
                             cw_launch_info *out);
 /* Runs EXEC like cw_exec but times every launch of the plan with its own pair of
- * events; launch_us [host] receives cw_plan_num_launches() values.  Synchronous. */
+ * events, issuing it `inner` (>= 1) times back to back between them (a launch is
+ * idempotent); launch_us [host] receives cw_plan_num_launches() averages, each
+ * including the dispatch cost of one launch.  Synchronous. */
 int32_t cw_exec_timed_launches(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot,
-                               float *launch_us, void *stream);
+                               int32_t inner, float *launch_us, void *stream);
 /* Copies the output of op `op_index` from the slot's last EXEC to host_out [host]
  * as fp32 NCHW [batch][cout][h][w].  Needs the context to have been created with
  * debug retention (cw_set_debug_keep) before the plan was built; otherwise the

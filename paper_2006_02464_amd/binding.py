@@ -64,7 +64,7 @@ SIGNATURES = {
     "cw_profile_get": (c_int32, [c_void_p, c_int32, c_int32, POINTER(cw_profile)]),
     "cw_plan_num_launches": (c_int32, [c_void_p, c_int32, c_int32]),
     "cw_plan_launch_info": (c_int32, [c_void_p, c_int32, c_int32, c_int32, POINTER(cw_launch_info)]),
-    "cw_exec_timed_launches": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]),
+    "cw_exec_timed_launches": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p]),
     "cw_debug_read_op": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_size_t]),
     "cw_set_debug_keep": (c_int32, [c_void_p, c_int32]),
     "cw_set_plan_override": (c_int32, [c_void_p, c_int32, c_int32]),
@@ -239,9 +239,9 @@ class Context:
     def plan(self, model_id, batch):
         return [self.plan_launch_info(model_id, batch, i) for i in range(self.plan_num_launches(model_id, batch))]
 
-    def exec_timed_launches(self, model_id, batch, slot, stream=None):
+    def exec_timed_launches(self, model_id, batch, slot, stream=None, inner=1):
         us = np.empty(self.plan_num_launches(model_id, batch), np.float32)
-        self._check(lib().cw_exec_timed_launches(self._h, model_id, batch, slot, _ptr(us), _stream(stream)))
+        self._check(lib().cw_exec_timed_launches(self._h, model_id, batch, slot, inner, _ptr(us), _stream(stream)))
         return us
 
     def debug_read_op(self, model_id, batch, op_index, shape):

@@ -450,8 +450,9 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     if ((e = hipMemcpyAsync(c->staging, host_blob, bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "hipMemcpyAsync");
     char *base = c->pool + off;
     for (const WeightSlot &ws : m->m.wslots) {
+        const bool is_conv = m->m.ops[ws.op_index].op == CW_OP_CONV;
         e = launch_pack_weights(c->staging + ws.blob_w_off, base + ws.packed_w_off, ws.cout, ws.cin, ws.kh, ws.kw, ws.kwp,
-                                ws.cinp, st);
+                                ws.cinp, is_conv, st);
         if (e != hipSuccess) return bail(e, "pack_weights");
         e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
                             reinterpret_cast<float *>(base + ws.packed_b_off), ws.cout, st);
@@ -518,11 +519,12 @@ int32_t cw_exec(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, void *
     return CW_OK;
 }
 
-int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, float *launch_us, void *stream) {
+int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, int32_t inner, float *launch_us,
+                               void *stream) {
     ModelRt *m; Plan *p; Slot *s;
     int32_t rc = exec_checks(c, model_id, batch, slot, &m, &p, &s);
     if (rc != CW_OK) return rc;
-    if (!launch_us) return set_err(c, CW_ERR_INVALID, "null output");
+    if (!launch_us || inner < 1) return set_err(c, CW_ERR_INVALID, "null output or inner < 1");
     DeviceGuard g(c->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = exec_gate(c, m, s, st);
@@ -533,15 +535,17 @@ int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32
         const size_t cnt = std::min<size_t>(kProfileEvents, n - base);
         for (size_t i = 0; i < cnt; ++i) {
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i], st));
-            hipError_t e = issue(c, m, s, p->launches[base + i], st);
-            if (e != hipSuccess) return hip_fail(c, e, p->launches[base + i].info.name);
+            for (int r = 0; r < inner; ++r) {
+                hipError_t e = issue(c, m, s, p->launches[base + i], st);
+                if (e != hipSuccess) return hip_fail(c, e, p->launches[base + i].info.name);
+            }
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i + 1], st));
         }
         CW_HIP(c, hipStreamSynchronize(st));
         for (size_t i = 0; i < cnt; ++i) {
             float ms = 0.f;
             CW_HIP(c, hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
-            launch_us[base + i] = ms * 1000.f;
+            launch_us[base + i] = ms * 1000.f / (float)inner;
         }
     }
     CW_HIP(c, hipEventRecord(s->exec_end, st));

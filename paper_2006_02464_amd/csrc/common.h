@@ -23,6 +23,20 @@ enum Kind : int32_t {
     K_SOFTMAX = 6,
 };
 
+// Division by a run-time constant as multiply + shifts (Granlund-Montgomery round-up method).
+struct FastDiv {
+    uint32_t magic, sh1, sh2;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;  // ceil(log2 d)
+    FastDiv f;
+    f.magic = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+
 // Implicit GEMM view of a convolution (also used for the stem with Cin padded to 4 and
 // the filter row padded to 8 taps): M = B*Ho*Wo output pixels, N = Cout, K = kh*kwp*Cin.
 struct ConvArgs {
@@ -37,6 +51,7 @@ struct ConvArgs {
     int32_t M, K;
     int32_t relu;
     int32_t split_k, ktiles_per_split;
+    FastDiv wo_div, ho_div;  // for m -> (image, row, column)
 };
 
 struct ReduceArgs {
@@ -88,9 +103,10 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
-// LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout][kh][kwp][cinp] (zero padded).
+// LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp] (zero padded);
+// permute = rows in the conv kernel's MFMA accumulator order (conv weights), else plain (FC).
 hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw,
-                               int kwp, int cinp, hipStream_t s);
+                               int kwp, int cinp, bool permute, hipStream_t s);
 hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t s);
 // debug read-back: NHWC storage type -> fp32 NCHW
 hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H,

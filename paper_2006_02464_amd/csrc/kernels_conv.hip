@@ -1,27 +1,33 @@
 // Implicit-GEMM convolution on gfx950 MFMA (v_mfma_f32_32x32x16_{f16,bf16}), fp32 accumulate.
 //
-// GEMM view: M = B*Ho*Wo output pixels (rows; NHWC, so a row of y is Cout contiguous values),
+// GEMM view: M = B*Ho*Wo output pixels (NHWC, so a pixel's Cout values are contiguous),
 // N = Cout, K = kh*kwp*Cin ordered (r, s, c), so that for one filter tap the K slice is the
-// Cin-contiguous run of one input pixel.  A (activations) is gathered on the fly with zero
-// fill for padded taps; B (weights) was re-laid out at LOAD as [Cout][K].
+// Cin-contiguous run of one input pixel.  Activations are gathered on the fly with zero fill
+// for padded taps; weights were re-laid out at LOAD as [Cout'][K] (see "weight rows" below).
 //
-// Per workgroup: a BM x BN output tile.  K is walked in slices of BK (64, or 32 for the stem and
-// for Cin not divisible by 64).  Slices travel global -> registers -> LDS: PF register sets
+// Per workgroup: a BM-pixel x BN-channel output tile.  K is walked in slices of BK (64; 32 for
+// the stem and for Cin % 64 != 0).  Slices travel global -> registers -> LDS: PF register sets
 // hold the next PF slices in flight while the MFMAs consume the current one out of one of two
 // LDS stages (one barrier per slice).  All global reads are raw buffer loads: a padded tap, a
-// row beyond M, a channel beyond Cout or a slice beyond the K range is given an offset outside
-// the buffer, for which the hardware returns zeros.  That keeps the steady-state loop free of
-// branches, so the compiler can wait for exactly the oldest register set (s_waitcnt vmcnt(n))
-// instead of draining every load in flight.  LDS rows are BK elements with the 16-byte chunk index
-// XOR-swizzled by the row, so both the 16-byte writes and the MFMA operand reads (lane = row,
-// 8 consecutive k) are free of bank conflicts without padding.
+// pixel beyond M or a slice beyond the K range gets a per-thread offset outside the buffer, for
+// which the hardware returns zeros.  That keeps the steady-state loop free of branches, so the
+// compiler waits for exactly the oldest register set (s_waitcnt vmcnt(n)) instead of draining
+// every load in flight.  The per-thread part of an address is fixed for the whole K walk; the
+// tap/channel part is uniform and rides in the instruction's scalar offset.
 //
-// Each wave owns a (BM/WARPS_M) x (BN/WARPS_N) sub-tile made of 32x32 MFMA tiles.
+// LDS rows are BK elements with the 16-byte chunk index XOR-swizzled by the row, so both the
+// 16-byte writes and the MFMA operand reads (lane = row, 8 consecutive k) are conflict free
+// without padding.
 //
-// Epilogue (fused): accumulators (+ bias) are transposed through LDS, 32 rows at a time per
-// wave, so that every lane then owns 8 consecutive output channels of one pixel: the residual
-// is read and the result written as 16-byte vectors (a row of a wave's sub-tile is one
-// contiguous run).  + residual, ReLU, one round-to-nearest-even to the storage type.
+// MFMA roles: the weight tile is the row operand, the pixel tile the column operand, so a lane
+// ends up with 16 channels of ONE pixel per 32x32 tile.  Weight rows: inside every group of 32
+// output channels the packer stores channel sigma(i) at row i, with
+//     i = 8g + 4h + k  ->  sigma(i) = 16*(g/2) + 8h + 4*(g%2) + k,
+// which makes those 16 accumulators two runs of 8 consecutive channels (registers 0..7 ->
+// channels 8h..8h+7, registers 8..15 -> 16+8h..16+8h+7; h = lane/32).  The fused epilogue
+// therefore works straight from registers: bias and residual arrive as 16-byte vectors, then
+// + bias, + residual, ReLU, one round-to-nearest-even to the storage type, 16-byte stores;
+// lanes l and l+32 complete 32 contiguous bytes of a pixel per store instruction.
 // With split-K (gridDim.y > 1) the raw fp32 partial sums go to a [split][M][Cout] buffer and a
 // second kernel reduces them in fixed order and applies the same epilogue.
 #include "common.h"
@@ -32,7 +38,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (tensors are < 2 GiB)
+constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (buffers are < 2 GiB)
+
+enum ConvMode : int { MODE_CONV = 0, MODE_GEMM = 1, MODE_STEM = 2 };
+
+// n / d for a divisor prepared on the host (round-up multiplier; exact for every 32-bit n).
+static __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &d) {
+    const unsigned t = __umulhi(d.magic, n);
+    return (t + ((n - t) >> d.sh1)) >> d.sh2;
+}
 
 static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes) {
     // raw buffer (stride 0), 32-bit data format word as on every CDNA part
@@ -44,15 +58,15 @@ struct Mfma;
 template <>
 struct Mfma<f16> {
     typedef _Float16 v8 __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ f32x16 mma(v8 a, v8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    static __device__ __forceinline__ f32x16 mma(v8 rows, v8 cols, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(rows, cols, c, 0, 0, 0);
     }
 };
 template <>
 struct Mfma<bf16> {
     typedef __bf16 v8 __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ f32x16 mma(v8 a, v8 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    static __device__ __forceinline__ f32x16 mma(v8 rows, v8 cols, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows, cols, c, 0, 0, 0);
     }
 };
 
@@ -63,33 +77,31 @@ static __device__ __forceinline__ int swz(int row, int c) {
     return row * 32 + ((c ^ ((row >> 1) & 3)) << 3);
 }
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, bool STEM>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, int MODE>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int NT = 64 * WARPS_M * WARPS_N;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int CPR = BK / 8;  // 16-byte chunks per LDS row
-    constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BN * CPR;
-    static_assert(A_CHUNKS % NT == 0 && B_CHUNKS % NT == 0, "tile/threads mismatch");
-    static_assert(!STEM || BK == 32, "the stem walks one filter row (8 taps x 4 channels) per slice");
-    constexpr int A_PER = A_CHUNKS / NT, B_PER = B_CHUNKS / NT;
+    constexpr int X_CHUNKS = BM * CPR, W_CHUNKS = BN * CPR;
+    static_assert(X_CHUNKS % NT == 0 && W_CHUNKS % NT == 0, "tile/threads mismatch");
+    static_assert(MODE != MODE_STEM || BK == 32, "the stem walks one filter row (8 taps x 4 channels) per slice");
+    constexpr int X_PER = X_CHUNKS / NT, W_PER = W_CHUNKS / NT;
     constexpr int STAGE = (BM + BN) * BK;  // elements per LDS stage
-    constexpr int EPI_PITCH = WN + 8;      // floats; (4*pitch) % 64 == 32 keeps half-waves on disjoint banks
-    constexpr int EPI_BYTES = WARPS_M * WARPS_N * 32 * EPI_PITCH * 4;
-    constexpr int LDS_BYTES = 2 * STAGE * 2 > EPI_BYTES ? 2 * STAGE * 2 : EPI_BYTES;
     typedef typename Mfma<T>::v8 v8;
 
-    __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
-    T *const lds = reinterpret_cast<T *>(smem);
+    __shared__ __attribute__((aligned(16))) T lds[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm0 = (wave / WARPS_N) * WM;
     const int wn0 = (wave % WARPS_N) * WN;
+    const int lrow = lane & 31;
+    const int lhalf = lane >> 5;
 
     // Workgroups go to the 8 XCDs round-robin; give each XCD a contiguous run of tiles so that
-    // tiles sharing activation rows (same tile_m) meet in one XCD's L2.
+    // tiles sharing pixels (same tile_m) meet in one XCD's L2.
     int tile_id;
     {
         const int nb = gridDim.x, bid = blockIdx.x;
@@ -97,7 +109,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         const int per = nb >> 3, rem = nb & 7;
         tile_id = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
     }
-    const int tiles_n = (a.Cout + BN - 1) / BN;
+    const int tiles_n = a.Cout / BN + (a.Cout % BN != 0);
     const int tile_m = tile_id / tiles_n;
     const int tile_n = tile_id - tile_m * tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -106,42 +118,66 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     const int kt0 = blockIdx.y * a.ktiles_per_split;
     const int kt1 = min(ktiles, kt0 + a.ktiles_per_split);
 
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (unsigned)a.B * a.H * a.W * a.Cin * 2u);
+    // The activation buffer is described from D bytes before its start, D = the offset of the
+    // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
+    // VGPR) + tap/channel offset (uniform, in an SGPR)  is never negative.
+    const unsigned x_bytes = (unsigned)a.B * a.H * a.W * a.Cin * 2u;
+    const unsigned x_shift = MODE == MODE_GEMM ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(static_cast<const char *>(a.x) - x_shift, x_bytes + x_shift);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (unsigned)a.Cout * a.K * 2u);
 
-    // Per-thread gather coordinates of its A chunks (fixed for the whole K walk).
-    int a_pix[A_PER];  // element offset of x[n][0][0][0], or -1 if the row is beyond M
-    int a_ih0[A_PER], a_iw0[A_PER];
+    // Per-thread gather state of its activation chunks, fixed for the whole K walk: byte offset
+    // of the chunk at the filter's centre pixel, and which taps fall inside the image.
+    //   conv: bit r*kw+s of x_mask = tap (r, s) is in range (kh*kw <= 32);
+    //   gemm: bit 0 = the pixel exists (1x1, stride 1, no padding: x is a plain [M][Cin] matrix);
+    //   stem: bits 0..kh-1 = filter row r is in range, bits 30/31 = the chunk's two columns are.
+    unsigned x_voff[X_PER], x_mask[X_PER];
 #pragma unroll
-    for (int j = 0; j < A_PER; ++j) {
-        const int m = m0 + (tid + j * NT) / CPR;
-        if (m < a.M) {
-            const int q = m % a.Wo;
-            const int t = m / a.Wo;
-            const int p = t % a.Ho;
-            const int n = t / a.Ho;
-            a_pix[j] = n * a.H * a.W * a.Cin;
-            a_ih0[j] = p * a.stride - a.pad;
-            a_iw0[j] = q * a.stride - a.pad;
-        } else {
-            a_pix[j] = -1;
-            a_ih0[j] = 0;
-            a_iw0[j] = 0;
+    for (int j = 0; j < X_PER; ++j) {
+        const int cid = tid + j * NT;
+        const int c = cid % CPR;
+        const unsigned m = m0 + cid / CPR;
+        unsigned mask = 0, voff = 0;
+        if (MODE == MODE_GEMM) {
+            voff = m * (unsigned)a.Cin * 2u + c * 16u;
+            mask = m < (unsigned)a.M ? 1u : 0u;
+        } else if (m < (unsigned)a.M) {
+            const unsigned t = fast_div(m, a.wo_div);
+            const int q = m - t * a.Wo;
+            const unsigned n = fast_div(t, a.ho_div);
+            const int p = t - n * a.Ho;
+            const int ihc = p * a.stride, iwc = q * a.stride;
+            voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u + c * 16u;
+            // filter rows r with 0 <= ihc - pad + r < H
+            const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
+            if (MODE == MODE_STEM) {
+                mask = ((1u << r_hi) - 1u) & ~((1u << r_lo) - 1u);
+                if ((unsigned)(iwc - a.pad + 2 * c) < (unsigned)a.W) mask |= 1u << 30;
+                if ((unsigned)(iwc - a.pad + 2 * c + 1) < (unsigned)a.W) mask |= 1u << 31;
+            } else {
+                const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+                const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
+                for (int r = r_lo; r < r_hi; ++r) mask |= cols << (r * a.kw);
+            }
         }
+        x_voff[j] = voff;
+        x_mask[j] = mask;
     }
-    // Byte offset of this thread's B chunks at slice 0, or out of bounds beyond Cout.
-    unsigned b_off[B_PER];
+    // Byte offset of this thread's weight chunks at slice 0, or out of bounds beyond Cout.
+    unsigned w_off[W_PER];
 #pragma unroll
-    for (int j = 0; j < B_PER; ++j) {
+    for (int j = 0; j < W_PER; ++j) {
         const int cid = tid + j * NT;
         const int n = n0 + cid / CPR;
-        b_off[j] = n < a.Cout ? ((unsigned)n * a.K + (cid % CPR) * 8) * 2u : kOob;
+        w_off[j] = n < a.Cout ? ((unsigned)n * a.K + (cid % CPR) * 8) * 2u : kOob;
     }
 
     // (r, s, c0) of the next K slice to load: k0 = kt*BK = (r*kwp + s)*Cin + c0.
-    int fr, fs, fc0;
-    if (STEM) {
-        fr = kt0; fs = 0; fc0 = 0;
+    int fr = 0, fs = 0, fc0 = 0;
+    if (MODE == MODE_STEM) {
+        fr = kt0;
+    } else if (MODE == MODE_GEMM) {
+        fc0 = kt0 * BK;
     } else {
         const int k0 = kt0 * BK;
         const int rs = k0 / a.Cin;
@@ -150,39 +186,41 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         fs = rs - fr * a.kwp;
     }
 
-    u32x4 ra[PF][A_PER], rb[PF][B_PER];
+    u32x4 rxa[PF][X_PER], rwa[PF][W_PER];
 
-    // Issues the loads of slice kt (all zeros if kt >= kt1).  No branches.
-    auto load_global = [&](int kt, u32x4(&qa)[A_PER], u32x4(&qb)[B_PER]) {
+    // Issues the loads of slice kt (all zeros if kt >= kt1).  No branches; the per-load vector
+    // work is one bit test and one select.  The out-of-bounds marker always travels in the
+    // per-thread offset: only that operand is sure to be range-checked.
+    auto load_global = [&](int kt, u32x4(&qx)[X_PER], u32x4(&qw)[W_PER]) {
         const bool live = kt < kt1;
+        if (MODE == MODE_STEM) {
+            // Cin == 4, kwp == 8: slice kt is filter row r = kt; chunk c holds taps 2c, 2c+1.
+            const unsigned soff = (unsigned)(fr * a.W) * 8u;
+            const unsigned rbit = live ? (1u << fr) : 0u;
 #pragma unroll
-        for (int j = 0; j < A_PER; ++j) {
-            const int c = (tid + j * NT) % CPR;
-            if (STEM) {
-                // Cin == 4, kwp == 8: slice kt is filter row r = kt; chunk c holds taps 2c, 2c+1.
-                const int ih = a_ih0[j] + fr;
-                const int iw = a_iw0[j] + 2 * c;
-                const bool row_ok = live && a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H;
-                const unsigned base = (unsigned)(a_pix[j] + (ih * a.W + iw) * 4) * 2u;
-                const unsigned o0 = (row_ok && (unsigned)iw < (unsigned)a.W) ? base : kOob;
-                const unsigned o1 = (row_ok && (unsigned)(iw + 1) < (unsigned)a.W) ? base + 8u : kOob;
-                const u32x2 t0 = __builtin_amdgcn_raw_buffer_load_b64(rx, o0, 0, 0);
-                const u32x2 t1 = __builtin_amdgcn_raw_buffer_load_b64(rx, o1, 0, 0);
-                qa[j] = u32x4{t0.x, t0.y, t1.x, t1.y};
-            } else {
-                const int ih = a_ih0[j] + fr, iw = a_iw0[j] + fs;
-                const bool ok = live && a_pix[j] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-                const unsigned o = ok ? (unsigned)(a_pix[j] + (ih * a.W + iw) * a.Cin + fc0 + c * 8) * 2u : kOob;
-                qa[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, o, 0, 0);
+            for (int j = 0; j < X_PER; ++j) {
+                const bool row_ok = (x_mask[j] & rbit) != 0;
+                const unsigned o0 = (row_ok && (x_mask[j] & (1u << 30))) ? x_voff[j] : kOob;
+                const unsigned o1 = (row_ok && (x_mask[j] & (1u << 31))) ? x_voff[j] + 8u : kOob;
+                const u32x2 t0 = __builtin_amdgcn_raw_buffer_load_b64(rx, o0, soff, 0);
+                const u32x2 t1 = __builtin_amdgcn_raw_buffer_load_b64(rx, o1, soff, 0);
+                qx[j] = u32x4{t0.x, t0.y, t1.x, t1.y};
             }
+        } else {
+            const unsigned soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+            const unsigned tbit = !live ? 0u : (MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs)));
+#pragma unroll
+            for (int j = 0; j < X_PER; ++j)
+                qx[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, (x_mask[j] & tbit) ? x_voff[j] : kOob, soff, 0);
         }
-        // b_off is a real offset or kOob; adding the slice offset (< 2 GiB) keeps kOob out of bounds
         const unsigned kb = (unsigned)kt * (BK * 2u);
 #pragma unroll
-        for (int j = 0; j < B_PER; ++j)
-            qb[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, live ? b_off[j] + kb : kOob, 0, 0);
-        if (STEM) {
+        for (int j = 0; j < W_PER; ++j)
+            qw[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, live ? w_off[j] : kOob, kb, 0);
+        if (MODE == MODE_STEM) {
             fr += 1;
+        } else if (MODE == MODE_GEMM) {
+            fc0 += BK;
         } else {
             fc0 += BK;
             if (fc0 == a.Cin) {
@@ -191,25 +229,22 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
             }
         }
     };
-    auto store_lds = [&](int buf, const u32x4(&qa)[A_PER], const u32x4(&qb)[B_PER]) {
-        T *sA = lds + buf * STAGE;
-        T *sB = sA + BM * BK;
+    auto store_lds = [&](int buf, const u32x4(&qx)[X_PER], const u32x4(&qw)[W_PER]) {
+        T *sX = lds + buf * STAGE;
+        T *sW = sX + BM * BK;
 #pragma unroll
-        for (int j = 0; j < A_PER; ++j) {
+        for (int j = 0; j < X_PER; ++j) {
             const int cid = tid + j * NT;
-            *reinterpret_cast<u32x4 *>(sA + swz<BK>(cid / CPR, cid % CPR)) = qa[j];
+            *reinterpret_cast<u32x4 *>(sX + swz<BK>(cid / CPR, cid % CPR)) = qx[j];
         }
 #pragma unroll
-        for (int j = 0; j < B_PER; ++j) {
+        for (int j = 0; j < W_PER; ++j) {
             const int cid = tid + j * NT;
-            *reinterpret_cast<u32x4 *>(sB + swz<BK>(cid / CPR, cid % CPR)) = qb[j];
+            *reinterpret_cast<u32x4 *>(sW + swz<BK>(cid / CPR, cid % CPR)) = qw[j];
         }
     };
 
-    const int lrow = lane & 31;
-    const int lhalf = lane >> 5;
-
-    f32x16 acc[TM][TN];
+    f32x16 acc[TM][TN];  // [pixel tile][channel tile]; MFMA rows = channels, columns = pixels
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -218,28 +253,28 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     auto compute = [&](int cur) {
-        const T *sA = lds + cur * STAGE;
-        const T *sB = sA + BM * BK;
+        const T *sX = lds + cur * STAGE;
+        const T *sW = sX + BM * BK;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            v8 fa[TM], fb[TN];
+            v8 fx[TM], fw[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const v8 *>(sA + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+                fx[i] = *reinterpret_cast<const v8 *>(sX + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const v8 *>(sB + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+                fw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fa[i], fb[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[j], fx[i], acc[i][j]);
         }
     };
 
     // Prologue: slices kt0 .. kt0+PF-1 into the register sets, the first one on into LDS.
 #pragma unroll
-    for (int u = 0; u < PF; ++u) load_global(kt0 + u, ra[u], rb[u]);
-    store_lds(0, ra[0], rb[0]);
+    for (int u = 0; u < PF; ++u) load_global(kt0 + u, rxa[u], rwa[u]);
+    store_lds(0, rxa[0], rwa[0]);
     __syncthreads();
 
     // Steady state, PF slices per trip, no branches inside: register set u held slice kt and
@@ -250,9 +285,9 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     for (; kt + PF <= kt1; kt += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            load_global(kt + u + PF, ra[u], rb[u]);
+            load_global(kt + u + PF, rxa[u], rwa[u]);
             compute(cur);
-            store_lds(cur ^ 1, ra[(u + 1) % PF], rb[(u + 1) % PF]);
+            store_lds(cur ^ 1, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
             __syncthreads();
             cur ^= 1;
         }
@@ -262,60 +297,87 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     for (int u = 0; u < PF - 1; ++u) {
         if (kt + u < kt1) {  // uniform across the workgroup
             compute(cur);
-            if (kt + u + 1 < kt1) store_lds(cur ^ 1, ra[(u + 1) % PF], rb[(u + 1) % PF]);
+            if (kt + u + 1 < kt1) store_lds(cur ^ 1, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
             __syncthreads();
             cur ^= 1;
         }
     }
 
-    // Epilogue.  In an MFMA tile the lane holds column lane%32 and rows 8*(e/4) + 4*(lane/32) + e%4.
-    constexpr int LPR = WN / 8;    // lanes per output row when each lane takes 8 channels
-    constexpr int RPP = 64 / LPR;  // rows per pass
-    float *stage = reinterpret_cast<float *>(smem) + wave * 32 * EPI_PITCH;
-    const int rr0 = lane / LPR, cc = lane % LPR;
-    const int n_out = n0 + wn0 + cc * 8;
-    float bias[TN];
+    // Epilogue from registers.  Lane: pixel m0+wm0+32i+lane%32; per channel tile j its registers
+    // 8q..8q+7 are channels n0+wn0+32j+16q+8*(lane/32) .. +7  (q = 0, 1).
+    const unsigned mn = (unsigned)a.M * a.Cout;
+    if (a.partial) {
+        const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)blockIdx.y * a.M * a.Cout, mn * 4u);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn0 + j * 32 + lrow;
-        bias[j] = (a.partial || n >= a.Cout) ? 0.f : a.bias[n];
+        for (int i = 0; i < TM; ++i) {
+            const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+                    const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
+                    const f32x16 &v = acc[i][j];
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        u32x4{__float_as_uint(v[8 * q + 0]), __float_as_uint(v[8 * q + 1]), __float_as_uint(v[8 * q + 2]),
+                              __float_as_uint(v[8 * q + 3])},
+                        rp, o, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        u32x4{__float_as_uint(v[8 * q + 4]), __float_as_uint(v[8 * q + 5]), __float_as_uint(v[8 * q + 6]),
+                              __float_as_uint(v[8 * q + 7])},
+                        rp, o + 16u, 0, 0);
+                }
+        }
+        return;
     }
+
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, mn * 2u);
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(a.res ? a.res : a.y, mn * 2u);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(a.bias, (unsigned)a.Cout * 4u);
+    const bool has_res = a.res != nullptr;
+    // every bias and residual vector first (independent loads, one exposed latency) ...
+    u32x4 bv[TN][2][2], rv[TM][TN][2];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+            const unsigned o = n < (unsigned)a.Cout ? n * 4u : kOob;
+            bv[j][q][0] = __builtin_amdgcn_raw_buffer_load_b128(rb, o, 0, 0);
+            bv[j][q][1] = __builtin_amdgcn_raw_buffer_load_b128(rb, o + 16u, 0, 0);
+        }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        const unsigned m = m0 + wm0 + i * 32 + lrow;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stage[(8 * (e >> 2) + 4 * lhalf + (e & 3)) * EPI_PITCH + j * 32 + lrow] = acc[i][j][e] + bias[j];
-        __syncthreads();
-#pragma unroll
-        for (int ps = 0; ps < 32 / RPP; ++ps) {
-            const int rr = ps * RPP + rr0;
-            const int m = m0 + wm0 + i * 32 + rr;
-            const float4 v0 = *reinterpret_cast<const float4 *>(stage + rr * EPI_PITCH + cc * 8);
-            const float4 v1 = *reinterpret_cast<const float4 *>(stage + rr * EPI_PITCH + cc * 8 + 4);
-            if (m < a.M && n_out < a.Cout) {
-                const size_t o = (size_t)m * a.Cout + n_out;
-                if (a.partial) {
-                    float *dst = a.partial + (size_t)blockIdx.y * a.M * a.Cout + o;
-                    *reinterpret_cast<float4 *>(dst) = v0;
-                    *reinterpret_cast<float4 *>(dst + 4) = v1;
-                } else {
-                    float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-                    if (a.res) {
-                        const uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const T *>(a.res) + o);
-                        const T *r = reinterpret_cast<const T *>(&raw);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] += (float)r[e];
-                    }
-                    T out[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) out[e] = (T)(a.relu ? fmaxf(v[e], 0.f) : v[e]);
-                    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + o) = *reinterpret_cast<const uint4 *>(out);
-                }
+            for (int q = 0; q < 2; ++q) {
+                const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+                const unsigned o = (has_res && m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 2u : kOob;
+                rv[i][j][q] = __builtin_amdgcn_raw_buffer_load_b128(rr, o, 0, 0);
             }
-        }
-        if (i + 1 < TM) __syncthreads();
+    }
+    // ... then the arithmetic and the stores
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+                const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 2u : kOob;
+                const T *r = reinterpret_cast<const T *>(&rv[i][j][q]);
+                const float *b = reinterpret_cast<const float *>(&bv[j][q][0]);
+                T out[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float v = acc[i][j][8 * q + e] + b[e] + (float)r[e];  // r is zero without a residual
+                    out[e] = (T)(a.relu ? fmaxf(v, 0.f) : v);
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
+            }
     }
 }
 
@@ -365,6 +427,10 @@ TileDim conv_tile_dim(ConvTile t) {
 
 int conv_bk(const ConvArgs &a, bool stem) { return (!stem && a.Cin % 64 == 0) ? 64 : 32; }
 
+static bool conv_is_gemm(const ConvArgs &a, bool stem) {
+    return !stem && a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.Cin % 64 == 0;
+}
+
 void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block) {
     const TileDim d = conv_tile_dim(tile);
     const unsigned tm = (a.M + d.bm - 1) / d.bm, tn = (a.Cout + d.bn - 1) / d.bn;
@@ -378,43 +444,48 @@ void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block) {
     *block = 256;
 }
 
-constexpr int kPrefetch = 3;  // K slices in flight in registers
-
-template <typename T, int BK, bool STEM>
+template <typename T, int BK, int MODE>
 static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s) {
     dim3 grid;
     int block;
     conv_grid(tile, a, &grid, &block);
+    // K slices in flight in registers: 2 for the largest tile (register budget), else 3
     switch (tile) {
-        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
-        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
-        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
-        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
-        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
-        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, kPrefetch, STEM><<<grid, block, 0, s>>>(a); break;
+        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
+        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t launch_conv_dt(ConvTile tile, bool stem, int bk, const ConvArgs &a, hipStream_t s) {
-    if (stem) return launch_conv_t<T, 32, true>(tile, a, s);
-    if (bk == 64) return launch_conv_t<T, 64, false>(tile, a, s);
-    return launch_conv_t<T, 32, false>(tile, a, s);
+static hipError_t launch_conv_dt(ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
+    if (stem) return launch_conv_t<T, 32, MODE_STEM>(tile, a, s);
+    if (conv_is_gemm(a, stem)) return launch_conv_t<T, 64, MODE_GEMM>(tile, a, s);
+    if (a.Cin % 64 == 0) return launch_conv_t<T, 64, MODE_CONV>(tile, a, s);
+    return launch_conv_t<T, 32, MODE_CONV>(tile, a, s);
 }
 
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
     // Shapes the kernel's indexing relies on; the plan compiler guarantees them, checked again
     // here so that a bad launch is an error instead of an out-of-bounds access.
     const int bk = conv_bk(a, stem);
-    if (a.K % bk != 0 || a.M <= 0 || a.Cout <= 0 || a.Cout % 8 != 0 || a.split_k < 1 || a.ktiles_per_split < 1)
+    if (a.K % bk != 0 || a.M <= 0 || a.Cout <= 0 || a.Cout % 32 != 0 || a.split_k < 1 || a.ktiles_per_split < 1)
         return hipErrorInvalidValue;
     if (stem ? (a.Cin != 4 || a.kwp != 8 || a.K != a.kh * 32) : (a.Cin % 32 != 0 || a.kwp != a.kw || a.K != a.kh * a.kw * a.Cin))
         return hipErrorInvalidValue;
+    if (stem ? a.kh > 30 : a.kh * a.kw > 32) return hipErrorInvalidValue;  // tap masks are 32 bits
     if ((long long)a.split_k * a.ktiles_per_split < a.K / bk) return hipErrorInvalidValue;
     if (a.split_k > 1 && !a.partial) return hipErrorInvalidValue;
-    return dt == DT_F16 ? launch_conv_dt<f16>(tile, stem, bk, a, s) : launch_conv_dt<bf16>(tile, stem, bk, a, s);
+    // buffer descriptors address less than 2 GiB each
+    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
+    if ((long long)a.M * a.Cout * (a.partial ? 4 : 2) >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31))
+        return hipErrorInvalidValue;
+    return dt == DT_F16 ? launch_conv_dt<f16>(tile, stem, a, s) : launch_conv_dt<bf16>(tile, stem, a, s);
 }
 
 hipError_t launch_splitk_reduce(DType dt, const ReduceArgs &a, hipStream_t s) {

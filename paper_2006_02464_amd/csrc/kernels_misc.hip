@@ -58,63 +58,80 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
     *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + i * 8) = *reinterpret_cast<const uint4 *>(out);
 }
 
-// ---- global average pool: NHWC [B][H*W][C] -> fp32 [B][C]; one thread = 8 channels ------
+// ---- global average pool: NHWC [B][H*W][C] -> fp32 [B][C] -------------------------------
+// One wave per (sample, 64 channels): lane = (part, group) with group = lane%8 owning 8
+// channels and part = lane/8 taking pixels part, part+8, ...; the 8 parts are then summed with
+// three xor-shuffles in a fixed order.  8 lanes read one pixel's 128 contiguous bytes.
 template <typename T>
 __global__ __launch_bounds__(64) void gavgpool_kernel(const PoolArgs a) {
-    const int c8 = a.C / 8;
-    const int i = blockIdx.x * 64 + threadIdx.x;
-    if (i >= a.B * c8) return;
-    const int n = i / c8, cg = i - n * c8;
+    const int groups = a.C / 64;
+    const int n = blockIdx.x / groups, cb = (blockIdx.x - n * groups) * 64;
+    const int lane = threadIdx.x, cg = lane & 7, part = lane >> 3;
     const int hw = a.H * a.W;
     float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const T *xg = static_cast<const T *>(a.x) + (size_t)n * hw * a.C + cg * 8;
-    for (int p = 0; p < hw; ++p) {
+    const T *xg = static_cast<const T *>(a.x) + (size_t)n * hw * a.C + cb + cg * 8;
+#pragma unroll 4
+    for (int p = part; p < hw; p += 8) {
         const uint4 raw = *reinterpret_cast<const uint4 *>(xg + (size_t)p * a.C);
         const T *v = reinterpret_cast<const T *>(&raw);
 #pragma unroll
         for (int e = 0; e < 8; ++e) s[e] += to_f32(v[e]);
     }
-    float *y = static_cast<float *>(a.y) + (size_t)n * a.C + cg * 8;
-    const float inv = 1.f / (float)hw;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) y[e] = s[e] * inv;
+    for (int off = 8; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += __shfl_xor(s[e], off, 64);
+    if (part == 0) {
+        float *y = static_cast<float *>(a.y) + (size_t)n * a.C + cb + cg * 8;
+        const float inv = 1.f / (float)hw;
+        *reinterpret_cast<float4 *>(y) = make_float4(s[0] * inv, s[1] * inv, s[2] * inv, s[3] * inv);
+        *reinterpret_cast<float4 *>(y + 4) = make_float4(s[4] * inv, s[5] * inv, s[6] * inv, s[7] * inv);
+    }
 }
 
-// ---- FC: z[n][j] = bias[j] + sum_i f[n][i] * W[j][i]; one wave per output j, up to 16 samples
-// per launch row (blockIdx.y selects the group of 16 samples).  Weight streaming.
+// ---- FC: z[n][j] = bias[j] + sum_i f[n][i] * W[j][i], fp32 features, fp32 result ---------
+// A workgroup computes 16 outputs x 16 samples on the fp32 matrix cores
+// (v_mfma_f32_16x16x4_f32: 16 output rows x 16 sample columns x 4 k per instruction).  Its 4 waves
+// split K; wave w walks chunks of 32 k: lane (r = lane%16, g = lane/16) loads 8 consecutive
+// weights of output row r and 8 consecutive features of sample r, both at k = chunk + 8g, and
+// issues 8 MFMAs, the e-th one multiplying the e-th element of each (the k index of an MFMA is
+// only a summation label, so any pairing that both operands share is valid).  The four partial
+// 16x16 tiles are summed through LDS in wave order, the bias is added and the logits written.
+typedef float fc_f32x4 __attribute__((ext_vector_type(4)));
+
 template <typename T>
 __global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= a.Out) return;  // whole wave exits together
-    const int nb0 = blockIdx.y * 16;
-    const int nb = min(16, a.B - nb0);
-    float acc[16];
+    __shared__ float part[4][16][17];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int j = blockIdx.x * 16 + r;   // output row this lane feeds
+    const int n = blockIdx.y * 16 + r;   // sample column this lane feeds
+    const bool j_ok = j < a.Out, n_ok = n < a.B;
+    const T *wrow = static_cast<const T *>(a.w) + (size_t)(j_ok ? j : 0) * a.In;
+    const float *frow = a.f + (size_t)(n_ok ? n : 0) * a.In;
+    fc_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int kq = a.In / 4;  // K range of this wave
+    for (int k = wave * kq + g * 8; k < (wave + 1) * kq; k += 32) {
+        uint4 wraw = *reinterpret_cast<const uint4 *>(wrow + k);
+        float4 f0 = *reinterpret_cast<const float4 *>(frow + k);
+        float4 f1 = *reinterpret_cast<const float4 *>(frow + k + 4);
+        if (!j_ok) wraw = make_uint4(0u, 0u, 0u, 0u);
+        if (!n_ok) { f0 = make_float4(0.f, 0.f, 0.f, 0.f); f1 = f0; }
+        const T *wv = reinterpret_cast<const T *>(&wraw);
+        const float fv[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
 #pragma unroll
-    for (int n = 0; n < 16; ++n) acc[n] = 0.f;
-    const T *wrow = static_cast<const T *>(a.w) + (size_t)j * a.In;
-    for (int i = lane * 8; i < a.In; i += 64 * 8) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(wrow + i);
-        const T *wv = reinterpret_cast<const T *>(&raw);
-        float wf[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wf[e] = to_f32(wv[e]);
-#pragma unroll
-        for (int n = 0; n < 16; ++n) {
-            if (n < nb) {
-                const float4 f0 = *reinterpret_cast<const float4 *>(a.f + (size_t)(nb0 + n) * a.In + i);
-                const float4 f1 = *reinterpret_cast<const float4 *>(a.f + (size_t)(nb0 + n) * a.In + i + 4);
-                acc[n] += f0.x * wf[0] + f0.y * wf[1] + f0.z * wf[2] + f0.w * wf[3] +
-                          f1.x * wf[4] + f1.y * wf[5] + f1.z * wf[6] + f1.w * wf[7];
-            }
-        }
+        for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(to_f32(wv[e]), fv[e], acc, 0, 0, 0);
     }
+    // lane holds column (sample) lane%16, rows (outputs) 4*(lane/16) + e
 #pragma unroll
-    for (int n = 0; n < 16; ++n) {
-        float v = acc[n];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        if (lane == 0 && n < nb) a.z[(size_t)(nb0 + n) * a.Out + j] = v + a.bias[j];
+    for (int e = 0; e < 4; ++e) part[wave][4 * g + e][r] = acc[e];
+    __syncthreads();
+    const int t = threadIdx.x;  // 256 threads = 16 outputs x 16 samples
+    const int oj = t >> 4, on = t & 15;
+    const int jj = blockIdx.x * 16 + oj, nn = blockIdx.y * 16 + on;
+    if (jj < a.Out && nn < a.B) {
+        const float v = ((part[0][oj][on] + part[1][oj][on]) + part[2][oj][on]) + part[3][oj][on];
+        a.z[(size_t)nn * a.Out + jj] = v + a.bias[jj];
     }
 }
 
@@ -143,10 +160,14 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SoftmaxArgs a) {
     for (int j = tid; j < a.D; j += 256) a.p[(size_t)row * a.D + j] = expf(z[j] - m) * inv;
 }
 
-// ---- LOAD: canonical W[cout][cin][kh][kw] -> [cout][kh][kwp][cinp], zero padded ----------
-// 16-bit elements are moved as raw bits, so one kernel serves fp16 and bf16.
+// ---- LOAD: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp], zero padded ---------
+// 16-bit elements are moved as raw bits, so one kernel serves fp16 and bf16.  With `permute`,
+// row i of every group of 32 output channels receives channel sigma(i) of that group,
+//     i = 8g + 4h + k  ->  sigma(i) = 16*(g/2) + 8h + 4*(g%2) + k,
+// the order in which the conv kernel's MFMA accumulators come out as runs of 8 channels.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                           int cout, int cin, int kh, int kw, int kwp, int cinp) {
+                                                           int cout, int cin, int kh, int kw, int kwp, int cinp,
+                                                           int permute) {
     const size_t total = (size_t)cout * kh * kwp * cinp;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
@@ -155,7 +176,11 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__res
     const int s = (int)(t % kwp);
     t /= kwp;
     const int r = (int)(t % kh);
-    const int k = (int)(t / kh);
+    int k = (int)(t / kh);
+    if (permute) {
+        const int row = k & 31, g = row >> 3, h = (row >> 2) & 1, kk = row & 3;
+        k = (k & ~31) + (g >> 1) * 16 + h * 8 + (g & 1) * 4 + kk;
+    }
     uint16_t v = 0;
     if (c < cin && s < kw) v = src[(((size_t)k * cin + c) * kh + r) * kw + s];
     dst[i] = v;
@@ -213,14 +238,14 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
 
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s) {
     if (a.C % 8 != 0 || a.B < 1) return hipErrorInvalidValue;
-    const size_t total = (size_t)a.B * (a.C / 8);
-    CW_DISPATCH(dt, gavgpool_kernel, dim3(blocks_for(total, 64)), 64, s, a);
+    if (a.C % 64 != 0) return hipErrorInvalidValue;
+    CW_DISPATCH(dt, gavgpool_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s) {
-    if (a.In % 512 != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
-    const dim3 grid(blocks_for(a.Out, 4), blocks_for(a.B, 16));
+    if (a.In % 128 != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
+    const dim3 grid(blocks_for(a.Out, 16), blocks_for(a.B, 16));
     CW_DISPATCH(dt, fc_kernel, grid, 256, s, a);
     return hipGetLastError();
 }
@@ -232,11 +257,12 @@ hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw, int kwp, int cinp,
-                               hipStream_t s) {
+                               bool permute, hipStream_t s) {
+    if (permute && cout % 32 != 0) return hipErrorInvalidValue;
     const size_t total = (size_t)cout * kh * kwp * cinp;
     pack_weights_kernel<<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const uint16_t *>(src),
                                                                     static_cast<uint16_t *>(dst), cout, cin, kh, kw,
-                                                                    kwp, cinp);
+                                                                    kwp, cinp, permute ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -143,8 +143,8 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
                 if (i == 0) {
                     if (o.cin > 4 || o.kw > 8)
                         return fail(err, CW_ERR_UNSUPPORTED, "first conv needs cin<=4 and kw<=8");
-                } else if (o.cin % 32 != 0) {
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cin must be a multiple of 32", i);
+                } else if (o.cin % 32 != 0 || o.kh * o.kw > 32) {
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs cin %% 32 == 0 and at most 5x5 taps", i);
                 }
                 if (o.cout % 32 != 0) return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cout must be a multiple of 32", i);
                 out.h = (sh + 2 * o.pad - o.kh) / o.stride + 1;
@@ -169,12 +169,12 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
                 out.w = (sw + 2 * o.pad - o.kw) / o.stride + 1;
                 break;
             case CW_OP_GAVGPOOL:
-                if (i == 0 || o.cout != o.cin || o.cin % 8 != 0)
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: unsupported average pool", i);
+                if (i == 0 || o.cout != o.cin || o.cin % 64 != 0)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: average pool needs channels %% 64 == 0", i);
                 break;
             case CW_OP_FC:
-                if (i != n_ops - 2 || ops[o.input_from].op != CW_OP_GAVGPOOL || o.cin % 512 != 0 || o.cout < 1)
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: FC must follow the global average pool, cin %% 512 == 0", i);
+                if (i != n_ops - 2 || ops[o.input_from].op != CW_OP_GAVGPOOL || o.cin % 128 != 0 || o.cout < 1)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: FC must follow the global average pool, cin %% 128 == 0", i);
                 break;
             case CW_OP_SOFTMAX:
                 if (i != n_ops - 1 || o.input_from != n_ops - 2 || o.cout != o.cin)
@@ -325,6 +325,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 a.M = batch * os.h * os.w;
                 a.K = o.kh * ws.kwp * ws.cinp;
                 a.relu = o.relu;
+                a.wo_div = make_fast_div((uint32_t)os.w);
+                a.ho_div = make_fast_div((uint32_t)os.h);
                 const int ktiles = a.K / conv_bk(a, l.stem);
                 pick_conv_tile(a.M, a.Cout, ktiles, ov, &l.tile, &a.split_k);
                 a.ktiles_per_split = (ktiles + a.split_k - 1) / a.split_k;
@@ -447,8 +449,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_SPLITK_REDUCE: reduce_grid(l.red, &g, &b); break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.H * l.cast.W + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
-            case K_GAVGPOOL: g = dim3((unsigned)((l.pool.B * (l.pool.C / 8) + 63) / 64)); b = 64; break;
-            case K_FC: g = dim3((l.fc.Out + 3) / 4, (l.fc.B + 15) / 16); b = 256; break;
+            case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
+            case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 256; break;
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
         }
         l.info.op_index = l.op_index;
