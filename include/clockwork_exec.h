@@ -200,8 +200,9 @@ int32_t cw_debug_read_op(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t o
 /* When keep != 0, plans built afterwards give every op output its own workspace
  * region (no reuse) so cw_debug_read_op can read them.  Costs workspace only. */
 int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..5 =
- * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32; -1 = the plan compiler's own choice)
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..8 =
+ * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
+ * 256x64; pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);

@@ -17,7 +17,8 @@ CW_ERR_UNSUPPORTED, CW_ERR_NO_SLOT = -9, -10
 CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX = 0, 1, 2, 3, 4
 CW_DTYPE_FP16, CW_DTYPE_BF16 = 0, 1
 DTYPES = {"fp16": CW_DTYPE_FP16, "bf16": CW_DTYPE_BF16}
-CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32x32": 5}
+CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32x32": 5,
+              "128x64w2": 6, "64x128w2": 7, "256x64": 8, "128x128w8": 9}
 
 
 class cw_op(Structure):

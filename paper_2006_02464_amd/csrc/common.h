@@ -89,7 +89,10 @@ struct SoftmaxArgs {
 };
 
 // Tile shapes the conv kernel is instantiated for (fixed at plan time per layer).
-enum ConvTile : int32_t { T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, N_CONV_TILES };
+// (pixels x channels per workgroup; "wN" = N waves when not 4, each wave then owning 64x64)
+enum ConvTile : int32_t {
+    T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8, N_CONV_TILES
+};
 struct TileDim {
     int bm, bn, threads;
 };

@@ -17,7 +17,8 @@
 //
 // LDS rows are BK elements with the 16-byte chunk index XOR-swizzled by the row, so both the
 // 16-byte writes and the MFMA operand reads (lane = row, 8 consecutive k) are conflict free
-// without padding.
+// without padding (measured: 237 B/clk/CU for this read pattern against 123 with a key of
+// row%8 and 31 without a swizzle).
 //
 // MFMA roles: the weight tile is the row operand, the pixel tile the column operand, so a lane
 // ends up with 16 channels of ONE pixel per 32x32 tile.  Weight rows: inside every group of 32
@@ -41,6 +42,24 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (buffers are < 2 GiB)
 
 enum ConvMode : int { MODE_CONV = 0, MODE_GEMM = 1, MODE_STEM = 2 };
+
+// Development aid: with -DCW_TRACE one lane per workgroup stamps the shader clock at phase
+// boundaries into a global array (64 stamps per workgroup).  Never compiled into the library.
+#ifdef CW_TRACE
+__device__ long long cw_trace_buf[4096 * 64];
+#define CW_STAMP(slot)                                                                                  \
+    do {                                                                                                \
+        const int sl__ = (slot);                                                                        \
+        if (threadIdx.x == 0 && blockIdx.x < 4096 && sl__ < 60) cw_trace_buf[blockIdx.x * 64 + sl__] = clock64(); \
+    } while (0)
+#define CW_STAMP_END(slot)                                                                              \
+    do {                                                                                                \
+        if (threadIdx.x == 0 && blockIdx.x < 4096) cw_trace_buf[blockIdx.x * 64 + (slot)] = clock64();  \
+    } while (0)
+#else
+#define CW_STAMP(slot) do { } while (0)
+#define CW_STAMP_END(slot) do { } while (0)
+#endif
 
 // n / d for a divisor prepared on the host (round-up multiplier; exact for every 32-bit n).
 static __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &d) {
@@ -70,11 +89,16 @@ struct Mfma<bf16> {
     }
 };
 
-// Element offset of 16-byte chunk c of `row` inside a [rows][BK] LDS stage.
+// Element offset of 16-byte chunk c of `row` inside a [rows][BK] LDS stage.  A 16-byte-per-lane
+// LDS access is served 16 lanes (256 bytes, all 64 banks) per clock, and an MFMA operand read
+// has 16 consecutive rows at one chunk index in such a group.  With 128-byte rows two rows
+// share 256 bytes, so the chunk index is XORed with (row/2)%8: rows of equal parity then land
+// on 8 different chunk positions and the two parities on the two halves.  With 64-byte rows
+// four rows share 256 bytes and the key is (row/4)%4.
 template <int BK>
 static __device__ __forceinline__ int swz(int row, int c) {
-    if (BK == 64) return row * 64 + ((c ^ (row & 7)) << 3);
-    return row * 32 + ((c ^ ((row >> 1) & 3)) << 3);
+    if (BK == 64) return row * 64 + ((c ^ ((row >> 1) & 7)) << 3);
+    return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
 }
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, int MODE>
@@ -92,6 +116,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 
     __shared__ __attribute__((aligned(16))) T lds[2 * STAGE];
 
+    CW_STAMP(0);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -252,42 +277,59 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // MFMAs of one K slice; operand fragments of 16-k step kk+1 are fetched from LDS while the
+    // MFMAs of step kk run.
     auto compute = [&](int cur) {
         const T *sX = lds + cur * STAGE;
         const T *sW = sX + BM * BK;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            v8 fx[TM], fw[TN];
+        v8 fx[2][TM], fw[2][TN];
+        auto fetch = [&](int kk, v8(&qx)[TM], v8(&qw)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fx[i] = *reinterpret_cast<const v8 *>(sX + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+                qx[i] = *reinterpret_cast<const v8 *>(sX + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+                qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+        };
+        fetch(0, fx[0], fw[0]);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) fetch(kk + 1, fx[(kk + 1) & 1], fw[(kk + 1) & 1]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[j], fx[i], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk & 1][j], fx[kk & 1][i], acc[i][j]);
         }
     };
 
-    // Prologue: slices kt0 .. kt0+PF-1 into the register sets, the first one on into LDS.
+    // Prologue: slices kt0 .. kt0+PF-1 into the register sets; the first one goes on into LDS
+    // stage 0 and its set is refilled with slice kt0+PF.
+    CW_STAMP(1);
 #pragma unroll
     for (int u = 0; u < PF; ++u) load_global(kt0 + u, rxa[u], rwa[u]);
+    CW_STAMP(2);
     store_lds(0, rxa[0], rwa[0]);
+    load_global(kt0 + PF, rxa[0], rwa[0]);
     __syncthreads();
+    CW_STAMP(3);
+    int trace_slot = 4;
+    (void)trace_slot;
 
-    // Steady state, PF slices per trip, no branches inside: register set u held slice kt and
-    // is in LDS by now, so it is refilled with slice kt+PF; the MFMAs run on slice kt; then
-    // set u+1 (slice kt+1, the oldest load in flight) goes to the other LDS stage.
+    // Steady state, PF slices per trip, no branches inside.  At the top of step kt the current
+    // LDS stage holds slice kt and register set (u+1)%PF holds slice kt+1, requested PF steps
+    // ago.  It is written to the other LDS stage first (every wave finished reading that stage
+    // before the last barrier), the set is refilled with slice kt+1+PF, and only then do the
+    // MFMAs of slice kt run, so the LDS write and the new loads sit in their shadow.
     int kt = kt0;
     int cur = 0;
     for (; kt + PF <= kt1; kt += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            load_global(kt + u + PF, rxa[u], rwa[u]);
-            compute(cur);
             store_lds(cur ^ 1, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
+            load_global(kt + u + 1 + PF, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
+            CW_STAMP(trace_slot++);
+            compute(cur);
+            CW_STAMP(trace_slot++);
             __syncthreads();
             cur ^= 1;
         }
@@ -296,13 +338,14 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 #pragma unroll
     for (int u = 0; u < PF - 1; ++u) {
         if (kt + u < kt1) {  // uniform across the workgroup
-            compute(cur);
             if (kt + u + 1 < kt1) store_lds(cur ^ 1, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
+            compute(cur);
             __syncthreads();
             cur ^= 1;
         }
     }
 
+    CW_STAMP_END(60);
     // Epilogue from registers.  Lane: pixel m0+wm0+32i+lane%32; per channel tile j its registers
     // 8q..8q+7 are channels n0+wn0+32j+16q+8*(lane/32) .. +7  (q = 0, 1).
     const unsigned mn = (unsigned)a.M * a.Cout;
@@ -358,6 +401,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
                 rv[i][j][q] = __builtin_amdgcn_raw_buffer_load_b128(rr, o, 0, 0);
             }
     }
+    CW_STAMP_END(61);
     // ... then the arithmetic and the stores
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -379,6 +423,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
                 __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
             }
     }
+    CW_STAMP_END(62);
 }
 
 // Fixed-order reduction of split-K partials + the fused epilogue.  One thread = 8 columns.
@@ -421,6 +466,10 @@ TileDim conv_tile_dim(ConvTile t) {
         case T64x64: return {64, 64, 256};
         case T64x32: return {64, 32, 128};
         case T32x64: return {32, 64, 128};
+        case T128x64w2: return {128, 64, 128};
+        case T64x128w2: return {64, 128, 128};
+        case T256x64: return {256, 64, 256};
+        case T128x128w8: return {128, 128, 512};
         default: return {32, 32, 64};
     }
 }
@@ -457,6 +506,10 @@ static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s)
         case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
         case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
         case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T128x64w2: conv_igemm_kernel<T, 128, 64, 2, 1, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
+        case T64x128w2: conv_igemm_kernel<T, 64, 128, 1, 2, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
+        case T256x64: conv_igemm_kernel<T, 256, 64, 4, 1, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
+        case T128x128w8: conv_igemm_kernel<T, 128, 128, 2, 4, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

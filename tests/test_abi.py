@@ -86,7 +86,7 @@ def test_plan_override_reaches_every_tile(ctx):
     for name, idx in cw.CONV_TILES.items():
         ctx.set_plan_override(idx, 2)
         m = ctx.model_define_resnet(18, 64, 64)
-        bm, bn = (int(v) for v in name.split("x"))
+        bm, bn = (int(v) for v in name.replace("w2", "").replace("w8", "").split("x"))
         convs = [l for l in ctx.plan(m, 4) if l["name"].startswith(("conv", "stem"))]
         assert convs and all((l["tile_m"], l["tile_n"]) == (bm, bn) for l in convs)
         assert all(l["split_k"] == 2 or l["gemm_k"] <= 64 for l in convs)   # one K slice cannot be split
