@@ -200,6 +200,11 @@ int32_t cw_debug_read_op(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t o
 /* When keep != 0, plans built afterwards give every op output its own workspace
  * region (no reuse) so cw_debug_read_op can read them.  Costs workspace only. */
 int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
+/* EXEC normally replays, for the slot-independent middle of a plan, a HIP graph recorded at
+ * LOAD (fewer, cheaper submissions; identical kernels and arguments).  on == 0 makes EXEC
+ * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
+ * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
+int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
 /* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..8 =
  * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
  * 256x64; pixels x channels per workgroup; -1 = the plan compiler's own choice)

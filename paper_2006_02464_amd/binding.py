@@ -69,6 +69,7 @@ SIGNATURES = {
     "cw_debug_read_op": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_size_t]),
     "cw_set_debug_keep": (c_int32, [c_void_p, c_int32]),
     "cw_set_plan_override": (c_int32, [c_void_p, c_int32, c_int32]),
+    "cw_set_use_graphs": (c_int32, [c_void_p, c_int32]),
     "cw_strerror": (c_char_p, [c_int32]),
     "cw_last_error": (c_char_p, [c_void_p]),
 }
@@ -252,6 +253,9 @@ class Context:
 
     def set_debug_keep(self, keep):
         self._check(lib().cw_set_debug_keep(self._h, int(keep)))
+
+    def set_use_graphs(self, on):
+        self._check(lib().cw_set_use_graphs(self._h, int(on)))
 
     def set_plan_override(self, conv_tile=-1, split_k=0):
         if isinstance(conv_tile, str):

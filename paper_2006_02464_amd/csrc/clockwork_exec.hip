@@ -29,11 +29,21 @@ struct Slot {
     bool release_pending = false;            // `released` guards reuse of the region
 };
 
+// The slot-independent middle of a plan (everything between the input cast and the FC) as one
+// executable HIP graph: kernel arguments only name workspace and weight-pool addresses, which
+// are fixed once the weights are resident.
+struct PlanGraph {
+    hipGraphExec_t exec = nullptr;
+    size_t first = 0, last = 0;  // launches [first, last] are inside the graph
+    size_t pool_off = 0;         // weight placement the graph was captured for
+};
+
 struct ModelRt {
     Model m;
     bool loaded = false;
     size_t pool_off = 0;
     hipEvent_t load_done = nullptr;
+    std::vector<PlanGraph> graphs;  // parallel to m.plans
 };
 
 }  // namespace
@@ -47,6 +57,8 @@ struct cw_ctx {
     std::vector<std::unique_ptr<ModelRt>> models;
     PlanOverride ov;
     hipStream_t internal_stream = nullptr;
+    hipStream_t capture_stream = nullptr;  // only ever used to record graphs
+    bool use_graphs = true;
     hipEvent_t staging_free = nullptr;  // last LOAD's pack kernels are done with the staging area
     bool staging_used = false;
     hipEvent_t prof_ev[2 * kProfileEvents] = {};
@@ -125,15 +137,8 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hi
             a.res = resolve(c, m, s, l.res);
             a.y = resolve(c, m, s, l.y);
             a.partial = reinterpret_cast<float *>(resolve(c, m, s, l.partial));
+            a.counters = reinterpret_cast<int32_t *>(resolve(c, m, s, l.counters));
             return launch_conv(dt, l.tile, l.stem, a, st);
-        }
-        case K_SPLITK_REDUCE: {
-            ReduceArgs a = l.red;
-            a.partial = reinterpret_cast<const float *>(resolve(c, m, s, l.partial));
-            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
-            a.res = resolve(c, m, s, l.res);
-            a.y = resolve(c, m, s, l.y);
-            return launch_splitk_reduce(dt, a, st);
         }
         case K_MAXPOOL:
         case K_GAVGPOOL: {
@@ -252,6 +257,71 @@ void free_slot(cw_ctx *c, Slot *s) {
     s->model = -1;
 }
 
+
+bool slot_free(const Launch &l) {
+    for (const Ref *r : {&l.x, &l.w, &l.bias, &l.res, &l.y, &l.partial, &l.counters})
+        if (r->space == SP_SLOT_INPUT || r->space == SP_SLOT_LOGITS || r->space == SP_SLOT_PROBS) return false;
+    return true;
+}
+
+void destroy_graphs(ModelRt *m) {
+    for (PlanGraph &g : m->graphs)
+        if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
+}
+
+// Records the slot-independent run of launches of every plan into a graph.  Host work only:
+// nothing executes.  Called at LOAD, when the weights' place in the pool is known.
+int32_t build_graphs(cw_ctx *c, ModelRt *m) {
+    m->graphs.resize(m->m.plans.size());
+    for (size_t pi = 0; pi < m->m.plans.size(); ++pi) {
+        const Plan &p = m->m.plans[pi];
+        PlanGraph &pg = m->graphs[pi];
+        if (pg.exec && pg.pool_off == m->pool_off) continue;  // still valid from an earlier LOAD
+        if (pg.exec) { (void)hipGraphExecDestroy(pg.exec); pg.exec = nullptr; }
+        // longest run of slot-independent launches
+        size_t best_a = 0, best_n = 0, a = 0;
+        for (size_t i = 0; i <= p.launches.size(); ++i) {
+            if (i == p.launches.size() || !slot_free(p.launches[i])) {
+                if (i - a > best_n) { best_n = i - a; best_a = a; }
+                a = i + 1;
+            }
+        }
+        if (best_n < 2) continue;
+        hipGraph_t graph = nullptr;
+        CW_HIP(c, hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal));
+        hipError_t e = hipSuccess;
+        for (size_t i = best_a; i < best_a + best_n && e == hipSuccess; ++i) e = issue(c, m, nullptr, p.launches[i], c->capture_stream);
+        hipError_t e2 = hipStreamEndCapture(c->capture_stream, &graph);
+        if (e != hipSuccess || e2 != hipSuccess) {
+            if (graph) (void)hipGraphDestroy(graph);
+            return hip_fail(c, e != hipSuccess ? e : e2, "graph capture");
+        }
+        e = hipGraphInstantiate(&pg.exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) { pg.exec = nullptr; return hip_fail(c, e, "hipGraphInstantiate"); }
+        pg.first = best_a;
+        pg.last = best_a + best_n - 1;
+        pg.pool_off = m->pool_off;
+    }
+    return CW_OK;
+}
+
+// Enqueues the launches of a plan: the recorded graph for its middle part when there is one.
+int32_t enqueue_plan(cw_ctx *c, ModelRt *m, const Plan *p, const Slot *s, hipStream_t st) {
+    const size_t pi = (size_t)(p - m->m.plans.data());
+    const PlanGraph *pg = (c->use_graphs && pi < m->graphs.size() && m->graphs[pi].exec) ? &m->graphs[pi] : nullptr;
+    for (size_t i = 0; i < p->launches.size(); ++i) {
+        if (pg && i == pg->first) {
+            CW_HIP(c, hipGraphLaunch(pg->exec, st));
+            i = pg->last;
+            continue;
+        }
+        hipError_t e = issue(c, m, s, p->launches[i], st);
+        if (e != hipSuccess) return hip_fail(c, e, p->launches[i].info.name);
+    }
+    return CW_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -314,7 +384,14 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
         cleanup();
         return CW_ERR_NO_MEMORY;
     }
+    // split-K arrival counters must start at zero; every launch leaves them at zero again
+    if (cfg->workspace_bytes < kCounterBytes || hipMemset(p->workspace, 0, kCounterBytes) != hipSuccess) {
+        g_create_err = "workspace smaller than the split-K counter area, or hipMemset failed";
+        cleanup();
+        return CW_ERR_NO_MEMORY;
+    }
     bool ok = hipStreamCreateWithFlags(&p->internal_stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&p->staging_free, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; ok && i < kMaxSlots; ++i) {
         Slot &s = p->slots[i];
@@ -337,8 +414,11 @@ int32_t cw_destroy(cw_ctx *c) {
     if (c->device >= 0) {
         DeviceGuard g(c->device);
         (void)hipDeviceSynchronize();
-        for (auto &m : c->models)
+        for (auto &m : c->models) {
+            if (m) destroy_graphs(m.get());
             if (m && m->load_done) (void)hipEventDestroy(m->load_done);
+        }
+        if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
         for (Slot &s : c->slots) {
             if (s.input_done) (void)hipEventDestroy(s.input_done);
             if (s.exec_start) (void)hipEventDestroy(s.exec_start);
@@ -463,6 +543,13 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     if ((e = hipEventRecord(m->load_done, st)) != hipSuccess) return bail(e, "hipEventRecord");
     m->pool_off = off;
     m->loaded = true;
+    if (c->use_graphs) {
+        const int32_t rc = build_graphs(c, m);
+        if (rc != CW_OK) {  // LOAD stays valid; EXEC falls back to plain launches for this model
+            destroy_graphs(m);
+            m->graphs.clear();
+        }
+    }
     return CW_OK;
 }
 
@@ -508,14 +595,18 @@ int32_t cw_exec(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, void *
     rc = exec_gate(c, m, s, st);
     if (rc != CW_OK) return rc;
     CW_HIP(c, hipEventRecord(s->exec_start, st));
-    for (const Launch &l : p->launches) {
-        hipError_t e = issue(c, m, s, l, st);
-        if (e != hipSuccess) return hip_fail(c, e, l.info.name);
-    }
+    rc = enqueue_plan(c, m, p, s, st);
+    if (rc != CW_OK) return rc;
     CW_HIP(c, hipEventRecord(s->exec_end, st));
     s->state = SLOT_EXECUTED;
     c->last_exec_stream = st;
     c->last_exec_end = s->exec_end;
+    return CW_OK;
+}
+
+int32_t cw_set_use_graphs(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->use_graphs = on != 0;
     return CW_OK;
 }
 
@@ -634,8 +725,7 @@ int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t 
         const uint32_t cnt = std::min<uint32_t>(kProfileEvents, repeats - done);
         for (uint32_t i = 0; i < cnt && rc == CW_OK; ++i) {
             if ((e = hipEventRecord(c->prof_ev[2 * i], st)) != hipSuccess) { rc = hip_fail(c, e, "hipEventRecord"); break; }
-            for (const Launch &l : p->launches)
-                if ((e = issue(c, m, &s, l, st)) != hipSuccess) { rc = hip_fail(c, e, l.info.name); break; }
+            rc = enqueue_plan(c, m, p, &s, st);
             if (rc == CW_OK && (e = hipEventRecord(c->prof_ev[2 * i + 1], st)) != hipSuccess) rc = hip_fail(c, e, "hipEventRecord");
         }
         if ((e = hipStreamSynchronize(st)) != hipSuccess && rc == CW_OK) rc = hip_fail(c, e, "hipStreamSynchronize");

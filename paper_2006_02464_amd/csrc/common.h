@@ -15,8 +15,7 @@ enum DType : int32_t { DT_F16 = 0, DT_BF16 = 1 };
 // Kernel families (cw_launch_info.kind).
 enum Kind : int32_t {
     K_CAST_INPUT = 0,  // fp32 NCHW -> storage-type NHWC4
-    K_CONV = 1,        // implicit-GEMM convolution on MFMA (fused epilogue or split-K partials)
-    K_SPLITK_REDUCE = 2,
+    K_CONV = 1,        // implicit-GEMM convolution on MFMA, fused epilogue, optional split-K
     K_MAXPOOL = 3,
     K_GAVGPOOL = 4,
     K_FC = 5,
@@ -46,20 +45,13 @@ struct ConvArgs {
     const void *res;    // NHWC like y, or nullptr
     void *y;            // NHWC [B][Ho][Wo][Cout]
     float *partial;     // split-K: [split][M][Cout] fp32, else nullptr
+    int32_t *counters;  // split-K: one arrival counter per output tile, zero between launches
     int32_t B, H, W, Cin, Ho, Wo, Cout;
     int32_t kh, kw, kwp, stride, pad;
     int32_t M, K;
     int32_t relu;
     int32_t split_k, ktiles_per_split;
     FastDiv wo_div, ho_div;  // for m -> (image, row, column)
-};
-
-struct ReduceArgs {
-    const float *partial;  // [split][M][Cout]
-    const float *bias;
-    const void *res;
-    void *y;
-    int32_t M, Cout, split_k, relu;
 };
 
 struct CastArgs {
@@ -100,7 +92,6 @@ TileDim conv_tile_dim(ConvTile t);
 
 // Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);
-hipError_t launch_splitk_reduce(DType dt, const ReduceArgs &a, hipStream_t s);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
@@ -118,8 +109,9 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 
 // K-slice width the conv kernel uses for a shape (64, or 32 for the stem / Cin % 64 != 0).
 int conv_bk(const ConvArgs &a, bool stem);
+// Bytes at the start of the workspace reserved for split-K arrival counters (one int per tile).
+constexpr size_t kCounterBytes = 256 * 1024;
 // Grid and block of a conv launch (pure function of tile and shape).
 void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block);
-void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block);
 
 }  // namespace cw

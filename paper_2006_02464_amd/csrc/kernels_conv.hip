@@ -29,8 +29,10 @@
 // therefore works straight from registers: bias and residual arrive as 16-byte vectors, then
 // + bias, + residual, ReLU, one round-to-nearest-even to the storage type, 16-byte stores;
 // lanes l and l+32 complete 32 contiguous bytes of a pixel per store instruction.
-// With split-K (gridDim.y > 1) the raw fp32 partial sums go to a [split][M][Cout] buffer and a
-// second kernel reduces them in fixed order and applies the same epilogue.
+// With split-K (gridDim.y > 1) the raw fp32 partial sums go to a [split][M][Cout] buffer; the
+// workgroup of a tile that finishes last (an arrival counter per tile) adds them up in split
+// order and applies the same epilogue, so no second launch is needed and the result does not
+// depend on the order of arrival.
 #include "common.h"
 
 namespace cw {
@@ -101,7 +103,7 @@ static __device__ __forceinline__ int swz(int row, int c) {
     return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
 }
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, int MODE>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, int MODE, bool SPLITK>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(const ConvArgs a) {
     constexpr int NT = 64 * WARPS_M * WARPS_N;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
@@ -349,29 +351,82 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     // Epilogue from registers.  Lane: pixel m0+wm0+32i+lane%32; per channel tile j its registers
     // 8q..8q+7 are channels n0+wn0+32j+16q+8*(lane/32) .. +7  (q = 0, 1).
     const unsigned mn = (unsigned)a.M * a.Cout;
-    if (a.partial) {
-        const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)blockIdx.y * a.M * a.Cout, mn * 4u);
+    if (SPLITK) {
+        // Split-K: every workgroup of a tile stores its raw fp32 partial tile, then takes a
+        // ticket.  The one that draws the last ticket adds the partial tiles of all splits in
+        // split order (its own included, re-read like the others, so the sum does not depend on
+        // which workgroup came last) and carries on into the common epilogue.
+        // Workgroups of one tile may sit on different XCDs, whose L2s are not coherent for plain
+        // accesses.  The partial sums therefore travel as device-scope accesses (sc1: stores
+        // write through, loads do not hit a stale local line), which costs no cache-wide
+        // write-back or invalidate; a store is complete once vmcnt has counted it.
+        constexpr int kDeviceScope = 16;  // cache-policy operand: sc1
+        __shared__ int s_last;
+        {
+            const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)blockIdx.y * a.M * a.Cout, mn * 4u);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const unsigned m = m0 + wm0 + i * 32 + lrow;
+            for (int i = 0; i < TM; ++i) {
+                const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+                        const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
+                        const f32x16 &v = acc[i][j];
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            u32x4{__float_as_uint(v[8 * q + 0]), __float_as_uint(v[8 * q + 1]), __float_as_uint(v[8 * q + 2]),
+                                  __float_as_uint(v[8 * q + 3])},
+                            rp, o, 0, kDeviceScope);
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            u32x4{__float_as_uint(v[8 * q + 4]), __float_as_uint(v[8 * q + 5]), __float_as_uint(v[8 * q + 6]),
+                                  __float_as_uint(v[8 * q + 7])},
+                            rp, o + 16u, 0, kDeviceScope);
+                    }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0): this thread's partial sums have been written
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();  // ... and so have those of the whole workgroup
+        if (tid == 0) {
+            const int ticket = __hip_atomic_fetch_add(&a.counters[tile_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = ticket == (int)gridDim.y - 1;
+            if (last) __hip_atomic_store(&a.counters[tile_id], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+            s_last = last;
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-                    const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
-                    const f32x16 &v = acc[i][j];
-                    __builtin_amdgcn_raw_buffer_store_b128(
-                        u32x4{__float_as_uint(v[8 * q + 0]), __float_as_uint(v[8 * q + 1]), __float_as_uint(v[8 * q + 2]),
-                              __float_as_uint(v[8 * q + 3])},
-                        rp, o, 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(
-                        u32x4{__float_as_uint(v[8 * q + 4]), __float_as_uint(v[8 * q + 5]), __float_as_uint(v[8 * q + 6]),
-                              __float_as_uint(v[8 * q + 7])},
-                        rp, o + 16u, 0, 0);
-                }
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int z = 0; z < (int)gridDim.y; ++z) {
+            const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)z * a.M * a.Cout, mn * 4u);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
+                        const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
+                        const u32x4 p0 = __builtin_amdgcn_raw_buffer_load_b128(rp, o, 0, kDeviceScope);
+                        const u32x4 p1 = __builtin_amdgcn_raw_buffer_load_b128(rp, o + 16u, 0, kDeviceScope);
+                        acc[i][j][8 * q + 0] += __uint_as_float(p0.x);
+                        acc[i][j][8 * q + 1] += __uint_as_float(p0.y);
+                        acc[i][j][8 * q + 2] += __uint_as_float(p0.z);
+                        acc[i][j][8 * q + 3] += __uint_as_float(p0.w);
+                        acc[i][j][8 * q + 4] += __uint_as_float(p1.x);
+                        acc[i][j][8 * q + 5] += __uint_as_float(p1.y);
+                        acc[i][j][8 * q + 6] += __uint_as_float(p1.z);
+                        acc[i][j][8 * q + 7] += __uint_as_float(p1.w);
+                    }
+            }
         }
-        return;
     }
 
     const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, mn * 2u);
@@ -426,39 +481,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     CW_STAMP_END(62);
 }
 
-// Fixed-order reduction of split-K partials + the fused epilogue.  One thread = 8 columns.
-template <typename T>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const ReduceArgs a) {
-    const size_t total8 = (size_t)a.M * a.Cout / 8;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total8) return;
-    const size_t o = idx * 8;
-    const int n = (int)(o % a.Cout);
-    const size_t plane = (size_t)a.M * a.Cout;
-    float4 s0 = *reinterpret_cast<const float4 *>(a.partial + o);
-    float4 s1 = *reinterpret_cast<const float4 *>(a.partial + o + 4);
-    for (int z = 1; z < a.split_k; ++z) {
-        const float4 t0 = *reinterpret_cast<const float4 *>(a.partial + z * plane + o);
-        const float4 t1 = *reinterpret_cast<const float4 *>(a.partial + z * plane + o + 4);
-        s0.x += t0.x; s0.y += t0.y; s0.z += t0.z; s0.w += t0.w;
-        s1.x += t1.x; s1.y += t1.y; s1.z += t1.z; s1.w += t1.w;
-    }
-    const float4 b0 = *reinterpret_cast<const float4 *>(a.bias + n);
-    const float4 b1 = *reinterpret_cast<const float4 *>(a.bias + n + 4);
-    float v[8] = {s0.x + b0.x, s0.y + b0.y, s0.z + b0.z, s0.w + b0.w,
-                  s1.x + b1.x, s1.y + b1.y, s1.z + b1.z, s1.w + b1.w};
-    if (a.res) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const T *>(a.res) + o);
-        const T *r = reinterpret_cast<const T *>(&raw);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] += (float)r[i];
-    }
-    T out[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = (T)(a.relu ? fmaxf(v[i], 0.f) : v[i]);
-    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + o) = *reinterpret_cast<const uint4 *>(out);
-}
-
 TileDim conv_tile_dim(ConvTile t) {
     switch (t) {
         case T128x128: return {128, 128, 256};
@@ -487,40 +509,34 @@ void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block) {
     *block = d.threads;
 }
 
-void reduce_grid(const ReduceArgs &a, dim3 *grid, int *block) {
-    const size_t total8 = (size_t)a.M * a.Cout / 8;
-    *grid = dim3((unsigned)((total8 + 255) / 256), 1, 1);
-    *block = 256;
-}
-
-template <typename T, int BK, int MODE>
+template <typename T, int BK, int MODE, bool SPLITK>
 static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s) {
     dim3 grid;
     int block;
     conv_grid(tile, a, &grid, &block);
-    // K slices in flight in registers: 2 for the largest tile (register budget), else 3
+    // K slices in flight in registers: 2 for the tiles with 64x64 per wave (register budget), else 3
     switch (tile) {
-        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
-        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
-        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
-        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
-        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
-        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
-        case T128x64w2: conv_igemm_kernel<T, 128, 64, 2, 1, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
-        case T64x128w2: conv_igemm_kernel<T, 64, 128, 1, 2, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
-        case T256x64: conv_igemm_kernel<T, 256, 64, 4, 1, BK, 2, MODE><<<grid, block, 0, s>>>(a); break;
-        case T128x128w8: conv_igemm_kernel<T, 128, 128, 2, 4, BK, 3, MODE><<<grid, block, 0, s>>>(a); break;
+        case T128x128: conv_igemm_kernel<T, 128, 128, 2, 2, BK, 2, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T128x64: conv_igemm_kernel<T, 128, 64, 2, 2, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T64x64: conv_igemm_kernel<T, 64, 64, 2, 2, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T64x32: conv_igemm_kernel<T, 64, 32, 2, 1, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T32x64: conv_igemm_kernel<T, 32, 64, 1, 2, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T32x32: conv_igemm_kernel<T, 32, 32, 1, 1, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T128x64w2: conv_igemm_kernel<T, 128, 64, 2, 1, BK, 2, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T64x128w2: conv_igemm_kernel<T, 64, 128, 1, 2, BK, 2, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T256x64: conv_igemm_kernel<T, 256, 64, 4, 1, BK, 2, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
+        case T128x128w8: conv_igemm_kernel<T, 128, 128, 2, 4, BK, 3, MODE, SPLITK><<<grid, block, 0, s>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, bool SPLITK>
 static hipError_t launch_conv_dt(ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
-    if (stem) return launch_conv_t<T, 32, MODE_STEM>(tile, a, s);
-    if (conv_is_gemm(a, stem)) return launch_conv_t<T, 64, MODE_GEMM>(tile, a, s);
-    if (a.Cin % 64 == 0) return launch_conv_t<T, 64, MODE_CONV>(tile, a, s);
-    return launch_conv_t<T, 32, MODE_CONV>(tile, a, s);
+    if (stem) return launch_conv_t<T, 32, MODE_STEM, SPLITK>(tile, a, s);
+    if (conv_is_gemm(a, stem)) return launch_conv_t<T, 64, MODE_GEMM, SPLITK>(tile, a, s);
+    if (a.Cin % 64 == 0) return launch_conv_t<T, 64, MODE_CONV, SPLITK>(tile, a, s);
+    return launch_conv_t<T, 32, MODE_CONV, SPLITK>(tile, a, s);
 }
 
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
@@ -533,24 +549,14 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
         return hipErrorInvalidValue;
     if (stem ? a.kh > 30 : a.kh * a.kw > 32) return hipErrorInvalidValue;  // tap masks are 32 bits
     if ((long long)a.split_k * a.ktiles_per_split < a.K / bk) return hipErrorInvalidValue;
-    if (a.split_k > 1 && !a.partial) return hipErrorInvalidValue;
+    if (a.split_k > 1 && (!a.partial || !a.counters)) return hipErrorInvalidValue;
+    if (a.split_k == 1 && a.partial) return hipErrorInvalidValue;
     // buffer descriptors address less than 2 GiB each
     if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)a.M * a.Cout * (a.partial ? 4 : 2) >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31))
         return hipErrorInvalidValue;
-    return dt == DT_F16 ? launch_conv_dt<f16>(tile, stem, a, s) : launch_conv_dt<bf16>(tile, stem, a, s);
-}
-
-hipError_t launch_splitk_reduce(DType dt, const ReduceArgs &a, hipStream_t s) {
-    if (a.Cout % 8 != 0 || a.split_k < 1) return hipErrorInvalidValue;
-    dim3 grid;
-    int block;
-    reduce_grid(a, &grid, &block);
-    if (dt == DT_F16)
-        splitk_reduce_kernel<f16><<<grid, block, 0, s>>>(a);
-    else
-        splitk_reduce_kernel<bf16><<<grid, block, 0, s>>>(a);
-    return hipGetLastError();
+    if (a.split_k > 1) return dt == DT_F16 ? launch_conv_dt<f16, true>(tile, stem, a, s) : launch_conv_dt<bf16, true>(tile, stem, a, s);
+    return dt == DT_F16 ? launch_conv_dt<f16, false>(tile, stem, a, s) : launch_conv_dt<bf16, false>(tile, stem, a, s);
 }
 
 }  // namespace cw

@@ -286,6 +286,9 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         return off;
     };
 
+    // the split-K arrival counters live at the very start of the workspace, never reused
+    (void)ws_alloc(kCounterBytes);
+
     // input cast: fp32 NCHW in the IO slot -> NHWC4 in the workspace
     const size_t cast_bytes = (size_t)batch * m.in_h * m.in_w * 4 * esz;
     const size_t cast_off = ws_alloc(cast_bytes);
@@ -329,6 +332,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 a.ho_div = make_fast_div((uint32_t)os.h);
                 const int ktiles = a.K / conv_bk(a, l.stem);
                 pick_conv_tile(a.M, a.Cout, ktiles, ov, &l.tile, &a.split_k);
+                {
+                    const TileDim tdc = conv_tile_dim(l.tile);
+                    const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);
+                    if (tiles * 4 > (int64_t)kCounterBytes || (int64_t)a.M * a.Cout * 4 >= (1ll << 31)) a.split_k = 1;
+                }
                 a.ktiles_per_split = (ktiles + a.split_k - 1) / a.split_k;
                 a.split_k = (ktiles + a.ktiles_per_split - 1) / a.ktiles_per_split;  // no empty splits
                 l.x = src;
@@ -350,23 +358,15 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     partial_bytes = (size_t)a.split_k * a.M * a.Cout * 4;
                     partial_off = ws_alloc(partial_bytes);
                     l.partial = Ref{SP_WORKSPACE, partial_off};
-                    l.info.bytes = in_b + w_b + (int64_t)partial_bytes;
-                    snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d_splitk", o.kh, o.kw, o.stride);
-                    p.launches.push_back(l);
-                    Launch r{};
-                    r.kind = K_SPLITK_REDUCE;
-                    r.op_index = i;
-                    r.red.M = a.M; r.red.Cout = a.Cout; r.red.split_k = a.split_k; r.red.relu = o.relu;
-                    r.partial = l.partial; r.bias = l.bias; r.res = l.res; r.y = l.y;
-                    r.info.bytes = (int64_t)partial_bytes + out_b + res_b;
-                    r.info.split_k = a.split_k;
-                    snprintf(r.info.name, sizeof r.info.name, "splitk_reduce");
-                    p.launches.push_back(r);
+                    l.counters = Ref{SP_WORKSPACE, 0};
+                    // partial sums are written once and read once by the tile's last workgroup
+                    l.info.bytes = in_b + w_b + out_b + res_b + 2 * (int64_t)partial_bytes;
+                    snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d_splitk%d", o.kh, o.kw, o.stride, a.split_k);
                 } else {
                     l.info.bytes = in_b + w_b + out_b + res_b;
                     snprintf(l.info.name, sizeof l.info.name, i == 0 ? "stem%dx%d_s%d" : "conv%dx%d_s%d", o.kh, o.kw, o.stride);
-                    p.launches.push_back(l);
                 }
+                p.launches.push_back(l);
                 break;
             }
             case CW_OP_MAXPOOL: {
@@ -446,7 +446,6 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         int b = 0;
         switch (l.kind) {
             case K_CONV: conv_grid(l.tile, l.conv, &g, &b); break;
-            case K_SPLITK_REDUCE: reduce_grid(l.red, &g, &b); break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.H * l.cast.W + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;

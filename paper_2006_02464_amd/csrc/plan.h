@@ -27,12 +27,11 @@ struct Launch {
     bool stem = false;
     // Shape fields are final; pointer fields are filled from the Refs at EXEC time.
     ConvArgs conv{};
-    ReduceArgs red{};
     CastArgs cast{};
     PoolArgs pool{};
     FcArgs fc{};
     SoftmaxArgs sm{};
-    Ref x, w, bias, res, y, partial;
+    Ref x, w, bias, res, y, partial, counters;
     cw_launch_info info{};
 };
 

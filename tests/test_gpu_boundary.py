@@ -97,13 +97,14 @@ def test_io_cache_exhaustion_and_reuse(setup):
 def test_second_exec_on_another_stream_is_busy(setup):
     w, case = setup
     ctx = w.ctx
-    mid = ctx.model_define_resnet(18, 224, 224)     # ~1 ms per EXEC at batch 16
+    mid = ctx.model_define_resnet(18, 224, 224)
     w.load(mid, case.blob)
     x = torch.zeros((16, 3, 224, 224), dtype=torch.float32).pin_memory()
     slot = ctx.input(mid, 16, x, w.stream)
     other = torch.cuda.Stream()
-    for _ in range(20):                     # keep the EXEC stream busy
-        ctx.exec(mid, 16, slot, w.stream)
+    with torch.cuda.stream(w.stream):       # ~50 ms of spinning ahead of the EXEC on its stream
+        torch.cuda._sleep(120_000_000)
+    ctx.exec(mid, 16, slot, w.stream)
     st = None
     try:
         ctx.exec(mid, 16, slot, other)
@@ -137,3 +138,32 @@ def test_profile_measure(setup):
     assert len(per_launch) == ctx.plan_num_launches(mid, 4) and (per_launch > 0).all()
     ctx.release(slot)
     ctx.unload_weights(mid)
+
+
+def test_graph_replay_equals_plain_launches(setup):
+    """EXEC through the recorded graph and EXEC as plain launches give bit-identical results,
+    on every replay, with other work and synchronisations in between."""
+    w, case = setup
+    ctx = w.ctx
+    mid = ctx.model_define_resnet(18, 64, 64)
+    w.load(mid, case.blob)
+    x = case.images(0, 4)
+    ctx.set_use_graphs(False)
+    plain = w.infer(mid, x)[1]
+    ctx.set_use_graphs(True)
+    for i in range(6):
+        got = w.infer(mid, x)[1]
+        assert np.array_equal(got, plain), "replay %d differs" % i
+        ctx.set_use_graphs(False)                       # eager work between replays
+        other = w.infer(mid, case.images(10 + i, 4))[1]
+        ctx.set_use_graphs(True)
+        assert not np.array_equal(other, plain)
+        torch.cuda.synchronize()
+    # a model loaded while graphs are off runs without one, and still agrees
+    ctx.set_use_graphs(False)
+    m2 = ctx.model_define_resnet(18, 64, 64)
+    w.load(m2, case.blob)
+    ctx.set_use_graphs(True)
+    assert np.array_equal(w.infer(m2, x)[1], plain)
+    ctx.unload_weights(mid)
+    ctx.unload_weights(m2)

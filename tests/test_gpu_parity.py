@@ -259,6 +259,21 @@ def test_resnet50_224_small_batches(worker, r50, batch):
     worker.ctx.unload_weights(mid)
 
 
+def test_resnet50_split_k_is_reproducible(worker, r50):
+    """Batch 1 runs most layers split over K, each tile finished by whichever workgroup arrives
+    last; the sum must not depend on that order: 200 EXECs, bit-identical logits."""
+    case, x, ref = r50
+    mid = worker.ctx.model_define_resnet(50, 224, 224)
+    worker.load(mid, case.blob)
+    plan = worker.ctx.plan(mid, 1)
+    assert sum(l["split_k"] > 1 for l in plan) >= 10
+    first = worker.infer(mid, x[:1])[1]
+    assert rel_err_per_sample(first, ref[:1]).max() <= TOL
+    for _ in range(200):
+        assert np.array_equal(worker.infer(mid, x[:1])[1], first)
+    worker.ctx.unload_weights(mid)
+
+
 def test_resnet50_first_block_every_layer(worker):
     """Per-layer parity on the real 224x224 shapes (stem, max pool, first bottleneck, and on
     through the network) at batch 2."""
