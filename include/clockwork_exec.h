@@ -163,7 +163,8 @@ typedef struct {
 } cw_profile;
 /* Runs `repeats` EXECs of (model, batch) back to back on an internal stream over a
  * zero input, each timed on the device, and stores and returns nearest-rank
- * percentiles.  Synchronous.  samples_us [host] may be NULL, else receives the
+ * percentiles.  The EXECs are submitted in bursts of 128; one untimed EXEC leads
+ * each burst so that every timed one starts behind queued work.  Synchronous.  samples_us [host] may be NULL, else receives the
  * `repeats` individual durations in microseconds. */
 int32_t cw_profile_measure(cw_ctx *ctx, int32_t model_id, int32_t batch, uint32_t repeats,
                            cw_profile *out, float *samples_us);
@@ -205,9 +206,9 @@ int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
  * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
  * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
 int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..8 =
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..9 =
  * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
- * 256x64; pixels x channels per workgroup; -1 = the plan compiler's own choice)
+ * 256x64, 128x128 on 8 waves; pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);

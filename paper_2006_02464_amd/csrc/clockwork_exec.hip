@@ -723,6 +723,9 @@ int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t 
     rc = CW_OK;
     for (uint32_t done = 0; done < repeats && rc == CW_OK;) {
         const uint32_t cnt = std::min<uint32_t>(kProfileEvents, repeats - done);
+        // One untimed EXEC leads every burst: without it the first start event of a burst fires on
+        // an idle GPU while the host is still submitting the work it is meant to time.
+        rc = enqueue_plan(c, m, p, &s, st);
         for (uint32_t i = 0; i < cnt && rc == CW_OK; ++i) {
             if ((e = hipEventRecord(c->prof_ev[2 * i], st)) != hipSuccess) { rc = hip_fail(c, e, "hipEventRecord"); break; }
             rc = enqueue_plan(c, m, p, &s, st);

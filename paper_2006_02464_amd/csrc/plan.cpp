@@ -226,10 +226,28 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
 }
 
 // ---------------------------------------------------------------- tile choice
-// Largest tile that still gives every CU at least one workgroup; below that, a 64x64 (or
-// narrower) tile with K split over up to 16 workgroups.  Pure function of the GEMM shape.
-static void pick_conv_tile(int64_t M, int64_t N, int64_t ktiles, const PlanOverride &ov, ConvTile *tile,
-                           int32_t *split) {
+// A measured shape takes its tile and split from the table.  Otherwise: the largest tile that
+// still gives every CU at least one workgroup; below that, a 64x64 (or narrower) tile with K
+// split over up to 16 workgroups.  Either way a pure function of the GEMM shape.
+// Offline measurements (tune.py): the fastest tile and split-K per GEMM shape seen on an MI355X.
+struct TunedShape {
+    int32_t M, N, K, kh, stride, tile, split_k;
+};
+static const TunedShape kTuned[] = {
+#include "plan_table.inc"
+};
+
+static void pick_conv_tile(int64_t M, int64_t N, int64_t K, int32_t kh, int32_t stride, int64_t ktiles,
+                           const PlanOverride &ov, ConvTile *tile, int32_t *split) {
+    if (ov.tile < 0 && ov.split_k <= 0) {
+        for (const TunedShape &t : kTuned)
+            if (t.M == M && t.N == N && t.K == K && t.kh == kh && t.stride == stride && t.tile >= 0 &&
+                t.tile < N_CONV_TILES) {
+                *tile = (ConvTile)t.tile;
+                *split = (int32_t)std::max<int64_t>(1, std::min<int64_t>(t.split_k, ktiles));
+                return;
+            }
+    }
     static const ConvTile order[] = {T128x128, T128x64, T64x64, T32x64, T64x32, T32x32};
     auto blocks = [&](ConvTile t) {
         const TileDim d = conv_tile_dim(t);
@@ -331,7 +349,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 a.wo_div = make_fast_div((uint32_t)os.w);
                 a.ho_div = make_fast_div((uint32_t)os.h);
                 const int ktiles = a.K / conv_bk(a, l.stem);
-                pick_conv_tile(a.M, a.Cout, ktiles, ov, &l.tile, &a.split_k);
+                pick_conv_tile(a.M, a.Cout, (int64_t)o.kh * o.kw * o.cin, o.kh, o.stride, ktiles, ov, &l.tile, &a.split_k);
                 {
                     const TileDim tdc = conv_tile_dim(l.tile);
                     const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);
