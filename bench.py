@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 BATCHES = (1, 2, 4, 8, 16)
+# HBM-side bytes of the 53 conv launches of one batch-16 EXEC, from the FETCH_SIZE / WRITE_SIZE
+# counter runs summarised in profiles/exec_resnet50_b16_hbm_traffic.txt (scaled by a 256 MiB copy).
+# Counters cannot be read from inside this process, so the figure is carried here.
+CONV_TRAFFIC_BYTES_B16 = 1300.1e6
 
 
 def cpu_baseline(seed, log):
@@ -51,6 +55,12 @@ def main():
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers-out", default="", help="write the per-launch table here (text)")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="profiling runs: only the timed EXECs and the per-launch pass at --batch "
+                         "(no per-batch latency profile, no CPU baseline)")
+    ap.add_argument("--no-graphs", action="store_true", help="issue every kernel as its own launch")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one device-to-device copy kernel of this many MiB (scale for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (an 8-GPU node is 8 independent workers); "
@@ -69,6 +79,16 @@ def main():
     wk = Worker(workspace_bytes=512 << 20, io_bytes=512 << 20, weight_pool_bytes=1 << 30,
                 load_staging_bytes=256 << 20)
     ctx, stream = wk.ctx, wk.stream
+    if args.no_graphs:
+        ctx.set_use_graphs(0)
+    if args.copy_calibration:
+        # a plain elementwise copy: reads and writes exactly this many bytes each
+        src = torch.ones(args.copy_calibration << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     mid = ctx.model_define_resnet(50, 224, 224, "fp16")
     ops = ctx.model_get_ops(mid)
     shapes = [(o[2], o[1], o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
@@ -123,7 +143,7 @@ def main():
 
     # ---- EXEC latency profile per batch size (on-device durations)
     latency = {}
-    for bs in BATCHES:
+    for bs in (() if args.timed_only else BATCHES):
         ctx.profile_measure(mid, bs, 100)
         p = ctx.profile_measure(mid, bs, args.profile_repeats)
         latency[str(bs)] = {"p50_us": round(p["p50_us"], 2), "p99_us": round(p["p99_us"], 2),
@@ -146,12 +166,15 @@ def main():
                    "batch": B, "global_batch": B, "parallelism": "single GPU"},
         "exec_latency_us": latency,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_MFMA_F16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4),
+                     "traffic": CONV_TRAFFIC_BYTES_B16 if B == 16 else None,
+                     "traffic_unit": "bytes per EXEC over the conv launches (counters, separate run)",
+                     "algorithmic_bytes": conv_bytes,
                      "kernel": "conv_igemm_kernel (all %d conv launches of one EXEC)" % len(conv),
                      "avg_launch_us": round(conv_us / len(conv), 3),
                      "algorithmic_GBps": round(conv_bytes / (conv_us * 1e-6) / 1e9, 1)},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.timed_only:
         out["cpu_baseline"] = cpu_baseline(seed, log)
     print(json.dumps(out), flush=True)
 
