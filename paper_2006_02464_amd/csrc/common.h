@@ -92,6 +92,8 @@ TileDim conv_tile_dim(ConvTile t);
 
 // Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);
+// The direct-to-LDS kernel for Cin % 64 == 0 (called by launch_conv after its checks).
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);

@@ -33,75 +33,9 @@
 // workgroup of a tile that finishes last (an arrival counter per tile) adds them up in split
 // order and applies the same epilogue, so no second launch is needed and the result does not
 // depend on the order of arrival.
-#include "common.h"
+#include "conv_common.h"
 
 namespace cw {
-
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (buffers are < 2 GiB)
-
-enum ConvMode : int { MODE_CONV = 0, MODE_GEMM = 1, MODE_STEM = 2 };
-
-// Development aid: with -DCW_TRACE one lane per workgroup stamps the shader clock at phase
-// boundaries into a global array (64 stamps per workgroup).  Never compiled into the library.
-#ifdef CW_TRACE
-__device__ long long cw_trace_buf[4096 * 64];
-#define CW_STAMP(slot)                                                                                  \
-    do {                                                                                                \
-        const int sl__ = (slot);                                                                        \
-        if (threadIdx.x == 0 && blockIdx.x < 4096 && sl__ < 60) cw_trace_buf[blockIdx.x * 64 + sl__] = clock64(); \
-    } while (0)
-#define CW_STAMP_END(slot)                                                                              \
-    do {                                                                                                \
-        if (threadIdx.x == 0 && blockIdx.x < 4096) cw_trace_buf[blockIdx.x * 64 + (slot)] = clock64();  \
-    } while (0)
-#else
-#define CW_STAMP(slot) do { } while (0)
-#define CW_STAMP_END(slot) do { } while (0)
-#endif
-
-// n / d for a divisor prepared on the host (round-up multiplier; exact for every 32-bit n).
-static __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &d) {
-    const unsigned t = __umulhi(d.magic, n);
-    return (t + ((n - t) >> d.sh1)) >> d.sh2;
-}
-
-static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes) {
-    // raw buffer (stride 0), 32-bit data format word as on every CDNA part
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
-}
-
-template <typename T>
-struct Mfma;
-template <>
-struct Mfma<f16> {
-    typedef _Float16 v8 __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ f32x16 mma(v8 rows, v8 cols, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(rows, cols, c, 0, 0, 0);
-    }
-};
-template <>
-struct Mfma<bf16> {
-    typedef __bf16 v8 __attribute__((ext_vector_type(8)));
-    static __device__ __forceinline__ f32x16 mma(v8 rows, v8 cols, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows, cols, c, 0, 0, 0);
-    }
-};
-
-// Element offset of 16-byte chunk c of `row` inside a [rows][BK] LDS stage.  A 16-byte-per-lane
-// LDS access is served 16 lanes (256 bytes, all 64 banks) per clock, and an MFMA operand read
-// has 16 consecutive rows at one chunk index in such a group.  With 128-byte rows two rows
-// share 256 bytes, so the chunk index is XORed with (row/2)%8: rows of equal parity then land
-// on 8 different chunk positions and the two parities on the two halves.  With 64-byte rows
-// four rows share 256 bytes and the key is (row/4)%4.
-template <int BK>
-static __device__ __forceinline__ int swz(int row, int c) {
-    if (BK == 64) return row * 64 + ((c ^ ((row >> 1) & 7)) << 3);
-    return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
-}
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int PF, int MODE, bool SPLITK>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(const ConvArgs a) {
@@ -127,15 +61,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     const int lrow = lane & 31;
     const int lhalf = lane >> 5;
 
-    // Workgroups go to the 8 XCDs round-robin; give each XCD a contiguous run of tiles so that
-    // tiles sharing pixels (same tile_m) meet in one XCD's L2.
-    int tile_id;
-    {
-        const int nb = gridDim.x, bid = blockIdx.x;
-        const int xcd = bid & 7, idx = bid >> 3;
-        const int per = nb >> 3, rem = nb & 7;
-        tile_id = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
-    }
+    const int tile_id = xcd_tile_id();
     const int tiles_n = a.Cout / BN + (a.Cout % BN != 0);
     const int tile_m = tile_id / tiles_n;
     const int tile_n = tile_id - tile_m * tiles_n;
@@ -348,136 +274,16 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     }
 
     CW_STAMP_END(60);
-    // Epilogue from registers.  Lane: pixel m0+wm0+32i+lane%32; per channel tile j its registers
-    // 8q..8q+7 are channels n0+wn0+32j+16q+8*(lane/32) .. +7  (q = 0, 1).
-    const unsigned mn = (unsigned)a.M * a.Cout;
+    const EpiPos pos{m0, n0, wm0, wn0, lrow, lhalf};
     if (SPLITK) {
-        // Split-K: every workgroup of a tile stores its raw fp32 partial tile, then takes a
-        // ticket.  The one that draws the last ticket adds the partial tiles of all splits in
-        // split order (its own included, re-read like the others, so the sum does not depend on
-        // which workgroup came last) and carries on into the common epilogue.
-        // Workgroups of one tile may sit on different XCDs, whose L2s are not coherent for plain
-        // accesses.  The partial sums therefore travel as device-scope accesses (sc1: stores
-        // write through, loads do not hit a stale local line), which costs no cache-wide
-        // write-back or invalidate; a store is complete once vmcnt has counted it.
-        constexpr int kDeviceScope = 16;  // cache-policy operand: sc1
-        __shared__ int s_last;
-        {
-            const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)blockIdx.y * a.M * a.Cout, mn * 4u);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const unsigned m = m0 + wm0 + i * 32 + lrow;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-                        const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
-                        const f32x16 &v = acc[i][j];
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            u32x4{__float_as_uint(v[8 * q + 0]), __float_as_uint(v[8 * q + 1]), __float_as_uint(v[8 * q + 2]),
-                                  __float_as_uint(v[8 * q + 3])},
-                            rp, o, 0, kDeviceScope);
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            u32x4{__float_as_uint(v[8 * q + 4]), __float_as_uint(v[8 * q + 5]), __float_as_uint(v[8 * q + 6]),
-                                  __float_as_uint(v[8 * q + 7])},
-                            rp, o + 16u, 0, kDeviceScope);
-                    }
-            }
-        }
-        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0): this thread's partial sums have been written
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();  // ... and so have those of the whole workgroup
-        if (tid == 0) {
-            const int ticket = __hip_atomic_fetch_add(&a.counters[tile_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int last = ticket == (int)gridDim.y - 1;
-            if (last) __hip_atomic_store(&a.counters[tile_id], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
-            s_last = last;
-        }
-        __syncthreads();
-        if (!s_last) return;
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-        for (int z = 0; z < (int)gridDim.y; ++z) {
-            const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)z * a.M * a.Cout, mn * 4u);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const unsigned m = m0 + wm0 + i * 32 + lrow;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 2; ++q) {
-                        const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-                        const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 4u : kOob;
-                        const u32x4 p0 = __builtin_amdgcn_raw_buffer_load_b128(rp, o, 0, kDeviceScope);
-                        const u32x4 p1 = __builtin_amdgcn_raw_buffer_load_b128(rp, o + 16u, 0, kDeviceScope);
-                        acc[i][j][8 * q + 0] += __uint_as_float(p0.x);
-                        acc[i][j][8 * q + 1] += __uint_as_float(p0.y);
-                        acc[i][j][8 * q + 2] += __uint_as_float(p0.z);
-                        acc[i][j][8 * q + 3] += __uint_as_float(p0.w);
-                        acc[i][j][8 * q + 4] += __uint_as_float(p1.x);
-                        acc[i][j][8 * q + 5] += __uint_as_float(p1.y);
-                        acc[i][j][8 * q + 6] += __uint_as_float(p1.z);
-                        acc[i][j][8 * q + 7] += __uint_as_float(p1.w);
-                    }
-            }
-        }
+        if (!splitk_exchange<TM, TN>(acc, a, pos, tile_id)) return;
     }
-
-    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, mn * 2u);
-    const __amdgpu_buffer_rsrc_t rr = make_rsrc(a.res ? a.res : a.y, mn * 2u);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(a.bias, (unsigned)a.Cout * 4u);
-    const bool has_res = a.res != nullptr;
-    // every bias and residual vector first (independent loads, one exposed latency) ...
-    u32x4 bv[TN][2][2], rv[TM][TN][2];
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-            const unsigned o = n < (unsigned)a.Cout ? n * 4u : kOob;
-            bv[j][q][0] = __builtin_amdgcn_raw_buffer_load_b128(rb, o, 0, 0);
-            bv[j][q][1] = __builtin_amdgcn_raw_buffer_load_b128(rb, o + 16u, 0, 0);
-        }
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const unsigned m = m0 + wm0 + i * 32 + lrow;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-                const unsigned o = (has_res && m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 2u : kOob;
-                rv[i][j][q] = __builtin_amdgcn_raw_buffer_load_b128(rr, o, 0, 0);
-            }
-    }
+    // every bias and residual vector first (independent loads, one exposed latency), then the
+    // arithmetic and the stores
+    EpiOperands<TM, TN> eo;
+    epilogue_load<TM, TN>(eo, a, pos);
     CW_STAMP_END(61);
-    // ... then the arithmetic and the stores
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const unsigned m = m0 + wm0 + i * 32 + lrow;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const unsigned n = n0 + wn0 + j * 32 + q * 16 + lhalf * 8;
-                const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 2u : kOob;
-                const T *r = reinterpret_cast<const T *>(&rv[i][j][q]);
-                const float *b = reinterpret_cast<const float *>(&bv[j][q][0]);
-                T out[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float v = acc[i][j][8 * q + e] + b[e] + (float)r[e];  // r is zero without a residual
-                    out[e] = (T)(a.relu ? fmaxf(v, 0.f) : v);
-                }
-                __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
-            }
-    }
+    epilogue_store<T, TM, TN>(acc, eo, a, pos);
     CW_STAMP_END(62);
 }
 
@@ -534,8 +340,6 @@ static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s)
 template <typename T, bool SPLITK>
 static hipError_t launch_conv_dt(ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
     if (stem) return launch_conv_t<T, 32, MODE_STEM, SPLITK>(tile, a, s);
-    if (conv_is_gemm(a, stem)) return launch_conv_t<T, 64, MODE_GEMM, SPLITK>(tile, a, s);
-    if (a.Cin % 64 == 0) return launch_conv_t<T, 64, MODE_CONV, SPLITK>(tile, a, s);
     return launch_conv_t<T, 32, MODE_CONV, SPLITK>(tile, a, s);
 }
 
@@ -555,6 +359,9 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
     if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)a.M * a.Cout * (a.partial ? 4 : 2) >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31))
         return hipErrorInvalidValue;
+    // K slices of 64 go global -> LDS directly (kernels_conv_dlds.hip); the stem and Cin % 64 != 0
+    // keep the register-staged kernel of this file.
+    if (!stem && a.Cin % 64 == 0) return launch_conv_dlds(dt, tile, conv_is_gemm(a, stem), a, s);
     if (a.split_k > 1) return dt == DT_F16 ? launch_conv_dt<f16, true>(tile, stem, a, s) : launch_conv_dt<bf16, true>(tile, stem, a, s);
     return dt == DT_F16 ? launch_conv_dt<f16, false>(tile, stem, a, s) : launch_conv_dt<bf16, false>(tile, stem, a, s);
 }

@@ -1,0 +1,309 @@
+// Implicit-GEMM convolution on gfx950 MFMA whose K slices travel global -> LDS directly.
+//
+// Same GEMM view, weight layout, LDS swizzle, MFMA roles and epilogue as the register-staged
+// kernel (kernels_conv.hip), for Cin % 64 == 0 (K slices of 64).  What differs is the pipeline:
+// a K slice is fetched by buffer loads that write LDS themselves (buffer_load_dwordx4 ... lds),
+// so no registers hold data in flight, no wave spends issue slots on LDS writes, and the LDS
+// is a ring of NS stages: while the MFMAs consume slice kt out of stage kt % NS, the loads of
+// slices kt+1 .. kt+NS-1 are in flight into the other stages.  One barrier per slice.
+//
+// Such a load writes the 64 lanes' 16-byte pieces to 1 KiB of consecutive LDS bytes starting
+// at the address in M0, i.e. (for 128-byte rows) lane l lands in row l/8 at chunk position l%8.
+// The XOR swizzle that the MFMA operand reads need is therefore applied on the global side:
+// the lane that owns LDS position (row, pc) fetches the row's logical chunk pc ^ key(row).
+// Padded taps and rows beyond M or Cout use an out-of-range offset, for which the load writes
+// zeros.  The compiler does not see these loads (inline asm), so the kernel counts them itself:
+// every slice is exactly LOADS instructions per thread, they complete in order, and before
+// slice kt is read each thread waits until at most (slices still in flight behind kt) * LOADS
+// of its loads are outstanding, then the barrier makes every thread's part visible.
+#include <type_traits>
+
+#include "conv_common.h"
+
+namespace cw {
+
+// One 16-byte-per-lane buffer load straight into LDS at byte address lds_addr (+ 16*lane).
+static __device__ __forceinline__ void load_to_lds(u32x4 desc, unsigned voff, unsigned soff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
+                 : "memory", "m0");
+}
+
+// Waits until at most N of this thread's loads are outstanding, then the workgroup barrier.
+template <int N>
+static __device__ __forceinline__ void wait_loads_and_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+// Raw buffer descriptor (stride 0) as four scalars, for use as an asm operand.
+static __device__ __forceinline__ u32x4 make_desc(const void *p, unsigned bytes) {
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    return u32x4{(unsigned)v, (unsigned)(v >> 32) & 0xffffu, bytes, 0x00020000u};
+}
+
+extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
+
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int NS, int MODE, bool SPLITK>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const ConvArgs a) {
+    constexpr int BK = 64;
+    constexpr int NT = 64 * WARPS_M * WARPS_N;
+    constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int CPR = BK / 8;  // 16-byte chunks per LDS row
+    constexpr int X_CHUNKS = BM * CPR, W_CHUNKS = BN * CPR;
+    static_assert(X_CHUNKS % NT == 0 && W_CHUNKS % NT == 0, "tile/threads mismatch");
+    static_assert(MODE == MODE_CONV || MODE == MODE_GEMM, "the stem keeps the register-staged kernel");
+    static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
+    constexpr int X_PER = X_CHUNKS / NT, W_PER = W_CHUNKS / NT;
+    constexpr int LOADS = X_PER + W_PER;               // load instructions per thread per slice
+    constexpr int STAGE = (BM + BN) * BK;              // elements per LDS stage
+    constexpr unsigned STAGE_BYTES = STAGE * 2u;
+    static_assert((NS - 2) * LOADS < 64, "too many loads in flight for vmcnt");
+    typedef typename Mfma<T>::v8 v8;
+
+    T *lds = reinterpret_cast<T *>(cw_dyn_lds);
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)cw_dyn_lds;
+
+    CW_STAMP(0);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave / WARPS_N) * WM;
+    const int wn0 = (wave % WARPS_N) * WN;
+    const int lrow = lane & 31;
+    const int lhalf = lane >> 5;
+
+    const int tile_id = xcd_tile_id();
+    const int tiles_n = a.Cout / BN + (a.Cout % BN != 0);
+    const int tile_m = tile_id / tiles_n;
+    const int tile_n = tile_id - tile_m * tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int ktiles = a.K / BK;
+    const int kt0 = blockIdx.y * a.ktiles_per_split;
+    const int kt1 = min(ktiles, kt0 + a.ktiles_per_split);
+    const int nsteps = kt1 - kt0;
+
+    // The activation buffer is described from D bytes before its start, D = the offset of the
+    // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
+    // VGPR) + tap/channel offset (uniform, in an SGPR)  is never negative.
+    const unsigned x_bytes = (unsigned)a.B * a.H * a.W * a.Cin * 2u;
+    const unsigned x_shift = MODE == MODE_GEMM ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
+    const u32x4 dx = make_desc(static_cast<const char *>(a.x) - x_shift, x_bytes + x_shift);
+    const u32x4 dw = make_desc(a.w, (unsigned)a.Cout * a.K * 2u);
+
+    // This thread's pieces of a slice.  Piece j is LDS position cid = tid + j*NT of the operand's
+    // [rows][8 chunks] stage: row cid/8, chunk position cid%8, holding logical chunk
+    // (cid%8) ^ key(row).  Per piece, fixed for the whole K walk: the byte offset of that chunk
+    // at the filter's centre pixel, and which taps fall inside the image (bit r*kw+s; for the
+    // 1x1 stride-1 case bit 0 = the pixel exists).
+    unsigned x_voff[X_PER], x_mask[X_PER];
+#pragma unroll
+    for (int j = 0; j < X_PER; ++j) {
+        const int cid = tid + j * NT;
+        const int row = cid / CPR;
+        const int c = (cid % CPR) ^ ((row >> 1) & 7);
+        const unsigned m = m0 + row;
+        unsigned mask = 0, voff = 0;
+        if (MODE == MODE_GEMM) {
+            voff = m * (unsigned)a.Cin * 2u + c * 16u;
+            mask = m < (unsigned)a.M ? 1u : 0u;
+        } else if (m < (unsigned)a.M) {
+            const unsigned t = fast_div(m, a.wo_div);
+            const int q = m - t * a.Wo;
+            const unsigned n = fast_div(t, a.ho_div);
+            const int p = t - n * a.Ho;
+            const int ihc = p * a.stride, iwc = q * a.stride;
+            voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u + c * 16u;
+            const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
+            const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+            const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
+            for (int r = r_lo; r < r_hi; ++r) mask |= cols << (r * a.kw);
+        }
+        x_voff[j] = voff;
+        x_mask[j] = mask;
+    }
+    unsigned w_off[W_PER];
+#pragma unroll
+    for (int j = 0; j < W_PER; ++j) {
+        const int cid = tid + j * NT;
+        const int row = cid / CPR;
+        const int c = (cid % CPR) ^ ((row >> 1) & 7);
+        const int n = n0 + row;
+        w_off[j] = n < a.Cout ? ((unsigned)n * a.K + c * 8) * 2u : kOob;
+    }
+
+    // (r, s, c0) of the next K slice to load: k0 = kt*BK = (r*kw + s)*Cin + c0.
+    int fr = 0, fs = 0, fc0 = 0;
+    if (MODE == MODE_GEMM) {
+        fc0 = kt0 * BK;
+    } else {
+        const int k0 = kt0 * BK;
+        const int rs = k0 / a.Cin;
+        fc0 = k0 - rs * a.Cin;
+        fr = rs / a.kw;
+        fs = rs - fr * a.kw;
+    }
+
+    // Issues the LOADS loads of slice kt (kt < kt1) into ring stage `stage`.
+    auto issue = [&](int kt, int stage) {
+        const unsigned soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+        const unsigned tbit = MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs));
+        const unsigned dst = lds_base + (unsigned)stage * STAGE_BYTES + (unsigned)wave * 1024u;
+#pragma unroll
+        for (int j = 0; j < X_PER; ++j)
+            load_to_lds(dx, (x_mask[j] & tbit) ? x_voff[j] : kOob, soff, dst + j * (NT * 16));
+        const unsigned kb = (unsigned)kt * (BK * 2u);
+#pragma unroll
+        for (int j = 0; j < W_PER; ++j) load_to_lds(dw, w_off[j], kb, dst + BM * BK * 2 + j * (NT * 16));
+        fc0 += BK;
+        if (MODE != MODE_GEMM && fc0 == a.Cin) {
+            fc0 = 0;
+            if (++fs == a.kw) { fs = 0; ++fr; }
+        }
+    };
+
+    f32x16 acc[TM][TN];  // [pixel tile][channel tile]; MFMA rows = channels, columns = pixels
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // MFMAs of one K slice; operand fragments of 16-k step kk+1 are fetched from LDS while the
+    // MFMAs of step kk run.
+    auto compute = [&](int stage) {
+        const T *sX = lds + stage * STAGE;
+        const T *sW = sX + BM * BK;
+        v8 fx[2][TM], fw[2][TN];
+        auto fetch = [&](int kk, v8(&qx)[TM], v8(&qw)[TN]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                qx[i] = *reinterpret_cast<const v8 *>(sX + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+        };
+        fetch(0, fx[0], fw[0]);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) fetch(kk + 1, fx[(kk + 1) & 1], fw[(kk + 1) & 1]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk & 1][j], fx[kk & 1][i], acc[i][j]);
+        }
+    };
+
+    const EpiPos pos{m0, n0, wm0, wn0, lrow, lhalf};
+    EpiOperands<TM, TN> eo;
+
+    // Prologue: the first min(NS-1, nsteps) slices into stages 0, 1, ...
+    CW_STAMP(1);
+    const int ahead = min(NS - 1, nsteps);
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (u < ahead) issue(kt0 + u, u);  // uniform
+    CW_STAMP(2);
+
+    // Steady state: slice kt sits in stage `cur`; behind it NS-2 more slices are in flight.  After
+    // the barrier every wave has finished the MFMAs of slice kt-1, so its stage (the one before
+    // `cur` in the ring) takes the loads of slice kt+NS-1, which then fly during NS-1 slices of
+    // MFMAs.
+    int cur = 0;
+    int kt = kt0;
+    int trace_slot = 4;
+    (void)trace_slot;
+    for (; kt + (NS - 1) < kt1; ++kt) {
+        wait_loads_and_barrier<(NS - 2) * LOADS>();
+        CW_STAMP(trace_slot++);
+        issue(kt + NS - 1, cur == 0 ? NS - 1 : cur - 1);
+        compute(cur);
+        CW_STAMP(trace_slot++);
+        cur = cur + 1 == NS ? 0 : cur + 1;
+    }
+    // Tail: the last `ahead` slices, nothing left to load; with r slices still behind the one
+    // about to be read, r*LOADS loads may stay outstanding.  Without split-K the operands of the
+    // epilogue are requested before the last slice's MFMAs.
+    auto tail = [&](auto behind) {
+        constexpr int u = decltype(behind)::value;  // slices still in flight behind this one
+        if (u < kt1 - kt) {                         // uniform
+            wait_loads_and_barrier<u * LOADS>();
+            if (!SPLITK && u == 0) epilogue_load<TM, TN>(eo, a, pos);
+            compute(cur);
+            cur = cur + 1 == NS ? 0 : cur + 1;
+            ++kt;
+        }
+    };
+    if constexpr (NS >= 4) tail(std::integral_constant<int, 2>{});
+    if constexpr (NS >= 3) tail(std::integral_constant<int, 1>{});
+    tail(std::integral_constant<int, 0>{});
+    if (!SPLITK && nsteps <= 0) epilogue_load<TM, TN>(eo, a, pos);
+
+    CW_STAMP_END(60);
+    if (SPLITK) {
+        if (!splitk_exchange<TM, TN>(acc, a, pos, tile_id)) return;
+        epilogue_load<TM, TN>(eo, a, pos);
+    }
+    CW_STAMP_END(61);
+    epilogue_store<T, TM, TN>(acc, eo, a, pos);
+    CW_STAMP_END(62);
+}
+
+// LDS stages per tile: as many as fit two workgroups per CU (160 KiB) for the small tiles, a
+// deeper ring for the large ones.
+template <int BM, int BN>
+struct RingDepth {
+    static constexpr int value = (BM + BN) * 128 * 4 <= 80 * 1024 ? 4 : 3;
+};
+
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int MODE, bool SPLITK>
+static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_t s) {
+    constexpr int NS = RingDepth<BM, BN>::value;
+    constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * 128;
+    auto kern = conv_dlds_kernel<T, BM, BN, WARPS_M, WARPS_N, NS, MODE, SPLITK>;
+    // More than 64 KiB of LDS per workgroup has to be requested once per kernel; done on first
+    // use (under LOAD's graph recording or the first plain EXEC), never per launch afterwards.
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (attr != hipSuccess) return attr;
+    kern<<<grid, block, lds_bytes, s>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T, int MODE, bool SPLITK>
+static hipError_t launch_tile(ConvTile tile, const ConvArgs &a, hipStream_t s) {
+    dim3 grid;
+    int block;
+    conv_grid(tile, a, &grid, &block);
+    switch (tile) {
+        case T128x128: return launch_one<T, 128, 128, 2, 2, MODE, SPLITK>(grid, block, a, s);
+        case T128x64: return launch_one<T, 128, 64, 2, 2, MODE, SPLITK>(grid, block, a, s);
+        case T64x64: return launch_one<T, 64, 64, 2, 2, MODE, SPLITK>(grid, block, a, s);
+        case T64x32: return launch_one<T, 64, 32, 2, 1, MODE, SPLITK>(grid, block, a, s);
+        case T32x64: return launch_one<T, 32, 64, 1, 2, MODE, SPLITK>(grid, block, a, s);
+        case T32x32: return launch_one<T, 32, 32, 1, 1, MODE, SPLITK>(grid, block, a, s);
+        case T128x64w2: return launch_one<T, 128, 64, 2, 1, MODE, SPLITK>(grid, block, a, s);
+        case T64x128w2: return launch_one<T, 64, 128, 1, 2, MODE, SPLITK>(grid, block, a, s);
+        case T256x64: return launch_one<T, 256, 64, 4, 1, MODE, SPLITK>(grid, block, a, s);
+        case T128x128w8: return launch_one<T, 128, 128, 2, 4, MODE, SPLITK>(grid, block, a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T>
+static hipError_t launch_dt(ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s) {
+    if (a.split_k > 1) return gemm ? launch_tile<T, MODE_GEMM, true>(tile, a, s) : launch_tile<T, MODE_CONV, true>(tile, a, s);
+    return gemm ? launch_tile<T, MODE_GEMM, false>(tile, a, s) : launch_tile<T, MODE_CONV, false>(tile, a, s);
+}
+
+// Called by launch_conv (which has validated the shapes) for every convolution with
+// Cin % 64 == 0 other than the stem.
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s) {
+    if (a.Cin % 64 != 0 || a.K != a.kh * a.kw * a.Cin) return hipErrorInvalidValue;
+    return dt == DT_F16 ? launch_dt<f16>(tile, gemm, a, s) : launch_dt<bf16>(tile, gemm, a, s);
+}
+
+}  // namespace cw
