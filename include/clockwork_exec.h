@@ -212,6 +212,14 @@ int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
+/* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
+ * The plan compiler takes the tile variant and split-K factor of a convolution from a table
+ * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
+ * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
+ * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
+ * kh, stride, conv_tile (0..9 as above), split_k >= 1}; copied.  Shapes in neither table get
+ * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
+int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
 
 const char *cw_strerror(int32_t status);
 const char *cw_last_error(cw_ctx *ctx);

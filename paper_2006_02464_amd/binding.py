@@ -69,6 +69,7 @@ SIGNATURES = {
     "cw_debug_read_op": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_size_t]),
     "cw_set_debug_keep": (c_int32, [c_void_p, c_int32]),
     "cw_set_plan_override": (c_int32, [c_void_p, c_int32, c_int32]),
+    "cw_set_plan_table": (c_int32, [c_void_p, c_void_p, c_int32]),
     "cw_set_use_graphs": (c_int32, [c_void_p, c_int32]),
     "cw_strerror": (c_char_p, [c_int32]),
     "cw_last_error": (c_char_p, [c_void_p]),
@@ -261,6 +262,12 @@ class Context:
         if isinstance(conv_tile, str):
             conv_tile = CONV_TILES[conv_tile]
         self._check(lib().cw_set_plan_override(self._h, conv_tile, split_k))
+
+    def set_plan_table(self, rows):
+        """rows: iterable of (M, N, K, kh, stride, conv_tile, split_k); empty removes the table."""
+        arr = np.ascontiguousarray(np.array([[CONV_TILES[v] if isinstance(v, str) else v for v in r] for r in rows],
+                                            dtype=np.int32).reshape(-1, 7))
+        self._check(lib().cw_set_plan_table(self._h, _ptr(arr) if len(arr) else None, len(arr)))
 
 
 __all__ = [n for n in dir() if n.startswith("CW_") or n.startswith("cw_")] + [

@@ -452,6 +452,18 @@ int32_t cw_set_plan_override(cw_ctx *c, int32_t conv_tile, int32_t split_k) {
     return CW_OK;
 }
 
+int32_t cw_set_plan_table(cw_ctx *c, const int32_t *rows, int32_t n_rows) {
+    if (!c || n_rows < 0 || (n_rows > 0 && !rows)) return set_err(c, CW_ERR_INVALID, "null table");
+    std::vector<TunedShape> t;
+    for (int32_t i = 0; i < n_rows; ++i) {
+        const int32_t *r = rows + 7 * i;
+        if (r[5] < 0 || r[5] >= (int32_t)N_CONV_TILES || r[6] < 1) return set_err(c, CW_ERR_INVALID, "bad tile or split-K in a table row");
+        t.push_back(TunedShape{r[0], r[1], r[2], r[3], r[4], r[5], r[6]});
+    }
+    c->ov.table.swap(t);
+    return CW_OK;
+}
+
 int32_t cw_model_define(cw_ctx *c, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
                         const int32_t *batch_sizes, int32_t n_batch, int32_t dtype, int32_t *model_id) {
     if (!c || !ops || !batch_sizes || n_batch < 1 || !model_id) return set_err(c, CW_ERR_INVALID, "null or empty argument");

@@ -16,6 +16,7 @@
 // every slice is exactly LOADS instructions per thread, they complete in order, and before
 // slice kt is read each thread waits until at most (slices still in flight behind kt) * LOADS
 // of its loads are outstanding, then the barrier makes every thread's part visible.
+#include <algorithm>
 #include <type_traits>
 
 #include "conv_common.h"
@@ -269,7 +270,9 @@ static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_
     // use (under LOAD's graph recording or the first plain EXEC), never per launch afterwards.
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (attr != hipSuccess) return attr;
-    kern<<<grid, block, lds_bytes, s>>>(a);
+    // a K walk shorter than the ring only ever touches its first stages
+    const size_t used = (size_t)std::min(NS, a.ktiles_per_split) * (BM + BN) * 128;
+    kern<<<grid, block, used, s>>>(a);
     return hipGetLastError();
 }
 

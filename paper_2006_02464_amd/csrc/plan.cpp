@@ -230,9 +230,6 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
 // still gives every CU at least one workgroup; below that, a 64x64 (or narrower) tile with K
 // split over up to 16 workgroups.  Either way a pure function of the GEMM shape.
 // Offline measurements (tune.py): the fastest tile and split-K per GEMM shape seen on an MI355X.
-struct TunedShape {
-    int32_t M, N, K, kh, stride, tile, split_k;
-};
 static const TunedShape kTuned[] = {
 #include "plan_table.inc"
 };
@@ -240,13 +237,17 @@ static const TunedShape kTuned[] = {
 static void pick_conv_tile(int64_t M, int64_t N, int64_t K, int32_t kh, int32_t stride, int64_t ktiles,
                            const PlanOverride &ov, ConvTile *tile, int32_t *split) {
     if (ov.tile < 0 && ov.split_k <= 0) {
+        auto match = [&](const TunedShape &t) {
+            if (t.M != M || t.N != N || t.K != K || t.kh != kh || t.stride != stride || t.tile < 0 || t.tile >= N_CONV_TILES)
+                return false;
+            *tile = (ConvTile)t.tile;
+            *split = (int32_t)std::max<int64_t>(1, std::min<int64_t>(t.split_k, ktiles));
+            return true;
+        };
+        for (const TunedShape &t : ov.table)
+            if (match(t)) return;
         for (const TunedShape &t : kTuned)
-            if (t.M == M && t.N == N && t.K == K && t.kh == kh && t.stride == stride && t.tile >= 0 &&
-                t.tile < N_CONV_TILES) {
-                *tile = (ConvTile)t.tile;
-                *split = (int32_t)std::max<int64_t>(1, std::min<int64_t>(t.split_k, ktiles));
-                return;
-            }
+            if (match(t)) return;
     }
     static const ConvTile order[] = {T128x128, T128x64, T64x64, T32x64, T64x32, T32x32};
     auto blocks = [&](ConvTile t) {

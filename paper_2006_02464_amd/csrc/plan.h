@@ -57,10 +57,16 @@ struct Plan {
     cw_profile profile{};
 };
 
+// Tile and split-K of one convolution GEMM shape (a row of the plan table).
+struct TunedShape {
+    int32_t M, N, K, kh, stride, tile, split_k;
+};
+
 struct PlanOverride {
     int32_t tile = -1;     // ConvTile or -1 = automatic
     int32_t split_k = 0;   // 0 = automatic
     bool keep_all = false; // no workspace reuse (debug read-back)
+    std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 
 struct Model {

@@ -1,63 +1,101 @@
 """Offline tuning of the conv launch plan (a development tool; needs an MI355X).
 
-Times every convolution of a ResNet under every (tile, split-K) override, through
-the public C ABI, and writes csrc/plan_table.inc: for each GEMM shape the fastest
-choice.  The plan compiler looks shapes up in that table and falls back to its
-size heuristic for shapes it does not list.  Nothing is tuned when EXEC runs: the
-table is compiled into the library.
+For every batch size and every convolution GEMM shape of a ResNet this tries each
+(tile, split-K) candidate *in place*: the candidate is installed for that one shape
+with cw_set_plan_table, the model is defined and loaded, and the median on-device
+duration of whole EXECs (the production path: HIP-graph replay, every other layer
+as currently chosen, caches as warm or cold as they really are) decides.  One
+pass of coordinate descent per batch size, starting from the library's current
+choice.  The result is written as csrc/plan_table.inc, which the library compiles
+in.  Nothing is tuned when EXEC runs.
 
-  python -m paper_2006_02464_amd.tune [--depth 50] [--hw 224] [--batches 1,2,4,8,16]
+  python -m paper_2006_02464_amd.tune [--depth 50] [--hw 224] [--batches 1,2,4,8,16] [--out FILE]
 """
 import argparse
 import os
 import sys
+import time
 
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE = os.path.join(HERE, "csrc", "plan_table.inc")
 SPLITS = (1, 2, 4, 8, 16)
+TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x32": (64, 32), "32x64": (32, 64),
+             "32x32": (32, 32), "256x64": (256, 64), "128x128w8": (128, 128)}
+POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 
 
-def sweep(wk, depth, hw, batch, tiles, inner=20):
-    """{(op_index): [(us, tile_name, split_requested, split_effective)]} for one batch size."""
-    from .runner import pinned_like
-    ctx = wk.ctx
-    x = pinned_like(np.zeros((batch, 3, hw, hw), np.float32))
-    blob = None
-    out, shapes = {}, {}
-    for tile in tiles:
-        for split in SPLITS:
-            ctx.set_plan_override(tile, split)
-            mid = ctx.model_define(ctx_ops(ctx, depth, hw), 3, hw, hw, batch_sizes=(batch,))
-            if blob is None:
-                blob = pinned_like(np.zeros(ctx.model_weight_bytes(mid), np.uint8))
-            ctx.load_weights(mid, blob, wk.stream)
-            wk.stream.synchronize()
-            slot = ctx.input(mid, batch, x, wk.stream)
-            plan = ctx.plan(mid, batch)
-            ctx.exec_timed_launches(mid, batch, slot, wk.stream, inner=3)
-            us = ctx.exec_timed_launches(mid, batch, slot, wk.stream, inner=inner)
-            for l, t in zip(plan, us):
-                if l["kind"] != 1 or l["name"].startswith("conv7x7"):  # the first convolution keeps its own kernel
-                    continue
-                out.setdefault(l["op_index"], []).append((float(t), tile, split, l["split_k"]))
-                shapes[l["op_index"]] = l
-            ctx.release(slot)
-            ctx.unload_weights(mid)
-    ctx.set_plan_override(-1, 0)
-    return out, shapes
+def candidates(M, N, K):
+    """(tile, split) pairs worth trying for one GEMM shape."""
+    ktiles = K // 64
+    out = []
+    for tile, (bm, bn) in TILE_DIMS.items():
+        if bn > N or (bm > 64 and bm > M):
+            continue
+        tiles = -(-M // bm) * -(-N // bn)
+        for s in SPLITS:
+            if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20)):
+                continue
+            out.append((tile, s))
+    return out
 
 
-_OPS_CACHE = {}
+def rows(table):
+    return [k + v for k, v in table.items()]
 
 
-def ctx_ops(ctx, depth, hw):
-    if (depth, hw) not in _OPS_CACHE:
-        ctx.set_plan_override(-1, 0)
+def tile_name(block, bm, bn):
+    if (bm, bn) == (128, 128) and block == 512:
+        return "128x128w8"
+    return "%dx%d" % (bm, bn)
+
+
+class Bench:
+    def __init__(self, depth, hw, reps):
+        from .runner import Worker, pinned_like
+        self.hw, self.reps = hw, reps
+        self.wk = Worker(**POOLS)
+        ctx = self.wk.ctx
         mid = ctx.model_define_resnet(depth, hw, hw)
-        _OPS_CACHE[(depth, hw)] = ctx.model_get_ops(mid)
-    return _OPS_CACHE[(depth, hw)]
+        self.ops = ctx.model_get_ops(mid)
+        self.blob = pinned_like(np.zeros(ctx.model_weight_bytes(mid), np.uint8))
+        self.n_models = 1
+
+    def _define(self, batch, table):
+        from .runner import Worker
+        if self.n_models > 400:   # models are never deleted from a context: start a new one now and then
+            self.wk.close()
+            self.wk = Worker(**POOLS)
+            self.n_models = 0
+        ctx = self.wk.ctx
+        ctx.set_plan_table(rows(table))
+        self.n_models += 1
+        return ctx.model_define(self.ops, 3, self.hw, self.hw, batch_sizes=(batch,))
+
+    def plan_choices(self, batch):
+        """{shape key: (tile index, split)} as the library plans this batch size now."""
+        from .binding import CONV_TILES
+        mid = self._define(batch, {})
+        out = {}
+        for l in self.wk.ctx.plan(mid, batch):
+            if l["kind"] != 1 or l["op_index"] == 0:   # the first convolution keeps its own kernel
+                continue
+            o = self.ops[l["op_index"]]
+            key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride
+            out[key] = (CONV_TILES[tile_name(l["block"], l["tile_m"], l["tile_n"])], l["split_k"])
+        return out
+
+    def measure(self, batch, table):
+        """Median on-device EXEC duration (us) with `table` installed."""
+        mid = self._define(batch, table)
+        ctx = self.wk.ctx
+        ctx.load_weights(mid, self.blob, self.wk.stream)
+        self.wk.stream.synchronize()
+        ctx.profile_measure(mid, batch, 8)
+        p = ctx.profile_measure(mid, batch, self.reps)
+        ctx.unload_weights(mid)
+        return p["p50_us"]
 
 
 def main():
@@ -65,35 +103,45 @@ def main():
     ap.add_argument("--depth", type=int, default=50)
     ap.add_argument("--hw", type=int, default=224)
     ap.add_argument("--batches", default="1,2,4,8,16")
+    ap.add_argument("--reps", type=int, default=60)
+    ap.add_argument("--eps", type=float, default=0.2, help="a candidate must win by this many us")
     ap.add_argument("--out", default=TABLE)
     args = ap.parse_args()
     from .binding import CONV_TILES
-    from .runner import Worker
-    wk = Worker(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=256 << 20,
-                load_staging_bytes=128 << 20)
-    tiles = [n for n in CONV_TILES if n not in ("128x64w2", "64x128w2")]
-    table = {}
-    for b in (int(v) for v in args.batches.split(",")):
-        res, shapes = sweep(wk, args.depth, args.hw, b, tiles)
-        total = 0.0
-        for op, cands in res.items():
-            l = shapes[op]
-            o = ctx_ops(wk.ctx, args.depth, args.hw)[op]
-            key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride
-            us, tile, _, split_eff = min(cands)
-            total += us
-            if key not in table or us < table[key][0]:
-                table[key] = (us, tile, split_eff)
-        print("batch %d: sum of best conv launches %.1f us" % (b, total), flush=True)
-    wk.close()
-    lines = ["// Generated by paper_2006_02464_amd/tune.py on an MI355X: fastest (tile, split-K) per GEMM shape.",
-             "// {M, N, K, kh, stride, tile, split_k}   (measured us per launch in the comment)"]
-    for key in sorted(table):
-        us, tile, split = table[key]
-        lines.append("{%d, %d, %d, %d, %d, %d, %d},  // %s, %.1f us" % (key + (CONV_TILES[tile], split, tile, us)))
+    b = Bench(args.depth, args.hw, args.reps)
+    final = {}
+    for batch in (int(v) for v in args.batches.split(",")):
+        t_start = time.time()
+        cur = b.plan_choices(batch)
+        t0 = b.measure(batch, cur)
+        print("batch %d: %d shapes, start %.1f us" % (batch, len(cur), t0), flush=True)
+        for key in sorted(cur, key=lambda k: -k[0] * k[1] * k[2]):
+            best, best_t = cur[key], b.measure(batch, cur)
+            for tile, s in candidates(*key[:3]):
+                cand = (CONV_TILES[tile], s)
+                if cand == cur[key]:
+                    continue
+                t = b.measure(batch, {**cur, key: cand})
+                if t < best_t - args.eps:
+                    best, best_t = cand, t
+            if best != cur[key]:
+                # confirm against a fresh measurement of the incumbent before switching
+                if b.measure(batch, {**cur, key: best}) < b.measure(batch, cur) - args.eps / 2:
+                    cur[key] = best
+            print("  %s -> tile %d split %d   (EXEC %.1f us)" % (key, cur[key][0], cur[key][1], best_t), flush=True)
+        t1 = b.measure(batch, cur)
+        print("batch %d: %.1f -> %.1f us in %.0f s" % (batch, t0, t1, time.time() - t_start), flush=True)
+        final.update(cur)
+    b.wk.close()
+    names = {v: k for k, v in CONV_TILES.items()}
+    lines = ["// Generated by paper_2006_02464_amd/tune.py on an MI355X: per GEMM shape the (tile, split-K) under which",
+             "// whole EXECs of ResNet-%d ran fastest.  {M, N, K, kh, stride, tile, split_k}" % args.depth]
+    for key in sorted(final):
+        tile, split = final[key]
+        lines.append("{%d, %d, %d, %d, %d, %d, %d},  // %s" % (key + (tile, split, names[tile])))
     with open(args.out, "w") as f:
         f.write("\n".join(lines) + "\n")
-    print("wrote %s (%d shapes)" % (args.out, len(table)))
+    print("wrote %s (%d shapes)" % (args.out, len(final)))
 
 
 if __name__ == "__main__":

@@ -138,3 +138,25 @@ def test_device_calls_on_planning_context_fail_loudly(ctx):
         ctx.exec(m, 1, 0)
     ctx.unload_weights(m)          # metadata only: always succeeds
     ctx.unload_weights(m)
+
+
+def test_plan_table_rows_take_precedence(ctx):
+    m0 = ctx.model_define_resnet(50, 224, 224)
+    base = ctx.plan(m0, 16)
+    target = next(l for l in base if l["kind"] == 1 and l["gemm_k"] == 576)      # a 3x3 of stage 1
+    other = "64x32" if (target["tile_m"], target["tile_n"]) != (64, 32) else "32x64"
+    ctx.set_plan_table([(target["gemm_m"], target["gemm_n"], target["gemm_k"], 3, 1, other, 2)])
+    try:
+        m1 = ctx.model_define_resnet(50, 224, 224)
+        plan = ctx.plan(m1, 16)
+        for a, b in zip(base, plan):
+            if a["kind"] == 1 and (a["gemm_m"], a["gemm_n"], a["gemm_k"]) == (target["gemm_m"], target["gemm_n"], 576):
+                assert "%dx%d" % (b["tile_m"], b["tile_n"]) == other and b["split_k"] == 2
+            else:
+                assert (a["tile_m"], a["tile_n"], a["split_k"]) == (b["tile_m"], b["tile_n"], b["split_k"])
+        with pytest.raises(cw.CwError):
+            ctx.set_plan_table([(1, 1, 1, 1, 1, 99, 1)])
+    finally:
+        ctx.set_plan_table([])
+    m2 = ctx.model_define_resnet(50, 224, 224)
+    assert ctx.plan(m2, 16) == base
