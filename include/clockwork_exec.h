@@ -178,7 +178,7 @@ typedef struct {
     int32_t op_index;      /* which op of the model this launch belongs to */
     int32_t kind;          /* internal kernel family id */
     int32_t grid_x, grid_y, grid_z, block;
-    int32_t tile_m, tile_n, split_k;
+    int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
     int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
     int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
     int64_t flops;         /* 2 * MACs */
@@ -206,9 +206,10 @@ int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
  * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
  * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
 int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..9 =
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..14 =
  * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
- * 256x64, 128x128 on 8 waves; pixels x channels per workgroup; -1 = the plan compiler's own choice)
+ * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
+ * instead of 64 (used where cin % 128 == 0, else their 64 form); pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
@@ -217,7 +218,7 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
  * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
  * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
- * kh, stride, conv_tile (0..9 as above), split_k >= 1}; copied.  Shapes in neither table get
+ * kh, stride, conv_tile (0..14 as above), split_k >= 1}; copied.  Shapes in neither table get
  * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
 int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
 

@@ -18,7 +18,8 @@ CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX = 0, 1, 2, 3,
 CW_DTYPE_FP16, CW_DTYPE_BF16 = 0, 1
 DTYPES = {"fp16": CW_DTYPE_FP16, "bf16": CW_DTYPE_BF16}
 CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32x32": 5,
-              "128x64w2": 6, "64x128w2": 7, "256x64": 8, "128x128w8": 9}
+              "128x64w2": 6, "64x128w2": 7, "256x64": 8, "128x128w8": 9,
+              "128x64k128": 10, "64x64k128": 11, "64x32k128": 12, "32x64k128": 13, "32x32k128": 14}
 
 
 class cw_op(Structure):
@@ -39,7 +40,7 @@ class cw_profile(Structure):
 class cw_launch_info(Structure):
     _fields_ = [("op_index", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
                 ("grid_z", c_int32), ("block", c_int32), ("tile_m", c_int32), ("tile_n", c_int32),
-                ("split_k", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
+                ("tile_k", c_int32), ("split_k", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
                 ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
 
 

@@ -81,19 +81,23 @@ struct SoftmaxArgs {
 };
 
 // Tile shapes the conv kernel is instantiated for (fixed at plan time per layer).
-// (pixels x channels per workgroup; "wN" = N waves when not 4, each wave then owning 64x64)
+// (pixels x channels per workgroup; "wN" = N waves when not 4, each wave then owning 64x64;
+// "k128" = K slices of 128 instead of 64, for Cin % 128 == 0)
 enum ConvTile : int32_t {
-    T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8, N_CONV_TILES
+    T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8,
+    T128x64k128, T64x64k128, T64x32k128, T32x64k128, T32x32k128, N_CONV_TILES
 };
 struct TileDim {
-    int bm, bn, threads;
+    int bm, bn, threads, bk;
 };
 TileDim conv_tile_dim(ConvTile t);
+// The same tile with K slices of 64 (for shapes a k128 tile cannot take).
+ConvTile conv_tile_k64(ConvTile t);
 
 // Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);
 // The direct-to-LDS kernel for Cin % 64 == 0 (called by launch_conv after its checks).
-hipError_t launch_conv_dlds(DType dt, ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s);
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
@@ -109,8 +113,9 @@ hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B,
                                    int W, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 
-// K-slice width the conv kernel uses for a shape (64, or 32 for the stem / Cin % 64 != 0).
-int conv_bk(const ConvArgs &a, bool stem);
+// K-slice width the conv kernel uses for a shape under a tile: the tile's (128 or 64) when Cin
+// is a multiple of it, else 64, else 32 (the stem and Cin % 64 != 0).
+int conv_bk(const ConvArgs &a, bool stem, ConvTile tile);
 // Bytes at the start of the workspace reserved for split-K arrival counters (one int per tile).
 constexpr size_t kCounterBytes = 256 * 1024;
 // Grid and block of a conv launch (pure function of tile and shape).

@@ -63,11 +63,15 @@ struct Mfma<bf16> {
 // has 16 consecutive rows at one chunk index in such a group.  With 128-byte rows two rows
 // share 256 bytes, so the chunk index is XORed with (row/2)%8: rows of equal parity then land
 // on 8 different chunk positions and the two parities on the two halves.  With 64-byte rows
-// four rows share 256 bytes and the key is (row/4)%4.
+// four rows share 256 bytes and the key is (row/4)%4; with 256-byte rows every row covers all
+// banks and the key is row%16.
+template <int BK>
+static __device__ __forceinline__ int swz_key(int row) {
+    return BK == 128 ? (row & 15) : BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
 template <int BK>
 static __device__ __forceinline__ int swz(int row, int c) {
-    if (BK == 64) return row * 64 + ((c ^ ((row >> 1) & 7)) << 3);
-    return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
+    return row * BK + ((c ^ swz_key<BK>(row)) << 3);
 }
 
 // ---- epilogue ------------------------------------------------------------------------------

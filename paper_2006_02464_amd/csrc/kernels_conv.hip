@@ -289,20 +289,39 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 
 TileDim conv_tile_dim(ConvTile t) {
     switch (t) {
-        case T128x128: return {128, 128, 256};
-        case T128x64: return {128, 64, 256};
-        case T64x64: return {64, 64, 256};
-        case T64x32: return {64, 32, 128};
-        case T32x64: return {32, 64, 128};
-        case T128x64w2: return {128, 64, 128};
-        case T64x128w2: return {64, 128, 128};
-        case T256x64: return {256, 64, 256};
-        case T128x128w8: return {128, 128, 512};
-        default: return {32, 32, 64};
+        case T128x128: return {128, 128, 256, 64};
+        case T128x64: return {128, 64, 256, 64};
+        case T64x64: return {64, 64, 256, 64};
+        case T64x32: return {64, 32, 128, 64};
+        case T32x64: return {32, 64, 128, 64};
+        case T128x64w2: return {128, 64, 128, 64};
+        case T64x128w2: return {64, 128, 128, 64};
+        case T256x64: return {256, 64, 256, 64};
+        case T128x128w8: return {128, 128, 512, 64};
+        case T128x64k128: return {128, 64, 256, 128};
+        case T64x64k128: return {64, 64, 256, 128};
+        case T64x32k128: return {64, 32, 128, 128};
+        case T32x64k128: return {32, 64, 128, 128};
+        case T32x32k128: return {32, 32, 64, 128};
+        default: return {32, 32, 64, 64};
     }
 }
 
-int conv_bk(const ConvArgs &a, bool stem) { return (!stem && a.Cin % 64 == 0) ? 64 : 32; }
+ConvTile conv_tile_k64(ConvTile t) {
+    switch (t) {
+        case T128x64k128: return T128x64;
+        case T64x64k128: return T64x64;
+        case T64x32k128: return T64x32;
+        case T32x64k128: return T32x64;
+        case T32x32k128: return T32x32;
+        default: return t;
+    }
+}
+
+int conv_bk(const ConvArgs &a, bool stem, ConvTile tile) {
+    if (stem || a.Cin % 64 != 0) return 32;
+    return (conv_tile_dim(tile).bk == 128 && a.Cin % 128 == 0) ? 128 : 64;
+}
 
 static bool conv_is_gemm(const ConvArgs &a, bool stem) {
     return !stem && a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0 && a.Cin % 64 == 0;
@@ -319,6 +338,7 @@ template <typename T, int BK, int MODE, bool SPLITK>
 static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s) {
     dim3 grid;
     int block;
+    tile = conv_tile_k64(tile);
     conv_grid(tile, a, &grid, &block);
     // K slices in flight in registers: 2 for the tiles with 64x64 per wave (register budget), else 3
     switch (tile) {
@@ -346,7 +366,7 @@ static hipError_t launch_conv_dt(ConvTile tile, bool stem, const ConvArgs &a, hi
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s) {
     // Shapes the kernel's indexing relies on; the plan compiler guarantees them, checked again
     // here so that a bad launch is an error instead of an out-of-bounds access.
-    const int bk = conv_bk(a, stem);
+    const int bk = conv_bk(a, stem, tile);
     if (a.K % bk != 0 || a.M <= 0 || a.Cout <= 0 || a.Cout % 32 != 0 || a.split_k < 1 || a.ktiles_per_split < 1)
         return hipErrorInvalidValue;
     if (stem ? (a.Cin != 4 || a.kwp != 8 || a.K != a.kh * 32) : (a.Cin % 32 != 0 || a.kwp != a.kw || a.K != a.kh * a.kw * a.Cin))
@@ -361,7 +381,7 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
         return hipErrorInvalidValue;
     // K slices of 64 go global -> LDS directly (kernels_conv_dlds.hip); the stem and Cin % 64 != 0
     // keep the register-staged kernel of this file.
-    if (!stem && a.Cin % 64 == 0) return launch_conv_dlds(dt, tile, conv_is_gemm(a, stem), a, s);
+    if (!stem && a.Cin % 64 == 0) return launch_conv_dlds(dt, tile, bk, conv_is_gemm(a, stem), a, s);
     if (a.split_k > 1) return dt == DT_F16 ? launch_conv_dt<f16, true>(tile, stem, a, s) : launch_conv_dt<bf16, true>(tile, stem, a, s);
     return dt == DT_F16 ? launch_conv_dt<f16, false>(tile, stem, a, s) : launch_conv_dt<bf16, false>(tile, stem, a, s);
 }

@@ -1,14 +1,16 @@
 // Implicit-GEMM convolution on gfx950 MFMA whose K slices travel global -> LDS directly.
 //
 // Same GEMM view, weight layout, LDS swizzle, MFMA roles and epilogue as the register-staged
-// kernel (kernels_conv.hip), for Cin % 64 == 0 (K slices of 64).  What differs is the pipeline:
+// kernel (kernels_conv.hip), for Cin % 64 == 0 (K slices of 64, or of 128 when Cin % 128 == 0
+// and the tile says so).  What differs is the pipeline:
 // a K slice is fetched by buffer loads that write LDS themselves (buffer_load_dwordx4 ... lds),
 // so no registers hold data in flight, no wave spends issue slots on LDS writes, and the LDS
 // is a ring of NS stages: while the MFMAs consume slice kt out of stage kt % NS, the loads of
 // slices kt+1 .. kt+NS-1 are in flight into the other stages.  One barrier per slice.
 //
 // Such a load writes the 64 lanes' 16-byte pieces to 1 KiB of consecutive LDS bytes starting
-// at the address in M0, i.e. (for 128-byte rows) lane l lands in row l/8 at chunk position l%8.
+// at the address in M0, i.e. (for 128-byte rows) lane l lands in row l/8 at chunk position l%8
+// (row l/16, position l%16 for 256-byte rows).
 // The XOR swizzle that the MFMA operand reads need is therefore applied on the global side:
 // the lane that owns LDS position (row, pc) fetches the row's logical chunk pc ^ key(row).
 // Padded taps and rows beyond M or Cout use an out-of-range offset, for which the load writes
@@ -46,9 +48,9 @@ static __device__ __forceinline__ u32x4 make_desc(const void *p, unsigned bytes)
 
 extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int NS, int MODE, bool SPLITK>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const ConvArgs a) {
-    constexpr int BK = 64;
+    static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
     constexpr int NT = 64 * WARPS_M * WARPS_N;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -96,16 +98,19 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     const u32x4 dw = make_desc(a.w, (unsigned)a.Cout * a.K * 2u);
 
     // This thread's pieces of a slice.  Piece j is LDS position cid = tid + j*NT of the operand's
-    // [rows][8 chunks] stage: row cid/8, chunk position cid%8, holding logical chunk
-    // (cid%8) ^ key(row).  Per piece, fixed for the whole K walk: the byte offset of that chunk
+    // [rows][CPR chunks] stage: row cid/CPR, chunk position cid%CPR, holding logical chunk
+    // (cid%CPR) ^ key(row).  Per piece, fixed for the whole K walk: the byte offset of that chunk
     // at the filter's centre pixel, and which taps fall inside the image (bit r*kw+s; for the
     // 1x1 stride-1 case bit 0 = the pixel exists).
     unsigned x_voff[X_PER], x_mask[X_PER];
+    unsigned row_units = 0;  // bit r*kw for every filter row r
+    if (MODE == MODE_CONV)
+        for (int r = 0; r < a.kh; ++r) row_units |= 1u << (r * a.kw);
 #pragma unroll
     for (int j = 0; j < X_PER; ++j) {
         const int cid = tid + j * NT;
         const int row = cid / CPR;
-        const int c = (cid % CPR) ^ ((row >> 1) & 7);
+        const int c = (cid % CPR) ^ swz_key<BK>(row);
         const unsigned m = m0 + row;
         unsigned mask = 0, voff = 0;
         if (MODE == MODE_GEMM) {
@@ -120,8 +125,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u + c * 16u;
             const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
             const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+            // in-range columns s_lo..s_hi-1 replicated into every in-range filter row r_lo..r_hi-1:
+            // a multiplication by the rows' unit bits (no carries: cols < 2^kw)
             const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
-            for (int r = r_lo; r < r_hi; ++r) mask |= cols << (r * a.kw);
+            const unsigned rows = row_units & (unsigned)((1ull << (r_hi * a.kw)) - 1ull) & ~((1u << (r_lo * a.kw)) - 1u);
+            mask = cols * rows;
         }
         x_voff[j] = voff;
         x_mask[j] = mask;
@@ -131,7 +139,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     for (int j = 0; j < W_PER; ++j) {
         const int cid = tid + j * NT;
         const int row = cid / CPR;
-        const int c = (cid % CPR) ^ ((row >> 1) & 7);
+        const int c = (cid % CPR) ^ swz_key<BK>(row);
         const int n = n0 + row;
         w_off[j] = n < a.Cout ? ((unsigned)n * a.K + c * 8) * 2u : kOob;
     }
@@ -174,12 +182,16 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // MFMAs of one K slice; operand fragments of 16-k step kk+1 are fetched from LDS while the
-    // MFMAs of step kk run.
+    // MFMAs of one K slice.  Operand fragments are fetched from LDS DEPTH-1 16-k steps ahead of
+    // the MFMAs that use them.  A wave tile of 64x64 has 4 MFMAs per step, enough to cover the
+    // LDS latency with one step of lookahead; the smaller wave tiles have 1 or 2, less than that
+    // latency, and look 3 steps ahead.
     auto compute = [&](int stage) {
         const T *sX = lds + stage * STAGE;
         const T *sW = sX + BM * BK;
-        v8 fx[2][TM], fw[2][TN];
+        constexpr int KK = BK / 16;
+        constexpr int DEPTH = TM * TN >= 4 ? 2 : 4;  // fragment sets held
+        v8 fx[DEPTH][TM], fw[DEPTH][TN];
         auto fetch = [&](int kk, v8(&qx)[TM], v8(&qw)[TN]) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -188,14 +200,15 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             for (int j = 0; j < TN; ++j)
                 qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
         };
-        fetch(0, fx[0], fw[0]);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) fetch(kk + 1, fx[(kk + 1) & 1], fw[(kk + 1) & 1]);
+        for (int kk = 0; kk < DEPTH - 1; ++kk) fetch(kk, fx[kk], fw[kk]);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk + DEPTH - 1 < KK) fetch(kk + DEPTH - 1, fx[(kk + DEPTH - 1) % DEPTH], fw[(kk + DEPTH - 1) % DEPTH]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk & 1][j], fx[kk & 1][i], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk % DEPTH][j], fx[kk % DEPTH][i], acc[i][j]);
         }
     };
 
@@ -228,13 +241,16 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     }
     // Tail: the last `ahead` slices, nothing left to load; with r slices still behind the one
     // about to be read, r*LOADS loads may stay outstanding.  Without split-K the operands of the
-    // epilogue are requested before the last slice's MFMAs.
+    // epilogue are requested before the last slice's MFMAs (measured: requesting them at the very
+    // start instead delays the first slice by as much as it saves at the end).
     auto tail = [&](auto behind) {
         constexpr int u = decltype(behind)::value;  // slices still in flight behind this one
         if (u < kt1 - kt) {                         // uniform
             wait_loads_and_barrier<u * LOADS>();
+            CW_STAMP(trace_slot++);
             if (!SPLITK && u == 0) epilogue_load<TM, TN>(eo, a, pos);
             compute(cur);
+            CW_STAMP(trace_slot++);
             cur = cur + 1 == NS ? 0 : cur + 1;
             ++kt;
         }
@@ -242,6 +258,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     if constexpr (NS >= 4) tail(std::integral_constant<int, 2>{});
     if constexpr (NS >= 3) tail(std::integral_constant<int, 1>{});
     tail(std::integral_constant<int, 0>{});
+
     if (!SPLITK && nsteps <= 0) epilogue_load<TM, TN>(eo, a, pos);
 
     CW_STAMP_END(60);
@@ -254,59 +271,65 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     CW_STAMP_END(62);
 }
 
-// LDS stages per tile: as many as fit two workgroups per CU (160 KiB) for the small tiles, a
-// deeper ring for the large ones.
-template <int BM, int BN>
+// LDS stages per tile: 4 where that still lets two workgroups share a CU's 160 KiB, else 3.
+template <int BM, int BN, int BK>
 struct RingDepth {
-    static constexpr int value = (BM + BN) * 128 * 4 <= 80 * 1024 ? 4 : 3;
+    static constexpr int value = (BM + BN) * BK * 2 * 4 <= 80 * 1024 ? 4 : 3;
 };
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int MODE, bool SPLITK>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK>
 static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_t s) {
-    constexpr int NS = RingDepth<BM, BN>::value;
-    constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * 128;
-    auto kern = conv_dlds_kernel<T, BM, BN, WARPS_M, WARPS_N, NS, MODE, SPLITK>;
+    constexpr int NS = RingDepth<BM, BN, BK>::value;
+    constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
+    static_assert(NS * stage_bytes <= 160 * 1024, "ring does not fit the LDS");
+    auto kern = conv_dlds_kernel<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK>;
     // More than 64 KiB of LDS per workgroup has to be requested once per kernel; done on first
     // use (under LOAD's graph recording or the first plain EXEC), never per launch afterwards.
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(NS * stage_bytes));
     if (attr != hipSuccess) return attr;
     // a K walk shorter than the ring only ever touches its first stages
-    const size_t used = (size_t)std::min(NS, a.ktiles_per_split) * (BM + BN) * 128;
+    const size_t used = (size_t)std::min(NS, a.ktiles_per_split) * stage_bytes;
     kern<<<grid, block, used, s>>>(a);
     return hipGetLastError();
 }
 
 template <typename T, int MODE, bool SPLITK>
-static hipError_t launch_tile(ConvTile tile, const ConvArgs &a, hipStream_t s) {
+static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStream_t s) {
+    if (bk != 128) tile = conv_tile_k64(tile);
     dim3 grid;
     int block;
     conv_grid(tile, a, &grid, &block);
     switch (tile) {
-        case T128x128: return launch_one<T, 128, 128, 2, 2, MODE, SPLITK>(grid, block, a, s);
-        case T128x64: return launch_one<T, 128, 64, 2, 2, MODE, SPLITK>(grid, block, a, s);
-        case T64x64: return launch_one<T, 64, 64, 2, 2, MODE, SPLITK>(grid, block, a, s);
-        case T64x32: return launch_one<T, 64, 32, 2, 1, MODE, SPLITK>(grid, block, a, s);
-        case T32x64: return launch_one<T, 32, 64, 1, 2, MODE, SPLITK>(grid, block, a, s);
-        case T32x32: return launch_one<T, 32, 32, 1, 1, MODE, SPLITK>(grid, block, a, s);
-        case T128x64w2: return launch_one<T, 128, 64, 2, 1, MODE, SPLITK>(grid, block, a, s);
-        case T64x128w2: return launch_one<T, 64, 128, 1, 2, MODE, SPLITK>(grid, block, a, s);
-        case T256x64: return launch_one<T, 256, 64, 4, 1, MODE, SPLITK>(grid, block, a, s);
-        case T128x128w8: return launch_one<T, 128, 128, 2, 4, MODE, SPLITK>(grid, block, a, s);
+        case T128x128: return launch_one<T, 128, 128, 2, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T128x64: return launch_one<T, 128, 64, 2, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T64x64: return launch_one<T, 64, 64, 2, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T64x32: return launch_one<T, 64, 32, 2, 1, 64, MODE, SPLITK>(grid, block, a, s);
+        case T32x64: return launch_one<T, 32, 64, 1, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T32x32: return launch_one<T, 32, 32, 1, 1, 64, MODE, SPLITK>(grid, block, a, s);
+        case T128x64w2: return launch_one<T, 128, 64, 2, 1, 64, MODE, SPLITK>(grid, block, a, s);
+        case T64x128w2: return launch_one<T, 64, 128, 1, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T256x64: return launch_one<T, 256, 64, 4, 1, 64, MODE, SPLITK>(grid, block, a, s);
+        case T128x128w8: return launch_one<T, 128, 128, 2, 4, 64, MODE, SPLITK>(grid, block, a, s);
+        case T128x64k128: return launch_one<T, 128, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
+        case T64x64k128: return launch_one<T, 64, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
+        case T64x32k128: return launch_one<T, 64, 32, 2, 1, 128, MODE, SPLITK>(grid, block, a, s);
+        case T32x64k128: return launch_one<T, 32, 64, 1, 2, 128, MODE, SPLITK>(grid, block, a, s);
+        case T32x32k128: return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK>(grid, block, a, s);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <typename T>
-static hipError_t launch_dt(ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s) {
-    if (a.split_k > 1) return gemm ? launch_tile<T, MODE_GEMM, true>(tile, a, s) : launch_tile<T, MODE_CONV, true>(tile, a, s);
-    return gemm ? launch_tile<T, MODE_GEMM, false>(tile, a, s) : launch_tile<T, MODE_CONV, false>(tile, a, s);
+static hipError_t launch_dt(ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s) {
+    if (a.split_k > 1) return gemm ? launch_tile<T, MODE_GEMM, true>(tile, bk, a, s) : launch_tile<T, MODE_CONV, true>(tile, bk, a, s);
+    return gemm ? launch_tile<T, MODE_GEMM, false>(tile, bk, a, s) : launch_tile<T, MODE_CONV, false>(tile, bk, a, s);
 }
 
 // Called by launch_conv (which has validated the shapes) for every convolution with
-// Cin % 64 == 0 other than the stem.
-hipError_t launch_conv_dlds(DType dt, ConvTile tile, bool gemm, const ConvArgs &a, hipStream_t s) {
-    if (a.Cin % 64 != 0 || a.K != a.kh * a.kw * a.Cin) return hipErrorInvalidValue;
-    return dt == DT_F16 ? launch_dt<f16>(tile, gemm, a, s) : launch_dt<bf16>(tile, gemm, a, s);
+// Cin % 64 == 0 other than the stem; bk = conv_bk() of the shape under this tile.
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s) {
+    if ((bk != 64 && bk != 128) || a.Cin % bk != 0 || a.K != a.kh * a.kw * a.Cin) return hipErrorInvalidValue;
+    return dt == DT_F16 ? launch_dt<f16>(tile, bk, gemm, a, s) : launch_dt<bf16>(tile, bk, gemm, a, s);
 }
 
 }  // namespace cw

@@ -349,8 +349,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 a.relu = o.relu;
                 a.wo_div = make_fast_div((uint32_t)os.w);
                 a.ho_div = make_fast_div((uint32_t)os.h);
-                const int ktiles = a.K / conv_bk(a, l.stem);
-                pick_conv_tile(a.M, a.Cout, (int64_t)o.kh * o.kw * o.cin, o.kh, o.stride, ktiles, ov, &l.tile, &a.split_k);
+                pick_conv_tile(a.M, a.Cout, (int64_t)o.kh * o.kw * o.cin, o.kh, o.stride, a.K / conv_bk(a, l.stem, T64x64), ov,
+                               &l.tile, &a.split_k);
+                if (conv_bk(a, l.stem, l.tile) != conv_tile_dim(l.tile).bk) l.tile = conv_tile_k64(l.tile);  // Cin % 128 != 0
+                const int ktiles = a.K / conv_bk(a, l.stem, l.tile);
+                a.split_k = std::max(1, std::min(a.split_k, ktiles));
                 {
                     const TileDim tdc = conv_tile_dim(l.tile);
                     const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);
@@ -372,7 +375,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = real_k;
                 l.info.flops = 2 * (int64_t)a.M * a.Cout * real_k;
                 const TileDim td = conv_tile_dim(l.tile);
-                l.info.tile_m = td.bm; l.info.tile_n = td.bn; l.info.split_k = a.split_k;
+                l.info.tile_m = td.bm; l.info.tile_n = td.bn; l.info.tile_k = conv_bk(a, l.stem, l.tile); l.info.split_k = a.split_k;
                 if (a.split_k > 1) {
                     partial_bytes = (size_t)a.split_k * a.M * a.Cout * 4;
                     partial_off = ws_alloc(partial_bytes);

@@ -22,17 +22,22 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE = os.path.join(HERE, "csrc", "plan_table.inc")
 SPLITS = (1, 2, 4, 8, 16)
 TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x32": (64, 32), "32x64": (32, 64),
-             "32x32": (32, 32), "256x64": (256, 64), "128x128w8": (128, 128)}
+             "32x32": (32, 32), "256x64": (256, 64), "128x128w8": (128, 128),
+             "128x64k128": (128, 64), "64x64k128": (64, 64), "64x32k128": (64, 32), "32x64k128": (32, 64),
+             "32x32k128": (32, 32)}
 POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 
 
-def candidates(M, N, K):
+def candidates(M, N, K, kh):
     """(tile, split) pairs worth trying for one GEMM shape."""
-    ktiles = K // 64
+    cin = K // (kh * kh)
     out = []
     for tile, (bm, bn) in TILE_DIMS.items():
         if bn > N or (bm > 64 and bm > M):
             continue
+        if tile.endswith("k128") and cin % 128 != 0:
+            continue
+        ktiles = K // (128 if tile.endswith("k128") else 64)
         tiles = -(-M // bm) * -(-N // bn)
         for s in SPLITS:
             if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20)):
@@ -45,10 +50,10 @@ def rows(table):
     return [k + v for k, v in table.items()]
 
 
-def tile_name(block, bm, bn):
+def tile_name(block, bm, bn, bk):
     if (bm, bn) == (128, 128) and block == 512:
         return "128x128w8"
-    return "%dx%d" % (bm, bn)
+    return "%dx%d%s" % (bm, bn, "k128" if bk == 128 else "")
 
 
 class Bench:
@@ -83,7 +88,7 @@ class Bench:
                 continue
             o = self.ops[l["op_index"]]
             key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride
-            out[key] = (CONV_TILES[tile_name(l["block"], l["tile_m"], l["tile_n"])], l["split_k"])
+            out[key] = (CONV_TILES[tile_name(l["block"], l["tile_m"], l["tile_n"], l["tile_k"])], l["split_k"])
         return out
 
     def measure(self, batch, table):
@@ -117,7 +122,7 @@ def main():
         print("batch %d: %d shapes, start %.1f us" % (batch, len(cur), t0), flush=True)
         for key in sorted(cur, key=lambda k: -k[0] * k[1] * k[2]):
             best, best_t = cur[key], b.measure(batch, cur)
-            for tile, s in candidates(*key[:3]):
+            for tile, s in candidates(*key[:4]):
                 cand = (CONV_TILES[tile], s)
                 if cand == cur[key]:
                     continue

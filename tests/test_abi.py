@@ -86,10 +86,16 @@ def test_plan_override_reaches_every_tile(ctx):
     for name, idx in cw.CONV_TILES.items():
         ctx.set_plan_override(idx, 2)
         m = ctx.model_define_resnet(18, 64, 64)
-        bm, bn = (int(v) for v in name.replace("w2", "").replace("w8", "").split("x"))
+        bm, bn = (int(v) for v in name.replace("w2", "").replace("w8", "").replace("k128", "").split("x"))
         convs = [l for l in ctx.plan(m, 4) if l["name"].startswith(("conv", "stem"))]
         assert convs and all((l["tile_m"], l["tile_n"]) == (bm, bn) for l in convs)
-        assert all(l["split_k"] == 2 or l["gemm_k"] <= 64 for l in convs)   # one K slice cannot be split
+        ops = ctx.model_get_ops(m)
+        for l in convs:
+            cin = ops[l["op_index"]][1]
+            # K slices: 32 for the first convolution, 128 only where the tile asks and cin allows
+            want = 32 if cin < 32 else (128 if name.endswith("k128") and cin % 128 == 0 else 64)
+            assert l["tile_k"] == want
+            assert l["split_k"] == 2 or l["gemm_k"] <= l["tile_k"] or cin < 32   # one K slice cannot be split
     ctx.set_plan_override(-1, 0)
 
 
