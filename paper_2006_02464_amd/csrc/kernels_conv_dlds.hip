@@ -156,22 +156,34 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         fs = rs - fr * a.kw;
     }
 
-    // Issues the LOADS loads of slice kt (kt < kt1) into ring stage `stage`.
-    auto issue = [&](int kt, int stage) {
-        const unsigned soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
-        const unsigned tbit = MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs));
-        const unsigned dst = lds_base + (unsigned)stage * STAGE_BYTES + (unsigned)wave * 1024u;
-#pragma unroll
-        for (int j = 0; j < X_PER; ++j)
-            load_to_lds(dx, (x_mask[j] & tbit) ? x_voff[j] : kOob, soff, dst + j * (NT * 16));
-        const unsigned kb = (unsigned)kt * (BK * 2u);
-#pragma unroll
-        for (int j = 0; j < W_PER; ++j) load_to_lds(dw, w_off[j], kb, dst + BM * BK * 2 + j * (NT * 16));
+    // The loads of the next slice to fetch, in pieces: piece idx < X_PER is an activation load,
+    // the others are weight loads.  begin() fixes the slice's uniform operands, piece() issues
+    // one load, end() advances (r, s, c0).
+    unsigned is_soff = 0, is_tbit = 0, is_dst = 0, is_kb = 0;
+    auto issue_begin = [&](int kt, int stage) {
+        is_soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+        is_tbit = MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs));
+        is_dst = lds_base + (unsigned)stage * STAGE_BYTES + (unsigned)wave * 1024u;
+        is_kb = (unsigned)kt * (BK * 2u);
+    };
+    auto issue_piece = [&](int idx) {  // idx is a compile-time constant after unrolling
+        if (idx < X_PER)
+            load_to_lds(dx, (x_mask[idx] & is_tbit) ? x_voff[idx] : kOob, is_soff, is_dst + idx * (NT * 16));
+        else
+            load_to_lds(dw, w_off[idx - X_PER], is_kb, is_dst + BM * BK * 2 + (idx - X_PER) * (NT * 16));
+    };
+    auto issue_end = [&]() {
         fc0 += BK;
         if (MODE != MODE_GEMM && fc0 == a.Cin) {
             fc0 = 0;
             if (++fs == a.kw) { fs = 0; ++fr; }
         }
+    };
+    auto issue = [&](int kt, int stage) {
+        issue_begin(kt, stage);
+#pragma unroll
+        for (int idx = 0; idx < LOADS; ++idx) issue_piece(idx);
+        issue_end();
     };
 
     f32x16 acc[TM][TN];  // [pixel tile][channel tile]; MFMA rows = channels, columns = pixels
@@ -186,7 +198,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     // the MFMAs that use them.  A wave tile of 64x64 has 4 MFMAs per step, enough to cover the
     // LDS latency with one step of lookahead; the smaller wave tiles have 1 or 2, less than that
     // latency, and look 3 steps ahead.
-    auto compute = [&](int stage) {
+    // with_loads: the loads of the slice announced by issue_begin() are issued a few at a time
+    // behind each 16-k step's MFMAs.  A load instruction occupies the CU's address path for 16
+    // clocks per wave; issued in one burst ahead of the MFMAs, the four waves' bursts would hold
+    // every wave back for about as long as the MFMAs themselves take.
+    auto compute = [&](int stage, auto with_loads) {
         const T *sX = lds + stage * STAGE;
         const T *sW = sX + BM * BK;
         constexpr int KK = BK / 16;
@@ -209,6 +225,10 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk % DEPTH][j], fx[kk % DEPTH][i], acc[i][j]);
+            if (decltype(with_loads)::value) {
+#pragma unroll
+                for (int idx = kk * LOADS / KK; idx < (kk + 1) * LOADS / KK; ++idx) issue_piece(idx);
+            }
         }
     };
 
@@ -234,8 +254,9 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     for (; kt + (NS - 1) < kt1; ++kt) {
         wait_loads_and_barrier<(NS - 2) * LOADS>();
         CW_STAMP(trace_slot++);
-        issue(kt + NS - 1, cur == 0 ? NS - 1 : cur - 1);
-        compute(cur);
+        issue_begin(kt + NS - 1, cur == 0 ? NS - 1 : cur - 1);
+        compute(cur, std::true_type{});
+        issue_end();
         CW_STAMP(trace_slot++);
         cur = cur + 1 == NS ? 0 : cur + 1;
     }
@@ -249,7 +270,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             wait_loads_and_barrier<u * LOADS>();
             CW_STAMP(trace_slot++);
             if (!SPLITK && u == 0) epilogue_load<TM, TN>(eo, a, pos);
-            compute(cur);
+            compute(cur, std::false_type{});
             CW_STAMP(trace_slot++);
             cur = cur + 1 == NS ? 0 : cur + 1;
             ++kt;
