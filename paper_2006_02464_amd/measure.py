@@ -1,0 +1,215 @@
+"""Measurements beyond bench.py's headline line, one per workload configuration (needs an MI355X).
+
+  python -m paper_2006_02464_amd.measure --config 3   EXEC latency with and without a concurrent LOAD
+  python -m paper_2006_02464_amd.measure --config 4   ResNet-152, bf16, batch 16: throughput and latency
+  python -m paper_2006_02464_amd.measure --config 5   64 resident ResNet-50s, Poisson arrivals, mixed batch sizes
+
+Each prints one JSON object.  All inputs are synthetic (seeded, workload/gen.py); EXEC time does not
+depend on the values.  Durations are on-device (the event pair around every EXEC); the host thread
+issues INPUT / EXEC / OUTPUT as the worker of the paper does: copies on one stream, EXEC on another,
+one EXEC at a time.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+
+def pct(v, q):
+    """Nearest-rank percentile of a sample."""
+    s = np.sort(np.asarray(v, dtype=np.float64))
+    k = min(len(s), max(1, int(np.ceil(q * len(s)))))
+    return float(s[k - 1])
+
+
+def summary(v):
+    return {"n": len(v), "p50_us": round(pct(v, 0.5), 2), "p99_us": round(pct(v, 0.99), 2),
+            "p999_us": round(pct(v, 0.999), 2), "max_us": round(float(np.max(v)), 2),
+            "p999_over_p50": round(pct(v, 0.999) / pct(v, 0.5), 4)}
+
+
+def resnet_blob(ctx, mid, seed, dtype):
+    from workload import gen
+    ops = ctx.model_get_ops(mid)
+    shapes = [(o[2], o[1], o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
+    w, b = gen.model_tensors(shapes, seed, dtype)
+    return gen.pack_blob(w, b, dtype)
+
+
+def exec_rounds(ctx, mid, batch, slots, stream, rounds, between=None):
+    """`rounds` x len(slots) back-to-back EXECs; returns every on-device duration in us."""
+    out = []
+    for r in range(rounds):
+        for s in slots:
+            ctx.exec(mid, batch, s, stream)
+        if between is not None:
+            between(r)
+        out.extend(ctx.exec_duration_ns(s) / 1e3 for s in slots)   # blocks until each has finished
+    return out
+
+
+def config3(args, log):
+    import torch
+    from .runner import Worker, pinned_like
+    from workload import gen
+    B, n_slots = 8, 20
+    wk = Worker(workspace_bytes=512 << 20, io_bytes=512 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20)
+    ctx, ex = wk.ctx, wk.stream
+    ld = torch.cuda.Stream()
+    m1 = ctx.model_define_resnet(50, 224, 224, "fp16")
+    m2 = ctx.model_define(ctx.model_get_ops(m1), 3, 224, 224, batch_sizes=(B,))
+    blob1 = pinned_like(resnet_blob(ctx, m1, 0, "fp16"))
+    blob2 = pinned_like(resnet_blob(ctx, m2, 1, "fp16"))
+    ctx.load_weights(m1, blob1, ex)
+    x = pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "fp16"))
+    slots = [ctx.input(m1, B, x, ex) for _ in range(n_slots)]
+    ex.synchronize()
+    exec_rounds(ctx, m1, B, slots, ex, 5)                                  # warm-up
+    alone = exec_rounds(ctx, m1, B, slots, ex, args.execs // n_slots)
+    loads = [0]
+
+    def reload(_):
+        # keep LOADs (51 MB host-to-device copy + weight packing each) queued on their own stream
+        for _k in range(args.loads_per_round):
+            ctx.unload_weights(m2)
+            ctx.load_weights(m2, blob2, ld)
+            loads[0] += 1
+
+    # device time of one LOAD on an otherwise idle GPU
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ctx.load_weights(m2, blob2, ld)
+    ld.synchronize()
+    ctx.unload_weights(m2)
+    e0.record(ld)
+    ctx.load_weights(m2, blob2, ld)
+    e1.record(ld)
+    ld.synchronize()
+    load_ms = e0.elapsed_time(e1)
+    t0 = time.perf_counter()
+    under = exec_rounds(ctx, m1, B, slots, ex, args.execs // n_slots, between=reload)
+    ld.synchronize()
+    dt = time.perf_counter() - t0
+    wk.close()
+    return {"config": 3, "workload": "ResNet-50 fp16 batch 8, %d back-to-back EXECs; second ResNet-50 (51 MB) "
+                                     "unloaded and re-LOADed from pinned memory on another stream throughout" % len(under),
+            "exec_alone": summary(alone), "exec_under_load": summary(under),
+            "p50_ratio": round(pct(under, 0.5) / pct(alone, 0.5), 4),
+            "loads_completed": loads[0], "one_load_ms_idle_gpu": round(load_ms, 3),
+            "load_busy_fraction_of_wall": round(min(1.0, loads[0] * load_ms * 1e-3 / dt), 3), "wall_s": round(dt, 3)}
+
+
+def config4(args, log):
+    import torch
+    from .runner import Worker, pinned_like
+    from workload import gen
+    B = 16
+    wk = Worker(workspace_bytes=512 << 20, io_bytes=256 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=512 << 20)
+    ctx, ex = wk.ctx, wk.stream
+    mid = ctx.model_define_resnet(152, 224, 224, "bf16")
+    ctx.load_weights(mid, pinned_like(resnet_blob(ctx, mid, 0, "bf16")), ex)
+    x = pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "bf16"))
+    slot = ctx.input(mid, B, x, ex)
+    ex.synchronize()
+    for _ in range(50):
+        ctx.exec(mid, B, slot, ex)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.execs):
+        ctx.exec(mid, B, slot, ex)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_measure(mid, B, 1000)
+    plan = ctx.plan(mid, B)
+    wk.close()
+    return {"config": 4, "workload": "ResNet-152 224x224 bf16 storage (fp16 overflows with these weights), batch 16",
+            "inferences_per_s": round(B * args.execs / dt, 1), "ms_per_exec_wall": round(dt / args.execs * 1e3, 4),
+            "exec": {k: round(prof[k], 2) for k in ("p50_us", "p99_us", "p999_us", "min_us", "max_us")},
+            "launches": len(plan), "gflop_per_exec": round(sum(l["flops"] for l in plan) / 1e9, 1),
+            "tflops": round(sum(l["flops"] for l in plan) / (prof["p50_us"] * 1e-6) / 1e12, 1)}
+
+
+def config5(args, log):
+    import torch
+    from .runner import Worker, pinned_like
+    from workload import gen
+    n_models, batches, distinct = 64, (1, 2, 4, 8, 16), 8
+    wk = Worker(workspace_bytes=512 << 20, io_bytes=1 << 30, weight_pool_bytes=4 << 30, load_staging_bytes=256 << 20)
+    ctx, ex = wk.ctx, wk.stream
+    cp = torch.cuda.Stream()
+    mids = [ctx.model_define_resnet(50, 224, 224, "fp16") for _ in range(n_models)]
+    blobs = [pinned_like(resnet_blob(ctx, mids[0], s, "fp16")) for s in range(distinct)]
+    for k, m in enumerate(mids):
+        ctx.load_weights(m, blobs[k % distinct], ex)
+    ex.synchronize()
+    log("64 models resident, %.2f GB of the weight pool in use" % (((4 << 30) - ctx.weight_pool_free()) / 1e9))
+    xs = {b: pinned_like(gen.images(0, 0, b, 3, 224, 224, "normal", "fp16")) for b in batches}
+    probs = torch.empty((16, 1000), dtype=torch.float32, pin_memory=True)
+    # capacity of the mix from the per-batch profile of one model
+    p50 = {b: ctx.profile_measure(mids[0], b, 200)["p50_us"] for b in batches}
+    mean_exec_us = float(np.mean(list(p50.values())))
+    lam = args.load / (mean_exec_us * 1e-6)                     # requests per second
+    # seeded arrivals and request mix (counter-based generator of the workload module)
+    n = args.requests
+    u = gen.uniform01(args.seed, 1000, 3 * n)
+    gaps = -np.log(1.0 - u[:n]) / lam
+    arrive = np.cumsum(gaps)
+    which = np.minimum((u[n:2 * n] * n_models).astype(int), n_models - 1)
+    bsel = np.array(batches)[np.minimum((u[2 * n:] * len(batches)).astype(int), len(batches) - 1)]
+    per_b = {b: [] for b in batches}
+    inflight = []
+    max_inflight = 24
+
+    def drain_one():
+        slot, b = inflight.pop(0)
+        per_b[b].append(ctx.exec_duration_ns(slot) / 1e3)
+        ctx.output(slot, probs[:b], None, cp)
+
+    late = 0.0
+    t0 = time.perf_counter()
+    for i in range(n):
+        while time.perf_counter() - t0 < arrive[i]:
+            pass
+        late = max(late, time.perf_counter() - t0 - arrive[i])
+        b, m = int(bsel[i]), mids[int(which[i])]
+        slot = ctx.input(m, b, xs[b], cp)
+        ctx.exec(m, b, slot, ex)
+        inflight.append((slot, b))
+        if len(inflight) >= max_inflight:
+            drain_one()
+    while inflight:
+        drain_one()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    wk.close()
+    images = int(bsel.sum())
+    return {"config": 5, "workload": "%d ResNet-50 fp16 weight sets resident (%d distinct seeds, each model its own "
+                                     "copy in the pool), %d requests, Poisson arrivals at %.0f req/s = %.2f x capacity of "
+                                     "the mix, model ~U{0..63}, batch ~U{1,2,4,8,16}, seed %d"
+                                     % (n_models, distinct, n, lam, args.load, args.seed),
+            "inferences_per_s": round(images / wall, 1), "requests_per_s": round(n / wall, 1), "wall_s": round(wall, 3),
+            "max_host_lateness_ms": round(late * 1e3, 3),
+            "single_model_p50_us": {str(b): round(p50[b], 2) for b in batches},
+            "exec_by_batch": {str(b): summary(per_b[b]) for b in batches}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5))
+    ap.add_argument("--execs", type=int, default=2000)
+    ap.add_argument("--loads-per-round", type=int, default=6, help="config 3: LOADs queued per 20 EXECs")
+    ap.add_argument("--requests", type=int, default=10000)
+    ap.add_argument("--load", type=float, default=0.7, help="config 5: arrival rate as a fraction of capacity")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+
+    def log(msg):
+        print("[measure] " + msg, file=sys.stderr, flush=True)
+
+    out = {3: config3, 4: config4, 5: config5}[args.config](args, log)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    sys.exit(main())
