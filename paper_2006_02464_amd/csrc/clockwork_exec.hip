@@ -543,8 +543,8 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     char *base = c->pool + off;
     for (const WeightSlot &ws : m->m.wslots) {
         const bool is_conv = m->m.ops[ws.op_index].op == CW_OP_CONV;
-        e = launch_pack_weights(c->staging + ws.blob_w_off, base + ws.packed_w_off, ws.cout, ws.cin, ws.kh, ws.kw, ws.kwp,
-                                ws.cinp, is_conv, st);
+        e = launch_pack_weights(c->staging + ws.blob_w_off, base + ws.packed_w_off, ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
+                                ws.kwp, ws.cinp, is_conv, st);
         if (e != hipSuccess) return bail(e, "pack_weights");
         e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
                             reinterpret_cast<float *>(base + ws.packed_b_off), ws.cout, st);

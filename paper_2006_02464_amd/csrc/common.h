@@ -48,6 +48,7 @@ struct ConvArgs {
     int32_t *counters;  // split-K: one arrival counter per output tile, zero between launches
     int32_t B, H, W, Cin, Ho, Wo, Cout;
     int32_t kh, kw, kwp, stride, pad;
+    int32_t khp;        // filter rows in the packed weights (first convolution: may be padded to 8)
     int32_t M, K;
     int32_t relu;
     int32_t split_k, ktiles_per_split;
@@ -56,8 +57,9 @@ struct ConvArgs {
 
 struct CastArgs {
     const float *x;  // NCHW fp32 [B][C][H][W]
-    void *y;         // NHWC4 [B][H][W][4]
+    void *y;         // NHWC4 [B][Hp][Wp][4]: the image inside a zero border of `pad` pixels
     int32_t B, C, H, W;
+    int32_t pad, Hp, Wp;  // Hp = H + 2*pad, Wp = W + 2*pad rounded up to even
 };
 
 struct PoolArgs {
@@ -96,17 +98,18 @@ ConvTile conv_tile_k64(ConvTile t);
 
 // Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);
-// The direct-to-LDS kernel for Cin % 64 == 0 (called by launch_conv after its checks).
-hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s);
+// The direct-to-LDS kernel for Cin % 64 == 0 and for a first convolution in its stem form
+// (called by launch_conv after its checks); mode = the kernel's addressing mode.
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, int mode, const ConvArgs &a, hipStream_t s);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
-// LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp] (zero padded);
+// LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout'][khp][kwp][cinp] (zero padded);
 // permute = rows in the conv kernel's MFMA accumulator order (conv weights), else plain (FC).
 hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw,
-                               int kwp, int cinp, bool permute, hipStream_t s);
+                               int khp, int kwp, int cinp, bool permute, hipStream_t s);
 hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t s);
 // debug read-back: NHWC storage type -> fp32 NCHW
 hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H,

@@ -318,8 +318,13 @@ ConvTile conv_tile_k64(ConvTile t) {
     }
 }
 
+// The first convolution takes the direct-to-LDS kernel's stem mode when its packed filter has 8
+// rows of 8 taps x 4 channels and its stride is even (16-byte aligned 8-tap windows).
+static bool stem_is_dlds(const ConvArgs &a) { return a.khp == 8 && a.kwp == 8 && a.Cin == 4 && a.stride % 2 == 0 && a.pad == 0; }
+
 int conv_bk(const ConvArgs &a, bool stem, ConvTile tile) {
-    if (stem || a.Cin % 64 != 0) return 32;
+    if (stem) return stem_is_dlds(a) ? 64 : 32;
+    if (a.Cin % 64 != 0) return 32;
     return (conv_tile_dim(tile).bk == 128 && a.Cin % 128 == 0) ? 128 : 64;
 }
 
@@ -369,7 +374,7 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
     const int bk = conv_bk(a, stem, tile);
     if (a.K % bk != 0 || a.M <= 0 || a.Cout <= 0 || a.Cout % 32 != 0 || a.split_k < 1 || a.ktiles_per_split < 1)
         return hipErrorInvalidValue;
-    if (stem ? (a.Cin != 4 || a.kwp != 8 || a.K != a.kh * 32) : (a.Cin % 32 != 0 || a.kwp != a.kw || a.K != a.kh * a.kw * a.Cin))
+    if (stem ? (a.Cin != 4 || a.kwp != 8 || a.khp < a.kh || a.K != a.khp * 32) : (a.Cin % 32 != 0 || a.kwp != a.kw || a.K != a.kh * a.kw * a.Cin))
         return hipErrorInvalidValue;
     if (stem ? a.kh > 30 : a.kh * a.kw > 32) return hipErrorInvalidValue;  // tap masks are 32 bits
     if ((long long)a.split_k * a.ktiles_per_split < a.K / bk) return hipErrorInvalidValue;
@@ -381,7 +386,8 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
         return hipErrorInvalidValue;
     // K slices of 64 go global -> LDS directly (kernels_conv_dlds.hip); the stem and Cin % 64 != 0
     // keep the register-staged kernel of this file.
-    if (!stem && a.Cin % 64 == 0) return launch_conv_dlds(dt, tile, bk, conv_is_gemm(a, stem), a, s);
+    if (stem && stem_is_dlds(a)) return launch_conv_dlds(dt, tile, bk, MODE_STEM, a, s);
+    if (!stem && a.Cin % 64 == 0) return launch_conv_dlds(dt, tile, bk, conv_is_gemm(a, stem) ? MODE_GEMM : MODE_CONV, a, s);
     if (a.split_k > 1) return dt == DT_F16 ? launch_conv_dt<f16, true>(tile, stem, a, s) : launch_conv_dt<bf16, true>(tile, stem, a, s);
     return dt == DT_F16 ? launch_conv_dt<f16, false>(tile, stem, a, s) : launch_conv_dt<bf16, false>(tile, stem, a, s);
 }

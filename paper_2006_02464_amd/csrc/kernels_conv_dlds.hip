@@ -57,7 +57,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     constexpr int CPR = BK / 8;  // 16-byte chunks per LDS row
     constexpr int X_CHUNKS = BM * CPR, W_CHUNKS = BN * CPR;
     static_assert(X_CHUNKS % NT == 0 && W_CHUNKS % NT == 0, "tile/threads mismatch");
-    static_assert(MODE == MODE_CONV || MODE == MODE_GEMM, "the stem keeps the register-staged kernel");
+    static_assert(MODE != MODE_STEM || BK == 64, "stem mode: one K slice = two filter rows of 8 taps x 4 channels");
     static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
     constexpr int X_PER = X_CHUNKS / NT, W_PER = W_CHUNKS / NT;
     constexpr int LOADS = X_PER + W_PER;               // load instructions per thread per slice
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
     // VGPR) + tap/channel offset (uniform, in an SGPR)  is never negative.
     const unsigned x_bytes = (unsigned)a.B * a.H * a.W * a.Cin * 2u;
-    const unsigned x_shift = MODE == MODE_GEMM ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
+    const unsigned x_shift = MODE != MODE_CONV ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
     const u32x4 dx = make_desc(static_cast<const char *>(a.x) - x_shift, x_bytes + x_shift);
     const u32x4 dw = make_desc(a.w, (unsigned)a.Cout * a.K * 2u);
 
@@ -115,6 +115,16 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         unsigned mask = 0, voff = 0;
         if (MODE == MODE_GEMM) {
             voff = m * (unsigned)a.Cin * 2u + c * 16u;
+            mask = m < (unsigned)a.M ? 1u : 0u;
+        } else if (MODE == MODE_STEM) {
+            // Input = 4-channel pixels (8 bytes) of an image already padded by the cast; no
+            // masks.  A K slice is filter rows 2kt, 2kt+1; of its 8 chunks, chunk c is row c/4,
+            // taps 2(c%4), 2(c%4)+1: 16 contiguous, 16-byte aligned bytes (even stride, even W).
+            const unsigned t = fast_div(m, a.wo_div);
+            const unsigned q = m - t * a.Wo;
+            const unsigned n = fast_div(t, a.ho_div);
+            const unsigned p = t - n * a.Ho;
+            voff = (((n * a.H + p * a.stride + (c >> 2)) * a.W + q * a.stride) * 4u + (c & 3) * 8u) * 2u;
             mask = m < (unsigned)a.M ? 1u : 0u;
         } else if (m < (unsigned)a.M) {
             const unsigned t = fast_div(m, a.wo_div);
@@ -148,7 +158,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     int fr = 0, fs = 0, fc0 = 0;
     if (MODE == MODE_GEMM) {
         fc0 = kt0 * BK;
-    } else {
+    } else if (MODE == MODE_CONV) {
         const int k0 = kt0 * BK;
         const int rs = k0 / a.Cin;
         fc0 = k0 - rs * a.Cin;
@@ -161,8 +171,10 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     // one load, end() advances (r, s, c0).
     unsigned is_soff = 0, is_tbit = 0, is_dst = 0, is_kb = 0;
     auto issue_begin = [&](int kt, int stage) {
-        is_soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
-        is_tbit = MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs));
+        is_soff = MODE == MODE_GEMM   ? (unsigned)fc0 * 2u
+                  : MODE == MODE_STEM ? (unsigned)kt * (2u * a.W * 8u)
+                                      : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+        is_tbit = MODE == MODE_CONV ? (1u << (fr * a.kw + fs)) : 1u;
         is_dst = lds_base + (unsigned)stage * STAGE_BYTES + (unsigned)wave * 1024u;
         is_kb = (unsigned)kt * (BK * 2u);
     };
@@ -174,7 +186,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     };
     auto issue_end = [&]() {
         fc0 += BK;
-        if (MODE != MODE_GEMM && fc0 == a.Cin) {
+        if (MODE == MODE_CONV && fc0 == a.Cin) {
             fc0 = 0;
             if (++fs == a.kw) { fs = 0; ++fr; }
         }
@@ -331,26 +343,49 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
         case T64x128w2: return launch_one<T, 64, 128, 1, 2, 64, MODE, SPLITK>(grid, block, a, s);
         case T256x64: return launch_one<T, 256, 64, 4, 1, 64, MODE, SPLITK>(grid, block, a, s);
         case T128x128w8: return launch_one<T, 128, 128, 2, 4, 64, MODE, SPLITK>(grid, block, a, s);
-        case T128x64k128: return launch_one<T, 128, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
-        case T64x64k128: return launch_one<T, 64, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
-        case T64x32k128: return launch_one<T, 64, 32, 2, 1, 128, MODE, SPLITK>(grid, block, a, s);
-        case T32x64k128: return launch_one<T, 32, 64, 1, 2, 128, MODE, SPLITK>(grid, block, a, s);
-        case T32x32k128: return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK>(grid, block, a, s);
+        case T128x64k128:
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 128, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x64k128:
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 64, 2, 2, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x32k128:
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 32, 2, 1, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x64k128:
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 64, 1, 2, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x32k128:
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
 
-template <typename T>
-static hipError_t launch_dt(ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s) {
-    if (a.split_k > 1) return gemm ? launch_tile<T, MODE_GEMM, true>(tile, bk, a, s) : launch_tile<T, MODE_CONV, true>(tile, bk, a, s);
-    return gemm ? launch_tile<T, MODE_GEMM, false>(tile, bk, a, s) : launch_tile<T, MODE_CONV, false>(tile, bk, a, s);
+template <typename T, bool SPLITK>
+static hipError_t launch_mode(ConvTile tile, int bk, int mode, const ConvArgs &a, hipStream_t s) {
+    switch (mode) {
+        case MODE_GEMM: return launch_tile<T, MODE_GEMM, SPLITK>(tile, bk, a, s);
+        case MODE_CONV: return launch_tile<T, MODE_CONV, SPLITK>(tile, bk, a, s);
+        case MODE_STEM: return launch_tile<T, MODE_STEM, SPLITK>(tile, 64, a, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 // Called by launch_conv (which has validated the shapes) for every convolution with
-// Cin % 64 == 0 other than the stem; bk = conv_bk() of the shape under this tile.
-hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, bool gemm, const ConvArgs &a, hipStream_t s) {
-    if ((bk != 64 && bk != 128) || a.Cin % bk != 0 || a.K != a.kh * a.kw * a.Cin) return hipErrorInvalidValue;
-    return dt == DT_F16 ? launch_dt<f16>(tile, bk, gemm, a, s) : launch_dt<bf16>(tile, bk, gemm, a, s);
+// Cin % 64 == 0 and for a first convolution in stem form; bk = conv_bk() of the shape under
+// this tile.
+hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, int mode, const ConvArgs &a, hipStream_t s) {
+    if (mode == MODE_STEM) {
+        if (bk != 64 || a.Cin != 4 || a.K != 256 || a.kwp != 8 || a.khp != 8 || a.pad != 0 || a.stride % 2 != 0 || a.W % 2 != 0)
+            return hipErrorInvalidValue;
+        // every 8-tap window must start inside the (padded) image
+        if ((a.Ho - 1) * a.stride >= a.H || (a.Wo - 1) * a.stride >= a.W) return hipErrorInvalidValue;
+    } else if ((bk != 64 && bk != 128) || a.Cin % bk != 0 || a.K != a.kh * a.kw * a.Cin) {
+        return hipErrorInvalidValue;
+    }
+    if (a.split_k > 1) return dt == DT_F16 ? launch_mode<f16, true>(tile, bk, mode, a, s) : launch_mode<bf16, true>(tile, bk, mode, a, s);
+    return dt == DT_F16 ? launch_mode<f16, false>(tile, bk, mode, a, s) : launch_mode<bf16, false>(tile, bk, mode, a, s);
 }
 
 }  // namespace cw

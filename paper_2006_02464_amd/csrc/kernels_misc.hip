@@ -8,18 +8,23 @@ template <typename T>
 static __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 
 // ---- input: fp32 NCHW [B][C][H][W] (C <= 4) -> NHWC4, channels C..3 zero ----------------
-// One thread per pixel: C strided 4-byte reads (each coalesced across the wave along W), one
-// 8-byte write.
+// One thread per pixel of the padded output: inside the image C strided 4-byte reads (each
+// coalesced across the wave along W), zeros in the border; one 8-byte write either way.
 template <typename T>
 __global__ __launch_bounds__(256) void cast_input_kernel(const CastArgs a) {
-    const size_t hw = (size_t)a.H * a.W;
-    const size_t total = (size_t)a.B * hw;
+    const size_t hwp = (size_t)a.Hp * a.Wp;
+    const size_t total = (size_t)a.B * hwp;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const size_t n = i / hw, p = i - n * hw;
-    T v[4];
+    const size_t n = i / hwp, pp = i - n * hwp;
+    const int ih = (int)(pp / a.Wp) - a.pad, iw = (int)(pp % a.Wp) - a.pad;
+    T v[4] = {(T)0.f, (T)0.f, (T)0.f, (T)0.f};
+    if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W) {
+        const size_t hw = (size_t)a.H * a.W, p = (size_t)ih * a.W + iw;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] = (T)(c < a.C ? a.x[(n * a.C + c) * hw + p] : 0.f);
+        for (int c = 0; c < 4; ++c)
+            if (c < a.C) v[c] = (T)a.x[(n * a.C + c) * hw + p];
+    }
     *reinterpret_cast<uint2 *>(static_cast<T *>(a.y) + i * 4) = *reinterpret_cast<const uint2 *>(v);
 }
 
@@ -166,23 +171,23 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SoftmaxArgs a) {
 //     i = 8g + 4h + k  ->  sigma(i) = 16*(g/2) + 8h + 4*(g%2) + k,
 // the order in which the conv kernel's MFMA accumulators come out as runs of 8 channels.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
-                                                           int cout, int cin, int kh, int kw, int kwp, int cinp,
+                                                           int cout, int cin, int kh, int kw, int khp, int kwp, int cinp,
                                                            int permute) {
-    const size_t total = (size_t)cout * kh * kwp * cinp;
+    const size_t total = (size_t)cout * khp * kwp * cinp;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     const int c = (int)(i % cinp);
     size_t t = i / cinp;
     const int s = (int)(t % kwp);
     t /= kwp;
-    const int r = (int)(t % kh);
-    int k = (int)(t / kh);
+    const int r = (int)(t % khp);
+    int k = (int)(t / khp);
     if (permute) {
         const int row = k & 31, g = row >> 3, h = (row >> 2) & 1, kk = row & 3;
         k = (k & ~31) + (g >> 1) * 16 + h * 8 + (g & 1) * 4 + kk;
     }
     uint16_t v = 0;
-    if (c < cin && s < kw) v = src[(((size_t)k * cin + c) * kh + r) * kw + s];
+    if (c < cin && s < kw && r < kh) v = src[(((size_t)k * cin + c) * kh + r) * kw + s];
     dst[i] = v;
 }
 
@@ -223,8 +228,8 @@ static inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + pe
     } while (0)
 
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s) {
-    if (a.C < 1 || a.C > 4 || a.B < 1) return hipErrorInvalidValue;
-    const size_t total = (size_t)a.B * a.H * a.W;
+    if (a.C < 1 || a.C > 4 || a.B < 1 || a.pad < 0 || a.Hp != a.H + 2 * a.pad || a.Wp < a.W + 2 * a.pad) return hipErrorInvalidValue;
+    const size_t total = (size_t)a.B * a.Hp * a.Wp;
     CW_DISPATCH(dt, cast_input_kernel, dim3(blocks_for(total, 256)), 256, s, a);
     return hipGetLastError();
 }
@@ -256,13 +261,13 @@ hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw, int kwp, int cinp,
+hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw, int khp, int kwp, int cinp,
                                bool permute, hipStream_t s) {
     if (permute && cout % 32 != 0) return hipErrorInvalidValue;
-    const size_t total = (size_t)cout * kh * kwp * cinp;
+    const size_t total = (size_t)cout * khp * kwp * cinp;
     pack_weights_kernel<<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const uint16_t *>(src),
                                                                     static_cast<uint16_t *>(dst), cout, cin, kh, kw,
-                                                                    kwp, cinp, permute ? 1 : 0);
+                                                                    khp, kwp, cinp, permute ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -201,6 +201,9 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
             ws.kw = o.op == CW_OP_FC ? 1 : o.kw;
             ws.kwp = (i == 0) ? 8 : ws.kw;
             ws.cinp = (i == 0) ? 4 : ws.cin;
+            // first convolution: with an even stride and at most 8 filter rows, the rows are padded
+            // to 8 so that two of them make one K slice of 64 (see the stem mode of the conv kernel)
+            ws.khp = (i == 0 && o.op == CW_OP_CONV && o.stride % 2 == 0 && ws.kh <= 8) ? 8 : ws.kh;
             ws.blob_w_off = blob_w;
             blob_w += (size_t)ws.cout * ws.cin * ws.kh * ws.kw * 2;
             m->op_wslot[i] = (int)m->wslots.size();
@@ -213,7 +216,7 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         ws.blob_b_off = blob_b;
         blob_b += (size_t)ws.cout * 4;
         ws.packed_w_off = packed;
-        ws.packed_w_bytes = (size_t)ws.cout * ws.kh * ws.kwp * ws.cinp * 2;
+        ws.packed_w_bytes = (size_t)ws.cout * ws.khp * ws.kwp * ws.cinp * 2;
         packed = align_up(packed + ws.packed_w_bytes, 256);
     }
     for (WeightSlot &ws : m->wslots) {
@@ -308,14 +311,18 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // the split-K arrival counters live at the very start of the workspace, never reused
     (void)ws_alloc(kCounterBytes);
 
-    // input cast: fp32 NCHW in the IO slot -> NHWC4 in the workspace
-    const size_t cast_bytes = (size_t)batch * m.in_h * m.in_w * 4 * esz;
+    // input cast: fp32 NCHW in the IO slot -> NHWC4 in the workspace, inside a zero border as wide
+    // as the first convolution's padding (that convolution then runs unpadded over the larger image)
+    const int in_pad = m.ops[0].op == CW_OP_CONV ? m.ops[0].pad : 0;
+    const int in_hp = m.in_h + 2 * in_pad, in_wp = (m.in_w + 2 * in_pad + 1) / 2 * 2;
+    const size_t cast_bytes = (size_t)batch * in_hp * in_wp * 4 * esz;
     const size_t cast_off = ws_alloc(cast_bytes);
     {
         Launch l{};
         l.kind = K_CAST_INPUT;
         l.op_index = 0;
         l.cast.B = batch; l.cast.C = m.in_c; l.cast.H = m.in_h; l.cast.W = m.in_w;
+        l.cast.pad = in_pad; l.cast.Hp = in_hp; l.cast.Wp = in_wp;
         l.x = Ref{SP_SLOT_INPUT, 0};
         l.y = Ref{SP_WORKSPACE, cast_off};
         l.info.bytes = (int64_t)batch * m.in_c * m.in_h * m.in_w * 4 + (int64_t)cast_bytes;
@@ -328,7 +335,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         const OpShape &os = m.shapes[i];
         int sc, sh, sw;
         Ref src;
-        if (o.input_from < 0) { sc = 4; sh = m.in_h; sw = m.in_w; src = Ref{SP_WORKSPACE, cast_off}; }
+        if (o.input_from < 0) { sc = 4; sh = m.in_h; sw = m.in_w; src = Ref{SP_WORKSPACE, cast_off}; }  // logical size; see below
         else { sc = m.shapes[o.input_from].c; sh = m.shapes[o.input_from].h; sw = m.shapes[o.input_from].w; src = p.op_out[o.input_from]; }
         size_t partial_off = 0, partial_bytes = 0;
 
@@ -343,9 +350,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 l.stem = (i == 0);
                 ConvArgs &a = l.conv;
                 a.B = batch; a.H = sh; a.W = sw; a.Cin = ws.cinp; a.Ho = os.h; a.Wo = os.w; a.Cout = o.cout;
-                a.kh = o.kh; a.kw = o.kw; a.kwp = ws.kwp; a.stride = o.stride; a.pad = o.pad;
+                a.kh = o.kh; a.kw = o.kw; a.kwp = ws.kwp; a.khp = ws.khp; a.stride = o.stride; a.pad = o.pad;
+                if (o.input_from < 0) { a.H = in_hp; a.W = in_wp; a.pad = 0; }  // the cast already padded the image
                 a.M = batch * os.h * os.w;
-                a.K = o.kh * ws.kwp * ws.cinp;
+                a.K = ws.khp * ws.kwp * ws.cinp;
                 a.relu = o.relu;
                 a.wo_div = make_fast_div((uint32_t)os.w);
                 a.ho_div = make_fast_div((uint32_t)os.h);
@@ -468,7 +476,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         int b = 0;
         switch (l.kind) {
             case K_CONV: conv_grid(l.tile, l.conv, &g, &b); break;
-            case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.H * l.cast.W + 255) / 256)); b = 256; break;
+            case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
             case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 256; break;

@@ -46,7 +46,7 @@ struct WeightSlot {        // one op that owns weights
     size_t packed_w_off;   // byte offset of packed W inside the model's weight-pool region
     size_t packed_b_off;   // byte offset of the fp32 bias there
     size_t packed_w_bytes;
-    int32_t cout, cin, kh, kw, kwp, cinp;
+    int32_t cout, cin, kh, kw, khp, kwp, cinp;
 };
 
 struct Plan {

@@ -92,8 +92,9 @@ def test_plan_override_reaches_every_tile(ctx):
         ops = ctx.model_get_ops(m)
         for l in convs:
             cin = ops[l["op_index"]][1]
-            # K slices: 32 for the first convolution, 128 only where the tile asks and cin allows
-            want = 32 if cin < 32 else (128 if name.endswith("k128") and cin % 128 == 0 else 64)
+            # K slices: 64 for the first convolution (stride 2: two padded filter rows per slice),
+            # 128 only where the tile asks and cin allows
+            want = 64 if cin < 32 else (128 if name.endswith("k128") and cin % 128 == 0 else 64)
             assert l["tile_k"] == want
             assert l["split_k"] == 2 or l["gemm_k"] <= l["tile_k"] or cin < 32   # one K slice cannot be split
     ctx.set_plan_override(-1, 0)
