@@ -98,7 +98,8 @@ int32_t cw_destroy(cw_ctx *ctx);
  * ops, batch_sizes: [host], copied.  The first op must read the network input
  * (in_c x in_h x in_w, NCHW fp32 at the boundary); the list must end FC, SOFTMAX.
  * Supported: CONV with cin % 32 == 0, cout % 32 == 0 and kh == kw <= 5 anywhere,
- * plus a first CONV with cin <= 4 and kh == kw <= 8.  Returns CW_ERR_UNSUPPORTED otherwise,
+ * plus a first CONV with cin <= 4 and kh == kw <= 8; GAVGPOOL over a multiple of 64
+ * channels; FC with cin % 256 == 0 reading the GAVGPOOL.  Returns CW_ERR_UNSUPPORTED otherwise,
  * CW_ERR_NO_MEMORY if a plan's workspace exceeds workspace_bytes. */
 int32_t cw_model_define(cw_ctx *ctx, const cw_op *ops, int32_t n_ops,
                         int32_t in_c, int32_t in_h, int32_t in_w,

@@ -96,17 +96,20 @@ __global__ __launch_bounds__(64) void gavgpool_kernel(const PoolArgs a) {
 
 // ---- FC: z[n][j] = bias[j] + sum_i f[n][i] * W[j][i], fp32 features, fp32 result ---------
 // A workgroup computes 16 outputs x 16 samples on the fp32 matrix cores
-// (v_mfma_f32_16x16x4_f32: 16 output rows x 16 sample columns x 4 k per instruction).  Its 4 waves
+// (v_mfma_f32_16x16x4_f32: 16 output rows x 16 sample columns x 4 k per instruction).  Its 8 waves
 // split K; wave w walks chunks of 32 k: lane (r = lane%16, g = lane/16) loads 8 consecutive
 // weights of output row r and 8 consecutive features of sample r, both at k = chunk + 8g, and
 // issues 8 MFMAs, the e-th one multiplying the e-th element of each (the k index of an MFMA is
-// only a summation label, so any pairing that both operands share is valid).  The four partial
+// only a summation label, so any pairing that both operands share is valid).  The layer streams
+// its weights once from HBM, so the loads of four chunks are requested together before their 32
+// MFMAs: the memory latency is paid once per 128 k, not once per chunk.  The eight partial
 // 16x16 tiles are summed through LDS in wave order, the bias is added and the logits written.
 typedef float fc_f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kFcWaves = 8;
 
 template <typename T>
-__global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
-    __shared__ float part[4][16][17];
+__global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const FcArgs a) {
+    __shared__ float part[kFcWaves][16][17];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int j = blockIdx.x * 16 + r;   // output row this lane feeds
@@ -115,28 +118,44 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
     const T *wrow = static_cast<const T *>(a.w) + (size_t)(j_ok ? j : 0) * a.In;
     const float *frow = a.f + (size_t)(n_ok ? n : 0) * a.In;
     fc_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    const int kq = a.In / 4;  // K range of this wave
-    for (int k = wave * kq + g * 8; k < (wave + 1) * kq; k += 32) {
-        uint4 wraw = *reinterpret_cast<const uint4 *>(wrow + k);
-        float4 f0 = *reinterpret_cast<const float4 *>(frow + k);
-        float4 f1 = *reinterpret_cast<const float4 *>(frow + k + 4);
-        if (!j_ok) wraw = make_uint4(0u, 0u, 0u, 0u);
-        if (!n_ok) { f0 = make_float4(0.f, 0.f, 0.f, 0.f); f1 = f0; }
-        const T *wv = reinterpret_cast<const T *>(&wraw);
-        const float fv[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+    const int kq = a.In / kFcWaves;  // K range of this wave (a multiple of 32)
+    const int k_end = (wave + 1) * kq;
+    for (int k0 = wave * kq + g * 8; k0 < k_end; k0 += 128) {
+        uint4 wraw[4];
+        float4 f0[4], f1[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(to_f32(wv[e]), fv[e], acc, 0, 0, 0);
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + 32 * u;
+            const bool live = k < k_end;  // uniform per wave
+            const int kc = live ? k : k0;
+            wraw[u] = *reinterpret_cast<const uint4 *>(wrow + kc);
+            f0[u] = *reinterpret_cast<const float4 *>(frow + kc);
+            f1[u] = *reinterpret_cast<const float4 *>(frow + kc + 4);
+            if (!j_ok || !live) wraw[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (!n_ok) { f0[u] = make_float4(0.f, 0.f, 0.f, 0.f); f1[u] = f0[u]; }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const T *wv = reinterpret_cast<const T *>(&wraw[u]);
+            const float fv[8] = {f0[u].x, f0[u].y, f0[u].z, f0[u].w, f1[u].x, f1[u].y, f1[u].z, f1[u].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(to_f32(wv[e]), fv[e], acc, 0, 0, 0);
+        }
     }
     // lane holds column (sample) lane%16, rows (outputs) 4*(lane/16) + e
 #pragma unroll
     for (int e = 0; e < 4; ++e) part[wave][4 * g + e][r] = acc[e];
     __syncthreads();
-    const int t = threadIdx.x;  // 256 threads = 16 outputs x 16 samples
-    const int oj = t >> 4, on = t & 15;
-    const int jj = blockIdx.x * 16 + oj, nn = blockIdx.y * 16 + on;
-    if (jj < a.Out && nn < a.B) {
-        const float v = ((part[0][oj][on] + part[1][oj][on]) + part[2][oj][on]) + part[3][oj][on];
-        a.z[(size_t)nn * a.Out + jj] = v + a.bias[jj];
+    const int t = threadIdx.x;
+    if (t < 256) {  // 16 outputs x 16 samples
+        const int oj = t >> 4, on = t & 15;
+        const int jj = blockIdx.x * 16 + oj, nn = blockIdx.y * 16 + on;
+        if (jj < a.Out && nn < a.B) {
+            float v = part[0][oj][on];
+#pragma unroll
+            for (int w = 1; w < kFcWaves; ++w) v += part[w][oj][on];
+            a.z[(size_t)nn * a.Out + jj] = v + a.bias[jj];
+        }
     }
 }
 
@@ -249,9 +268,9 @@ hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s) {
-    if (a.In % 128 != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
+    if (a.In % (32 * kFcWaves) != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
     const dim3 grid(blocks_for(a.Out, 16), blocks_for(a.B, 16));
-    CW_DISPATCH(dt, fc_kernel, grid, 256, s, a);
+    CW_DISPATCH(dt, fc_kernel, grid, 64 * kFcWaves, s, a);
     return hipGetLastError();
 }
 

@@ -173,8 +173,8 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
                     return fail(err, CW_ERR_UNSUPPORTED, "op %d: average pool needs channels %% 64 == 0", i);
                 break;
             case CW_OP_FC:
-                if (i != n_ops - 2 || ops[o.input_from].op != CW_OP_GAVGPOOL || o.cin % 128 != 0 || o.cout < 1)
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: FC must follow the global average pool, cin %% 128 == 0", i);
+                if (i != n_ops - 2 || ops[o.input_from].op != CW_OP_GAVGPOOL || o.cin % 256 != 0 || o.cout < 1)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: FC must follow the global average pool, cin %% 256 == 0", i);
                 break;
             case CW_OP_SOFTMAX:
                 if (i != n_ops - 1 || o.input_from != n_ops - 2 || o.cout != o.cin)
@@ -479,7 +479,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
-            case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 256; break;
+            case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; break;
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
         }
         l.info.op_index = l.op_index;
