@@ -176,7 +176,8 @@ int32_t cw_profile_get(cw_ctx *ctx, int32_t model_id, int32_t batch, cw_profile 
  * Number of kernel launches in the plan of (model, batch); negative on error. */
 int32_t cw_plan_num_launches(cw_ctx *ctx, int32_t model_id, int32_t batch);
 typedef struct {
-    int32_t op_index;      /* which op of the model this launch belongs to */
+    int32_t op_index;      /* which op of the model this launch belongs to (fused launch: the last) */
+    int32_t fused_op;      /* -1, or the op this launch computes first, fused with op_index */
     int32_t kind;          /* internal kernel family id */
     int32_t grid_x, grid_y, grid_z, block;
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
@@ -214,6 +215,12 @@ int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
+/* A convolution with 64 or 128 output channels whose only consumer is a 1x1 stride-1
+ * convolution with a residual (the last two layers of a ResNet bottleneck) is planned as ONE
+ * launch when the batch gives it enough workgroups: the intermediate tensor then never leaves
+ * the chip.  on == 0 plans such pairs as two launches for models defined afterwards; on != 0
+ * restores the default.  Plans with debug retention are never fused. */
+int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
 /* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
  * The plan compiler takes the tile variant and split-K factor of a convolution from a table
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs

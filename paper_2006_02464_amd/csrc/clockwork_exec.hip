@@ -138,6 +138,11 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hi
             a.y = resolve(c, m, s, l.y);
             a.partial = reinterpret_cast<float *>(resolve(c, m, s, l.partial));
             a.counters = reinterpret_cast<int32_t *>(resolve(c, m, s, l.counters));
+            if (l.fused_bm > 0) {
+                a.w2 = resolve(c, m, s, l.w2);
+                a.bias2 = reinterpret_cast<const float *>(resolve(c, m, s, l.bias2));
+                return launch_conv_fused(dt, l.fused_bm, a, st);
+            }
             return launch_conv(dt, l.tile, l.stem, a, st);
         }
         case K_MAXPOOL:
@@ -449,6 +454,12 @@ int32_t cw_set_plan_override(cw_ctx *c, int32_t conv_tile, int32_t split_k) {
     if (conv_tile >= (int32_t)N_CONV_TILES || split_k < 0) return set_err(c, CW_ERR_INVALID, "bad override");
     c->ov.tile = conv_tile < 0 ? -1 : conv_tile;
     c->ov.split_k = split_k;
+    return CW_OK;
+}
+
+int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.fuse = on != 0;
     return CW_OK;
 }
 

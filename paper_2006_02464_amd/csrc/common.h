@@ -53,6 +53,12 @@ struct ConvArgs {
     int32_t relu;
     int32_t split_k, ktiles_per_split;
     FastDiv wo_div, ho_div;  // for m -> (image, row, column)
+    // Fused second layer (launch_conv_fused only): a 1x1 stride-1 convolution over this one's
+    // output, y = act2(res + bias2 + W2 * act(bias + W * x)).  `res`, `y` then belong to the second
+    // layer ([M][Cout2]); the first layer's output is never stored.
+    const void *w2;      // packed [Cout2][Cout]
+    const float *bias2;  // [Cout2]
+    int32_t Cout2, relu2;
 };
 
 struct CastArgs {
@@ -101,6 +107,11 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
 // The direct-to-LDS kernel for Cin % 64 == 0 and for a first convolution in its stem form
 // (called by launch_conv after its checks); mode = the kernel's addressing mode.
 hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, int mode, const ConvArgs &a, hipStream_t s);
+// A convolution (Cin % 64 == 0, Cout 64 or 128) and the 1x1 convolution that consumes it, in one
+// launch (kernels_conv_dlds.hip).  bm = pixels per workgroup (64 or 128).
+hipError_t launch_conv_fused(DType dt, int bm, const ConvArgs &a, hipStream_t s);
+// Workgroups of that launch.
+void conv_fused_grid(int bm, const ConvArgs &a, dim3 *grid, int *block);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);

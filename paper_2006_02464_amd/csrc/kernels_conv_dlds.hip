@@ -40,6 +40,13 @@ static __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
 }
 
+// The same, also waiting for this thread's own LDS accesses (reads returned, writes done).
+template <int N>
+static __device__ __forceinline__ void wait_lds_loads_and_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
 // Raw buffer descriptor (stride 0) as four scalars, for use as an asm operand.
 static __device__ __forceinline__ u32x4 make_desc(const void *p, unsigned bytes) {
     const unsigned long long v = reinterpret_cast<unsigned long long>(p);
@@ -48,9 +55,18 @@ static __device__ __forceinline__ u32x4 make_desc(const void *p, unsigned bytes)
 
 extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK>
+// LDS bytes of the fused second layer (see the end of the kernel): the first layer's tile, two
+// buffers of {a chunk of W2, the matching residual tile}.  Both layers' biases sit behind
+// whichever is larger, this or the ring, from the start of the kernel.
+constexpr unsigned fused_lds_bytes(int bm, int bn) {
+    return (unsigned)(bm * bn * 2 + 2 * (bn * bn * 2 + bm * bn * 2));
+}
+constexpr int kFusedMaxCout2 = 1024;
+
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const ConvArgs a) {
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
+    static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
     constexpr int NT = 64 * WARPS_M * WARPS_N;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -71,6 +87,14 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
 
     CW_STAMP(0);
     const int tid = threadIdx.x;
+    // Fused form: both layers' biases go to LDS now, with ordinary loads, while no counted load is
+    // in flight yet (visible to every wave after the first barrier).
+    constexpr unsigned BIAS_OFF = FUSED ? (NS * STAGE_BYTES > fused_lds_bytes(BM, BN) ? NS * STAGE_BYTES : fused_lds_bytes(BM, BN)) : 0u;
+    if constexpr (FUSED) {
+        float *sb = reinterpret_cast<float *>(cw_dyn_lds + BIAS_OFF);
+        for (int n = tid; n < BN; n += 64 * WARPS_M * WARPS_N) sb[n] = a.bias[n];
+        for (int n = tid; n < a.Cout2; n += 64 * WARPS_M * WARPS_N) sb[BN + n] = a.bias2[n];
+    }
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave / WARPS_N) * WM;
@@ -281,7 +305,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         if (u < kt1 - kt) {                         // uniform
             wait_loads_and_barrier<u * LOADS>();
             CW_STAMP(trace_slot++);
-            if (!SPLITK && u == 0) epilogue_load<TM, TN>(eo, a, pos);
+            if (!SPLITK && !FUSED && u == 0) epilogue_load<TM, TN>(eo, a, pos);
             compute(cur, std::false_type{});
             CW_STAMP(trace_slot++);
             cur = cur + 1 == NS ? 0 : cur + 1;
@@ -292,9 +316,120 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     if constexpr (NS >= 3) tail(std::integral_constant<int, 1>{});
     tail(std::integral_constant<int, 0>{});
 
-    if (!SPLITK && nsteps <= 0) epilogue_load<TM, TN>(eo, a, pos);
+    if (!SPLITK && !FUSED && nsteps <= 0) epilogue_load<TM, TN>(eo, a, pos);
 
     CW_STAMP_END(60);
+    if constexpr (FUSED) {
+        // ---- second layer: y[m][:] = act2(res[m][:] + bias2 + W2 * p[m][:]),  p = act(acc + bias) ----
+        // BN == Cout: the tile holds every channel of its BM pixels, so the 1x1 convolution that
+        // consumes them needs nothing from other workgroups.  p goes to LDS in operand layout
+        // (rows of BN elements, swizzled) and stays; the second layer's Cout2 channels are walked
+        // in chunks of BN with the same wave layout and accumulators.  Per chunk, W2[chunk] (BN x BN)
+        // and the residual tile (BM x BN) are fetched straight into LDS, double buffered: chunk
+        // c+1 is requested before the MFMAs of chunk c.  Loads and stores complete in issue order,
+        // so when chunk c is awaited only the stores of chunk c-1 may still be outstanding.
+        constexpr int CP2 = BN / 8;                                // 16-byte chunks per row
+        constexpr int W2_PER = BN * CP2 / NT, R_PER = BM * CP2 / NT;
+        static_assert(BN * CP2 % NT == 0 && BM * CP2 % NT == 0, "tile/threads mismatch");
+        constexpr int ST = TM * TN * 2;                            // stores per thread per chunk
+        constexpr unsigned P_BYTES = BM * BN * 2u, W2_BYTES = BN * BN * 2u, R_BYTES = BM * BN * 2u;
+        constexpr unsigned BUF_BYTES = W2_BYTES + R_BYTES;
+        static_assert(BIAS_OFF + (BN + kFusedMaxCout2) * 4 <= 160 * 1024, "second layer does not fit the LDS");
+        T *sP = lds;
+        const float *sBias1 = reinterpret_cast<const float *>(cw_dyn_lds + BIAS_OFF);
+        const float *sBias = sBias1 + BN;
+        const int chunks = a.Cout2 / BN;
+        const u32x4 dw2 = make_desc(a.w2, (unsigned)a.Cout2 * BN * 2u);
+        const u32x4 dres = make_desc(a.res, (unsigned)a.M * a.Cout2 * 2u);
+        unsigned w2_voff[W2_PER], r_voff[R_PER];
+#pragma unroll
+        for (int j = 0; j < W2_PER; ++j) {
+            const int cid = tid + j * NT, row = cid / CP2, c = (cid % CP2) ^ swz_key<BN>(row);
+            w2_voff[j] = (unsigned)(row * BN + c * 8) * 2u;
+        }
+#pragma unroll
+        for (int j = 0; j < R_PER; ++j) {
+            const int cid = tid + j * NT, row = cid / CP2, c = (cid % CP2) ^ swz_key<BN>(row);
+            const unsigned m = m0 + row;
+            r_voff[j] = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + c * 8) * 2u : kOob;
+        }
+        auto issue_chunk = [&](int c) {
+            const unsigned dst = lds_base + P_BYTES + (unsigned)(c & 1) * BUF_BYTES + (unsigned)wave * 1024u;
+#pragma unroll
+            for (int j = 0; j < W2_PER; ++j) load_to_lds(dw2, w2_voff[j], (unsigned)c * (BN * BN * 2u), dst + j * (NT * 16));
+#pragma unroll
+            for (int j = 0; j < R_PER; ++j) load_to_lds(dres, r_voff[j], (unsigned)c * (BN * 2u), dst + W2_BYTES + j * (NT * 16));
+        };
+
+        // every wave is done with the ring (the last slice's barrier came before its MFMAs)
+        wait_loads_and_barrier<0>();
+        issue_chunk(0);
+        // first layer's epilogue into LDS: + bias, activation, one rounding to the storage type
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int n = wn0 + j * 32 + q * 16 + lhalf * 8;
+                    T out[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float v = acc[i][j][8 * q + e] + sBias1[n + e];
+                        out[e] = (T)(a.relu ? fmaxf(v, 0.f) : v);
+                    }
+                    *reinterpret_cast<u32x4 *>(sP + swz<BN>(wm0 + i * 32 + lrow, n >> 3)) = *reinterpret_cast<const u32x4 *>(out);
+                }
+        const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (unsigned)a.M * a.Cout2 * 2u);
+        for (int c = 0; c < chunks; ++c) {
+            // chunk c has landed (mine: vmcnt; everyone's: barrier); p and the bias are visible;
+            // every wave has finished reading the buffer that chunk c+1 is about to overwrite
+            if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
+            if (c + 1 < chunks) issue_chunk(c + 1);
+            const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + P_BYTES + (unsigned)(c & 1) * BUF_BYTES);
+            const T *sR = reinterpret_cast<const T *>(cw_dyn_lds + P_BYTES + (unsigned)(c & 1) * BUF_BYTES + W2_BYTES);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < BN / 16; ++kk) {
+                v8 px[TM], pw[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sP + swz<BN>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+                for (int j = 0; j < TN; ++j) pw[j] = *reinterpret_cast<const v8 *>(sW2 + swz<BN>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(pw[j], px[i], acc[i][j]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int nl = wn0 + j * 32 + q * 16 + lhalf * 8;   // channel inside the chunk
+                        const u32x4 rraw = *reinterpret_cast<const u32x4 *>(sR + swz<BN>(wm0 + i * 32 + lrow, nl >> 3));
+                        const T *r = reinterpret_cast<const T *>(&rraw);
+                        const float *b = sBias + c * BN + nl;
+                        T out[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float v = acc[i][j][8 * q + e] + b[e] + (float)r[e];
+                            out[e] = (T)(a.relu2 ? fmaxf(v, 0.f) : v);
+                        }
+                        const unsigned o = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + (unsigned)(c * BN + nl)) * 2u : kOob;
+                        __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
+                    }
+            }
+        }
+        return;
+    }
     if (SPLITK) {
         if (!splitk_exchange<TM, TN>(acc, a, pos, tile_id)) return;
         epilogue_load<TM, TN>(eo, a, pos);
@@ -360,6 +495,44 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
+}
+
+template <typename T, int BM, int BN, int MODE>
+static hipError_t launch_fused_one(const ConvArgs &a, hipStream_t s) {
+    constexpr int NS = RingDepth<BM, BN, 64>::value;
+    constexpr size_t ring = (size_t)NS * (BM + BN) * 64 * 2;
+    auto kern = conv_dlds_kernel<T, BM, BN, 2, 2, 64, NS, MODE, false, true>;
+    constexpr size_t bias_off = std::max<size_t>(ring, fused_lds_bytes(BM, BN));
+    const size_t need = bias_off + (size_t)(BN + a.Cout2) * 4;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 (int)(bias_off + (BN + kFusedMaxCout2) * 4));
+    if (attr != hipSuccess) return attr;
+    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256, need, s>>>(a);
+    return hipGetLastError();
+}
+
+void conv_fused_grid(int bm, const ConvArgs &a, dim3 *grid, int *block) {
+    *grid = dim3((a.M + bm - 1) / bm, 1, 1);
+    *block = 256;
+}
+
+hipError_t launch_conv_fused(DType dt, int bm, const ConvArgs &a, hipStream_t s) {
+    // first layer: any convolution this kernel takes, Cout 64 or 128, whole K in one workgroup;
+    // second layer: 1x1 over its output with a residual
+    if (a.Cin % 64 != 0 || a.K != a.kh * a.kw * a.Cin || a.K % 64 != 0 || a.split_k != 1 || a.ktiles_per_split != a.K / 64 || a.partial)
+        return hipErrorInvalidValue;
+    if ((a.Cout != 64 && a.Cout != 128) || (bm != 64 && bm != 128) || (bm == 128 && a.Cout == 128)) return hipErrorInvalidValue;
+    if (!a.w2 || !a.bias2 || !a.res || a.Cout2 < a.Cout || a.Cout2 % a.Cout != 0 || a.Cout2 > kFusedMaxCout2) return hipErrorInvalidValue;
+    if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;
+    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
+    const bool gemm = a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0;
+#define CW_FUSED(BM_, BN_)                                                                                    \
+    return dt == DT_F16 ? (gemm ? launch_fused_one<f16, BM_, BN_, MODE_GEMM>(a, s) : launch_fused_one<f16, BM_, BN_, MODE_CONV>(a, s)) \
+                        : (gemm ? launch_fused_one<bf16, BM_, BN_, MODE_GEMM>(a, s) : launch_fused_one<bf16, BM_, BN_, MODE_CONV>(a, s))
+    if (a.Cout == 64 && bm == 128) { CW_FUSED(128, 64); }
+    if (a.Cout == 64) { CW_FUSED(64, 64); }
+    CW_FUSED(64, 128);
+#undef CW_FUSED
 }
 
 template <typename T, bool SPLITK>

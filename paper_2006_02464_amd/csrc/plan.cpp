@@ -300,6 +300,34 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = i;
         if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) last_use[m.ops[i].residual_from] = i;
     }
+    // Pairs planned as one launch: op i = a convolution with 64 or 128 output channels (Cin % 64
+    // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
+    // convolution with a residual; enough pixels for the launch to fill the GPU.
+    std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0);
+    if (ov.fuse && !ov.keep_all && ov.tile < 0 && ov.split_k <= 0) {
+        std::vector<int> uses(n_ops, 0);
+        for (int i = 0; i < n_ops; ++i) {
+            if (m.ops[i].input_from >= 0) ++uses[m.ops[i].input_from];
+            if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) ++uses[m.ops[i].residual_from];
+        }
+        for (int i = 1; i + 1 < n_ops; ++i) {
+            const cw_op &o1 = m.ops[i];
+            if (o1.op != CW_OP_CONV || o1.residual_from >= 0 || o1.input_from < 0 || o1.cin % 64 != 0 || uses[i] != 1) continue;
+            if ((o1.cout != 64 && o1.cout != 128) || o1.kh * o1.kw > 32 || o1.kh != o1.kw) continue;
+            int j = -1;
+            for (int t = i + 1; t <= i + 2 && t < n_ops; ++t)
+                if (m.ops[t].op == CW_OP_CONV && m.ops[t].input_from == i) j = t;
+            if (j < 0) continue;
+            const cw_op &o2 = m.ops[j];
+            if (o2.kh != 1 || o2.kw != 1 || o2.stride != 1 || o2.pad != 0 || o2.residual_from < 0 || o2.residual_from == i) continue;
+            if (o2.cin != o1.cout || o2.cout % o1.cout != 0 || o2.cout > 1024) continue;
+            const int64_t M = (int64_t)batch * m.shapes[i].h * m.shapes[i].w;
+            const int bm = (o1.cout == 64 && M / 128 >= 256) ? 128 : 64;
+            if ((M + bm - 1) / bm < 190) continue;
+            fuse_into[i] = j; fused_first[j] = i; fused_bm[j] = bm;
+            last_use[o1.input_from] = std::max(last_use[o1.input_from], j);  // read by the fused launch at j
+        }
+    }
     std::vector<size_t> out_bytes(n_ops, 0);
     RangeAllocator arena((size_t)1 << 46);
     auto ws_alloc = [&](size_t bytes) {
@@ -342,6 +370,47 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         switch (o.op) {
             case CW_OP_CONV: {
                 const WeightSlot &ws = m.wslots[m.op_wslot[i]];
+                if (fuse_into[i] >= 0) break;  // computed inside the launch of op fuse_into[i]; its output is never stored
+                if (fused_first[i] >= 0) {
+                    const int f = fused_first[i];
+                    const cw_op &o1 = m.ops[f];
+                    const OpShape &s1 = m.shapes[f];
+                    const OpShape &sin = m.shapes[o1.input_from];
+                    const WeightSlot &ws1 = m.wslots[m.op_wslot[f]];
+                    out_bytes[i] = (size_t)batch * os.h * os.w * os.c * esz;
+                    p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
+                    Launch l{};
+                    l.kind = K_CONV;
+                    l.op_index = i;
+                    l.fused_bm = fused_bm[i];
+                    ConvArgs &a = l.conv;
+                    a.B = batch; a.H = sin.h; a.W = sin.w; a.Cin = o1.cin; a.Ho = s1.h; a.Wo = s1.w; a.Cout = o1.cout;
+                    a.kh = o1.kh; a.kw = o1.kw; a.kwp = o1.kw; a.khp = o1.kh; a.stride = o1.stride; a.pad = o1.pad;
+                    a.M = batch * s1.h * s1.w;
+                    a.K = o1.kh * o1.kw * o1.cin;
+                    a.relu = o1.relu;
+                    a.split_k = 1; a.ktiles_per_split = a.K / 64;
+                    a.wo_div = make_fast_div((uint32_t)s1.w);
+                    a.ho_div = make_fast_div((uint32_t)s1.h);
+                    a.Cout2 = o.cout; a.relu2 = o.relu;
+                    l.x = p.op_out[o1.input_from];
+                    l.w = Ref{SP_WEIGHTS, ws1.packed_w_off};
+                    l.bias = Ref{SP_WEIGHTS, ws1.packed_b_off};
+                    l.w2 = Ref{SP_WEIGHTS, ws.packed_w_off};
+                    l.bias2 = Ref{SP_WEIGHTS, ws.packed_b_off};
+                    l.res = p.op_out[o.residual_from];
+                    l.y = p.op_out[i];
+                    const int64_t in_pixels = (o1.kh == 1 && o1.stride > 1) ? (int64_t)a.M : (int64_t)batch * sin.h * sin.w;
+                    l.info.fused_op = f;
+                    l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = a.K;
+                    l.info.flops = 2 * (int64_t)a.M * a.Cout * a.K + 2 * (int64_t)a.M * o.cout * o.cin;
+                    l.info.bytes = in_pixels * o1.cin * esz + ((int64_t)o1.cout * a.K + (int64_t)o.cout * o.cin) * esz + (o1.cout + o.cout) * 4 +
+                                   2 * (int64_t)out_bytes[i];
+                    l.info.tile_m = l.fused_bm; l.info.tile_n = a.Cout; l.info.tile_k = 64; l.info.split_k = 1;
+                    snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1", o1.kh, o1.kw, o1.stride);
+                    p.launches.push_back(l);
+                    break;
+                }
                 out_bytes[i] = (size_t)batch * os.h * os.w * os.c * esz;
                 p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
                 Launch l{};
@@ -475,7 +544,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         dim3 g(1, 1, 1);
         int b = 0;
         switch (l.kind) {
-            case K_CONV: conv_grid(l.tile, l.conv, &g, &b); break;
+            case K_CONV:
+                if (l.fused_bm > 0) conv_fused_grid(l.fused_bm, l.conv, &g, &b);
+                else conv_grid(l.tile, l.conv, &g, &b);
+                break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
@@ -483,6 +555,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
         }
         l.info.op_index = l.op_index;
+        if (l.fused_bm <= 0) l.info.fused_op = -1;
         l.info.kind = l.kind;
         l.info.grid_x = g.x; l.info.grid_y = g.y; l.info.grid_z = g.z; l.info.block = b;
         if (l.info.split_k == 0) l.info.split_k = 1;

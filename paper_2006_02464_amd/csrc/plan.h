@@ -25,6 +25,7 @@ struct Launch {
     int32_t op_index;
     ConvTile tile = T64x64;
     bool stem = false;
+    int32_t fused_bm = 0;  // > 0: this convolution and the 1x1 one after it in one launch (pixels per workgroup)
     // Shape fields are final; pointer fields are filled from the Refs at EXEC time.
     ConvArgs conv{};
     CastArgs cast{};
@@ -32,6 +33,7 @@ struct Launch {
     FcArgs fc{};
     SoftmaxArgs sm{};
     Ref x, w, bias, res, y, partial, counters;
+    Ref w2, bias2;         // second layer of a fused launch
     cw_launch_info info{};
 };
 
@@ -66,6 +68,7 @@ struct PlanOverride {
     int32_t tile = -1;     // ConvTile or -1 = automatic
     int32_t split_k = 0;   // 0 = automatic
     bool keep_all = false; // no workspace reuse (debug read-back)
+    bool fuse = true;      // allow two-layer launches
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 

@@ -84,7 +84,7 @@ class Bench:
         mid = self._define(batch, {})
         out = {}
         for l in self.wk.ctx.plan(mid, batch):
-            if l["kind"] != 1:
+            if l["kind"] != 1 or l["fused_op"] >= 0:   # a fused pair has its own fixed tile
                 continue
             o = self.ops[l["op_index"]]
             key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride

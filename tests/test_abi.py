@@ -58,8 +58,9 @@ def test_plan_is_fixed_and_covers_every_op(ctx):
     for b in (1, 2, 4, 8, 16):
         plan = ctx.plan(m, b)
         assert plan == ctx.plan(m2, b)                      # pure function of (model, batch)
-        ops_hit = {l["op_index"] for l in plan}
-        assert ops_hit == set(range(57))
+        ops_hit = {l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0}
+        assert ops_hit == set(range(57))                    # a fused launch covers two ops
+        assert len(plan) == 58 - sum(l["fused_op"] >= 0 for l in plan)
         flops = sum(l["flops"] for l in plan)
         assert flops == 2 * b * T.mac_count(T.resnet(50), 224, 224)
         for l in plan:
@@ -150,14 +151,16 @@ def test_device_calls_on_planning_context_fail_loudly(ctx):
 def test_plan_table_rows_take_precedence(ctx):
     m0 = ctx.model_define_resnet(50, 224, 224)
     base = ctx.plan(m0, 16)
-    target = next(l for l in base if l["kind"] == 1 and l["gemm_k"] == 576)      # a 3x3 of stage 1
+    target = next(l for l in base if l["kind"] == 1 and l["gemm_k"] == 2304 and l["fused_op"] < 0)   # a 3x3 of stage 3
     other = "64x32" if (target["tile_m"], target["tile_n"]) != (64, 32) else "32x64"
-    ctx.set_plan_table([(target["gemm_m"], target["gemm_n"], target["gemm_k"], 3, 1, other, 2)])
+    ops = ctx.model_get_ops(m0)
+    stride = ops[target["op_index"]][5]
+    ctx.set_plan_table([(target["gemm_m"], target["gemm_n"], target["gemm_k"], 3, stride, other, 2)])
     try:
         m1 = ctx.model_define_resnet(50, 224, 224)
         plan = ctx.plan(m1, 16)
         for a, b in zip(base, plan):
-            if a["kind"] == 1 and (a["gemm_m"], a["gemm_n"], a["gemm_k"]) == (target["gemm_m"], target["gemm_n"], 576):
+            if a["kind"] == 1 and (a["gemm_m"], a["gemm_n"], a["gemm_k"], ops[a["op_index"]][5]) == (target["gemm_m"], target["gemm_n"], 2304, stride):
                 assert "%dx%d" % (b["tile_m"], b["tile_n"]) == other and b["split_k"] == 2
             else:
                 assert (a["tile_m"], a["tile_n"], a["split_k"]) == (b["tile_m"], b["tile_n"], b["split_k"])
@@ -167,3 +170,29 @@ def test_plan_table_rows_take_precedence(ctx):
         ctx.set_plan_table([])
     m2 = ctx.model_define_resnet(50, 224, 224)
     assert ctx.plan(m2, 16) == base
+
+
+def test_fusion_of_bottleneck_tail(ctx):
+    """At batch 16 the 3x3 + 1x1 tail of every stage-1 and stage-2 bottleneck of ResNet-50 is one
+    launch; with fusion off, with debug retention, or at batch 1 (too few pixels) it is two."""
+    m = ctx.model_define_resnet(50, 224, 224)
+    ops = ctx.model_get_ops(m)
+    fused = [l for l in ctx.plan(m, 16) if l["fused_op"] >= 0]
+    assert len(fused) == 7
+    for l in fused:
+        first, second = ops[l["fused_op"]], ops[l["op_index"]]
+        assert first[3] == 3 and second[3] == 1 and second[1] == first[2] and first[2] in (64, 128)
+        assert l["grid_x"] == -(-l["gemm_m"] // l["tile_m"]) and l["grid_y"] == 1 and l["split_k"] == 1
+    assert not [l for l in ctx.plan(m, 1) if l["fused_op"] >= 0]
+    ctx.set_fusion(0)
+    try:
+        m2 = ctx.model_define_resnet(50, 224, 224)
+        assert not [l for l in ctx.plan(m2, 16) if l["fused_op"] >= 0]
+    finally:
+        ctx.set_fusion(1)
+    ctx.set_debug_keep(True)
+    try:
+        m3 = ctx.model_define_resnet(50, 224, 224)
+        assert not [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0]
+    finally:
+        ctx.set_debug_keep(False)

@@ -248,6 +248,34 @@ def test_resnet50_224_batch16(worker, r50):
     worker.ctx.unload_weights(mid)
 
 
+def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
+    """Batch 16 and 8 plan the 3x3 + 1x1 tail of the early bottlenecks as one launch.  Both plans
+    must meet the tolerance against the oracle, and they compute the same sums in the same order
+    (the intermediate is rounded to the storage type either way), so they should agree far more
+    closely than either does with the fp32 oracle."""
+    case, x, ref = r50
+    ctx = worker.ctx
+    fused = ctx.model_define_resnet(50, 224, 224)
+    ctx.set_fusion(0)
+    try:
+        plain = ctx.model_define_resnet(50, 224, 224)
+    finally:
+        ctx.set_fusion(1)
+    for batch in (16, 8):
+        n_fused = sum(l["fused_op"] >= 0 for l in ctx.plan(fused, batch))
+        assert n_fused > 0 and not any(l["fused_op"] >= 0 for l in ctx.plan(plain, batch))
+        out = {}
+        for name, mid in (("fused", fused), ("plain", plain)):
+            worker.load(mid, case.blob)
+            out[name] = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 16, batch)])
+            ctx.unload_weights(mid)
+            assert rel_err_per_sample(out[name], ref).max() <= TOL
+            assert np.array_equal(N.argmax(out[name]), N.argmax(ref))
+        d = rel_err_per_sample(out["fused"], out["plain"]).max()
+        print("batch %d: %d fused launches, fused vs plain max rel diff %.3e" % (batch, n_fused, d))
+        assert d <= 2e-3
+
+
 @pytest.mark.parametrize("batch", [1, 2, 4, 8])
 def test_resnet50_224_small_batches(worker, r50, batch):
     case, x, ref = r50
