@@ -95,17 +95,29 @@ __global__ __launch_bounds__(64) void gavgpool_kernel(const PoolArgs a) {
 }
 
 // ---- FC: z[n][j] = bias[j] + sum_i f[n][i] * W[j][i], fp32 features, fp32 result ---------
-// A workgroup computes 16 outputs x 16 samples on the fp32 matrix cores
-// (v_mfma_f32_16x16x4_f32: 16 output rows x 16 sample columns x 4 k per instruction).  Its 8 waves
-// split K; wave w walks chunks of 32 k: lane (r = lane%16, g = lane/16) loads 8 consecutive
-// weights of output row r and 8 consecutive features of sample r, both at k = chunk + 8g, and
-// issues 8 MFMAs, the e-th one multiplying the e-th element of each (the k index of an MFMA is
-// only a summation label, so any pairing that both operands share is valid).  The layer streams
+// A workgroup computes 16 outputs x 16 samples on the matrix cores (v_mfma_f32_16x16x32 in the
+// storage type: 16 output rows x 16 sample columns x 32 k per instruction).  Its 8 waves split K;
+// wave w walks chunks of 32 k: lane (r = lane%16, g = lane/16) loads 8 consecutive weights of
+// output row r and 8 consecutive features of sample r, both at k = chunk + 8g.  The layer streams
 // its weights once from HBM, so the loads of four chunks are requested together before their 32
 // MFMAs: the memory latency is paid once per 128 k, not once per chunk.  The eight partial
 // 16x16 tiles are summed through LDS in wave order, the bias is added and the logits written.
 typedef float fc_f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFcWaves = 8;
+template <typename T>
+struct FcMfma;
+template <>
+struct FcMfma<f16> {
+    typedef _Float16 elem;
+    typedef _Float16 v8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ fc_f32x4 mma(v8 rows, v8 cols, fc_f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(rows, cols, c, 0, 0, 0); }
+};
+template <>
+struct FcMfma<bf16> {
+    typedef __bf16 elem;
+    typedef __bf16 v8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ fc_f32x4 mma(v8 rows, v8 cols, fc_f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(rows, cols, c, 0, 0, 0); }
+};
 
 template <typename T>
 __global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const FcArgs a) {
@@ -136,10 +148,21 @@ __global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const FcArgs a) {
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const T *wv = reinterpret_cast<const T *>(&wraw[u]);
+            // 16x16x32 MFMA in the storage type: the lane's 8 weights and 8 features are exactly its
+            // operand fragments (row/column lane%16, k = 8*(lane/16)..+7).  The fp32 features are
+            // split into a storage-type head and the rounding remainder, two MFMAs per chunk, so
+            // nothing of the fp32 value is lost beyond the remainder's own rounding (2^-22 relative
+            // for fp16, 2^-17 for bf16).
             const float fv[8] = {f0[u].x, f0[u].y, f0[u].z, f0[u].w, f1[u].x, f1[u].y, f1[u].z, f1[u].w};
+            typename FcMfma<T>::v8 hi, lo;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(to_f32(wv[e]), fv[e], acc, 0, 0, 0);
+            for (int e = 0; e < 8; ++e) {
+                hi[e] = (typename FcMfma<T>::elem)fv[e];
+                lo[e] = (typename FcMfma<T>::elem)(fv[e] - (float)hi[e]);
+            }
+            const typename FcMfma<T>::v8 wv = *reinterpret_cast<const typename FcMfma<T>::v8 *>(&wraw[u]);
+            acc = FcMfma<T>::mma(wv, hi, acc);
+            acc = FcMfma<T>::mma(wv, lo, acc);
         }
     }
     // lane holds column (sample) lane%16, rows (outputs) 4*(lane/16) + e
