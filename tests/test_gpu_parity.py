@@ -181,6 +181,43 @@ def test_every_conv_tile_and_split_k(worker, tile, split_k):
     worker.ctx.unload_weights(mid)
 
 
+# ---------------------------------------------------------------- shapes off the ResNet path
+def test_small_custom_net_narrow_channels_and_odd_stride_stem(worker):
+    """A net none of whose layers takes the main kernel: a 3x3 stride-1 first convolution (odd
+    stride: the register-staged stem with 3 filter rows), Cin = 32 and Cin = 96 (K slices of 32),
+    a 5x5 convolution, a residual over a 1x1.  Every layer teacher-forced against the oracle."""
+    O = T.Op
+    ops = [
+        O(T.CONV, 3, 32, 3, 3, 1, 1, 1, -1, -1),        # 0  first conv, stride 1
+        O(T.CONV, 32, 96, 3, 3, 1, 1, 1, -1, 0),        # 1  Cin 32
+        O(T.CONV, 96, 64, 1, 1, 1, 0, 1, -1, 1),        # 2  Cin 96, 1x1
+        O(T.MAXPOOL, 64, 64, 3, 3, 2, 1, 0, -1, 2),     # 3
+        O(T.CONV, 64, 96, 5, 5, 2, 2, 1, -1, 3),        # 4  5x5 stride 2 (main kernel, 25 taps)
+        O(T.CONV, 96, 96, 3, 3, 1, 1, 0, -1, 4),        # 5  Cin 96, no activation
+        O(T.CONV, 96, 96, 1, 1, 1, 0, 1, 4, 5),         # 6  Cin 96 with a residual
+        O(T.CONV, 96, 256, 3, 3, 2, 1, 1, -1, 6),       # 7
+        O(T.GAVGPOOL, 256, 256, 0, 0, 1, 0, 0, -1, 7),  # 8
+        O(T.FC, 256, 10, 1, 1, 1, 0, 0, -1, 8),         # 9
+        O(T.SOFTMAX, 10, 10, 0, 0, 1, 0, 0, -1, 9),     # 10
+    ]
+    case = Case(ops, 45, seed=5, dist="uniform")         # odd size: ragged rows and floor division
+    worker.ctx.set_debug_keep(True)
+    try:
+        mid = worker.ctx.model_define(case.ops, 3, 45, 45, batch_sizes=(1, 5))
+    finally:
+        worker.ctx.set_debug_keep(False)
+    plan = worker.ctx.plan(mid, 5)
+    assert {l["tile_k"] for l in plan if l["kind"] == 1} == {32, 64}
+    worker.load(mid, case.blob)
+    for batch in (5, 1):
+        x = case.images(0, batch)
+        probs, logits, _ = worker.infer(mid, x, classes=10)
+        outs, _, gpu = check_all_ops(worker, case, mid, batch, x)
+        check_head(case, gpu[-1], logits, probs)
+        assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+    worker.ctx.unload_weights(mid)
+
+
 # ---------------------------------------------------------------- bf16
 def test_resnet18_bf16(worker):
     case = Case(T.resnet(18), 64, seed=2, dtype="bf16", dist="uniform")
