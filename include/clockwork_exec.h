@@ -178,6 +178,7 @@ int32_t cw_plan_num_launches(cw_ctx *ctx, int32_t model_id, int32_t batch);
 typedef struct {
     int32_t op_index;      /* which op of the model this launch belongs to (fused launch: the last) */
     int32_t fused_op;      /* -1, or the op this launch computes first, fused with op_index */
+    int32_t proj_op;       /* -1, or the projection-shortcut op this launch computes as well */
     int32_t kind;          /* internal kernel family id */
     int32_t grid_x, grid_y, grid_z, block;
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */

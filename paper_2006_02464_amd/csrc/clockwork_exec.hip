@@ -141,6 +141,9 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hi
             if (l.fused_bm > 0) {
                 a.w2 = resolve(c, m, s, l.w2);
                 a.bias2 = reinterpret_cast<const float *>(resolve(c, m, s, l.bias2));
+                a.x2 = resolve(c, m, s, l.x2);
+                a.wd = resolve(c, m, s, l.wd);
+                a.biasd = reinterpret_cast<const float *>(resolve(c, m, s, l.biasd));
                 return launch_conv_fused(dt, l.fused_bm, a, st);
             }
             return launch_conv(dt, l.tile, l.stem, a, st);

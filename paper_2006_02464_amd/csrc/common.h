@@ -59,6 +59,12 @@ struct ConvArgs {
     const void *w2;      // packed [Cout2][Cout]
     const float *bias2;  // [Cout2]
     int32_t Cout2, relu2;
+    // Optional projection shortcut computed in the same launch instead of read as `res`:
+    // res[m][:] = biasd + Wd * x2[m][:], x2 = [M][Cout] pixels aligned with the output (a 1x1
+    // stride-1 projection of a tensor with Cout channels).  wd == nullptr: `res` is read.
+    const void *x2;      // NHWC [M][Cout]
+    const void *wd;      // packed [Cout2][Cout]
+    const float *biasd;  // [Cout2]
 };
 
 struct CastArgs {

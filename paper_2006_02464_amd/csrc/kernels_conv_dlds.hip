@@ -59,7 +59,10 @@ extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 // buffers of {a chunk of W2, the matching residual tile}.  Both layers' biases sit behind
 // whichever is larger, this or the ring, from the start of the kernel.
 constexpr unsigned fused_lds_bytes(int bm, int bn) {
-    return (unsigned)(bm * bn * 2 + 2 * (bn * bn * 2 + bm * bn * 2));
+    const int p = bm * bn * 2, w2 = bn * bn * 2, r = bm * bn * 2;
+    // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile
+    const int plain = 2 * (w2 + r), proj = bn == 64 ? 4 * w2 + r : 0;
+    return (unsigned)(p + (plain > proj ? plain : proj));
 }
 constexpr int kFusedMaxCout2 = 1024;
 
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     if constexpr (FUSED) {
         float *sb = reinterpret_cast<float *>(cw_dyn_lds + BIAS_OFF);
         for (int n = tid; n < BN; n += 64 * WARPS_M * WARPS_N) sb[n] = a.bias[n];
-        for (int n = tid; n < a.Cout2; n += 64 * WARPS_M * WARPS_N) sb[BN + n] = a.bias2[n];
+        for (int n = tid; n < a.Cout2; n += 64 * WARPS_M * WARPS_N) sb[BN + n] = a.bias2[n] + (a.wd ? a.biasd[n] : 0.f);
     }
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -353,12 +356,36 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             const unsigned m = m0 + row;
             r_voff[j] = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + c * 8) * 2u : kOob;
         }
+        // With a projection shortcut (a.wd): no residual tile is read.  The x2 tile (BM x BN) is
+        // fetched once with chunk 0 and stays; per chunk Wd[chunk] (BN x BN) comes with W2[chunk],
+        // and the chunk's sum runs over both products (K = 2*BN).
+        const bool proj = BN == 64 && a.wd != nullptr;  // uniform
+        const u32x4 dwd = make_desc(proj ? a.wd : a.w2, (unsigned)a.Cout2 * BN * 2u);
+        const u32x4 dx2 = make_desc(proj ? a.x2 : a.res, (unsigned)a.M * BN * 2u);
+        unsigned x2_voff[R_PER];
+#pragma unroll
+        for (int j = 0; j < R_PER; ++j) {
+            const int cid = tid + j * NT, row = cid / CP2, c = (cid % CP2) ^ swz_key<BN>(row);
+            const unsigned m = m0 + row;
+            x2_voff[j] = m < (unsigned)a.M ? (m * (unsigned)BN + c * 8) * 2u : kOob;
+        }
+        constexpr unsigned XB_OFF = P_BYTES + 4 * W2_BYTES;   // x2 tile, projection form only
+        auto buf_off = [&](int c) { return P_BYTES + (unsigned)(c & 1) * (proj ? 2 * W2_BYTES : BUF_BYTES); };
         auto issue_chunk = [&](int c) {
-            const unsigned dst = lds_base + P_BYTES + (unsigned)(c & 1) * BUF_BYTES + (unsigned)wave * 1024u;
+            const unsigned dst = lds_base + buf_off(c) + (unsigned)wave * 1024u;
 #pragma unroll
             for (int j = 0; j < W2_PER; ++j) load_to_lds(dw2, w2_voff[j], (unsigned)c * (BN * BN * 2u), dst + j * (NT * 16));
+            if (proj) {
 #pragma unroll
-            for (int j = 0; j < R_PER; ++j) load_to_lds(dres, r_voff[j], (unsigned)c * (BN * 2u), dst + W2_BYTES + j * (NT * 16));
+                for (int j = 0; j < W2_PER; ++j) load_to_lds(dwd, w2_voff[j], (unsigned)c * (BN * BN * 2u), dst + W2_BYTES + j * (NT * 16));
+                if (c == 0) {
+#pragma unroll
+                    for (int j = 0; j < R_PER; ++j) load_to_lds(dx2, x2_voff[j], 0u, lds_base + XB_OFF + (unsigned)wave * 1024u + j * (NT * 16));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < R_PER; ++j) load_to_lds(dres, r_voff[j], (unsigned)c * (BN * 2u), dst + W2_BYTES + j * (NT * 16));
+            }
         };
 
         // every wave is done with the ring (the last slice's barrier came before its MFMAs)
@@ -386,26 +413,31 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             // every wave has finished reading the buffer that chunk c+1 is about to overwrite
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
             if (c + 1 < chunks) issue_chunk(c + 1);
-            const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + P_BYTES + (unsigned)(c & 1) * BUF_BYTES);
-            const T *sR = reinterpret_cast<const T *>(cw_dyn_lds + P_BYTES + (unsigned)(c & 1) * BUF_BYTES + W2_BYTES);
+            const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
+            const T *sR = sW2 + BN * BN;   // residual tile, or Wd[chunk] in projection form
+            const T *sXb = reinterpret_cast<const T *>(cw_dyn_lds + XB_OFF);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            auto product = [&](const T *sA, const T *sB) {
 #pragma unroll
-            for (int kk = 0; kk < BN / 16; ++kk) {
-                v8 px[TM], pw[TN];
+                for (int kk = 0; kk < BN / 16; ++kk) {
+                    v8 px[TM], pw[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sP + swz<BN>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+                    for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sA + swz<BN>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
-                for (int j = 0; j < TN; ++j) pw[j] = *reinterpret_cast<const v8 *>(sW2 + swz<BN>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+                    for (int j = 0; j < TN; ++j) pw[j] = *reinterpret_cast<const v8 *>(sB + swz<BN>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(pw[j], px[i], acc[i][j]);
-            }
+                        for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(pw[j], px[i], acc[i][j]);
+                }
+            };
+            product(sP, sW2);
+            if (proj) product(sXb, sR);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const unsigned m = m0 + wm0 + i * 32 + lrow;
@@ -414,7 +446,8 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const int nl = wn0 + j * 32 + q * 16 + lhalf * 8;   // channel inside the chunk
-                        const u32x4 rraw = *reinterpret_cast<const u32x4 *>(sR + swz<BN>(wm0 + i * 32 + lrow, nl >> 3));
+                        u32x4 rraw = *reinterpret_cast<const u32x4 *>(sR + swz<BN>(wm0 + i * 32 + lrow, nl >> 3));
+                        if (proj) rraw = u32x4{0u, 0u, 0u, 0u};   // the shortcut is already in the sum
                         const T *r = reinterpret_cast<const T *>(&rraw);
                         const float *b = sBias + c * BN + nl;
                         T out[8];
@@ -522,7 +555,9 @@ hipError_t launch_conv_fused(DType dt, int bm, const ConvArgs &a, hipStream_t s)
     if (a.Cin % 64 != 0 || a.K != a.kh * a.kw * a.Cin || a.K % 64 != 0 || a.split_k != 1 || a.ktiles_per_split != a.K / 64 || a.partial)
         return hipErrorInvalidValue;
     if ((a.Cout != 64 && a.Cout != 128) || (bm != 64 && bm != 128) || (bm == 128 && a.Cout == 128)) return hipErrorInvalidValue;
-    if (!a.w2 || !a.bias2 || !a.res || a.Cout2 < a.Cout || a.Cout2 % a.Cout != 0 || a.Cout2 > kFusedMaxCout2) return hipErrorInvalidValue;
+    if (!a.w2 || !a.bias2 || a.Cout2 < a.Cout || a.Cout2 % a.Cout != 0 || a.Cout2 > kFusedMaxCout2) return hipErrorInvalidValue;
+    if (a.wd ? (a.Cout != 64 || !a.x2 || !a.biasd) : !a.res) return hipErrorInvalidValue;
+    if (!a.res && !a.wd) return hipErrorInvalidValue;
     if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     const bool gemm = a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0;

@@ -303,7 +303,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // Pairs planned as one launch: op i = a convolution with 64 or 128 output channels (Cin % 64
     // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
     // convolution with a residual; enough pixels for the launch to fill the GPU.
-    std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0);
+    std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), proj_of(n_ops, -1);
     if (ov.fuse && !ov.keep_all && ov.tile < 0 && ov.split_k <= 0) {
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
@@ -326,6 +326,19 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             if ((M + bm - 1) / bm < 190) continue;  // measured: below that the two-launch form is faster
             fuse_into[i] = j; fused_first[j] = i; fused_bm[j] = bm;
             last_use[o1.input_from] = std::max(last_use[o1.input_from], j);  // read by the fused launch at j
+            // The residual of op j may itself be a projection of a tensor as wide as op i's output
+            // and aligned with it pixel for pixel (1x1, stride 1, no activation, used by nothing
+            // else): then it is computed inside the launch too (64-channel form only).
+            const int d = o2.residual_from;
+            const cw_op &od = m.ops[d];
+            if (o1.cout == 64 && od.op == CW_OP_CONV && od.kh == 1 && od.kw == 1 && od.stride == 1 && od.pad == 0 && !od.relu &&
+                od.residual_from < 0 && od.input_from >= 0 && od.cin == o1.cout && od.cout == o2.cout && uses[d] == 1 && d < j &&
+                fuse_into[d] < 0 && fused_first[d] < 0 && m.shapes[od.input_from].h == m.shapes[i].h &&
+                m.shapes[od.input_from].w == m.shapes[i].w) {
+                proj_of[j] = d;
+                fuse_into[d] = j;
+                last_use[od.input_from] = std::max(last_use[od.input_from], j);
+            }
         }
     }
     std::vector<size_t> out_bytes(n_ops, 0);
@@ -398,16 +411,29 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     l.bias = Ref{SP_WEIGHTS, ws1.packed_b_off};
                     l.w2 = Ref{SP_WEIGHTS, ws.packed_w_off};
                     l.bias2 = Ref{SP_WEIGHTS, ws.packed_b_off};
-                    l.res = p.op_out[o.residual_from];
                     l.y = p.op_out[i];
                     const int64_t in_pixels = (o1.kh == 1 && o1.stride > 1) ? (int64_t)a.M : (int64_t)batch * sin.h * sin.w;
                     l.info.fused_op = f;
+                    l.info.proj_op = proj_of[i];
                     l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = a.K;
                     l.info.flops = 2 * (int64_t)a.M * a.Cout * a.K + 2 * (int64_t)a.M * o.cout * o.cin;
                     l.info.bytes = in_pixels * o1.cin * esz + ((int64_t)o1.cout * a.K + (int64_t)o.cout * o.cin) * esz + (o1.cout + o.cout) * 4 +
-                                   2 * (int64_t)out_bytes[i];
+                                   (int64_t)out_bytes[i];
+                    if (proj_of[i] >= 0) {
+                        const int d = proj_of[i];
+                        const WeightSlot &wsd = m.wslots[m.op_wslot[d]];
+                        l.x2 = p.op_out[m.ops[d].input_from];
+                        l.wd = Ref{SP_WEIGHTS, wsd.packed_w_off};
+                        l.biasd = Ref{SP_WEIGHTS, wsd.packed_b_off};
+                        l.info.flops += 2 * (int64_t)a.M * m.ops[d].cout * m.ops[d].cin;
+                        l.info.bytes += (int64_t)a.M * m.ops[d].cin * esz + (int64_t)m.ops[d].cout * m.ops[d].cin * esz + m.ops[d].cout * 4;
+                        snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1+proj", o1.kh, o1.kw, o1.stride);
+                    } else {
+                        l.res = p.op_out[o.residual_from];
+                        l.info.bytes += (int64_t)out_bytes[i];   // the residual tensor
+                        snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1", o1.kh, o1.kw, o1.stride);
+                    }
                     l.info.tile_m = l.fused_bm; l.info.tile_n = a.Cout; l.info.tile_k = 64; l.info.split_k = 1;
-                    snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1", o1.kh, o1.kw, o1.stride);
                     p.launches.push_back(l);
                     break;
                 }
@@ -555,7 +581,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
         }
         l.info.op_index = l.op_index;
-        if (l.fused_bm <= 0) l.info.fused_op = -1;
+        if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }
         l.info.kind = l.kind;
         l.info.grid_x = g.x; l.info.grid_y = g.y; l.info.grid_z = g.z; l.info.block = b;
         if (l.info.split_k == 0) l.info.split_k = 1;

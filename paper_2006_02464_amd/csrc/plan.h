@@ -34,6 +34,7 @@ struct Launch {
     SoftmaxArgs sm{};
     Ref x, w, bias, res, y, partial, counters;
     Ref w2, bias2;         // second layer of a fused launch
+    Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
     cw_launch_info info{};
 };
 

@@ -58,9 +58,10 @@ def test_plan_is_fixed_and_covers_every_op(ctx):
     for b in (1, 2, 4, 8, 16):
         plan = ctx.plan(m, b)
         assert plan == ctx.plan(m2, b)                      # pure function of (model, batch)
-        ops_hit = {l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0}
-        assert ops_hit == set(range(57))                    # a fused launch covers two ops
-        assert len(plan) == 58 - sum(l["fused_op"] >= 0 for l in plan)
+        ops_hit = ({l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0} |
+                   {l["proj_op"] for l in plan if l["proj_op"] >= 0})
+        assert ops_hit == set(range(57))                    # a fused launch covers two or three ops
+        assert len(plan) == 58 - sum((l["fused_op"] >= 0) + (l["proj_op"] >= 0) for l in plan)
         flops = sum(l["flops"] for l in plan)
         assert flops == 2 * b * T.mac_count(T.resnet(50), 224, 224)
         for l in plan:
@@ -179,6 +180,9 @@ def test_fusion_of_bottleneck_tail(ctx):
     ops = ctx.model_get_ops(m)
     fused = [l for l in ctx.plan(m, 16) if l["fused_op"] >= 0]
     assert len(fused) == 7
+    assert [l["proj_op"] >= 0 for l in fused] == [True] + [False] * 6   # the stride-1 projection of the first block
+    proj = ops[fused[0]["proj_op"]]
+    assert proj[3] == 1 and proj[5] == 1 and proj[7] == 0 and proj[1] == 64 and proj[2] == 256
     for l in fused:
         first, second = ops[l["fused_op"]], ops[l["op_index"]]
         assert first[3] == 3 and second[3] == 1 and second[1] == first[2] and first[2] in (64, 128)

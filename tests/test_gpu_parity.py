@@ -288,8 +288,9 @@ def test_resnet50_224_batch16(worker, r50):
 def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
     """Batch 16 and 8 plan the 3x3 + 1x1 tail of the early bottlenecks as one launch.  Both plans
     must meet the tolerance against the oracle, and they compute the same sums in the same order
-    (the intermediate is rounded to the storage type either way), so they should agree far more
-    closely than either does with the fp32 oracle."""
+    (the intermediate is rounded to the storage type either way; only a projection shortcut folded
+    into the launch skips its rounding), so they should agree far more closely than either does
+    with the fp32 oracle."""
     case, x, ref = r50
     ctx = worker.ctx
     fused = ctx.model_define_resnet(50, 224, 224)
@@ -310,7 +311,9 @@ def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
             assert np.array_equal(N.argmax(out[name]), N.argmax(ref))
         d = rel_err_per_sample(out["fused"], out["plain"]).max()
         print("batch %d: %d fused launches, fused vs plain max rel diff %.3e" % (batch, n_fused, d))
-        assert d <= 2e-3
+        # identical sums in identical order, except that a projection shortcut computed inside a
+        # fused launch is not rounded to the storage type on its way into the sum
+        assert d <= 5e-3
 
 
 @pytest.mark.parametrize("batch", [1, 2, 4, 8])
