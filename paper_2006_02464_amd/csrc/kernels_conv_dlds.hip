@@ -58,8 +58,9 @@ extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 // LDS bytes of the fused second layer (see the end of the kernel): the first layer's tile, two
 // buffers of {a chunk of W2, the matching residual tile}.  Both layers' biases sit behind
 // whichever is larger, this or the ring, from the start of the kernel.
+constexpr int fused_chunk(int bn) { return bn == 128 ? 64 : bn; }   // second-layer channels per chunk
 constexpr unsigned fused_lds_bytes(int bm, int bn) {
-    const int p = bm * bn * 2, w2 = bn * bn * 2, r = bm * bn * 2;
+    const int p = bm * bn * 2, w2 = fused_chunk(bn) * bn * 2, r = bm * fused_chunk(bn) * 2;
     // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile
     const int plain = 2 * (w2 + r), proj = bn == 64 ? 4 * w2 + r : 0;
     return (unsigned)(p + (plain > proj ? plain : proj));
@@ -327,21 +328,26 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         // BN == Cout: the tile holds every channel of its BM pixels, so the 1x1 convolution that
         // consumes them needs nothing from other workgroups.  p goes to LDS in operand layout
         // (rows of BN elements, swizzled) and stays; the second layer's Cout2 channels are walked
-        // in chunks of BN with the same wave layout and accumulators.  Per chunk, W2[chunk] (BN x BN)
-        // and the residual tile (BM x BN) are fetched straight into LDS, double buffered: chunk
+        // in chunks of BN2 (= BN, or 64 when BN is 128 so that two workgroups still share a CU's
+        // LDS) with the same waves and accumulators.  Per chunk, W2[chunk] (BN2 x BN) and the
+        // residual tile (BM x BN2) are fetched straight into LDS, double buffered: chunk
         // c+1 is requested before the MFMAs of chunk c.  Loads and stores complete in issue order,
         // so when chunk c is awaited only the stores of chunk c-1 may still be outstanding.
-        constexpr int CP2 = BN / 8;                                // 16-byte chunks per row
-        constexpr int W2_PER = BN * CP2 / NT, R_PER = BM * CP2 / NT;
-        static_assert(BN * CP2 % NT == 0 && BM * CP2 % NT == 0, "tile/threads mismatch");
-        constexpr int ST = TM * TN * 2;                            // stores per thread per chunk
-        constexpr unsigned P_BYTES = BM * BN * 2u, W2_BYTES = BN * BN * 2u, R_BYTES = BM * BN * 2u;
+        constexpr int BN2 = fused_chunk(BN);                       // second-layer channels per chunk
+        constexpr int CP2 = BN / 8, CR2 = BN2 / 8;                 // 16-byte chunks per row: p and W2 / residual
+        constexpr int W2_PER = BN2 * CP2 / NT, R_PER = BM * CR2 / NT;
+        static_assert(BN2 * CP2 % NT == 0 && BM * CR2 % NT == 0, "tile/threads mismatch");
+        constexpr int TN2 = BN2 / WARPS_N / 32;                    // channel tiles per wave in the second layer
+        static_assert(TN2 >= 1 && TN2 <= TN, "second-layer wave tile");
+        const int wn2 = (wave % WARPS_N) * (BN2 / WARPS_N);
+        constexpr int ST = TM * TN2 * 2;                           // stores per thread per chunk
+        constexpr unsigned P_BYTES = BM * BN * 2u, W2_BYTES = BN2 * BN * 2u, R_BYTES = BM * BN2 * 2u;
         constexpr unsigned BUF_BYTES = W2_BYTES + R_BYTES;
         static_assert(BIAS_OFF + (BN + kFusedMaxCout2) * 4 <= 160 * 1024, "second layer does not fit the LDS");
         T *sP = lds;
         const float *sBias1 = reinterpret_cast<const float *>(cw_dyn_lds + BIAS_OFF);
         const float *sBias = sBias1 + BN;
-        const int chunks = a.Cout2 / BN;
+        const int chunks = a.Cout2 / BN2;
         const u32x4 dw2 = make_desc(a.w2, (unsigned)a.Cout2 * BN * 2u);
         const u32x4 dres = make_desc(a.res, (unsigned)a.M * a.Cout2 * 2u);
         unsigned w2_voff[W2_PER], r_voff[R_PER];
@@ -352,7 +358,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         }
 #pragma unroll
         for (int j = 0; j < R_PER; ++j) {
-            const int cid = tid + j * NT, row = cid / CP2, c = (cid % CP2) ^ swz_key<BN>(row);
+            const int cid = tid + j * NT, row = cid / CR2, c = (cid % CR2) ^ swz_key<BN2>(row);
             const unsigned m = m0 + row;
             r_voff[j] = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + c * 8) * 2u : kOob;
         }
@@ -374,17 +380,17 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         auto issue_chunk = [&](int c) {
             const unsigned dst = lds_base + buf_off(c) + (unsigned)wave * 1024u;
 #pragma unroll
-            for (int j = 0; j < W2_PER; ++j) load_to_lds(dw2, w2_voff[j], (unsigned)c * (BN * BN * 2u), dst + j * (NT * 16));
+            for (int j = 0; j < W2_PER; ++j) load_to_lds(dw2, w2_voff[j], (unsigned)c * W2_BYTES, dst + j * (NT * 16));
             if (proj) {
 #pragma unroll
-                for (int j = 0; j < W2_PER; ++j) load_to_lds(dwd, w2_voff[j], (unsigned)c * (BN * BN * 2u), dst + W2_BYTES + j * (NT * 16));
+                for (int j = 0; j < W2_PER; ++j) load_to_lds(dwd, w2_voff[j], (unsigned)c * W2_BYTES, dst + W2_BYTES + j * (NT * 16));
                 if (c == 0) {
 #pragma unroll
                     for (int j = 0; j < R_PER; ++j) load_to_lds(dx2, x2_voff[j], 0u, lds_base + XB_OFF + (unsigned)wave * 1024u + j * (NT * 16));
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < R_PER; ++j) load_to_lds(dres, r_voff[j], (unsigned)c * (BN * 2u), dst + W2_BYTES + j * (NT * 16));
+                for (int j = 0; j < R_PER; ++j) load_to_lds(dres, r_voff[j], (unsigned)c * (BN2 * 2u), dst + W2_BYTES + j * (NT * 16));
             }
         };
 
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
             if (c + 1 < chunks) issue_chunk(c + 1);
             const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
-            const T *sR = sW2 + BN * BN;   // residual tile, or Wd[chunk] in projection form
+            const T *sR = sW2 + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
             const T *sXb = reinterpret_cast<const T *>(cw_dyn_lds + XB_OFF);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -425,15 +431,15 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             auto product = [&](const T *sA, const T *sB) {
 #pragma unroll
                 for (int kk = 0; kk < BN / 16; ++kk) {
-                    v8 px[TM], pw[TN];
+                    v8 px[TM], pw[TN2];
 #pragma unroll
                     for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sA + swz<BN>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) pw[j] = *reinterpret_cast<const v8 *>(sB + swz<BN>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
+                    for (int j = 0; j < TN2; ++j) pw[j] = *reinterpret_cast<const v8 *>(sB + swz<BN>(wn2 + j * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(pw[j], px[i], acc[i][j]);
+                        for (int j = 0; j < TN2; ++j) acc[i][j] = Mfma<T>::mma(pw[j], px[i], acc[i][j]);
                 }
             };
             product(sP, sW2);
@@ -442,21 +448,21 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
             for (int i = 0; i < TM; ++i) {
                 const unsigned m = m0 + wm0 + i * 32 + lrow;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN2; ++j)
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
-                        const int nl = wn0 + j * 32 + q * 16 + lhalf * 8;   // channel inside the chunk
-                        u32x4 rraw = *reinterpret_cast<const u32x4 *>(sR + swz<BN>(wm0 + i * 32 + lrow, nl >> 3));
+                        const int nl = wn2 + j * 32 + q * 16 + lhalf * 8;   // channel inside the chunk
+                        u32x4 rraw = *reinterpret_cast<const u32x4 *>(sR + swz<BN2>(wm0 + i * 32 + lrow, nl >> 3));
                         if (proj) rraw = u32x4{0u, 0u, 0u, 0u};   // the shortcut is already in the sum
                         const T *r = reinterpret_cast<const T *>(&rraw);
-                        const float *b = sBias + c * BN + nl;
+                        const float *b = sBias + c * BN2 + nl;
                         T out[8];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             const float v = acc[i][j][8 * q + e] + b[e] + (float)r[e];
                             out[e] = (T)(a.relu2 ? fmaxf(v, 0.f) : v);
                         }
-                        const unsigned o = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + (unsigned)(c * BN + nl)) * 2u : kOob;
+                        const unsigned o = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + (unsigned)(c * BN2 + nl)) * 2u : kOob;
                         __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
                     }
             }
