@@ -3,8 +3,8 @@
 
 A step is one EXEC of ResNet-50 (224x224, fp16 storage, fp32 accumulation) at
 batch 16 over a synthetic batch that is already resident in HBM (INPUT done once
-before the timed region): input cast, stem, max pool, 52 convolutions (14 of
-them as 7 two-layer launches), global average pool, FC and softmax, all through
+before the timed region): input cast, stem, max pool, 52 convolutions (15 of
+them inside 7 fused launches), global average pool, FC and softmax, all through
 the C ABI.  Prints one JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
@@ -25,7 +25,7 @@ BATCHES = (1, 2, 4, 8, 16)
 # HBM-side bytes of the 53 conv launches of one batch-16 EXEC, from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised in profiles/exec_resnet50_b16_hbm_traffic.txt (scaled by a 256 MiB copy).
 # Counters cannot be read from inside this process, so the figure is carried here.
-CONV_TRAFFIC_BYTES_B16 = 1197.6e6
+CONV_TRAFFIC_BYTES_B16 = 1146.2e6
 
 
 def cpu_baseline(seed, log):
