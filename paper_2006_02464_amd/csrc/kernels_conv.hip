@@ -1,4 +1,10 @@
-// Implicit-GEMM convolution on gfx950 MFMA (v_mfma_f32_32x32x16_{f16,bf16}), fp32 accumulate.
+// Implicit-GEMM convolution on gfx950 MFMA (v_mfma_f32_32x32x16_{f16,bf16}), fp32 accumulate:
+// the register-staged kernel, the tile table and the launch entry point.
+//
+// launch_conv() sends every convolution with Cin % 64 == 0, and a first convolution with an even
+// stride, to the direct-to-LDS kernel (kernels_conv_dlds.hip).  The kernel in this file serves
+// what is left: Cin % 64 != 0 (K slices of 32) and a first convolution with an odd stride.  What
+// follows describes the layout and conventions both kernels share, and this kernel's pipeline.
 //
 // GEMM view: M = B*Ho*Wo output pixels (NHWC, so a pixel's Cout values are contiguous),
 // N = Cout, K = kh*kwp*Cin ordered (r, s, c), so that for one filter tap the K slice is the
