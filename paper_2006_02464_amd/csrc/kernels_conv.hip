@@ -295,31 +295,38 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 
 TileDim conv_tile_dim(ConvTile t) {
     switch (t) {
-        case T128x128: return {128, 128, 256, 64};
-        case T128x64: return {128, 64, 256, 64};
-        case T64x64: return {64, 64, 256, 64};
-        case T64x32: return {64, 32, 128, 64};
-        case T32x64: return {32, 64, 128, 64};
-        case T128x64w2: return {128, 64, 128, 64};
-        case T64x128w2: return {64, 128, 128, 64};
-        case T256x64: return {256, 64, 256, 64};
-        case T128x128w8: return {128, 128, 512, 64};
-        case T128x64k128: return {128, 64, 256, 128};
-        case T64x64k128: return {64, 64, 256, 128};
-        case T64x32k128: return {64, 32, 128, 128};
-        case T32x64k128: return {32, 64, 128, 128};
-        case T32x32k128: return {32, 32, 64, 128};
-        default: return {32, 32, 64, 64};
+        case T128x128: return {128, 128, 256, 64, 1};
+        case T128x64: return {128, 64, 256, 64, 1};
+        case T64x64: return {64, 64, 256, 64, 1};
+        case T64x32: return {64, 32, 128, 64, 1};
+        case T32x64: return {32, 64, 128, 64, 1};
+        case T128x64w2: return {128, 64, 128, 64, 1};
+        case T64x128w2: return {64, 128, 128, 64, 1};
+        case T256x64: return {256, 64, 256, 64, 1};
+        case T128x128w8: return {128, 128, 512, 64, 1};
+        case T128x64k128: return {128, 64, 256, 128, 1};
+        case T64x64k128: return {64, 64, 256, 128, 1};
+        case T64x32k128: return {64, 32, 128, 128, 1};
+        case T32x64k128: return {32, 64, 128, 128, 1};
+        case T32x32k128: return {32, 32, 64, 128, 1};
+        case T128x64k128g2: return {128, 64, 512, 128, 2};
+        case T64x64k128g2: return {64, 64, 512, 128, 2};
+        case T64x64k128g4: return {64, 64, 1024, 128, 4};
+        case T64x32k128g4: return {64, 32, 512, 128, 4};
+        case T32x64k128g4: return {32, 64, 512, 128, 4};
+        case T32x32k128g4: return {32, 32, 256, 128, 4};
+        default: return {32, 32, 64, 64, 1};
     }
 }
 
+// The same tile with K slices of 64 and one group of waves (for shapes the tile cannot take).
 ConvTile conv_tile_k64(ConvTile t) {
     switch (t) {
-        case T128x64k128: return T128x64;
-        case T64x64k128: return T64x64;
-        case T64x32k128: return T64x32;
-        case T32x64k128: return T32x64;
-        case T32x32k128: return T32x32;
+        case T128x64k128: case T128x64k128g2: return T128x64;
+        case T64x64k128: case T64x64k128g2: case T64x64k128g4: return T64x64;
+        case T64x32k128: case T64x32k128g4: return T64x32;
+        case T32x64k128: case T32x64k128g4: return T32x64;
+        case T32x32k128: case T32x32k128g4: return T32x32;
         default: return t;
     }
 }
@@ -327,6 +334,17 @@ ConvTile conv_tile_k64(ConvTile t) {
 // The first convolution takes the direct-to-LDS kernel's stem mode when its packed filter has 8
 // rows of 8 taps x 4 channels and its stride is even (16-byte aligned 8-tap windows).
 static bool stem_is_dlds(const ConvArgs &a) { return a.khp == 8 && a.kwp == 8 && a.Cin == 4 && a.stride % 2 == 0 && a.pad == 0; }
+
+ConvTile conv_tile_one_group(ConvTile t) {
+    switch (t) {
+        case T128x64k128g2: return T128x64k128;
+        case T64x64k128g2: case T64x64k128g4: return T64x64k128;
+        case T64x32k128g4: return T64x32k128;
+        case T32x64k128g4: return T32x64k128;
+        case T32x32k128g4: return T32x32k128;
+        default: return t;
+    }
+}
 
 int conv_bk(const ConvArgs &a, bool stem, ConvTile tile) {
     if (stem) return stem_is_dlds(a) ? 64 : 32;

@@ -67,11 +67,16 @@ constexpr unsigned fused_lds_bytes(int bm, int bn) {
 }
 constexpr int kFusedMaxCout2 = 1024;
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const ConvArgs a) {
+// KG > 1: KG groups of WARPS_M x WARPS_N waves share the tile; group g takes the 16-k steps
+// g, g+KG, ... of every slice and the groups' accumulators are added through LDS at the end.  For
+// small tiles with a long K this shortens the per-slice MFMA chain of a wave (and puts several
+// waves on each SIMD) without the global exchange of split-K.
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
+    static_assert(KG == 1 || (!SPLITK && !FUSED && (BK / 16) % KG == 0), "K groups: plain form, whole steps per group");
     static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
-    constexpr int NT = 64 * WARPS_M * WARPS_N;
+    constexpr int NT = 64 * WARPS_M * WARPS_N * KG;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int CPR = BK / 8;  // 16-byte chunks per LDS row
@@ -96,13 +101,15 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     constexpr unsigned BIAS_OFF = FUSED ? (NS * STAGE_BYTES > fused_lds_bytes(BM, BN) ? NS * STAGE_BYTES : fused_lds_bytes(BM, BN)) : 0u;
     if constexpr (FUSED) {
         float *sb = reinterpret_cast<float *>(cw_dyn_lds + BIAS_OFF);
-        for (int n = tid; n < BN; n += 64 * WARPS_M * WARPS_N) sb[n] = a.bias[n];
-        for (int n = tid; n < a.Cout2; n += 64 * WARPS_M * WARPS_N) sb[BN + n] = a.bias2[n] + (a.wd ? a.biasd[n] : 0.f);
+        for (int n = tid; n < BN; n += NT) sb[n] = a.bias[n];
+        for (int n = tid; n < a.Cout2; n += NT) sb[BN + n] = a.bias2[n] + (a.wd ? a.biasd[n] : 0.f);
     }
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave / WARPS_N) * WM;
-    const int wn0 = (wave % WARPS_N) * WN;
+    const int kg = wave / (WARPS_M * WARPS_N);        // K group of this wave
+    const int wq = wave - kg * (WARPS_M * WARPS_N);   // its place in the WARPS_M x WARPS_N layout
+    const int wm0 = (wq / WARPS_N) * WM;
+    const int wn0 = (wq % WARPS_N) * WN;
     const int lrow = lane & 31;
     const int lhalf = lane >> 5;
 
@@ -245,10 +252,12 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     auto compute = [&](int stage, auto with_loads) {
         const T *sX = lds + stage * STAGE;
         const T *sW = sX + BM * BK;
-        constexpr int KK = BK / 16;
-        constexpr int DEPTH = TM * TN >= 4 ? 2 : 4;  // fragment sets held
+        constexpr int KK = BK / 16 / KG;                               // 16-k steps of this wave per slice
+        constexpr int DEPTH0 = TM * TN >= 4 ? 2 : 4;
+        constexpr int DEPTH = DEPTH0 < KK ? DEPTH0 : (KK > 1 ? KK : 2);  // fragment sets held
         v8 fx[DEPTH][TM], fw[DEPTH][TN];
-        auto fetch = [&](int kk, v8(&qx)[TM], v8(&qw)[TN]) {
+        auto fetch = [&](int t, v8(&qx)[TM], v8(&qw)[TN]) {
+            const int kk = KG == 1 ? t : kg + t * KG;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 qx[i] = *reinterpret_cast<const v8 *>(sX + swz<BK>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
@@ -257,17 +266,17 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
                 qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
         };
 #pragma unroll
-        for (int kk = 0; kk < DEPTH - 1; ++kk) fetch(kk, fx[kk], fw[kk]);
+        for (int t = 0; t < DEPTH - 1 && t < KK; ++t) fetch(t, fx[t], fw[t]);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            if (kk + DEPTH - 1 < KK) fetch(kk + DEPTH - 1, fx[(kk + DEPTH - 1) % DEPTH], fw[(kk + DEPTH - 1) % DEPTH]);
+        for (int t = 0; t < KK; ++t) {
+            if (t + DEPTH - 1 < KK) fetch(t + DEPTH - 1, fx[(t + DEPTH - 1) % DEPTH], fw[(t + DEPTH - 1) % DEPTH]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[kk % DEPTH][j], fx[kk % DEPTH][i], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[t % DEPTH][j], fx[t % DEPTH][i], acc[i][j]);
             if (decltype(with_loads)::value) {
 #pragma unroll
-                for (int idx = kk * LOADS / KK; idx < (kk + 1) * LOADS / KK; ++idx) issue_piece(idx);
+                for (int idx = t * LOADS / KK; idx < (t + 1) * LOADS / KK; ++idx) issue_piece(idx);
             }
         }
     };
@@ -309,7 +318,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
         if (u < kt1 - kt) {                         // uniform
             wait_loads_and_barrier<u * LOADS>();
             CW_STAMP(trace_slot++);
-            if (!SPLITK && !FUSED && u == 0) epilogue_load<TM, TN>(eo, a, pos);
+            if (!SPLITK && !FUSED && u == 0 && kg == 0) epilogue_load<TM, TN>(eo, a, pos);
             compute(cur, std::false_type{});
             CW_STAMP(trace_slot++);
             cur = cur + 1 == NS ? 0 : cur + 1;
@@ -320,7 +329,35 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_dlds_kernel(const
     if constexpr (NS >= 3) tail(std::integral_constant<int, 1>{});
     tail(std::integral_constant<int, 0>{});
 
-    if (!SPLITK && !FUSED && nsteps <= 0) epilogue_load<TM, TN>(eo, a, pos);
+    if (!SPLITK && !FUSED && nsteps <= 0 && kg == 0) epilogue_load<TM, TN>(eo, a, pos);
+    if constexpr (KG > 1) {
+        // Groups 1.. hand their accumulators to group 0 through LDS (the ring is free once every
+        // wave has passed the barrier); group 0 adds them in group order and goes on alone.
+        static_assert((KG - 1) * BM * BN * 4 <= NS * (int)STAGE_BYTES, "K-group exchange does not fit the ring");
+        float *xch = reinterpret_cast<float *>(cw_dyn_lds);
+        wait_lds_loads_and_barrier<0>();
+        if (kg > 0) {
+            float *dst = xch + ((kg - 1) * (WARPS_M * WARPS_N) + wq) * (TM * TN * 16 * 64) + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) dst[((i * TN + j) * 16 + e) * 64] = acc[i][j][e];
+        }
+        wait_lds_loads_and_barrier<0>();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KG; ++g) {
+            const float *src = xch + ((g - 1) * (WARPS_M * WARPS_N) + wq) * (TM * TN * 16 * 64) + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] += src[((i * TN + j) * 16 + e) * 64];
+        }
+    }
 
     CW_STAMP_END(60);
     if constexpr (FUSED) {
@@ -484,18 +521,19 @@ struct RingDepth {
     static constexpr int value = (BM + BN) * BK * 2 * 4 <= 80 * 1024 ? 4 : 3;
 };
 
-template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK>
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK, int KG = 1>
 static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_t s) {
     constexpr int NS = RingDepth<BM, BN, BK>::value;
     constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
     static_assert(NS * stage_bytes <= 160 * 1024, "ring does not fit the LDS");
-    auto kern = conv_dlds_kernel<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK>;
+    auto kern = conv_dlds_kernel<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, false, KG>;
     // More than 64 KiB of LDS per workgroup has to be requested once per kernel; done on first
     // use (under LOAD's graph recording or the first plain EXEC), never per launch afterwards.
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(NS * stage_bytes));
     if (attr != hipSuccess) return attr;
-    // a K walk shorter than the ring only ever touches its first stages
-    const size_t used = (size_t)std::min(NS, a.ktiles_per_split) * stage_bytes;
+    // a K walk shorter than the ring only ever touches its first stages (the wave groups' exchange
+    // at the end needs its own room)
+    const size_t used = std::max((size_t)std::min(NS, a.ktiles_per_split) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
     kern<<<grid, block, used, s>>>(a);
     return hipGetLastError();
 }
@@ -531,6 +569,24 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
             return hipErrorInvalidValue;
         case T32x32k128:
             if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T128x64k128g2:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 128, 64, 2, 2, 128, MODE, false, 2>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x64k128g2:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 128, MODE, false, 2>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x64k128g4:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 128, MODE, false, 4>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x32k128g4:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 32, 2, 1, 128, MODE, false, 4>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x64k128g4:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 64, 1, 2, 128, MODE, false, 4>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x32k128g4:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 128, MODE, false, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }

@@ -457,6 +457,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 if (conv_bk(a, l.stem, l.tile) != conv_tile_dim(l.tile).bk) l.tile = conv_tile_k64(l.tile);  // Cin % 128 != 0
                 const int ktiles = a.K / conv_bk(a, l.stem, l.tile);
                 a.split_k = std::max(1, std::min(a.split_k, ktiles));
+                if (a.split_k > 1) l.tile = conv_tile_one_group(l.tile);   // wave groups and split-K exclude each other
                 {
                     const TileDim tdc = conv_tile_dim(l.tile);
                     const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);

@@ -24,7 +24,10 @@ SPLITS = (1, 2, 4, 8, 16)
 TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x32": (64, 32), "32x64": (32, 64),
              "32x32": (32, 32), "256x64": (256, 64), "128x128w8": (128, 128),
              "128x64k128": (128, 64), "64x64k128": (64, 64), "64x32k128": (64, 32), "32x64k128": (32, 64),
-             "32x32k128": (32, 32)}
+             "32x32k128": (32, 32),
+             "128x64k128g2": (128, 64), "64x64k128g2": (64, 64), "64x64k128g4": (64, 64), "64x32k128g4": (64, 32),
+             "32x64k128g4": (32, 64), "32x32k128g4": (32, 32)}
+BASE_THREADS = {(128, 128): 256, (128, 64): 256, (64, 64): 256, (64, 32): 128, (32, 64): 128, (32, 32): 64, (256, 64): 256}
 POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 
 
@@ -35,12 +38,12 @@ def candidates(M, N, K, kh):
     for tile, (bm, bn) in TILE_DIMS.items():
         if bn > N or (bm > 64 and bm > M):
             continue
-        if tile.endswith("k128") and cin % 128 != 0:
+        if "k128" in tile and cin % 128 != 0:
             continue
-        ktiles = K // (128 if tile.endswith("k128") else 64)
+        ktiles = K // (128 if "k128" in tile else 64)
         tiles = -(-M // bm) * -(-N // bn)
         for s in SPLITS:
-            if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20)):
+            if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20) or "g" in tile):
                 continue
             out.append((tile, s))
     return out
@@ -53,7 +56,8 @@ def rows(table):
 def tile_name(block, bm, bn, bk):
     if (bm, bn) == (128, 128) and block == 512:
         return "128x128w8"
-    return "%dx%d%s" % (bm, bn, "k128" if bk == 128 else "")
+    groups = block // BASE_THREADS[(bm, bn)]
+    return "%dx%d%s%s" % (bm, bn, "k128" if bk == 128 else "", "g%d" % groups if groups > 1 else "")
 
 
 class Bench:

@@ -65,7 +65,7 @@ def test_plan_is_fixed_and_covers_every_op(ctx):
         flops = sum(l["flops"] for l in plan)
         assert flops == 2 * b * T.mac_count(T.resnet(50), 224, 224)
         for l in plan:
-            assert l["grid_x"] >= 1 and l["block"] in (64, 128, 256, 512)
+            assert l["grid_x"] >= 1 and l["block"] in (64, 128, 256, 512, 1024)
             if l["name"].startswith("conv") and l["split_k"] == 1:
                 tiles = -(-l["gemm_m"] // l["tile_m"]) * -(-l["gemm_n"] // l["tile_n"])
                 assert l["grid_x"] == tiles and l["grid_y"] == 1
@@ -88,7 +88,7 @@ def test_plan_override_reaches_every_tile(ctx):
     for name, idx in cw.CONV_TILES.items():
         ctx.set_plan_override(idx, 2)
         m = ctx.model_define_resnet(18, 64, 64)
-        bm, bn = (int(v) for v in name.replace("w2", "").replace("w8", "").replace("k128", "").split("x"))
+        bm, bn = (int(v) for v in re.sub(r"(w2|w8|k128|g2|g4)", "", name).split("x"))
         convs = [l for l in ctx.plan(m, 4) if l["name"].startswith(("conv", "stem"))]
         assert convs and all((l["tile_m"], l["tile_n"]) == (bm, bn) for l in convs)
         ops = ctx.model_get_ops(m)
@@ -96,7 +96,7 @@ def test_plan_override_reaches_every_tile(ctx):
             cin = ops[l["op_index"]][1]
             # K slices: 64 for the first convolution (stride 2: two padded filter rows per slice),
             # 128 only where the tile asks and cin allows
-            want = 64 if cin < 32 else (128 if name.endswith("k128") and cin % 128 == 0 else 64)
+            want = 64 if cin < 32 else (128 if "k128" in name and cin % 128 == 0 else 64)
             assert l["tile_k"] == want
             assert l["split_k"] == 2 or l["gemm_k"] <= l["tile_k"] or cin < 32   # one K slice cannot be split
     ctx.set_plan_override(-1, 0)

@@ -159,7 +159,9 @@ def test_resnet18_top1_agreement_2048_samples(worker):
 # ---------------------------------------------------------------- every conv instantiation
 @pytest.mark.parametrize("tile", ["128x128", "128x64", "64x64", "64x32", "32x64", "32x32",
                                   "128x64w2", "64x128w2", "256x64", "128x128w8",
-                                  "128x64k128", "64x64k128", "64x32k128", "32x64k128", "32x32k128"])
+                                  "128x64k128", "64x64k128", "64x32k128", "32x64k128", "32x32k128",
+                                  "128x64k128g2", "64x64k128g2", "64x64k128g4", "64x32k128g4", "32x64k128g4",
+                                  "32x32k128g4"])
 @pytest.mark.parametrize("split_k", [1, 3])
 def test_every_conv_tile_and_split_k(worker, tile, split_k):
     """Forces one tile shape and split-K factor on every convolution of ResNet-18 at 64x64
