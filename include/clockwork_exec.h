@@ -209,12 +209,14 @@ int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
  * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
  * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
 int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..20 =
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..24 =
  * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
  * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
- * instead of 64 (used where cin % 128 == 0, else their 64 form), then 128x64 in 2 and 64x64 in 2
- * and 4 and 64x32, 32x64, 32x32 in 4 groups of waves that share every 128-wide K slice (no
- * split-K with those: a request for both drops the groups); pixels x channels per workgroup; -1 = the plan compiler's own choice)
+ * instead of 64 (used where cin % 128 == 0, else their 64 form), then tiles whose waves come in
+ * 2, 4 or 8 groups that share every K slice (128 wide: 128x64 in 2, 64x64 in 2 and 4, 64x32,
+ * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; no split-K
+ * with those: a request for both drops the groups);
+ * pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
 int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
@@ -229,7 +231,7 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
  * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
  * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
- * kh, stride, conv_tile (0..20 as above), split_k >= 1}; copied.  Shapes in neither table get
+ * kh, stride, conv_tile (0..24 as above), split_k >= 1}; copied.  Shapes in neither table get
  * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
 int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
 

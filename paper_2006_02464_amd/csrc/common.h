@@ -101,13 +101,14 @@ struct SoftmaxArgs {
 enum ConvTile : int32_t {
     T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8,
     T128x64k128, T64x64k128, T64x32k128, T32x64k128, T32x32k128,
-    T128x64k128g2, T64x64k128g2, T64x64k128g4, T64x32k128g4, T32x64k128g4, T32x32k128g4, N_CONV_TILES
+    T128x64k128g2, T64x64k128g2, T64x64k128g4, T64x32k128g4, T32x64k128g4, T32x32k128g4,
+    T32x32k128g8, T128x64g2, T64x64g2, T32x32g4, N_CONV_TILES
 };
 struct TileDim {
     int bm, bn, threads, bk, kg;
 };
 TileDim conv_tile_dim(ConvTile t);
-// The same tile with K slices of 64 and one group of waves (for shapes a k128 / gN tile cannot take).
+// The same tile with K slices of 64 (for shapes a k128 tile cannot take).
 ConvTile conv_tile_k64(ConvTile t);
 // The same tile with one group of waves (split-K needs that).
 ConvTile conv_tile_one_group(ConvTile t);

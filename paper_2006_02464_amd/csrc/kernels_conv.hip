@@ -315,18 +315,27 @@ TileDim conv_tile_dim(ConvTile t) {
         case T64x32k128g4: return {64, 32, 512, 128, 4};
         case T32x64k128g4: return {32, 64, 512, 128, 4};
         case T32x32k128g4: return {32, 32, 256, 128, 4};
+        case T32x32k128g8: return {32, 32, 512, 128, 8};
+        case T128x64g2: return {128, 64, 512, 64, 2};
+        case T64x64g2: return {64, 64, 512, 64, 2};
+        case T32x32g4: return {32, 32, 256, 64, 4};
         default: return {32, 32, 64, 64, 1};
     }
 }
 
-// The same tile with K slices of 64 and one group of waves (for shapes the tile cannot take).
+// The same tile with K slices of 64 (for Cin % 128 != 0), with as many wave groups as a 64-wide
+// slice and the tile's thread count allow.
 ConvTile conv_tile_k64(ConvTile t) {
     switch (t) {
-        case T128x64k128: case T128x64k128g2: return T128x64;
-        case T64x64k128: case T64x64k128g2: case T64x64k128g4: return T64x64;
+        case T128x64k128: return T128x64;
+        case T128x64k128g2: return T128x64g2;
+        case T64x64k128: return T64x64;
+        case T64x64k128g2: return T64x64g2;
+        case T64x64k128g4: return T64x64g2;
         case T64x32k128: case T64x32k128g4: return T64x32;
         case T32x64k128: case T32x64k128g4: return T32x64;
-        case T32x32k128: case T32x32k128g4: return T32x32;
+        case T32x32k128: return T32x32;
+        case T32x32k128g4: case T32x32k128g8: return T32x32g4;
         default: return t;
     }
 }
@@ -341,7 +350,10 @@ ConvTile conv_tile_one_group(ConvTile t) {
         case T64x64k128g2: case T64x64k128g4: return T64x64k128;
         case T64x32k128g4: return T64x32k128;
         case T32x64k128g4: return T32x64k128;
-        case T32x32k128g4: return T32x32k128;
+        case T32x32k128g4: case T32x32k128g8: return T32x32k128;
+        case T128x64g2: return T128x64;
+        case T64x64g2: return T64x64;
+        case T32x32g4: return T32x32;
         default: return t;
     }
 }

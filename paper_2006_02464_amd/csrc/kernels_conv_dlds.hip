@@ -540,6 +540,7 @@ static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_
 
 template <typename T, int MODE, bool SPLITK>
 static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStream_t s) {
+    if (MODE == MODE_STEM) tile = conv_tile_one_group(tile);
     if (bk != 128) tile = conv_tile_k64(tile);
     dim3 grid;
     int block;
@@ -587,6 +588,18 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
             return hipErrorInvalidValue;
         case T32x32k128g4:
             if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 128, MODE, false, 4>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x32k128g8:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 128, MODE, false, 8>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T128x64g2:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 128, 64, 2, 2, 64, MODE, false, 2>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T64x64g2:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 64, MODE, false, 2>(grid, block, a, s);
+            return hipErrorInvalidValue;
+        case T32x32g4:
+            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 64, MODE, false, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }

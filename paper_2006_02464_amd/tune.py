@@ -26,7 +26,8 @@ TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x
              "128x64k128": (128, 64), "64x64k128": (64, 64), "64x32k128": (64, 32), "32x64k128": (32, 64),
              "32x32k128": (32, 32),
              "128x64k128g2": (128, 64), "64x64k128g2": (64, 64), "64x64k128g4": (64, 64), "64x32k128g4": (64, 32),
-             "32x64k128g4": (32, 64), "32x32k128g4": (32, 32)}
+             "32x64k128g4": (32, 64), "32x32k128g4": (32, 32),
+             "32x32k128g8": (32, 32), "128x64g2": (128, 64), "64x64g2": (64, 64), "32x32g4": (32, 32)}
 BASE_THREADS = {(128, 128): 256, (128, 64): 256, (64, 64): 256, (64, 32): 128, (32, 64): 128, (32, 32): 64, (256, 64): 256}
 POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 

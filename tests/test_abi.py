@@ -88,7 +88,7 @@ def test_plan_override_reaches_every_tile(ctx):
     for name, idx in cw.CONV_TILES.items():
         ctx.set_plan_override(idx, 2)
         m = ctx.model_define_resnet(18, 64, 64)
-        bm, bn = (int(v) for v in re.sub(r"(w2|w8|k128|g2|g4)", "", name).split("x"))
+        bm, bn = (int(v) for v in re.sub(r"(w2|w8|k128|g2|g4|g8)", "", name).split("x"))
         convs = [l for l in ctx.plan(m, 4) if l["name"].startswith(("conv", "stem"))]
         assert convs and all((l["tile_m"], l["tile_n"]) == (bm, bn) for l in convs)
         ops = ctx.model_get_ops(m)

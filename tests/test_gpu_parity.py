@@ -161,7 +161,7 @@ def test_resnet18_top1_agreement_2048_samples(worker):
                                   "128x64w2", "64x128w2", "256x64", "128x128w8",
                                   "128x64k128", "64x64k128", "64x32k128", "32x64k128", "32x32k128",
                                   "128x64k128g2", "64x64k128g2", "64x64k128g4", "64x32k128g4", "32x64k128g4",
-                                  "32x32k128g4"])
+                                  "32x32k128g4", "32x32k128g8", "128x64g2", "64x64g2", "32x32g4"])
 @pytest.mark.parametrize("split_k", [1, 3])
 def test_every_conv_tile_and_split_k(worker, tile, split_k):
     """Forces one tile shape and split-K factor on every convolution of ResNet-18 at 64x64
@@ -331,18 +331,28 @@ def test_resnet50_224_small_batches(worker, r50, batch):
 
 
 def test_resnet50_split_k_is_reproducible(worker, r50):
-    """Batch 1 runs most layers split over K, each tile finished by whichever workgroup arrives
-    last; the sum must not depend on that order: 200 EXECs, bit-identical logits."""
+    """With K split over 4 workgroups in every layer, each tile is finished by whichever workgroup
+    arrives last; the sum must not depend on that order: 200 EXECs, bit-identical logits.  The
+    default batch-1 plan (wave groups inside a workgroup, a few split layers) likewise."""
     case, x, ref = r50
-    mid = worker.ctx.model_define_resnet(50, 224, 224)
-    worker.load(mid, case.blob)
-    plan = worker.ctx.plan(mid, 1)
-    assert sum(l["split_k"] > 1 for l in plan) >= 10
-    first = worker.infer(mid, x[:1])[1]
-    assert rel_err_per_sample(first, ref[:1]).max() <= TOL
-    for _ in range(200):
-        assert np.array_equal(worker.infer(mid, x[:1])[1], first)
-    worker.ctx.unload_weights(mid)
+    worker.ctx.set_plan_override(-1, 4)
+    try:
+        split = worker.ctx.model_define_resnet(50, 224, 224)
+    finally:
+        worker.ctx.set_plan_override(-1, 0)
+    default = worker.ctx.model_define_resnet(50, 224, 224)
+    assert sum(l["split_k"] > 1 for l in worker.ctx.plan(split, 1)) >= 40
+    base = {(128, 128): 256, (128, 64): 256, (64, 64): 256, (64, 32): 128, (32, 64): 128, (32, 32): 64, (256, 64): 256}
+    grouped = [l for l in worker.ctx.plan(default, 1) if l["kind"] == 1 and
+               (l["block"] > base[(l["tile_m"], l["tile_n"])] or l["split_k"] > 1)]
+    assert len(grouped) >= 10   # several waves (or workgroups) add up one tile
+    for mid, reps in ((split, 200), (default, 50)):
+        worker.load(mid, case.blob)
+        first = worker.infer(mid, x[:1])[1]
+        assert rel_err_per_sample(first, ref[:1]).max() <= TOL
+        for _ in range(reps):
+            assert np.array_equal(worker.infer(mid, x[:1])[1], first)
+        worker.ctx.unload_weights(mid)
 
 
 def test_resnet50_first_block_every_layer(worker):
