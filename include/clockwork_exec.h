@@ -223,8 +223,11 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
 /* A convolution with 64 or 128 output channels whose only consumer is a 1x1 stride-1
  * convolution with a residual (the last two layers of a ResNet bottleneck) is planned as ONE
  * launch when the batch gives it enough workgroups: the intermediate tensor then never leaves
- * the chip.  on == 0 plans such pairs as two launches for models defined afterwards; on != 0
- * restores the default.  Plans with debug retention are never fused. */
+ * the chip.  Where the first layer has 128 output channels (and the second a multiple of 128)
+ * the launch runs two groups of four waves: they split every K slice of the first layer and
+ * the channels of every chunk of the second.  on == 0 plans such pairs as two launches for models defined
+ * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
+ * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
 int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
 /* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
  * The plan compiler takes the tile variant and split-K factor of a convolution from a table

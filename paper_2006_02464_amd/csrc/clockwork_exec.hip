@@ -144,7 +144,7 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hi
                 a.x2 = resolve(c, m, s, l.x2);
                 a.wd = resolve(c, m, s, l.wd);
                 a.biasd = reinterpret_cast<const float *>(resolve(c, m, s, l.biasd));
-                return launch_conv_fused(dt, l.fused_bm, a, st);
+                return launch_conv_fused(dt, l.fused_bm, l.fused_kg, a, st);
             }
             return launch_conv(dt, l.tile, l.stem, a, st);
         }
@@ -462,7 +462,8 @@ int32_t cw_set_plan_override(cw_ctx *c, int32_t conv_tile, int32_t split_k) {
 
 int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
-    c->ov.fuse = on != 0;
+    if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "fusion mode must be 0, 1 or 2");
+    c->ov.fuse = on;
     return CW_OK;
 }
 

@@ -120,9 +120,10 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
 hipError_t launch_conv_dlds(DType dt, ConvTile tile, int bk, int mode, const ConvArgs &a, hipStream_t s);
 // A convolution (Cin % 64 == 0, Cout 64 or 128) and the 1x1 convolution that consumes it, in one
 // launch (kernels_conv_dlds.hip).  bm = pixels per workgroup (64 or 128).
-hipError_t launch_conv_fused(DType dt, int bm, const ConvArgs &a, hipStream_t s);
+hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStream_t s);
 // Workgroups of that launch.
-void conv_fused_grid(int bm, const ConvArgs &a, dim3 *grid, int *block);
+void conv_fused_grid(int bm, int kg, const ConvArgs &a, dim3 *grid, int *block);
+bool conv_fused_ok(int bm, int kg, int cout, int cout2);   // a (pixels per workgroup, wave groups) form exists for these widths
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);

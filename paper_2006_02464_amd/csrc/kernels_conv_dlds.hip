@@ -58,11 +58,11 @@ extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 // LDS bytes of the fused second layer (see the end of the kernel): the first layer's tile, two
 // buffers of {a chunk of W2, the matching residual tile}.  Both layers' biases sit behind
 // whichever is larger, this or the ring, from the start of the kernel.
-constexpr int fused_chunk(int bn) { return bn == 128 ? 64 : bn; }   // second-layer channels per chunk
-constexpr unsigned fused_lds_bytes(int bm, int bn) {
-    const int p = bm * bn * 2, w2 = fused_chunk(bn) * bn * 2, r = bm * fused_chunk(bn) * 2;
-    // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile
-    const int plain = 2 * (w2 + r), proj = bn == 64 ? 4 * w2 + r : 0;
+constexpr int fused_chunk(int bn, int kg) { return kg > 1 ? 128 : (bn == 128 ? 64 : bn); }   // second-layer channels per chunk
+constexpr unsigned fused_lds_bytes(int bm, int bn, int kg) {
+    const int p = bm * bn * 2, w2 = fused_chunk(bn, kg) * bn * 2, r = bm * fused_chunk(bn, kg) * 2;
+    // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile (as large as p)
+    const int plain = 2 * (w2 + r), proj = bn == 64 ? 4 * w2 + p : 0;
     return (unsigned)(p + (plain > proj ? plain : proj));
 }
 constexpr int kFusedMaxCout2 = 1024;
@@ -74,7 +74,7 @@ constexpr int kFusedMaxCout2 = 1024;
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
-    static_assert(KG == 1 || (!SPLITK && !FUSED && (BK / 16) % KG == 0), "K groups: plain form, whole steps per group");
+    static_assert(KG == 1 || (!SPLITK && (BK / 16) % KG == 0 && (!FUSED || KG == 2)), "K groups: no split-K, whole steps per group");
     static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
     constexpr int NT = 64 * WARPS_M * WARPS_N * KG;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
@@ -95,15 +95,28 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)cw_dyn_lds;
 
     CW_STAMP(0);
+#ifdef CW_TRACE
+    asm volatile("" ::"s"(a.M), "s"(a.Cin));
+    CW_STAMP(3);
+#endif
     const int tid = threadIdx.x;
-    // Fused form: both layers' biases go to LDS now, with ordinary loads, while no counted load is
-    // in flight yet (visible to every wave after the first barrier).
-    constexpr unsigned BIAS_OFF = FUSED ? (NS * STAGE_BYTES > fused_lds_bytes(BM, BN) ? NS * STAGE_BYTES : fused_lds_bytes(BM, BN)) : 0u;
+    // Fused form: both layers' biases are requested now, with ordinary loads, and go to LDS at the
+    // end of the set-up arithmetic below, which covers their latency; no counted load is in
+    // flight yet at that point (visible to every wave after the first barrier).
+    constexpr unsigned BIAS_OFF = FUSED ? (NS * STAGE_BYTES > fused_lds_bytes(BM, BN, KG) ? NS * STAGE_BYTES : fused_lds_bytes(BM, BN, KG)) : 0u;
+    constexpr int B2_PER = FUSED ? (kFusedMaxCout2 + NT - 1) / NT : 1;
+    float bias1_v = 0.f, bias2_v[B2_PER];
     if constexpr (FUSED) {
-        float *sb = reinterpret_cast<float *>(cw_dyn_lds + BIAS_OFF);
-        for (int n = tid; n < BN; n += NT) sb[n] = a.bias[n];
-        for (int n = tid; n < a.Cout2; n += NT) sb[BN + n] = a.bias2[n] + (a.wd ? a.biasd[n] : 0.f);
+        if (tid < BN) bias1_v = a.bias[tid];
+#pragma unroll
+        for (int j = 0; j < B2_PER; ++j) {
+            const int n = tid + j * NT;
+            bias2_v[j] = n < a.Cout2 ? a.bias2[n] + (a.wd ? a.biasd[n] : 0.f) : 0.f;
+        }
     }
+#ifdef CW_TRACE
+    CW_STAMP_END(59);
+#endif
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = wave / (WARPS_M * WARPS_N);        // K group of this wave
@@ -120,9 +133,10 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int ktiles = a.K / BK;
-    const int kt0 = blockIdx.y * a.ktiles_per_split;
+    const int kt0 = SPLITK ? blockIdx.y * a.ktiles_per_split : 0;
     const int kt1 = min(ktiles, kt0 + a.ktiles_per_split);
     const int nsteps = kt1 - kt0;
+    int kt = kt0;  // the slice being computed
 
     // The activation buffer is described from D bytes before its start, D = the offset of the
     // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
@@ -138,46 +152,63 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     // at the filter's centre pixel, and which taps fall inside the image (bit r*kw+s; for the
     // 1x1 stride-1 case bit 0 = the pixel exists).
     unsigned x_voff[X_PER], x_mask[X_PER];
-    unsigned row_units = 0;  // bit r*kw for every filter row r
-    if (MODE == MODE_CONV)
-        for (int r = 0; r < a.kh; ++r) row_units |= 1u << (r * a.kw);
+    if constexpr (MODE == MODE_GEMM) {
 #pragma unroll
-    for (int j = 0; j < X_PER; ++j) {
-        const int cid = tid + j * NT;
-        const int row = cid / CPR;
-        const int c = (cid % CPR) ^ swz_key<BK>(row);
-        const unsigned m = m0 + row;
-        unsigned mask = 0, voff = 0;
-        if (MODE == MODE_GEMM) {
-            voff = m * (unsigned)a.Cin * 2u + c * 16u;
-            mask = m < (unsigned)a.M ? 1u : 0u;
-        } else if (MODE == MODE_STEM) {
-            // Input = 4-channel pixels (8 bytes) of an image already padded by the cast; no
-            // masks.  A K slice is filter rows 2kt, 2kt+1; of its 8 chunks, chunk c is row c/4,
-            // taps 2(c%4), 2(c%4)+1: 16 contiguous, 16-byte aligned bytes (even stride, even W).
-            const unsigned t = fast_div(m, a.wo_div);
-            const unsigned q = m - t * a.Wo;
-            const unsigned n = fast_div(t, a.ho_div);
-            const unsigned p = t - n * a.Ho;
-            voff = (((n * a.H + p * a.stride + (c >> 2)) * a.W + q * a.stride) * 4u + (c & 3) * 8u) * 2u;
-            mask = m < (unsigned)a.M ? 1u : 0u;
-        } else if (m < (unsigned)a.M) {
-            const unsigned t = fast_div(m, a.wo_div);
-            const int q = m - t * a.Wo;
-            const unsigned n = fast_div(t, a.ho_div);
-            const int p = t - n * a.Ho;
-            const int ihc = p * a.stride, iwc = q * a.stride;
-            voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u + c * 16u;
-            const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
-            const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
-            // in-range columns s_lo..s_hi-1 replicated into every in-range filter row r_lo..r_hi-1:
-            // a multiplication by the rows' unit bits (no carries: cols < 2^kw)
-            const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
-            const unsigned rows = row_units & (unsigned)((1ull << (r_hi * a.kw)) - 1ull) & ~((1u << (r_lo * a.kw)) - 1u);
-            mask = cols * rows;
+        for (int j = 0; j < X_PER; ++j) {
+            const int cid = tid + j * NT;
+            const int row = cid / CPR;
+            const int c = (cid % CPR) ^ swz_key<BK>(row);
+            const unsigned m = m0 + row;
+            x_voff[j] = m * (unsigned)a.Cin * 2u + c * 16u;
+            x_mask[j] = m < (unsigned)a.M ? 1u : 0u;
         }
-        x_voff[j] = voff;
-        x_mask[j] = mask;
+    } else {
+        // The pixel arithmetic (two divisions and the tap mask) is done once per tile row, by
+        // thread `row`, and handed to the threads that load the row's chunks through LDS: a
+        // thread has up to 8 pieces in as many rows, and with one wave per SIMD the arithmetic
+        // of each would cost about as much as a K slice.
+        static_assert(NT >= BM, "one thread per tile row");
+        __shared__ u32x2 s_row[BM];
+        if (tid < BM) {
+            const unsigned m = m0 + tid;
+            unsigned mask = 0, voff = 0;
+            if (m < (unsigned)a.M) {
+                const unsigned t = fast_div(m, a.wo_div);
+                const unsigned q = m - t * a.Wo;
+                const unsigned n = fast_div(t, a.ho_div);
+                const unsigned p = t - n * a.Ho;
+                if (MODE == MODE_STEM) {
+                    // Input = 4-channel pixels (8 bytes) of an image already padded by the cast; no masks.
+                    voff = ((n * a.H + p * a.stride) * a.W + q * a.stride) * 8u;
+                    mask = 1u;
+                } else {
+                    const int ihc = p * a.stride, iwc = q * a.stride;
+                    voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u;
+                    const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
+                    const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+                    // in-range columns s_lo..s_hi-1 replicated into every in-range filter row r_lo..r_hi-1:
+                    // a multiplication by the rows' unit bits (no carries: cols < 2^kw)
+                    unsigned row_units = 0;  // bit r*kw for every filter row r
+                    for (int r = 0; r < a.kh; ++r) row_units |= 1u << (r * a.kw);
+                    const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
+                    const unsigned rows = row_units & (unsigned)((1ull << (r_hi * a.kw)) - 1ull) & ~((1u << (r_lo * a.kw)) - 1u);
+                    mask = cols * rows;
+                }
+            }
+            s_row[tid] = u32x2{voff, mask};
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < X_PER; ++j) {
+            const int cid = tid + j * NT;
+            const int row = cid / CPR;
+            const int c = (cid % CPR) ^ swz_key<BK>(row);
+            const u32x2 ri = s_row[row];
+            // Stem: a K slice is filter rows 2kt, 2kt+1; of its 8 chunks, chunk c is row c/4, taps
+            // 2(c%4), 2(c%4)+1: 16 contiguous, 16-byte aligned bytes (even stride, even W).
+            x_voff[j] = ri.x + (MODE == MODE_STEM ? (unsigned)(c >> 2) * a.W * 8u + (c & 3) * 16u : c * 16u);
+            x_mask[j] = ri.y;
+        }
     }
     unsigned w_off[W_PER];
 #pragma unroll
@@ -188,10 +219,21 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         const int n = n0 + row;
         w_off[j] = n < a.Cout ? ((unsigned)n * a.K + c * 8) * 2u : kOob;
     }
+    if constexpr (FUSED) {
+        float *sb = reinterpret_cast<float *>(cw_dyn_lds + BIAS_OFF);
+        if (tid < BN) sb[tid] = bias1_v;
+#pragma unroll
+        for (int j = 0; j < B2_PER; ++j) {
+            const int n = tid + j * NT;
+            if (n < a.Cout2) sb[BN + n] = bias2_v[j];
+        }
+    }
 
     // (r, s, c0) of the next K slice to load: k0 = kt*BK = (r*kw + s)*Cin + c0.
     int fr = 0, fs = 0, fc0 = 0;
-    if (MODE == MODE_GEMM) {
+    if (!SPLITK) {
+        // one workgroup walks the whole K: it starts at (0, 0, 0), no divisions needed
+    } else if (MODE == MODE_GEMM) {
         fc0 = kt0 * BK;
     } else if (MODE == MODE_CONV) {
         const int k0 = kt0 * BK;
@@ -214,6 +256,9 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         is_kb = (unsigned)kt * (BK * 2u);
     };
     auto issue_piece = [&](int idx) {  // idx is a compile-time constant after unrolling
+#ifdef CW_EXP_NOLOADS
+        if (kt > kt0) return;
+#endif
         if (idx < X_PER)
             load_to_lds(dx, (x_mask[idx] & is_tbit) ? x_voff[idx] : kOob, is_soff, is_dst + idx * (NT * 16));
         else
@@ -265,19 +310,35 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
             for (int j = 0; j < TN; ++j)
                 qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
         };
+#ifdef CW_TRACE
+        const bool detail = kt == kt0 + 4;
+        if (detail) CW_STAMP_END(24);
+#endif
 #pragma unroll
         for (int t = 0; t < DEPTH - 1 && t < KK; ++t) fetch(t, fx[t], fw[t]);
+#ifdef CW_TRACE
+        if (detail) CW_STAMP_END(25);
+#endif
 #pragma unroll
         for (int t = 0; t < KK; ++t) {
             if (t + DEPTH - 1 < KK) fetch(t + DEPTH - 1, fx[(t + DEPTH - 1) % DEPTH], fw[(t + DEPTH - 1) % DEPTH]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[t % DEPTH][j], fx[t % DEPTH][i], acc[i][j]);
+                for (int j = 0; j < TN; ++j) {
+#ifdef CW_EXP_NOMFMA
+                    acc[i][j][0] += (float)fw[t % DEPTH][j][0] * (float)fx[t % DEPTH][i][0];
+#else
+                    acc[i][j] = Mfma<T>::mma(fw[t % DEPTH][j], fx[t % DEPTH][i], acc[i][j]);
+#endif
+                }
             if (decltype(with_loads)::value) {
 #pragma unroll
                 for (int idx = t * LOADS / KK; idx < (t + 1) * LOADS / KK; ++idx) issue_piece(idx);
             }
+#ifdef CW_TRACE
+            if (detail) CW_STAMP_END(26 + t);
+#endif
         }
     };
 
@@ -297,7 +358,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     // `cur` in the ring) takes the loads of slice kt+NS-1, which then fly during NS-1 slices of
     // MFMAs.
     int cur = 0;
-    int kt = kt0;
     int trace_slot = 4;
     (void)trace_slot;
     for (; kt + (NS - 1) < kt1; ++kt) {
@@ -330,7 +390,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     tail(std::integral_constant<int, 0>{});
 
     if (!SPLITK && !FUSED && nsteps <= 0 && kg == 0) epilogue_load<TM, TN>(eo, a, pos);
-    if constexpr (KG > 1) {
+    if constexpr (KG > 1 && !FUSED) {
         // Groups 1.. hand their accumulators to group 0 through LDS (the ring is free once every
         // wave has passed the barrier); group 0 adds them in group order and goes on alone.
         static_assert((KG - 1) * BM * BN * 4 <= NS * (int)STAGE_BYTES, "K-group exchange does not fit the ring");
@@ -370,13 +430,15 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         // residual tile (BM x BN2) are fetched straight into LDS, double buffered: chunk
         // c+1 is requested before the MFMAs of chunk c.  Loads and stores complete in issue order,
         // so when chunk c is awaited only the stores of chunk c-1 may still be outstanding.
-        constexpr int BN2 = fused_chunk(BN);                       // second-layer channels per chunk
+        // With two wave groups (which split K in the first layer) the chunk is 128 channels wide and
+        // the groups take its two halves.
+        constexpr int BN2 = fused_chunk(BN, KG);                   // second-layer channels per chunk
         constexpr int CP2 = BN / 8, CR2 = BN2 / 8;                 // 16-byte chunks per row: p and W2 / residual
-        constexpr int W2_PER = BN2 * CP2 / NT, R_PER = BM * CR2 / NT;
-        static_assert(BN2 * CP2 % NT == 0 && BM * CR2 % NT == 0, "tile/threads mismatch");
-        constexpr int TN2 = BN2 / WARPS_N / 32;                    // channel tiles per wave in the second layer
+        constexpr int W2_PER = BN2 * CP2 / NT, R_PER = BM * CR2 / NT, X2_PER = BM * CP2 / NT;
+        static_assert(BN2 * CP2 % NT == 0 && BM * CR2 % NT == 0 && BM * CP2 % NT == 0, "tile/threads mismatch");
+        constexpr int TN2 = BN2 / (WARPS_N * KG) / 32;             // channel tiles per wave in the second layer
         static_assert(TN2 >= 1 && TN2 <= TN, "second-layer wave tile");
-        const int wn2 = (wave % WARPS_N) * (BN2 / WARPS_N);
+        const int wn2 = (kg * WARPS_N + wq % WARPS_N) * (BN2 / (WARPS_N * KG));
         constexpr int ST = TM * TN2 * 2;                           // stores per thread per chunk
         constexpr unsigned P_BYTES = BM * BN * 2u, W2_BYTES = BN2 * BN * 2u, R_BYTES = BM * BN2 * 2u;
         constexpr unsigned BUF_BYTES = W2_BYTES + R_BYTES;
@@ -405,9 +467,9 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         const bool proj = BN == 64 && a.wd != nullptr;  // uniform
         const u32x4 dwd = make_desc(proj ? a.wd : a.w2, (unsigned)a.Cout2 * BN * 2u);
         const u32x4 dx2 = make_desc(proj ? a.x2 : a.res, (unsigned)a.M * BN * 2u);
-        unsigned x2_voff[R_PER];
+        unsigned x2_voff[X2_PER];
 #pragma unroll
-        for (int j = 0; j < R_PER; ++j) {
+        for (int j = 0; j < X2_PER; ++j) {
             const int cid = tid + j * NT, row = cid / CP2, c = (cid % CP2) ^ swz_key<BN>(row);
             const unsigned m = m0 + row;
             x2_voff[j] = m < (unsigned)a.M ? (m * (unsigned)BN + c * 8) * 2u : kOob;
@@ -423,7 +485,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
                 for (int j = 0; j < W2_PER; ++j) load_to_lds(dwd, w2_voff[j], (unsigned)c * W2_BYTES, dst + W2_BYTES + j * (NT * 16));
                 if (c == 0) {
 #pragma unroll
-                    for (int j = 0; j < R_PER; ++j) load_to_lds(dx2, x2_voff[j], 0u, lds_base + XB_OFF + (unsigned)wave * 1024u + j * (NT * 16));
+                    for (int j = 0; j < X2_PER; ++j) load_to_lds(dx2, x2_voff[j], 0u, lds_base + XB_OFF + (unsigned)wave * 1024u + j * (NT * 16));
                 }
             } else {
 #pragma unroll
@@ -434,7 +496,32 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         // every wave is done with the ring (the last slice's barrier came before its MFMAs)
         wait_loads_and_barrier<0>();
         issue_chunk(0);
+        if constexpr (KG > 1) {
+            // The second group hands its accumulators to the first through the room of chunk
+            // buffer 1, which chunk 1 claims only after the barrier that ends the additions;
+            // chunk 0's loads stay in flight meanwhile.
+            static_assert((KG - 1) * BM * BN * 4 <= (int)(2 * W2_BYTES < BUF_BYTES ? 2 * W2_BYTES : BUF_BYTES), "K-group exchange does not fit a chunk buffer");
+            float *xch = reinterpret_cast<float *>(cw_dyn_lds + buf_off(1)) + wq * (TM * TN * 16 * 64) + lane;
+            if (kg > 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) xch[((i * TN + j) * 16 + e) * 64] = acc[i][j][e];
+            }
+            wait_lds_loads_and_barrier<2 * W2_PER + (R_PER > X2_PER ? R_PER : X2_PER)>();
+            if (kg == 0) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[i][j][e] += xch[((i * TN + j) * 16 + e) * 64];
+            }
+        }
         // first layer's epilogue into LDS: + bias, activation, one rounding to the storage type
+        if (kg == 0) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -450,11 +537,14 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
                     }
                     *reinterpret_cast<u32x4 *>(sP + swz<BN>(wm0 + i * 32 + lrow, n >> 3)) = *reinterpret_cast<const u32x4 *>(out);
                 }
+        }
         const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (unsigned)a.M * a.Cout2 * 2u);
+        CW_STAMP_END(61);
         for (int c = 0; c < chunks; ++c) {
             // chunk c has landed (mine: vmcnt; everyone's: barrier); p and the bias are visible;
             // every wave has finished reading the buffer that chunk c+1 is about to overwrite
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
+            CW_STAMP(40 + c);
             if (c + 1 < chunks) issue_chunk(c + 1);
             const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
             const T *sR = sW2 + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
@@ -504,6 +594,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
                     }
             }
         }
+        CW_STAMP_END(62);
         return;
     }
     if (SPLITK) {
@@ -605,44 +696,59 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
     }
 }
 
-template <typename T, int BM, int BN, int MODE>
+template <typename T, int BM, int BN, int MODE, int KG>
 static hipError_t launch_fused_one(const ConvArgs &a, hipStream_t s) {
     constexpr int NS = RingDepth<BM, BN, 64>::value;
     constexpr size_t ring = (size_t)NS * (BM + BN) * 64 * 2;
-    auto kern = conv_dlds_kernel<T, BM, BN, 2, 2, 64, NS, MODE, false, true>;
-    constexpr size_t bias_off = std::max<size_t>(ring, fused_lds_bytes(BM, BN));
+    auto kern = conv_dlds_kernel<T, BM, BN, 2, 2, 64, NS, MODE, false, true, KG>;
+    constexpr size_t bias_off = std::max<size_t>(ring, fused_lds_bytes(BM, BN, KG));
+    static_assert(bias_off + (BN + kFusedMaxCout2) * 4 <= 160 * 1024, "fused form does not fit the LDS");
     const size_t need = bias_off + (size_t)(BN + a.Cout2) * 4;
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  (int)(bias_off + (BN + kFusedMaxCout2) * 4));
     if (attr != hipSuccess) return attr;
-    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256, need, s>>>(a);
+    if (a.Cout2 % fused_chunk(BN, KG) != 0) return hipErrorInvalidValue;
+    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a);
     return hipGetLastError();
 }
 
-void conv_fused_grid(int bm, const ConvArgs &a, dim3 *grid, int *block) {
+void conv_fused_grid(int bm, int kg, const ConvArgs &a, dim3 *grid, int *block) {
     *grid = dim3((a.M + bm - 1) / bm, 1, 1);
-    *block = 256;
+    *block = 256 * kg;
 }
 
-hipError_t launch_conv_fused(DType dt, int bm, const ConvArgs &a, hipStream_t s) {
+bool conv_fused_ok(int bm, int kg, int cout, int cout2) {
+    if ((cout != 64 && cout != 128) || (bm != 64 && bm != 128) || (bm == 128 && cout == 128) || (kg != 1 && kg != 2)) return false;
+    return cout2 >= cout && cout2 % fused_chunk(cout, kg) == 0 && cout2 <= kFusedMaxCout2;
+}
+
+hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStream_t s) {
     // first layer: any convolution this kernel takes, Cout 64 or 128, whole K in one workgroup;
     // second layer: 1x1 over its output with a residual
     if (a.Cin % 64 != 0 || a.K != a.kh * a.kw * a.Cin || a.K % 64 != 0 || a.split_k != 1 || a.ktiles_per_split != a.K / 64 || a.partial)
         return hipErrorInvalidValue;
-    if ((a.Cout != 64 && a.Cout != 128) || (bm != 64 && bm != 128) || (bm == 128 && a.Cout == 128)) return hipErrorInvalidValue;
-    if (!a.w2 || !a.bias2 || a.Cout2 < a.Cout || a.Cout2 % a.Cout != 0 || a.Cout2 > kFusedMaxCout2) return hipErrorInvalidValue;
+    if (!conv_fused_ok(bm, kg, a.Cout, a.Cout2)) return hipErrorInvalidValue;
+    if (!a.w2 || !a.bias2) return hipErrorInvalidValue;
     if (a.wd ? (a.Cout != 64 || !a.x2 || !a.biasd) : !a.res) return hipErrorInvalidValue;
     if (!a.res && !a.wd) return hipErrorInvalidValue;
     if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     const bool gemm = a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0;
-#define CW_FUSED(BM_, BN_)                                                                                    \
-    return dt == DT_F16 ? (gemm ? launch_fused_one<f16, BM_, BN_, MODE_GEMM>(a, s) : launch_fused_one<f16, BM_, BN_, MODE_CONV>(a, s)) \
-                        : (gemm ? launch_fused_one<bf16, BM_, BN_, MODE_GEMM>(a, s) : launch_fused_one<bf16, BM_, BN_, MODE_CONV>(a, s))
-    if (a.Cout == 64 && bm == 128) { CW_FUSED(128, 64); }
-    if (a.Cout == 64) { CW_FUSED(64, 64); }
+#define CW_FUSED_T(T_, BM_, BN_, KG_) return gemm ? launch_fused_one<T_, BM_, BN_, MODE_GEMM, KG_>(a, s) : launch_fused_one<T_, BM_, BN_, MODE_CONV, KG_>(a, s)
+#define CW_FUSED(BM_, BN_)                                                       \
+    do {                                                                         \
+        if (dt == DT_F16) {                                                      \
+            if (kg == 2) { CW_FUSED_T(f16, BM_, BN_, 2); }                       \
+            CW_FUSED_T(f16, BM_, BN_, 1);                                        \
+        }                                                                        \
+        if (kg == 2) { CW_FUSED_T(bf16, BM_, BN_, 2); }                          \
+        CW_FUSED_T(bf16, BM_, BN_, 1);                                           \
+    } while (0)
+    if (a.Cout == 64 && bm == 128) CW_FUSED(128, 64);
+    if (a.Cout == 64) CW_FUSED(64, 64);
     CW_FUSED(64, 128);
 #undef CW_FUSED
+#undef CW_FUSED_T
 }
 
 template <typename T, bool SPLITK>

@@ -303,7 +303,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // Pairs planned as one launch: op i = a convolution with 64 or 128 output channels (Cin % 64
     // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
     // convolution with a residual; enough pixels for the launch to fill the GPU.
-    std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), proj_of(n_ops, -1);
+    std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), fused_kg(n_ops, 1), proj_of(n_ops, -1);
     if (ov.fuse && !ov.keep_all && ov.tile < 0 && ov.split_k <= 0) {
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
@@ -325,6 +325,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             const int bm = (o1.cout == 64 && M / 128 >= 256) ? 128 : 64;
             if ((M + bm - 1) / bm < 190) continue;  // measured: below that the two-launch form is faster
             fuse_into[i] = j; fused_first[j] = i; fused_bm[j] = bm;
+            // two wave groups pay off where one workgroup per CU is all the launch has anyway (the 128-channel form)
+            fused_kg[j] = (ov.fuse == 1 && o1.cout == 128 && conv_fused_ok(bm, 2, o1.cout, o2.cout)) ? 2 : 1;
             last_use[o1.input_from] = std::max(last_use[o1.input_from], j);  // read by the fused launch at j
             // The residual of op j may itself be a projection of a tensor as wide as op i's output
             // and aligned with it pixel for pixel (1x1, stride 1, no activation, used by nothing
@@ -396,6 +398,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     l.kind = K_CONV;
                     l.op_index = i;
                     l.fused_bm = fused_bm[i];
+                    l.fused_kg = fused_kg[i];
                     ConvArgs &a = l.conv;
                     a.B = batch; a.H = sin.h; a.W = sin.w; a.Cin = o1.cin; a.Ho = s1.h; a.Wo = s1.w; a.Cout = o1.cout;
                     a.kh = o1.kh; a.kw = o1.kw; a.kwp = o1.kw; a.khp = o1.kh; a.stride = o1.stride; a.pad = o1.pad;
@@ -573,7 +576,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         int b = 0;
         switch (l.kind) {
             case K_CONV:
-                if (l.fused_bm > 0) conv_fused_grid(l.fused_bm, l.conv, &g, &b);
+                if (l.fused_bm > 0) conv_fused_grid(l.fused_bm, l.fused_kg, l.conv, &g, &b);
                 else conv_grid(l.tile, l.conv, &g, &b);
                 break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;

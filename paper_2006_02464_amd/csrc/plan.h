@@ -26,6 +26,7 @@ struct Launch {
     ConvTile tile = T64x64;
     bool stem = false;
     int32_t fused_bm = 0;  // > 0: this convolution and the 1x1 one after it in one launch (pixels per workgroup)
+    int32_t fused_kg = 1;  // wave groups of that launch (1 or 2)
     // Shape fields are final; pointer fields are filled from the Refs at EXEC time.
     ConvArgs conv{};
     CastArgs cast{};
@@ -69,7 +70,7 @@ struct PlanOverride {
     int32_t tile = -1;     // ConvTile or -1 = automatic
     int32_t split_k = 0;   // 0 = automatic
     bool keep_all = false; // no workspace reuse (debug read-back)
-    bool fuse = true;      // allow two-layer launches
+    int32_t fuse = 1;      // two-layer launches: 0 = none, 1 = yes, 2 = yes but never with two wave groups
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 
