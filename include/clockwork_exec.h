@@ -182,6 +182,8 @@ typedef struct {
     int32_t kind;          /* internal kernel family id */
     int32_t grid_x, grid_y, grid_z, block;
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
+    int32_t conv_tile;     /* conv: the tile variant in cw_set_plan_override's numbering; -1 for a fused pair and for other kinds */
+    int32_t wave_groups;   /* conv: groups of waves that split every K slice (1 = none) */
     int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
     int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
     int64_t flops;         /* 2 * MACs */

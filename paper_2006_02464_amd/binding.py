@@ -42,7 +42,7 @@ class cw_profile(Structure):
 class cw_launch_info(Structure):
     _fields_ = [("op_index", c_int32), ("fused_op", c_int32), ("proj_op", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
                 ("grid_z", c_int32), ("block", c_int32), ("tile_m", c_int32), ("tile_n", c_int32),
-                ("tile_k", c_int32), ("split_k", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
+                ("tile_k", c_int32), ("split_k", c_int32), ("conv_tile", c_int32), ("wave_groups", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
                 ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
 
 

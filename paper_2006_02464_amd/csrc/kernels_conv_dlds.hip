@@ -256,9 +256,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
         is_kb = (unsigned)kt * (BK * 2u);
     };
     auto issue_piece = [&](int idx) {  // idx is a compile-time constant after unrolling
-#ifdef CW_EXP_NOLOADS
-        if (kt > kt0) return;
-#endif
         if (idx < X_PER)
             load_to_lds(dx, (x_mask[idx] & is_tbit) ? x_voff[idx] : kOob, is_soff, is_dst + idx * (NT * 16));
         else
@@ -325,13 +322,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-#ifdef CW_EXP_NOMFMA
-                    acc[i][j][0] += (float)fw[t % DEPTH][j][0] * (float)fx[t % DEPTH][i][0];
-#else
-                    acc[i][j] = Mfma<T>::mma(fw[t % DEPTH][j], fx[t % DEPTH][i], acc[i][j]);
-#endif
-                }
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[t % DEPTH][j], fx[t % DEPTH][i], acc[i][j]);
             if (decltype(with_loads)::value) {
 #pragma unroll
                 for (int idx = t * LOADS / KK; idx < (t + 1) * LOADS / KK; ++idx) issue_piece(idx);

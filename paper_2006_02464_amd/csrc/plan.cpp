@@ -437,6 +437,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                         snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1", o1.kh, o1.kw, o1.stride);
                     }
                     l.info.tile_m = l.fused_bm; l.info.tile_n = a.Cout; l.info.tile_k = 64; l.info.split_k = 1;
+                    l.info.conv_tile = -1; l.info.wave_groups = l.fused_kg;
                     p.launches.push_back(l);
                     break;
                 }
@@ -459,9 +460,12 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                                &l.tile, &a.split_k);
                 if (l.stem) l.tile = conv_tile_one_group(l.tile);   // the first convolution's mode has no wave groups
                 if (conv_bk(a, l.stem, l.tile) != conv_tile_dim(l.tile).bk) l.tile = conv_tile_k64(l.tile);  // Cin % 128 != 0
-                const int ktiles = a.K / conv_bk(a, l.stem, l.tile);
+                int ktiles = a.K / conv_bk(a, l.stem, l.tile);
                 a.split_k = std::max(1, std::min(a.split_k, ktiles));
-                if (a.split_k > 1) l.tile = conv_tile_one_group(l.tile);   // wave groups and split-K exclude each other
+                if (a.split_k > 1) {
+                    l.tile = conv_tile_one_group(l.tile);   // wave groups and split-K exclude each other
+                    ktiles = a.K / conv_bk(a, l.stem, l.tile);   // the one-group form may have narrower K slices
+                }
                 {
                     const TileDim tdc = conv_tile_dim(l.tile);
                     const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);
@@ -484,6 +488,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 l.info.flops = 2 * (int64_t)a.M * a.Cout * real_k;
                 const TileDim td = conv_tile_dim(l.tile);
                 l.info.tile_m = td.bm; l.info.tile_n = td.bn; l.info.tile_k = conv_bk(a, l.stem, l.tile); l.info.split_k = a.split_k;
+                l.info.conv_tile = l.tile; l.info.wave_groups = td.kg;
                 if (a.split_k > 1) {
                     partial_bytes = (size_t)a.split_k * a.M * a.Cout * 4;
                     partial_off = ws_alloc(partial_bytes);
@@ -588,6 +593,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         l.info.op_index = l.op_index;
         if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }
         l.info.kind = l.kind;
+        if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }
         l.info.grid_x = g.x; l.info.grid_y = g.y; l.info.grid_z = g.z; l.info.block = b;
         if (l.info.split_k == 0) l.info.split_k = 1;
     }

@@ -28,7 +28,6 @@ TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x
              "128x64k128g2": (128, 64), "64x64k128g2": (64, 64), "64x64k128g4": (64, 64), "64x32k128g4": (64, 32),
              "32x64k128g4": (32, 64), "32x32k128g4": (32, 32),
              "32x32k128g8": (32, 32), "128x64g2": (128, 64), "64x64g2": (64, 64), "32x32g4": (32, 32)}
-BASE_THREADS = {(128, 128): 256, (128, 64): 256, (64, 64): 256, (64, 32): 128, (32, 64): 128, (32, 32): 64, (256, 64): 256}
 POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 
 
@@ -52,13 +51,6 @@ def candidates(M, N, K, kh):
 
 def rows(table):
     return [k + v for k, v in table.items()]
-
-
-def tile_name(block, bm, bn, bk):
-    if (bm, bn) == (128, 128) and block == 512:
-        return "128x128w8"
-    groups = block // BASE_THREADS[(bm, bn)]
-    return "%dx%d%s%s" % (bm, bn, "k128" if bk == 128 else "", "g%d" % groups if groups > 1 else "")
 
 
 class Bench:
@@ -85,7 +77,6 @@ class Bench:
 
     def plan_choices(self, batch):
         """{shape key: (tile index, split)} as the library plans this batch size now."""
-        from .binding import CONV_TILES
         mid = self._define(batch, {})
         out = {}
         for l in self.wk.ctx.plan(mid, batch):
@@ -93,7 +84,7 @@ class Bench:
                 continue
             o = self.ops[l["op_index"]]
             key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride
-            out[key] = (CONV_TILES[tile_name(l["block"], l["tile_m"], l["tile_n"], l["tile_k"])], l["split_k"])
+            out[key] = (l["conv_tile"], l["split_k"])
         return out
 
     def measure(self, batch, table):
