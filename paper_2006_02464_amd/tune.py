@@ -31,7 +31,7 @@ TILE_DIMS = {"128x128": (128, 128), "128x64": (128, 64), "64x64": (64, 64), "64x
 POOLS = dict(workspace_bytes=1024 << 20, io_bytes=64 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
 
 
-def candidates(M, N, K, kh):
+def candidates(M, N, K, kh, stride=1):
     """(tile, split) pairs worth trying for one GEMM shape."""
     cin = K // (kh * kh)   # 3 for the first convolution: no k128 tiles, K slices are pairs of filter rows
     out = []
@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--batches", default="1,2,4,8,16")
     ap.add_argument("--reps", type=int, default=60)
     ap.add_argument("--eps", type=float, default=0.2, help="a candidate must win by this many us")
+    ap.add_argument("--kh", type=int, default=0, help="only retune shapes with this filter size (the others keep the library's choice)")
+    ap.add_argument("--only-suffix", default="", help="only try tiles whose name ends like this")
+    ap.add_argument("--verbose", action="store_true", help="print every candidate's time")
     ap.add_argument("--out", default=TABLE)
     args = ap.parse_args()
     from .binding import CONV_TILES
@@ -118,11 +121,17 @@ def main():
         print("batch %d: %d shapes, start %.1f us" % (batch, len(cur), t0), flush=True)
         for key in sorted(cur, key=lambda k: -k[0] * k[1] * k[2]):
             best, best_t = cur[key], b.measure(batch, cur)
-            for tile, s in candidates(*key[:4]):
+            if args.kh and key[3] != args.kh:
+                continue
+            for tile, s in candidates(*key):
+                if args.only_suffix and not tile.endswith(args.only_suffix):
+                    continue
                 cand = (CONV_TILES[tile], s)
                 if cand == cur[key]:
                     continue
                 t = b.measure(batch, {**cur, key: cand})
+                if args.verbose:
+                    print("      %s %s split %d: %.1f us (incumbent %.1f)" % (key, tile, s, t, best_t), flush=True)
                 if t < best_t - args.eps:
                     best, best_t = cand, t
             if best != cur[key]:
