@@ -216,8 +216,8 @@ int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
  * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
  * instead of 64 (used where cin % 128 == 0, else their 64 form), then tiles whose waves come in
  * 2, 4 or 8 groups that share every K slice (128 wide: 128x64 in 2, 64x64 in 2 and 4, 64x32,
- * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; no split-K
- * with those: a request for both drops the groups);
+ * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; the first
+ * convolution takes a grouped tile's one-group form);
  * pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */

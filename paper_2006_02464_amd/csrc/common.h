@@ -97,7 +97,7 @@ struct SoftmaxArgs {
 // Tile shapes the conv kernel is instantiated for (fixed at plan time per layer).
 // (pixels x channels per workgroup; "wN" = N waves when not 4, each wave then owning 64x64;
 // "k128" = K slices of 128 instead of 64, for Cin % 128 == 0; "gN" = N groups of waves that split
-// every K slice between them and add up at the end; no split-K with those)
+// every K slice between them and add up at the end)
 enum ConvTile : int32_t {
     T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8,
     T128x64k128, T64x64k128, T64x32k128, T32x64k128, T32x32k128,

@@ -70,11 +70,12 @@ constexpr int kFusedMaxCout2 = 1024;
 // KG > 1: KG groups of WARPS_M x WARPS_N waves share the tile; group g takes the 16-k steps
 // g, g+KG, ... of every slice and the groups' accumulators are added through LDS at the end.  For
 // small tiles with a long K this shortens the per-slice MFMA chain of a wave (and puts several
-// waves on each SIMD) without the global exchange of split-K.
+// waves on each SIMD) without the global exchange of split-K; with split-K on top (tiny M*N, very
+// long K) the first group carries the workgroup's sum into that exchange and the others end.
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
-    static_assert(KG == 1 || (!SPLITK && (BK / 16) % KG == 0 && (!FUSED || KG == 2)), "K groups: no split-K, whole steps per group");
+    static_assert(KG == 1 || ((BK / 16) % KG == 0 && (!FUSED || KG == 2)), "K groups: whole steps per group");
     static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
     constexpr int NT = 64 * WARPS_M * WARPS_N * KG;
     constexpr int WM = BM / WARPS_M, WN = BN / WARPS_N;
@@ -654,34 +655,34 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
             if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T128x64k128g2:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 128, 64, 2, 2, 128, MODE, false, 2>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 128, 64, 2, 2, 128, MODE, SPLITK, 2>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T64x64k128g2:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 128, MODE, false, 2>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 64, 2, 2, 128, MODE, SPLITK, 2>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T64x64k128g4:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 128, MODE, false, 4>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 64, 2, 2, 128, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T64x32k128g4:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 32, 2, 1, 128, MODE, false, 4>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 32, 2, 1, 128, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T32x64k128g4:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 64, 1, 2, 128, MODE, false, 4>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 64, 1, 2, 128, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T32x32k128g4:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 128, MODE, false, 4>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T32x32k128g8:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 128, MODE, false, 8>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 128, MODE, SPLITK, 8>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T128x64g2:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 128, 64, 2, 2, 64, MODE, false, 2>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 128, 64, 2, 2, 64, MODE, SPLITK, 2>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T64x64g2:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 64, 64, 2, 2, 64, MODE, false, 2>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 64, 64, 2, 2, 64, MODE, SPLITK, 2>(grid, block, a, s);
             return hipErrorInvalidValue;
         case T32x32g4:
-            if constexpr (MODE != MODE_STEM && !SPLITK) return launch_one<T, 32, 32, 1, 1, 64, MODE, false, 4>(grid, block, a, s);
+            if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 64, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }

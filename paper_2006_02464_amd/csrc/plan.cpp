@@ -460,12 +460,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                                &l.tile, &a.split_k);
                 if (l.stem) l.tile = conv_tile_one_group(l.tile);   // the first convolution's mode has no wave groups
                 if (conv_bk(a, l.stem, l.tile) != conv_tile_dim(l.tile).bk) l.tile = conv_tile_k64(l.tile);  // Cin % 128 != 0
-                int ktiles = a.K / conv_bk(a, l.stem, l.tile);
+                const int ktiles = a.K / conv_bk(a, l.stem, l.tile);
                 a.split_k = std::max(1, std::min(a.split_k, ktiles));
-                if (a.split_k > 1) {
-                    l.tile = conv_tile_one_group(l.tile);   // wave groups and split-K exclude each other
-                    ktiles = a.K / conv_bk(a, l.stem, l.tile);   // the one-group form may have narrower K slices
-                }
                 {
                     const TileDim tdc = conv_tile_dim(l.tile);
                     const int64_t tiles = ((int64_t)a.M + tdc.bm - 1) / tdc.bm * ((a.Cout + tdc.bn - 1) / tdc.bn);

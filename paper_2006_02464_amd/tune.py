@@ -43,7 +43,7 @@ def candidates(M, N, K, kh, stride=1):
         ktiles = K // (128 if "k128" in tile else 64)
         tiles = -(-M // bm) * -(-N // bn)
         for s in SPLITS:
-            if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20) or "g" in tile):
+            if s > 1 and (s > ktiles or tiles >= 1024 or M * N * 4 * s > (64 << 20)):
                 continue
             out.append((tile, s))
     return out
