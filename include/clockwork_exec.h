@@ -81,9 +81,11 @@ typedef struct {
     int32_t device;             /* HIP device ordinal */
     size_t workspace_bytes;     /* intermediates of the one EXEC in flight (paper: 512 MB) */
     size_t io_bytes;            /* IO cache: inputs and outputs of in-flight INFERs (paper: 512 MB) */
-    size_t weight_pool_bytes;   /* packed weights of all resident models */
+    size_t weight_pool_bytes;   /* packed weights of all resident models, handed out in pages */
     size_t load_staging_bytes;  /* device landing zone of one canonical blob during LOAD;
                                    must be >= the largest blob that will be loaded */
+    size_t weight_page_bytes;   /* page size of the weight pool; 0 = 16 MiB (the paper's, section 5.1);
+                                   a multiple of 256, and no weight tensor may be larger */
 } cw_config;
 
 /* Allocates every device buffer the context will ever use.  [host] cfg. */
@@ -120,16 +122,24 @@ size_t cw_model_workspace_bytes(cw_ctx *ctx, int32_t model_id, int32_t batch);
  * Canonical blob [host]: for every op that owns weights (CONV, FC), in op order,
  * W[cout][cin][kh][kw] in the model's storage type, back to back; zero padding to
  * a multiple of 4 bytes; then every bias[cout] as fp32 in the same op order.
- * LOAD reserves room in the weight pool (CW_ERR_NO_MEMORY if it does not fit: the
- * paper's LOAD aborts when no pages are free), copies the blob to the device on
- * `stream` and re-lays it out there for the MFMA kernels.  The same packed
- * weights serve every batch size.  `bytes` must equal cw_model_weight_bytes(). */
+ * The weight pool is a set of equal pages (section 5.1; cw_config.weight_page_bytes).  A
+ * model's packed tensors were given places in cw_model_weight_pages() pages of its own when it
+ * was defined, none straddling a page boundary; LOAD takes that many free pages of the pool,
+ * whichever they are (lowest-numbered first; CW_ERR_NO_MEMORY when fewer are free: the
+ * paper's LOAD aborts when no pages are free), copies the blob to the device on `stream`
+ * and re-lays it out there, tensor by tensor, for the MFMA kernels, which receive each
+ * tensor's address as a kernel argument.  The same packed weights serve every batch size.
+ * `bytes` must equal cw_model_weight_bytes(). */
 int32_t cw_load_weights(cw_ctx *ctx, int32_t model_id, const void *host_blob,
                         size_t bytes, void *stream);
 /* Metadata only; succeeds whether or not the model is resident (section 5.2). */
 int32_t cw_unload_weights(cw_ctx *ctx, int32_t model_id);
-/* Bytes currently free in the weight pool (the controller-visible memory state). */
+/* Free pages of the weight pool: the only memory state a controller needs (section 5.1);
+ * in bytes (free pages x page size), and as a count.  cw_model_weight_pages: the pages one
+ * LOAD of the model takes (negative: unknown id). */
 size_t cw_weight_pool_free(cw_ctx *ctx);
+int32_t cw_weight_pages_free(cw_ctx *ctx);
+int32_t cw_model_weight_pages(cw_ctx *ctx, int32_t model_id);
 
 /* ---- INFER = INPUT, EXEC, OUTPUT (section 5.2) --------------------------------
  * INPUT: takes an IO slot and copies host_nchw [host], fp32 [batch][in_c][in_h][in_w],

@@ -31,7 +31,7 @@ class cw_op(Structure):
 
 class cw_config(Structure):
     _fields_ = [("device", c_int32), ("workspace_bytes", c_size_t), ("io_bytes", c_size_t),
-                ("weight_pool_bytes", c_size_t), ("load_staging_bytes", c_size_t)]
+                ("weight_pool_bytes", c_size_t), ("load_staging_bytes", c_size_t), ("weight_page_bytes", c_size_t)]
 
 
 class cw_profile(Structure):
@@ -59,6 +59,8 @@ SIGNATURES = {
     "cw_load_weights": (c_int32, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
     "cw_unload_weights": (c_int32, [c_void_p, c_int32]),
     "cw_weight_pool_free": (c_size_t, [c_void_p]),
+    "cw_weight_pages_free": (c_int32, [c_void_p]),
+    "cw_model_weight_pages": (c_int32, [c_void_p, c_int32]),
     "cw_input": (c_int32, [c_void_p, c_int32, c_int32, c_void_p, POINTER(c_int32), c_void_p]),
     "cw_exec": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p]),
     "cw_output": (c_int32, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]),
@@ -137,9 +139,9 @@ class Context:
     raise :class:`CwError` on a negative status."""
 
     def __init__(self, device=0, workspace_bytes=512 << 20, io_bytes=512 << 20,
-                 weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20):
+                 weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20, weight_page_bytes=0):
         self._h = c_void_p()
-        cfg = cw_config(device, workspace_bytes, io_bytes, weight_pool_bytes, load_staging_bytes)
+        cfg = cw_config(device, workspace_bytes, io_bytes, weight_pool_bytes, load_staging_bytes, weight_page_bytes)
         st = lib().cw_create(byref(self._h), byref(cfg))
         if st != CW_OK:
             self._h = c_void_p()
@@ -198,6 +200,12 @@ class Context:
 
     def weight_pool_free(self):
         return lib().cw_weight_pool_free(self._h)
+
+    def weight_pages_free(self):
+        return self._check(lib().cw_weight_pages_free(self._h))
+
+    def model_weight_pages(self, model_id):
+        return self._check(lib().cw_model_weight_pages(self._h, model_id))
 
     # -- INFER
     def input(self, model_id, batch, host_nchw, stream=None):

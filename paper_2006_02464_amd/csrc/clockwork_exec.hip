@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <memory>
 #include <string>
 #include <vector>
@@ -16,6 +17,7 @@ using namespace cw;
 namespace {
 
 constexpr int kMaxSlots = 64;
+constexpr size_t kDefaultPageBytes = (size_t)16 << 20;  // the paper's page size (section 5.1)
 constexpr int kProfileEvents = 128;  // EXECs timed back to back between two host syncs
 
 enum SlotState { SLOT_FREE = 0, SLOT_INPUT, SLOT_EXECUTED };
@@ -35,13 +37,13 @@ struct Slot {
 struct PlanGraph {
     hipGraphExec_t exec = nullptr;
     size_t first = 0, last = 0;  // launches [first, last] are inside the graph
-    size_t pool_off = 0;         // weight placement the graph was captured for
+    std::vector<int32_t> pages;  // weight placement the graph was captured for
 };
 
 struct ModelRt {
     Model m;
     bool loaded = false;
-    size_t pool_off = 0;
+    std::vector<int32_t> pages;  // pool page of each of the model's weight pages while resident
     hipEvent_t load_done = nullptr;
     std::vector<PlanGraph> graphs;  // parallel to m.plans
 };
@@ -52,7 +54,9 @@ struct cw_ctx {
     int device = -1;       // -1: planning-only context without a GPU
     cw_config cfg{};
     char *workspace = nullptr, *io = nullptr, *pool = nullptr, *staging = nullptr;
-    RangeAllocator io_alloc, pool_alloc;
+    RangeAllocator io_alloc;
+    size_t page_bytes = 0;            // weight pool page size
+    std::vector<int32_t> free_pages;  // free pages of the weight pool, lowest index last (taken first)
     Slot slots[kMaxSlots];
     std::vector<std::unique_ptr<ModelRt>> models;
     PlanOverride ov;
@@ -112,7 +116,7 @@ Plan *get_plan(ModelRt *m, int32_t batch) {
 char *resolve(cw_ctx *c, const ModelRt *m, const Slot *s, const Ref &r) {
     switch (r.space) {
         case SP_WORKSPACE: return c->workspace + r.offset;
-        case SP_WEIGHTS: return c->pool + m->pool_off + r.offset;
+        case SP_WEIGHTS: return c->pool + (size_t)m->pages[r.offset / c->page_bytes] * c->page_bytes + r.offset % c->page_bytes;
         case SP_SLOT_INPUT: return c->io + s->in_off;
         case SP_SLOT_LOGITS: return c->io + s->logits_off;
         case SP_SLOT_PROBS: return c->io + s->probs_off;
@@ -284,7 +288,7 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
     for (size_t pi = 0; pi < m->m.plans.size(); ++pi) {
         const Plan &p = m->m.plans[pi];
         PlanGraph &pg = m->graphs[pi];
-        if (pg.exec && pg.pool_off == m->pool_off) continue;  // still valid from an earlier LOAD
+        if (pg.exec && pg.pages == m->pages) continue;  // still valid from an earlier LOAD into the same pages
         if (pg.exec) { (void)hipGraphExecDestroy(pg.exec); pg.exec = nullptr; }
         // longest run of slot-independent launches
         size_t best_a = 0, best_n = 0, a = 0;
@@ -309,7 +313,7 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
         if (e != hipSuccess) { pg.exec = nullptr; return hip_fail(c, e, "hipGraphInstantiate"); }
         pg.first = best_a;
         pg.last = best_a + best_n - 1;
-        pg.pool_off = m->pool_off;
+        pg.pages = m->pages;
     }
     return CW_OK;
 }
@@ -361,7 +365,9 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
     c->cfg = *cfg;
     c->device = cfg->device;
     c->io_alloc.reset(cfg->io_bytes);
-    c->pool_alloc.reset(cfg->weight_pool_bytes);
+    c->page_bytes = cfg->weight_page_bytes ? cfg->weight_page_bytes : kDefaultPageBytes;
+    if (c->page_bytes % 256 != 0) { g_create_err = "weight_page_bytes must be a multiple of 256"; return CW_ERR_INVALID; }
+    for (int32_t pg = (int32_t)(cfg->weight_pool_bytes / c->page_bytes) - 1; pg >= 0; --pg) c->free_pages.push_back(pg);
     if (cfg->device < 0) {  // planning-only: models and plans can be defined and inspected
         *out = c.release();
         return CW_OK;
@@ -484,7 +490,7 @@ int32_t cw_model_define(cw_ctx *c, const cw_op *ops, int32_t n_ops, int32_t in_c
     if (!c || !ops || !batch_sizes || n_batch < 1 || !model_id) return set_err(c, CW_ERR_INVALID, "null or empty argument");
     std::unique_ptr<ModelRt> m(new ModelRt);
     std::string err;
-    int32_t rc = model_init(&m->m, ops, n_ops, in_c, in_h, in_w, dtype, &err);
+    int32_t rc = model_init(&m->m, ops, n_ops, in_c, in_h, in_w, dtype, c->page_bytes, &err);
     if (rc != CW_OK) return set_err(c, rc, err);
     m->m.keep_all = c->ov.keep_all;
     for (int i = 0; i < n_batch; ++i) {
@@ -533,7 +539,20 @@ size_t cw_model_workspace_bytes(cw_ctx *c, int32_t model_id, int32_t batch) {
     return p ? p->workspace_bytes : 0;
 }
 
-size_t cw_weight_pool_free(cw_ctx *c) { return c ? c->pool_alloc.free_bytes() : 0; }
+size_t cw_weight_pool_free(cw_ctx *c) { return c ? c->free_pages.size() * c->page_bytes : 0; }
+int32_t cw_weight_pages_free(cw_ctx *c) { return c ? (int32_t)c->free_pages.size() : CW_ERR_INVALID; }
+int32_t cw_model_weight_pages(cw_ctx *c, int32_t model_id) {
+    ModelRt *m = c ? get_model(c, model_id) : nullptr;
+    return m ? m->m.n_pages : CW_ERR_INVALID;
+}
+
+// Returns a model's pages to the pool; the free list stays sorted so that the lowest page is
+// taken first and placement is a function of the LOAD/UNLOAD history alone.
+static void release_pages(cw_ctx *c, ModelRt *m) {
+    c->free_pages.insert(c->free_pages.end(), m->pages.begin(), m->pages.end());
+    std::sort(c->free_pages.begin(), c->free_pages.end(), std::greater<int32_t>());
+    m->pages.clear();
+}
 
 int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size_t bytes, void *stream) {
     if (!c) return CW_ERR_INVALID;
@@ -543,32 +562,35 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     if (bytes != m->m.blob_bytes) return set_err(c, CW_ERR_INVALID, "blob size does not match the model");
     if (m->loaded) return set_err(c, CW_ERR_ALREADY_LOADED, "model is resident");
     if (bytes > c->cfg.load_staging_bytes) return set_err(c, CW_ERR_NO_MEMORY, "blob larger than the LOAD staging area");
-    size_t off = 0;
-    if (!c->pool_alloc.alloc(m->m.packed_bytes, &off)) return set_err(c, CW_ERR_NO_MEMORY, "weight pool is full");
+    // LOAD takes whole pages, any that are free (paper section 5.1): no fragmentation, and whether a
+    // LOAD fits depends on the free-page count alone.
+    if ((size_t)m->m.n_pages > c->free_pages.size()) return set_err(c, CW_ERR_NO_MEMORY, "not enough free weight pages");
+    m->pages.assign(c->free_pages.end() - m->m.n_pages, c->free_pages.end());
+    std::reverse(m->pages.begin(), m->pages.end());  // lowest page first
+    c->free_pages.resize(c->free_pages.size() - m->m.n_pages);
     DeviceGuard g(c->device);
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto bail = [&](hipError_t e, const char *what) {
-        c->pool_alloc.free(off, m->m.packed_bytes);
+        release_pages(c, m);
         return hip_fail(c, e, what);
     };
     hipError_t e;
     // One staging area: a LOAD waits for the previous LOAD's pack kernels.
     if (c->staging_used && (e = hipStreamWaitEvent(st, c->staging_free, 0)) != hipSuccess) return bail(e, "hipStreamWaitEvent");
     if ((e = hipMemcpyAsync(c->staging, host_blob, bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "hipMemcpyAsync");
-    char *base = c->pool + off;
+    auto at = [&](size_t off) { return c->pool + (size_t)m->pages[off / c->page_bytes] * c->page_bytes + off % c->page_bytes; };
     for (const WeightSlot &ws : m->m.wslots) {
         const bool is_conv = m->m.ops[ws.op_index].op == CW_OP_CONV;
-        e = launch_pack_weights(c->staging + ws.blob_w_off, base + ws.packed_w_off, ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
+        e = launch_pack_weights(c->staging + ws.blob_w_off, at(ws.packed_w_off), ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
                                 ws.kwp, ws.cinp, is_conv, st);
         if (e != hipSuccess) return bail(e, "pack_weights");
         e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
-                            reinterpret_cast<float *>(base + ws.packed_b_off), ws.cout, st);
+                            reinterpret_cast<float *>(at(ws.packed_b_off)), ws.cout, st);
         if (e != hipSuccess) return bail(e, "copy bias");
     }
     if ((e = hipEventRecord(c->staging_free, st)) != hipSuccess) return bail(e, "hipEventRecord");
     c->staging_used = true;
     if ((e = hipEventRecord(m->load_done, st)) != hipSuccess) return bail(e, "hipEventRecord");
-    m->pool_off = off;
     m->loaded = true;
     if (c->use_graphs) {
         const int32_t rc = build_graphs(c, m);
@@ -584,7 +606,7 @@ int32_t cw_unload_weights(cw_ctx *c, int32_t model_id) {
     ModelRt *m = get_model(c, model_id);
     if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
     if (m->loaded) {
-        c->pool_alloc.free(m->pool_off, m->m.packed_bytes);
+        release_pages(c, m);
         m->loaded = false;
     }
     return CW_OK;

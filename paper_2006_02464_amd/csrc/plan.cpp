@@ -110,7 +110,7 @@ static int32_t fail(std::string *err, int32_t code, const char *fmt, int a = 0, 
 }
 
 int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
-                   int32_t dtype, std::string *err) {
+                   int32_t dtype, size_t page_bytes, std::string *err) {
     if (!ops || n_ops < 3) return fail(err, CW_ERR_INVALID, "need at least 3 ops");
     if (dtype != CW_DTYPE_FP16 && dtype != CW_DTYPE_BF16) return fail(err, CW_ERR_INVALID, "bad dtype %d", dtype);
     if (in_c < 1 || in_h < 1 || in_w < 1) return fail(err, CW_ERR_INVALID, "bad input size");
@@ -211,20 +211,33 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         }
     }
     m->classes = ops[n_ops - 2].cout;
+    // Packed tensors get offsets in the model's own address range, which LOAD maps page by page
+    // onto whatever pages of the weight pool are free (paper section 5.1: weights live in fixed-size
+    // pages): a tensor that would cross a page boundary starts on the next page instead, so every
+    // tensor is contiguous in device memory wherever its page lands.  Fixed here, once, for every
+    // batch size.
+    if (page_bytes == 0 || page_bytes % 256 != 0) return fail(err, CW_ERR_INVALID, "weight page size must be a positive multiple of 256");
     size_t blob_b = align_up(blob_w, 4), packed = 0;
+    bool too_big = false;
+    auto place = [&](size_t bytes) {
+        if (bytes > page_bytes) too_big = true;
+        if (packed % page_bytes + bytes > page_bytes) packed = align_up(packed, page_bytes);
+        const size_t at = packed;
+        packed = align_up(packed + bytes, 256);
+        return at;
+    };
     for (WeightSlot &ws : m->wslots) {
         ws.blob_b_off = blob_b;
         blob_b += (size_t)ws.cout * 4;
-        ws.packed_w_off = packed;
         ws.packed_w_bytes = (size_t)ws.cout * ws.khp * ws.kwp * ws.cinp * 2;
-        packed = align_up(packed + ws.packed_w_bytes, 256);
+        ws.packed_w_off = place(ws.packed_w_bytes);
     }
-    for (WeightSlot &ws : m->wslots) {
-        ws.packed_b_off = packed;
-        packed = align_up(packed + (size_t)ws.cout * 4, 256);
-    }
+    for (WeightSlot &ws : m->wslots) ws.packed_b_off = place((size_t)ws.cout * 4);
+    if (too_big) return fail(err, CW_ERR_UNSUPPORTED, "a weight tensor is larger than a weight page (%d bytes)", (int)page_bytes);
     m->blob_bytes = blob_b;
     m->packed_bytes = packed;
+    m->page_bytes = page_bytes;
+    m->n_pages = (int32_t)((packed + page_bytes - 1) / page_bytes);
     return CW_OK;
 }
 

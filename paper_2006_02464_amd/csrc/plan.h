@@ -83,7 +83,9 @@ struct Model {
     std::vector<WeightSlot> wslots;
     std::vector<int32_t> op_wslot;  // op index -> index in wslots or -1
     size_t blob_bytes = 0;
-    size_t packed_bytes = 0;
+    size_t packed_bytes = 0;   // end of the packed weights in the model's own (virtual) address range
+    size_t page_bytes = 0;     // weight page size the layout was made for; no tensor straddles a multiple of it
+    int32_t n_pages = 0;       // pages a LOAD takes
     std::vector<Plan> plans;
     bool keep_all = false;
 };
@@ -91,7 +93,7 @@ struct Model {
 // Validates the op list and fills shapes, weight slots and sizes.  Returns CW_OK or an error
 // with a message in *err.
 int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
-                   int32_t dtype, std::string *err);
+                   int32_t dtype, size_t page_bytes, std::string *err);
 // Compiles the plan of one batch size.
 int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err);
 // Operator list of ResNet-18/50/152.

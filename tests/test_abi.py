@@ -200,3 +200,33 @@ def test_fusion_of_bottleneck_tail(ctx):
         assert not [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0]
     finally:
         ctx.set_debug_keep(False)
+
+
+def test_weight_pages():
+    """The weight pool is paged (paper section 5.1): page counts per model, the limits, the free count."""
+    c = cw.Context(device=-1, weight_pool_bytes=1 << 30)          # default page: 16 MiB
+    try:
+        assert c.weight_pages_free() == 64 and c.weight_pool_free() == 1 << 30
+        pages = {d: c.model_weight_pages(c.model_define_resnet(d, 224, 224)) for d in (18, 50, 152)}
+        assert pages == {18: 2, 50: 4, 152: 8}
+    finally:
+        c.destroy()
+    c = cw.Context(device=-1, weight_pool_bytes=100 << 20, weight_page_bytes=8 << 20)
+    try:
+        assert c.weight_pages_free() == 12                        # the pool's tail below a page is unused
+        m = c.model_define_resnet(50, 224, 224)
+        n = c.model_weight_pages(m)
+        packed_at_least = c.model_weight_bytes(m)                 # packing only ever pads
+        assert -(-packed_at_least // (8 << 20)) <= n <= 8         # 51 MB: 7 pages minimum, little lost at page ends
+        assert c.model_weight_pages(c.model_define_resnet(50, 224, 224)) == n   # a pure function of the model
+    finally:
+        c.destroy()
+    c = cw.Context(device=-1, weight_page_bytes=4 << 20)          # ResNet's largest tensor (4.7 MB) does not fit a page
+    try:
+        with pytest.raises(cw.CwError) as e:
+            c.model_define_resnet(18, 64, 64)
+        assert e.value.status == cw.CW_ERR_UNSUPPORTED
+    finally:
+        c.destroy()
+    with pytest.raises(cw.CwError):
+        cw.Context(device=-1, weight_page_bytes=1000)             # not a multiple of 256

@@ -15,8 +15,9 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def setup():
     from paper_2006_02464_amd.runner import Worker
-    w = Worker(workspace_bytes=64 << 20, io_bytes=32 << 20, weight_pool_bytes=60 << 20,
-               load_staging_bytes=32 << 20)
+    # 8 weight pages of 8 MiB; a ResNet-18 takes 4 of them
+    w = Worker(workspace_bytes=64 << 20, io_bytes=32 << 20, weight_pool_bytes=64 << 20,
+               load_staging_bytes=32 << 20, weight_page_bytes=8 << 20)
     case = Case(T.resnet(18), 64, seed=0, dist="uniform")
     yield w, case
     w.close()
@@ -62,7 +63,8 @@ def test_load_aborts_when_pool_is_full_and_unload_frees(setup):
     b = ctx.model_define_resnet(18, 64, 64)
     c = ctx.model_define_resnet(18, 64, 64)
     w.load(a, case.blob)
-    w.load(b, case.blob)                   # 2 x 23.4 MB fit in 60 MB
+    w.load(b, case.blob)                   # 2 x 4 pages fill the pool of 8
+    assert ctx.model_weight_pages(a) == 4 and ctx.weight_pages_free() == 0
     assert ctx.weight_pool_free() < free0 - 2 * 23_000_000
     assert _status(w.load, c, case.blob) == cw.CW_ERR_NO_MEMORY
     ctx.unload_weights(a)
@@ -74,6 +76,52 @@ def test_load_aborts_when_pool_is_full_and_unload_frees(setup):
     for m in (b, c):
         ctx.unload_weights(m)
     assert ctx.weight_pool_free() == free0
+
+
+def test_load_takes_any_free_pages(setup):
+    """Paper section 5.1: weights live in pages and a LOAD takes whichever are free.  Two one-page
+    models around a four-page one are unloaded: the 4 free pages are {0, 5, 6, 7}, no 4 of them
+    adjacent.  A second ResNet-18 must still LOAD into them and compute bit for bit what the copy in
+    pages 1-4 computes."""
+    w, case = setup
+    ctx = w.ctx
+    O = T.Op
+    small_ops = [O(T.CONV, 3, 64, 7, 7, 2, 3, 1, -1, -1), O(T.MAXPOOL, 64, 64, 3, 3, 2, 1, 0, -1, 0),
+                 O(T.CONV, 64, 512, 3, 3, 1, 1, 1, -1, 1), O(T.GAVGPOOL, 512, 512, 0, 0, 1, 0, 0, -1, 2),
+                 O(T.FC, 512, 10, 1, 1, 1, 0, 0, -1, 3), O(T.SOFTMAX, 10, 10, 0, 0, 1, 0, 0, -1, 4)]
+    small = Case(small_ops, 32, seed=3, dist="uniform")
+    assert ctx.weight_pages_free() == 8
+    s1 = ctx.model_define([tuple(o) for o in small_ops], 3, 32, 32)
+    s2 = ctx.model_define([tuple(o) for o in small_ops], 3, 32, 32)
+    a = ctx.model_define_resnet(18, 64, 64)
+    b = ctx.model_define_resnet(18, 64, 64)
+    assert ctx.model_weight_pages(s1) == 1
+    w.load(s1, small.blob)                 # page 0
+    w.load(a, case.blob)                   # pages 1-4
+    w.load(s2, small.blob)                 # page 5
+    assert ctx.weight_pages_free() == 2
+    assert _status(w.load, b, case.blob) == cw.CW_ERR_NO_MEMORY
+    ctx.unload_weights(s1)
+    ctx.unload_weights(s2)
+    assert ctx.weight_pages_free() == 4    # 0, 5, 6, 7
+    w.load(b, case.blob)
+    assert ctx.weight_pages_free() == 0
+    x = case.images(0, 4)
+    za = np.concatenate([w.infer(a, x[i:i + 2])[1] for i in (0, 2)])
+    zb = np.concatenate([w.infer(b, x[i:i + 2])[1] for i in (0, 2)])
+    assert np.array_equal(za, zb)
+    ref = case.oracle(x)["logits"]
+    assert (np.abs(zb - ref).max(axis=1) / np.abs(ref).max(axis=1)).max() <= 2e-2
+    # the small model again, now into a page that a ResNet-18 just used
+    ctx.unload_weights(a)
+    w.load(s1, small.blob)
+    xs = small.images(0, 2)
+    zs = w.infer(s1, xs, classes=10)[1]
+    rs = small.oracle(xs)["logits"]
+    assert (np.abs(zs - rs).max(axis=1) / np.abs(rs).max(axis=1)).max() <= 2e-2
+    for m in (b, s1):
+        ctx.unload_weights(m)
+    assert ctx.weight_pages_free() == 8
 
 
 def test_io_cache_exhaustion_and_reuse(setup):
