@@ -189,6 +189,7 @@ typedef struct {
     int32_t op_index;      /* which op of the model this launch belongs to (fused launch: the last) */
     int32_t fused_op;      /* -1, or the op this launch computes first, fused with op_index */
     int32_t proj_op;       /* -1, or the projection-shortcut op this launch computes as well */
+    int32_t pair_op;       /* -1, or a second, independent convolution over the same input computed by this launch */
     int32_t kind;          /* internal kernel family id */
     int32_t grid_x, grid_y, grid_z, block;
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
@@ -241,6 +242,13 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
  * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
  * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
 int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
+/* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
+ * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
+ * one launch whose first workgroups compute the one and the rest the other: one dispatch and one
+ * set-up latency instead of two.  Both run on one tile shape, so a member's sums may be added up
+ * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
+ * models defined afterwards; on != 0 restores the default. */
+int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
 /* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
  * The plan compiler takes the tile variant and split-K factor of a convolution from a table
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs

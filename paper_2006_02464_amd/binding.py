@@ -40,7 +40,7 @@ class cw_profile(Structure):
 
 
 class cw_launch_info(Structure):
-    _fields_ = [("op_index", c_int32), ("fused_op", c_int32), ("proj_op", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
+    _fields_ = [("op_index", c_int32), ("fused_op", c_int32), ("proj_op", c_int32), ("pair_op", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
                 ("grid_z", c_int32), ("block", c_int32), ("tile_m", c_int32), ("tile_n", c_int32),
                 ("tile_k", c_int32), ("split_k", c_int32), ("conv_tile", c_int32), ("wave_groups", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
                 ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
@@ -76,6 +76,7 @@ SIGNATURES = {
     "cw_set_plan_override": (c_int32, [c_void_p, c_int32, c_int32]),
     "cw_set_plan_table": (c_int32, [c_void_p, c_void_p, c_int32]),
     "cw_set_fusion": (c_int32, [c_void_p, c_int32]),
+    "cw_set_pair_launches": (c_int32, [c_void_p, c_int32]),
     "cw_set_use_graphs": (c_int32, [c_void_p, c_int32]),
     "cw_strerror": (c_char_p, [c_int32]),
     "cw_last_error": (c_char_p, [c_void_p]),
@@ -274,6 +275,9 @@ class Context:
         if isinstance(conv_tile, str):
             conv_tile = CONV_TILES[conv_tile]
         self._check(lib().cw_set_plan_override(self._h, conv_tile, split_k))
+
+    def set_pair_launches(self, on):
+        self._check(lib().cw_set_pair_launches(self._h, int(on)))
 
     def set_fusion(self, on):
         self._check(lib().cw_set_fusion(self._h, int(on)))

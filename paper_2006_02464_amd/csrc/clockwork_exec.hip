@@ -150,6 +150,15 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hi
                 a.biasd = reinterpret_cast<const float *>(resolve(c, m, s, l.biasd));
                 return launch_conv_fused(dt, l.fused_bm, l.fused_kg, a, st);
             }
+            if (l.pair_op >= 0) {
+                ConvArgs a0 = l.conv0;
+                a0.x = a.x;
+                a0.w = resolve(c, m, s, l.w0);
+                a0.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias0));
+                a0.res = resolve(c, m, s, l.res0);
+                a0.y = resolve(c, m, s, l.y0);
+                return launch_conv_pair(dt, l.tile, a0, a, st);
+            }
             return launch_conv(dt, l.tile, l.stem, a, st);
         }
         case K_MAXPOOL:
@@ -470,6 +479,12 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "fusion mode must be 0, 1 or 2");
     c->ov.fuse = on;
+    return CW_OK;
+}
+
+int32_t cw_set_pair_launches(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.pair = on != 0;
     return CW_OK;
 }
 

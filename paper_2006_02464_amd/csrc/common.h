@@ -124,6 +124,11 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
 // Workgroups of that launch.
 void conv_fused_grid(int bm, int kg, const ConvArgs &a, dim3 *grid, int *block);
 bool conv_fused_ok(int bm, int kg, int cout, int cout2);   // a (pixels per workgroup, wave groups) form exists for these widths
+// Two convolutions over the same input tensor in one launch (kernels_conv_dlds.hip), both on `tile`
+// (one of conv_pair_tile_ok), neither split along K.
+hipError_t launch_conv_pair(DType dt, ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, hipStream_t s);
+bool conv_pair_tile_ok(ConvTile tile);
+void conv_pair_grid(ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, dim3 *grid, int *block);
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);

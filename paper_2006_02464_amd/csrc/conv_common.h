@@ -229,11 +229,11 @@ static __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[TM][TN
 
 // Workgroups go to the 8 XCDs round-robin; give each XCD a contiguous run of tiles so that
 // tiles sharing pixels (same tile_m) meet in one XCD's L2.
-static __device__ __forceinline__ int xcd_tile_id() {
-    const int nb = gridDim.x, bid = blockIdx.x;
+static __device__ __forceinline__ int xcd_tile_id(int bid, int nb) {
     const int xcd = bid & 7, idx = bid >> 3;
     const int per = nb >> 3, rem = nb & 7;
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
+static __device__ __forceinline__ int xcd_tile_id() { return xcd_tile_id(blockIdx.x, gridDim.x); }
 
 }  // namespace cw

@@ -72,8 +72,10 @@ constexpr int kFusedMaxCout2 = 1024;
 // small tiles with a long K this shortens the per-slice MFMA chain of a wave (and puts several
 // waves on each SIMD) without the global exchange of split-K; with split-K on top (tiny M*N, very
 // long K) the first group carries the workgroup's sum into that exchange and the others end.
+// The body takes the launch's arguments and this workgroup's place bid among the nb workgroups of
+// the convolution (a launch may hold two convolutions, see conv_dlds_pair_kernel).
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
+static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const int bid, const int nb) {
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
     static_assert(KG == 1 || ((BK / 16) % KG == 0 && (!FUSED || KG == 2)), "K groups: whole steps per group");
     static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     const int lrow = lane & 31;
     const int lhalf = lane >> 5;
 
-    const int tile_id = xcd_tile_id();
+    const int tile_id = xcd_tile_id(bid, nb);
     const int tiles_n = a.Cout / BN + (a.Cout % BN != 0);
     const int tile_m = tile_id / tiles_n;
     const int tile_n = tile_id - tile_m * tiles_n;
@@ -598,6 +600,24 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     CW_STAMP_END(62);
 }
 
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
+    conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, gridDim.x);
+}
+
+// Two independent convolutions that read the same tensor (the first 1x1 of a bottleneck and the
+// projection shortcut beside it) in one launch: the first nb0 workgroups take the first, the rest
+// the second.  Same instantiation for both (general addressing mode, no split-K); one dispatch,
+// one set-up latency and one tail instead of two.
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int KG>
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_pair_kernel(const ConvArgs a0, const ConvArgs a1) {
+    const int nb0 = ((a0.M + BM - 1) / BM) * ((a0.Cout + BN - 1) / BN);
+    if ((int)blockIdx.x < nb0)
+        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a0, blockIdx.x, nb0);
+    else
+        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a1, blockIdx.x - nb0, gridDim.x - nb0);
+}
+
 // LDS stages per tile: 4 where that still lets two workgroups share a CU's 160 KiB, else 3.
 template <int BM, int BN, int BK>
 struct RingDepth {
@@ -741,6 +761,65 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
     CW_FUSED(64, 128);
 #undef CW_FUSED
 #undef CW_FUSED_T
+}
+
+template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int KG>
+static hipError_t launch_pair_one(const ConvArgs &a0, const ConvArgs &a1, hipStream_t s) {
+    constexpr int NS = RingDepth<BM, BN, BK>::value;
+    constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
+    auto kern = conv_dlds_pair_kernel<T, BM, BN, WARPS_M, WARPS_N, BK, NS, KG>;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(NS * stage_bytes));
+    if (attr != hipSuccess) return attr;
+    const size_t used = std::max((size_t)std::min(NS, std::max(a0.ktiles_per_split, a1.ktiles_per_split)) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
+    const unsigned nb0 = ((a0.M + BM - 1) / BM) * ((a0.Cout + BN - 1) / BN), nb1 = ((a1.M + BM - 1) / BM) * ((a1.Cout + BN - 1) / BN);
+    kern<<<dim3(nb0 + nb1, 1, 1), 64 * WARPS_M * WARPS_N * KG, used, s>>>(a0, a1);
+    return hipGetLastError();
+}
+
+bool conv_pair_tile_ok(ConvTile tile) {
+    switch (tile) {
+        case T128x64: case T128x64k128: case T64x64: case T64x64k128: case T64x32k128: case T32x64k128: case T32x32k128:
+        case T32x32k128g4: case T64x64k128g2: case T128x128: case T128x128w8: case T32x32: case T32x32g4: return true;
+        default: return false;
+    }
+}
+
+static bool conv_pair_member_ok(const ConvArgs &a, int bk) {
+    if (a.Cin % bk != 0 || a.K != a.kh * a.kw * a.Cin || a.kwp != a.kw || a.kh * a.kw > 32 || a.split_k != 1 || a.partial) return false;
+    if (a.ktiles_per_split != a.K / bk || a.M <= 0 || a.Cout % 32 != 0) return false;
+    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return false;
+    return (long long)a.M * a.Cout * 2 < (1ll << 31) && (long long)a.Cout * a.K * 2 < (1ll << 31);
+}
+
+void conv_pair_grid(ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, dim3 *grid, int *block) {
+    const TileDim d = conv_tile_dim(tile);
+    *grid = dim3(((a0.M + d.bm - 1) / d.bm) * ((a0.Cout + d.bn - 1) / d.bn) + ((a1.M + d.bm - 1) / d.bm) * ((a1.Cout + d.bn - 1) / d.bn), 1, 1);
+    *block = d.threads;
+}
+
+hipError_t launch_conv_pair(DType dt, ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, hipStream_t s) {
+    if (!conv_pair_tile_ok(tile)) return hipErrorInvalidValue;
+    const int bk = conv_tile_dim(tile).bk;
+    if (!conv_pair_member_ok(a0, bk) || !conv_pair_member_ok(a1, bk)) return hipErrorInvalidValue;
+#define CW_PAIR(BM_, BN_, WM_, WN_, BK_, KG_)                                                           \
+    return dt == DT_F16 ? launch_pair_one<f16, BM_, BN_, WM_, WN_, BK_, KG_>(a0, a1, s) : launch_pair_one<bf16, BM_, BN_, WM_, WN_, BK_, KG_>(a0, a1, s)
+    switch (tile) {
+        case T128x64: CW_PAIR(128, 64, 2, 2, 64, 1);
+        case T128x64k128: CW_PAIR(128, 64, 2, 2, 128, 1);
+        case T64x64: CW_PAIR(64, 64, 2, 2, 64, 1);
+        case T64x64k128: CW_PAIR(64, 64, 2, 2, 128, 1);
+        case T64x32k128: CW_PAIR(64, 32, 2, 1, 128, 1);
+        case T32x64k128: CW_PAIR(32, 64, 1, 2, 128, 1);
+        case T32x32k128: CW_PAIR(32, 32, 1, 1, 128, 1);
+        case T32x32k128g4: CW_PAIR(32, 32, 1, 1, 128, 4);
+        case T64x64k128g2: CW_PAIR(64, 64, 2, 2, 128, 2);
+        case T128x128: CW_PAIR(128, 128, 2, 2, 64, 1);
+        case T128x128w8: CW_PAIR(128, 128, 2, 4, 64, 1);
+        case T32x32: CW_PAIR(32, 32, 1, 1, 64, 1);
+        case T32x32g4: CW_PAIR(32, 32, 1, 1, 64, 4);
+        default: return hipErrorInvalidValue;
+    }
+#undef CW_PAIR
 }
 
 template <typename T, bool SPLITK>

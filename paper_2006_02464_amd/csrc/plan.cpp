@@ -308,11 +308,6 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (biggest >= (int64_t)1 << 30) return fail(err, CW_ERR_BAD_BATCH, "batch %d: a tensor exceeds 2^30 elements", batch);
     }
 
-    std::vector<int> last_use(n_ops, -1);
-    for (int i = 0; i < n_ops; ++i) {
-        if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = i;
-        if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) last_use[m.ops[i].residual_from] = i;
-    }
     // Pairs planned as one launch: op i = a convolution with 64 or 128 output channels (Cin % 64
     // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
     // convolution with a residual; enough pixels for the launch to fill the GPU.
@@ -340,7 +335,6 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             fuse_into[i] = j; fused_first[j] = i; fused_bm[j] = bm;
             // two wave groups pay off where one workgroup per CU is all the launch has anyway (the 128-channel form)
             fused_kg[j] = (ov.fuse == 1 && o1.cout == 128 && conv_fused_ok(bm, 2, o1.cout, o2.cout)) ? 2 : 1;
-            last_use[o1.input_from] = std::max(last_use[o1.input_from], j);  // read by the fused launch at j
             // The residual of op j may itself be a projection of a tensor as wide as op i's output
             // and aligned with it pixel for pixel (1x1, stride 1, no activation, used by nothing
             // else): then it is computed inside the launch too (64-channel form only).
@@ -352,9 +346,45 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 m.shapes[od.input_from].w == m.shapes[i].w) {
                 proj_of[j] = d;
                 fuse_into[d] = j;
-                last_use[od.input_from] = std::max(last_use[od.input_from], j);
             }
         }
+    }
+    // Order in which the ops are planned and launched: op order, except that a convolution j which
+    // reads the same tensor as an earlier convolution i and depends on nothing after i (a ResNet
+    // block's projection shortcut, i = the block's first 1x1) moves to right behind i, where the two
+    // become one launch (below).
+    std::vector<int> order;
+    {
+        std::vector<char> moved(n_ops, 0);
+        std::vector<int> partner(n_ops, -1);
+        if (ov.pair && ov.tile < 0 && ov.split_k <= 0) {
+            for (int i = 1; i < n_ops; ++i) {
+                const cw_op &a = m.ops[i];
+                if (a.op != CW_OP_CONV || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
+                for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
+                    const cw_op &b = m.ops[j];
+                    if (b.op != CW_OP_CONV || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j]) continue;
+                    if (b.residual_from >= i) continue;
+                    partner[i] = j; moved[j] = 1;
+                    break;
+                }
+            }
+        }
+        for (int i = 0; i < n_ops; ++i) {
+            if (moved[i]) continue;
+            order.push_back(i);
+            if (partner[i] >= 0) order.push_back(partner[i]);
+        }
+    }
+    std::vector<int> pos(n_ops);
+    for (int t = 0; t < n_ops; ++t) pos[order[t]] = t;
+    // Time (position in `order`) of the last read of every op's output.  An op computed inside a
+    // fused launch reads its inputs when that launch runs.
+    std::vector<int> last_use(n_ops, -1);
+    for (int i = 0; i < n_ops; ++i) {
+        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : i];
+        if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = std::max(last_use[m.ops[i].input_from], at);
+        if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
     }
     std::vector<size_t> out_bytes(n_ops, 0);
     RangeAllocator arena((size_t)1 << 46);
@@ -386,7 +416,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         p.launches.push_back(l);
     }
 
-    for (int i = 0; i < n_ops; ++i) {
+    for (int t = 0; t < n_ops; ++t) {
+        const int i = order[t];
         const cw_op &o = m.ops[i];
         const OpShape &os = m.shapes[i];
         int sc, sh, sw;
@@ -508,6 +539,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d_splitk%d", o.kh, o.kw, o.stride, a.split_k);
                 } else {
                     l.info.bytes = in_b + w_b + out_b + res_b;
+                    l.in_bytes = in_b;
                     snprintf(l.info.name, sizeof l.info.name, i == 0 ? "stem%dx%d_s%d" : "conv%dx%d_s%d", o.kh, o.kw, o.stride);
                 }
                 p.launches.push_back(l);
@@ -574,8 +606,9 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (partial_bytes) arena.free(partial_off, partial_bytes);
         if (!ov.keep_all) {
             if (i == 0) arena.free(cast_off, cast_bytes);
-            for (int j = 0; j <= i; ++j) {
-                const bool dead_now = (last_use[j] == i) || (j == i && last_use[j] < 0);
+            for (int j = 0; j < n_ops; ++j) {
+                if (pos[j] > t) continue;
+                const bool dead_now = (last_use[j] == t) || (j == i && last_use[j] < 0);
                 if (dead_now && p.op_out[j].space == SP_WORKSPACE && out_bytes[j]) {
                     arena.free(p.op_out[j].offset, out_bytes[j]);
                     out_bytes[j] = 0;
@@ -584,6 +617,43 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
     }
 
+    // Two consecutive convolution launches that read the same tensor and do not depend on each other
+    // (in a ResNet: the first 1x1 of a block and the projection shortcut beside it) become one
+    // launch on one tile shape: that of the one with more work, if the pair kernel has it and the
+    // other is at least a tile wide.
+    if (ov.pair && ov.tile < 0 && ov.split_k <= 0) {
+        for (size_t i = 0; i + 1 < p.launches.size(); ++i) {
+            Launch &l0 = p.launches[i], &l1 = p.launches[i + 1];
+            if (l0.kind != K_CONV || l1.kind != K_CONV || l0.stem || l1.stem || l0.fused_bm > 0 || l1.fused_bm > 0) continue;
+            if (l0.pair_op >= 0 || l1.pair_op >= 0 || l0.conv.split_k != 1 || l1.conv.split_k != 1) continue;
+            if (l0.x.space != l1.x.space || l0.x.offset != l1.x.offset || l0.conv.Cin != l1.conv.Cin || l0.conv.Cin % 64 != 0) continue;
+            if (m.ops[l1.op_index].input_from == l0.op_index || m.ops[l1.op_index].residual_from == l0.op_index) continue;
+            const ConvTile cand[2] = {l1.info.flops >= l0.info.flops ? l1.tile : l0.tile, l1.info.flops >= l0.info.flops ? l0.tile : l1.tile};
+            int pick = -1;
+            for (int k = 0; k < 2 && pick < 0; ++k) {
+                const TileDim d = conv_tile_dim(cand[k]);
+                if (conv_pair_tile_ok(cand[k]) && l0.conv.Cin % d.bk == 0 && d.bn <= l0.conv.Cout && d.bn <= l1.conv.Cout) pick = k;
+            }
+            if (pick < 0) continue;
+            const ConvTile tile = cand[pick];
+            const TileDim d = conv_tile_dim(tile);
+            Launch l = l1;
+            l.tile = tile;
+            l.pair_op = l0.op_index;
+            l.conv0 = l0.conv;
+            l.conv0.ktiles_per_split = l.conv0.K / d.bk;
+            l.conv.ktiles_per_split = l.conv.K / d.bk;
+            l.w0 = l0.w; l.bias0 = l0.bias; l.res0 = l0.res; l.y0 = l0.y;
+            l.info.flops = l0.info.flops + l1.info.flops;
+            l.info.bytes = l0.info.bytes + l1.info.bytes - std::min(l0.in_bytes, l1.in_bytes);   // the shared input once
+            l.info.tile_m = d.bm; l.info.tile_n = d.bn; l.info.tile_k = d.bk; l.info.conv_tile = tile; l.info.wave_groups = d.kg;
+            char name[48];
+            snprintf(name, sizeof name, "%.20s|%.20s", l0.info.name, l1.info.name);
+            memcpy(l.info.name, name, sizeof l.info.name);
+            p.launches[i] = l;
+            p.launches.erase(p.launches.begin() + i + 1);
+        }
+    }
     // grid/block of every launch, for introspection
     for (Launch &l : p.launches) {
         dim3 g(1, 1, 1);
@@ -591,6 +661,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         switch (l.kind) {
             case K_CONV:
                 if (l.fused_bm > 0) conv_fused_grid(l.fused_bm, l.fused_kg, l.conv, &g, &b);
+                else if (l.pair_op >= 0) conv_pair_grid(l.tile, l.conv0, l.conv, &g, &b);
                 else conv_grid(l.tile, l.conv, &g, &b);
                 break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
@@ -601,6 +672,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
         l.info.op_index = l.op_index;
         if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }
+        l.info.pair_op = l.pair_op;
         l.info.kind = l.kind;
         if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }
         l.info.grid_x = g.x; l.info.grid_y = g.y; l.info.grid_z = g.z; l.info.block = b;

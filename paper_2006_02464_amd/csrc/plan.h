@@ -36,6 +36,12 @@ struct Launch {
     Ref x, w, bias, res, y, partial, counters;
     Ref w2, bias2;         // second layer of a fused launch
     Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
+    // A pair launch (pair_op >= 0): a second, independent convolution over the same input tensor runs
+    // in this launch's first workgroups; its arguments and tensors:
+    int32_t pair_op = -1;
+    ConvArgs conv0{};
+    Ref w0, bias0, res0, y0;
+    int64_t in_bytes = 0;  // algorithmic bytes of the input tensor (counted once in a pair)
     cw_launch_info info{};
 };
 
@@ -71,6 +77,7 @@ struct PlanOverride {
     int32_t split_k = 0;   // 0 = automatic
     bool keep_all = false; // no workspace reuse (debug read-back)
     int32_t fuse = 1;      // two-layer launches: 0 = none, 1 = yes, 2 = yes but never with two wave groups
+    bool pair = true;      // two convolutions over one tensor as one launch
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 

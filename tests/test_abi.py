@@ -59,14 +59,14 @@ def test_plan_is_fixed_and_covers_every_op(ctx):
         plan = ctx.plan(m, b)
         assert plan == ctx.plan(m2, b)                      # pure function of (model, batch)
         ops_hit = ({l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0} |
-                   {l["proj_op"] for l in plan if l["proj_op"] >= 0})
-        assert ops_hit == set(range(57))                    # a fused launch covers two or three ops
-        assert len(plan) == 58 - sum((l["fused_op"] >= 0) + (l["proj_op"] >= 0) for l in plan)
+                   {l["proj_op"] for l in plan if l["proj_op"] >= 0} | {l["pair_op"] for l in plan if l["pair_op"] >= 0})
+        assert ops_hit == set(range(57))                    # a fused launch covers two or three ops, a pair launch two
+        assert len(plan) == 58 - sum((l["fused_op"] >= 0) + (l["proj_op"] >= 0) + (l["pair_op"] >= 0) for l in plan)
         flops = sum(l["flops"] for l in plan)
         assert flops == 2 * b * T.mac_count(T.resnet(50), 224, 224)
         for l in plan:
             assert l["grid_x"] >= 1 and l["block"] in (64, 128, 256, 512, 1024)
-            if l["name"].startswith("conv") and l["split_k"] == 1:
+            if l["name"].startswith("conv") and l["split_k"] == 1 and l["pair_op"] < 0:
                 tiles = -(-l["gemm_m"] // l["tile_m"]) * -(-l["gemm_n"] // l["tile_n"])
                 assert l["grid_x"] == tiles and l["grid_y"] == 1
         ws = ctx.model_workspace_bytes(m, b)
@@ -230,3 +230,28 @@ def test_weight_pages():
         c.destroy()
     with pytest.raises(cw.CwError):
         cw.Context(device=-1, weight_page_bytes=1000)             # not a multiple of 256
+
+
+def test_pair_launches(ctx):
+    """The first 1x1 of a bottleneck and the projection shortcut beside it read the same tensor: one
+    launch (three at batch 16, where the first block's projection is already inside a fused launch;
+    four at batch 1), unless switched off."""
+    m = ctx.model_define_resnet(50, 224, 224)
+    ops = ctx.model_get_ops(m)
+    for batch, want in ((16, 3), (1, 4)):
+        pairs = [l for l in ctx.plan(m, batch) if l["pair_op"] >= 0]
+        assert len(pairs) == want
+        for l in pairs:
+            a, b = ops[l["pair_op"]], ops[l["op_index"]]
+            assert a[9] == b[9] and a[0] == b[0] == 0 and a[3] == b[3] == 1      # same input, both 1x1 convolutions
+            assert l["split_k"] == 1 and l["grid_y"] == 1
+            tiles = lambda o, s: -(-(s // (o[5] * o[5])) // l["tile_m"]) * -(-o[2] // l["tile_n"])
+            assert "|" in l["name"]
+        assert sum(l["flops"] for l in ctx.plan(m, batch)) == 2 * batch * T.mac_count(T.resnet(50), 224, 224)
+    ctx.set_pair_launches(0)
+    try:
+        m2 = ctx.model_define_resnet(50, 224, 224)
+        assert not [l for l in ctx.plan(m2, 16) if l["pair_op"] >= 0]
+        assert len(ctx.plan(m2, 16)) == len(ctx.plan(m, 16)) + 3
+    finally:
+        ctx.set_pair_launches(1)

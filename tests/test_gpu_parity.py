@@ -323,6 +323,33 @@ def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
         assert d <= 5e-3
 
 
+def test_resnet50_pair_launches_change_nothing(worker, r50):
+    """The first 1x1 of a block and the projection shortcut beside it as one launch or as two: the same
+    products; a member may run on the other's tile shape, whose K slices and wave groups add them up
+    in another order, so the two plans agree to rounding, far closer than either to the fp32 oracle."""
+    case, x, ref = r50
+    ctx = worker.ctx
+    paired = ctx.model_define_resnet(50, 224, 224)
+    ctx.set_pair_launches(0)
+    try:
+        single = ctx.model_define_resnet(50, 224, 224)
+    finally:
+        ctx.set_pair_launches(1)
+    for batch in (16, 1):
+        n = 16 if batch == 16 else 4
+        assert sum(l["pair_op"] >= 0 for l in ctx.plan(paired, batch)) >= 3
+        assert not any(l["pair_op"] >= 0 for l in ctx.plan(single, batch))
+        out = {}
+        for name, mid in (("paired", paired), ("single", single)):
+            worker.load(mid, case.blob)
+            out[name] = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, n, batch)])
+            ctx.unload_weights(mid)
+        assert rel_err_per_sample(out["paired"], ref[:n]).max() <= TOL
+        d = rel_err_per_sample(out["paired"], out["single"]).max()
+        print("batch %d: paired vs single launches max rel diff %.3e" % (batch, d))
+        assert d <= 5e-3
+
+
 @pytest.mark.parametrize("batch", [1, 2, 4, 8])
 def test_resnet50_224_small_batches(worker, r50, batch):
     case, x, ref = r50
