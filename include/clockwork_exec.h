@@ -54,7 +54,9 @@ enum {
     CW_ERR_BAD_BATCH = -7,      /* batch size the model has no plan for */
     CW_ERR_BUSY = -8,           /* an EXEC is still in flight on another stream */
     CW_ERR_UNSUPPORTED = -9,    /* topology the kernels cannot run (see cw_model_define) */
-    CW_ERR_NO_SLOT = -10        /* every IO slot is in use */
+    CW_ERR_NO_SLOT = -10,       /* every IO slot is in use */
+    CW_ERR_TOO_LATE = -11,      /* an action's executor reached it after its `latest`: not executed */
+    CW_ERR_TIMEOUT = -12        /* cw_worker_next_result: no result within the time given */
 };
 
 enum { CW_OP_CONV = 0, CW_OP_MAXPOOL = 1, CW_OP_GAVGPOOL = 2, CW_OP_FC = 3, CW_OP_SOFTMAX = 4 };
@@ -257,6 +259,60 @@ int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
  * kh, stride, conv_tile (0..24 as above), split_k >= 1}; copied.  Shapes in neither table get
  * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
 int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
+
+/* Device ordinal the context was created on (-1: planning only). */
+int32_t cw_context_device(cw_ctx *ctx);
+
+/* ---- the worker's executors (section 5.2: actions with `earliest` / `latest`, results) ---------
+ * A cw_worker runs one executor thread per action type over one context: LOAD, UNLOAD, and for
+ * INFER the three steps INPUT (runs on receipt), EXEC (inherits the action's window; one at a
+ * time) and OUTPUT (follows EXEC at once), each with a stream of its own (default priority).  An
+ * executor takes its actions in order of `earliest` (arrival order among equals), waits until
+ * `earliest`, and does not execute an action it reaches after `latest` (CW_ERR_TOO_LATE; an
+ * INFER's IO slot is released).  Every action yields exactly one result.  While a worker exists,
+ * the context's own calls must not be used from other threads. */
+typedef struct cw_worker cw_worker;
+enum { CW_ACTION_LOAD = 1, CW_ACTION_UNLOAD = 2, CW_ACTION_INFER = 3 };
+typedef struct {
+    int64_t id;                 /* the caller's; returned in the result */
+    int32_t type;               /* CW_ACTION_* */
+    int32_t model_id;
+    int32_t batch;              /* INFER */
+    uint64_t earliest_ns;       /* the action may begin from this time on ... */
+    uint64_t latest_ns;         /* ... and is rejected when it has not begun by this time; both on the
+                                   clock of cw_worker_now_ns() */
+    const void *host_in;        /* [host] LOAD: canonical blob; INFER: fp32 [batch][in_c][in_h][in_w];
+                                   the caller keeps it alive and unchanged until the result arrives */
+    size_t host_in_bytes;       /* LOAD: size of the blob */
+    float *host_probs;          /* [host] INFER: [batch][classes], written before the result arrives */
+    float *host_logits;         /* [host] INFER: same shape, or NULL */
+} cw_action;
+typedef struct {
+    int64_t id;
+    int32_t type;
+    int32_t status;             /* CW_OK or the error of the step that failed */
+    uint64_t begin_ns, end_ns;  /* host clock: the executor began LOAD / UNLOAD / EXEC (or rejected
+                                   the action); the action was complete (INFER: outputs on the host) */
+    uint64_t device_ns;         /* on-device duration: EXEC of an INFER, copy and packing of a LOAD; else 0 */
+} cw_result;
+/* cores [host]: NULL, or 5 CPU numbers (-1 = unpinned) for the LOAD, UNLOAD, INPUT, EXEC and
+ * OUTPUT executors; the threads also ask for real-time priority (silently kept at normal
+ * priority where the process may not). */
+int32_t cw_worker_create(cw_ctx *ctx, const int32_t *cores, cw_worker **out);
+/* Stops the executors (actions not yet begun yield no result), waits for the GPU work they
+ * issued and frees the worker; the context stays. */
+int32_t cw_worker_destroy(cw_worker *w);
+/* Monotonic clock of the action windows and result times, in nanoseconds. */
+uint64_t cw_worker_now_ns(void);
+/* Copies the action [host] and queues it; returns at once.  CW_ERR_INVALID for a malformed one. */
+int32_t cw_worker_submit(cw_worker *w, const cw_action *action);
+/* Next finished action, in order of completion; waits up to timeout_ns (CW_ERR_TIMEOUT). */
+int32_t cw_worker_next_result(cw_worker *w, cw_result *out, uint64_t timeout_ns);
+/* Action profile (section 5.3): over the last 10 successful actions of (type, model, batch;
+ * batch ignored unless INFER), their count, mean and largest duration (device_ns where the
+ * action has one, else end - begin). */
+int32_t cw_worker_profile(cw_worker *w, int32_t type, int32_t model_id, int32_t batch, uint32_t *n,
+                          uint64_t *mean_ns, uint64_t *max_ns);
 
 const char *cw_strerror(int32_t status);
 const char *cw_last_error(cw_ctx *ctx);

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libclockwork_exec.so")
 CW_OK = 0
 CW_ERR_INVALID, CW_ERR_HIP, CW_ERR_NO_MEMORY, CW_ERR_NOT_LOADED = -1, -2, -3, -4
 CW_ERR_ALREADY_LOADED, CW_ERR_NO_INPUT, CW_ERR_BAD_BATCH, CW_ERR_BUSY = -5, -6, -7, -8
-CW_ERR_UNSUPPORTED, CW_ERR_NO_SLOT = -9, -10
+CW_ERR_UNSUPPORTED, CW_ERR_NO_SLOT, CW_ERR_TOO_LATE, CW_ERR_TIMEOUT = -9, -10, -11, -12
 CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX = 0, 1, 2, 3, 4
 CW_DTYPE_FP16, CW_DTYPE_BF16 = 0, 1
 DTYPES = {"fp16": CW_DTYPE_FP16, "bf16": CW_DTYPE_BF16}
@@ -46,6 +46,19 @@ class cw_launch_info(Structure):
                 ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
 
 
+class cw_action(Structure):
+    _fields_ = [("id", c_int64), ("type", c_int32), ("model_id", c_int32), ("batch", c_int32), ("earliest_ns", c_uint64),
+                ("latest_ns", c_uint64), ("host_in", c_void_p), ("host_in_bytes", c_size_t), ("host_probs", c_void_p),
+                ("host_logits", c_void_p)]
+
+
+class cw_result(Structure):
+    _fields_ = [("id", c_int64), ("type", c_int32), ("status", c_int32), ("begin_ns", c_uint64), ("end_ns", c_uint64),
+                ("device_ns", c_uint64)]
+
+
+CW_ACTION_LOAD, CW_ACTION_UNLOAD, CW_ACTION_INFER = 1, 2, 3
+
 # name -> (restype, argtypes); every symbol the header declares
 SIGNATURES = {
     "cw_create": (c_int32, [POINTER(c_void_p), POINTER(cw_config)]),
@@ -60,6 +73,13 @@ SIGNATURES = {
     "cw_unload_weights": (c_int32, [c_void_p, c_int32]),
     "cw_weight_pool_free": (c_size_t, [c_void_p]),
     "cw_weight_pages_free": (c_int32, [c_void_p]),
+    "cw_context_device": (c_int32, [c_void_p]),
+    "cw_worker_create": (c_int32, [c_void_p, POINTER(c_int32), POINTER(c_void_p)]),
+    "cw_worker_destroy": (c_int32, [c_void_p]),
+    "cw_worker_now_ns": (c_uint64, []),
+    "cw_worker_submit": (c_int32, [c_void_p, POINTER(cw_action)]),
+    "cw_worker_next_result": (c_int32, [c_void_p, POINTER(cw_result), c_uint64]),
+    "cw_worker_profile": (c_int32, [c_void_p, c_int32, c_int32, c_int32, POINTER(c_uint32), POINTER(c_uint64), POINTER(c_uint64)]),
     "cw_model_weight_pages": (c_int32, [c_void_p, c_int32]),
     "cw_input": (c_int32, [c_void_p, c_int32, c_int32, c_void_p, POINTER(c_int32), c_void_p]),
     "cw_exec": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p]),
@@ -291,3 +311,56 @@ class Context:
 
 __all__ = [n for n in dir() if n.startswith("CW_") or n.startswith("cw_")] + [
     "Context", "CwError", "lib", "LIB_PATH", "SIGNATURES", "DTYPES", "CONV_TILES"]
+
+
+class Executors:
+    """The worker's executors over one Context (C names without the ``cw_worker_`` prefix).  Host
+    buffers of submitted actions are kept alive here until their results have been fetched."""
+
+    def __init__(self, ctx, cores=None):
+        self._ctx = ctx
+        self._h = c_void_p()
+        arr = (c_int32 * 5)(*cores) if cores is not None else None
+        st = lib().cw_worker_create(ctx._h, arr, byref(self._h))
+        if st < 0:
+            raise CwError(st, "cw_worker_create")
+        self._keep = {}
+
+    @staticmethod
+    def now_ns():
+        return lib().cw_worker_now_ns()
+
+    def submit(self, action_id, type, model_id, earliest_ns, latest_ns, batch=0, host_in=None, host_probs=None, host_logits=None):
+        nbytes = 0
+        if host_in is not None:
+            nbytes = host_in.nbytes if isinstance(host_in, np.ndarray) else host_in.numel() * host_in.element_size()
+        a = cw_action(action_id, type, model_id, batch, earliest_ns, latest_ns, _ptr(host_in), nbytes, _ptr(host_probs), _ptr(host_logits))
+        self._keep[action_id] = (host_in, host_probs, host_logits)
+        st = lib().cw_worker_submit(self._h, byref(a))
+        if st < 0:
+            self._keep.pop(action_id, None)
+            raise CwError(st, "cw_worker_submit")
+
+    def next_result(self, timeout_s=5.0):
+        """dict of the next finished action, or None after the time-out."""
+        r = cw_result()
+        st = lib().cw_worker_next_result(self._h, byref(r), int(timeout_s * 1e9))
+        if st == CW_ERR_TIMEOUT:
+            return None
+        if st < 0:
+            raise CwError(st, "cw_worker_next_result")
+        self._keep.pop(r.id, None)
+        return {f: getattr(r, f) for f, _ in cw_result._fields_}
+
+    def profile(self, type, model_id, batch=0):
+        n, mean, mx = c_uint32(0), c_uint64(0), c_uint64(0)
+        st = lib().cw_worker_profile(self._h, type, model_id, batch, byref(n), byref(mean), byref(mx))
+        if st < 0:
+            raise CwError(st, "cw_worker_profile")
+        return {"n": n.value, "mean_ns": mean.value, "max_ns": mx.value}
+
+    def destroy(self):
+        if self._h:
+            lib().cw_worker_destroy(self._h)
+            self._h = c_void_p()
+            self._keep.clear()

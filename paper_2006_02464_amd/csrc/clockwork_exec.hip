@@ -360,9 +360,13 @@ const char *cw_strerror(int32_t st) {
         case CW_ERR_BUSY: return "an EXEC is already in flight";
         case CW_ERR_UNSUPPORTED: return "unsupported topology or request";
         case CW_ERR_NO_SLOT: return "no free IO slot";
+        case CW_ERR_TOO_LATE: return "action reached after its latest start time";
+        case CW_ERR_TIMEOUT: return "timed out";
         default: return "unknown status";
     }
 }
+
+int32_t cw_context_device(cw_ctx *c) { return c ? c->device : -1; }
 
 static thread_local std::string g_create_err;  // detail of a failed cw_create (no context yet)
 const char *cw_last_error(cw_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }

@@ -3,6 +3,7 @@
   python -m paper_2006_02464_amd.measure --config 3   EXEC latency with and without a concurrent LOAD
   python -m paper_2006_02464_amd.measure --config 4   ResNet-152, bf16, batch 16: throughput and latency
   python -m paper_2006_02464_amd.measure --config 5   64 resident ResNet-50s, Poisson arrivals, mixed batch sizes
+  python -m paper_2006_02464_amd.measure --config 6   INFER actions with earliest/latest through the worker's executors
 
 Each prints one JSON object.  All inputs are synthetic (seeded, workload/gen.py); EXEC time does not
 depend on the values.  Durations are on-device (the event pair around every EXEC); the host thread
@@ -194,9 +195,61 @@ def config5(args, log):
             "exec_by_batch": {str(b): summary(per_b[b]) for b in batches}}
 
 
+def config6(args, log):
+    """A schedule of INFER actions as a controller would send it (paper sections 4.4, 5.2): one ResNet-50,
+    batch 16, action i may begin at t0 + i * period with period = 1.15 x the measured EXEC p50 and must
+    have begun 1 ms later.  Reports how punctually EXEC begins, what the executors add around the
+    on-device time, and how many actions the window rejected."""
+    import torch
+    from .binding import CW_ACTION_INFER, CW_ACTION_LOAD, Executors
+    from .runner import Worker, pinned_like
+    from workload import gen
+    B, n = 16, args.requests if args.requests != 10000 else 2000
+    wk = Worker(workspace_bytes=512 << 20, io_bytes=512 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20)
+    ctx = wk.ctx
+    mid = ctx.model_define_resnet(50, 224, 224, "fp16")
+    blob = pinned_like(resnet_blob(ctx, mid, 0, "fp16"))
+    ctx.load_weights(mid, blob, wk.stream)
+    wk.stream.synchronize()
+    p50 = ctx.profile_measure(mid, B, 300)["p50_us"]
+    ctx.unload_weights(mid)
+    ex = Executors(ctx)
+    x = pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "fp16"))
+    probs = [torch.empty((B, 1000), dtype=torch.float32, pin_memory=True) for _ in range(32)]
+    now = ex.now_ns()
+    ex.submit(-1, CW_ACTION_LOAD, mid, now, now + 10**9, host_in=blob)
+    load = ex.next_result(10.0)
+    period = int(p50 * 1.15 * 1e3)
+    t0 = ex.now_ns() + 20_000_000
+    res, sent = [], 0
+    while len(res) < n:
+        while sent < n and sent - len(res) < 24:                 # a controller keeps a short queue ahead
+            ex.submit(sent, CW_ACTION_INFER, mid, t0 + sent * period, t0 + sent * period + 1_000_000, batch=B, host_in=x,
+                      host_probs=probs[sent % 32])
+            sent += 1
+        r = ex.next_result(10.0)
+        assert r is not None
+        res.append(r)
+    ex.destroy()
+    wk.close()
+    ok = [r for r in res if r["status"] == 0]
+    late = [(r["begin_ns"] - (t0 + r["id"] * period)) / 1e3 for r in ok]
+    over = [((r["end_ns"] - r["begin_ns"]) - r["device_ns"]) / 1e3 for r in ok]
+    dev = [r["device_ns"] / 1e3 for r in ok]
+    span = (max(r["end_ns"] for r in res) - t0) / 1e9
+    return {"config": 6, "workload": "ResNet-50 fp16 batch 16: %d INFER actions through the executors, action i may begin at "
+                                     "t0 + i x %.1f us (1.15 x EXEC p50 of %.1f us), window 1 ms" % (n, period / 1e3, p50),
+            "load_action": {"status": load["status"], "host_ms": round((load["end_ns"] - load["begin_ns"]) / 1e6, 3), "device_ms": round(load["device_ns"] / 1e6, 3)},
+            "executed": len(ok), "rejected_too_late": sum(r["status"] == -11 for r in res),
+            "begin_after_earliest_us": {"p50": round(pct(late, 0.5), 1), "p99": round(pct(late, 0.99), 1), "max": round(max(late), 1)},
+            "exec_device_us": summary(dev),
+            "host_end_minus_begin_minus_device_us": {"p50": round(pct(over, 0.5), 1), "p99": round(pct(over, 0.99), 1)},
+            "inferences_per_s": round(B * len(ok) / span, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5))
+    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5, 6))
     ap.add_argument("--execs", type=int, default=2000)
     ap.add_argument("--loads-per-round", type=int, default=6, help="config 3: LOADs queued per 20 EXECs")
     ap.add_argument("--requests", type=int, default=10000)
@@ -207,7 +260,7 @@ def main():
     def log(msg):
         print("[measure] " + msg, file=sys.stderr, flush=True)
 
-    out = {3: config3, 4: config4, 5: config5}[args.config](args, log)
+    out = {3: config3, 4: config4, 5: config5, 6: config6}[args.config](args, log)
     print(json.dumps(out), flush=True)
 
 

@@ -21,7 +21,7 @@ def _header_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _header_symbols()
-    assert len(names) >= 24
+    assert len(names) >= 34
     lib = cw.lib()
     for n in names:
         assert hasattr(lib, n), n
@@ -31,8 +31,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 def test_strerror():
     lib = cw.lib()
     assert lib.cw_strerror(0) == b"ok"
-    seen = {lib.cw_strerror(-i) for i in range(1, 11)}
-    assert len(seen) == 10 and b"unknown status" not in seen
+    seen = {lib.cw_strerror(-i) for i in range(1, 13)}
+    assert len(seen) == 12 and b"unknown status" not in seen
     assert lib.cw_strerror(-99) == b"unknown status"
 
 
