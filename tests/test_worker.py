@@ -36,13 +36,13 @@ def test_actions_wait_for_earliest_and_run_in_that_order(planning):
     t0 = ex.now_ns()
     # submitted out of order; the executor must begin them by `earliest`
     for aid, delay in ((1, 60), (2, 20), (3, 40)):
-        ex.submit(aid, CW_ACTION_UNLOAD, m, t0 + delay * MS, t0 + (delay + 30) * MS)
+        ex.submit(aid, CW_ACTION_UNLOAD, m, t0 + delay * MS, t0 + (delay + 500) * MS)
     res = drain(ex, 3)
     assert [r["id"] for r in res] == [2, 3, 1]
     for r, delay in zip(res, (20, 40, 60)):
         assert r["status"] == cw.CW_OK and r["type"] == CW_ACTION_UNLOAD
-        assert t0 + delay * MS <= r["begin_ns"] <= t0 + (delay + 30) * MS     # inside its window
-        assert r["begin_ns"] - (t0 + delay * MS) < 10 * MS                    # and promptly (loaded CI hosts: generous)
+        assert t0 + delay * MS <= r["begin_ns"] <= t0 + (delay + 500) * MS    # inside its window, never early
+        assert r["begin_ns"] - (t0 + delay * MS) < 15 * MS                    # and promptly (generous: shared test hosts)
         assert r["end_ns"] >= r["begin_ns"] and r["device_ns"] == 0
     assert ex.next_result(0.05) is None                                        # exactly one result each
 
