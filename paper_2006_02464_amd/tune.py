@@ -83,7 +83,9 @@ class Bench:
         mid = self._define(batch, {})
         out = {}
         for l in self.wk.ctx.plan(mid, batch):
-            if l["kind"] != 1 or l["fused_op"] >= 0 or l["pair_op"] >= 0:   # fused and paired launches derive their tiles
+            # a fused launch has its own fixed tile; a pair launch runs on the tile of its second member's
+            # shape (the one reported here), so that row is tuned like any other
+            if l["kind"] != 1 or l["fused_op"] >= 0:
                 continue
             o = self.ops[l["op_index"]]
             key = (l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5])   # M, N, K, kh, stride
