@@ -255,11 +255,20 @@ def main():
     ap.add_argument("--requests", type=int, default=10000)
     ap.add_argument("--load", type=float, default=0.7, help="config 5: arrival rate as a fraction of capacity")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--graphs", type=int, default=-1, help="1 / 0: replay HIP graphs in EXEC or issue every launch (default: the library's)")
     args = ap.parse_args()
 
     def log(msg):
         print("[measure] " + msg, file=sys.stderr, flush=True)
 
+    if args.graphs >= 0:   # applies to every context made below
+        from . import runner
+        make = runner.Worker.__init__
+
+        def patched(self, **kw):
+            make(self, **kw)
+            self.ctx.set_use_graphs(args.graphs)
+        runner.Worker.__init__ = patched
     out = {3: config3, 4: config4, 5: config5, 6: config6}[args.config](args, log)
     print(json.dumps(out), flush=True)
 
