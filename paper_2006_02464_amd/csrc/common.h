@@ -38,27 +38,39 @@ inline FastDiv make_fast_div(uint32_t d) {
 
 // Implicit GEMM view of a convolution (also used for the stem with Cin padded to 4 and
 // the filter row padded to 8 taps): M = B*Ho*Wo output pixels, N = Cout, K = kh*kwp*Cin.
-struct ConvArgs {
+// The fields are ordered by who reads them, in runs of 64 bytes (the struct is aligned to that, and
+// with it the kernel-argument segment): a workgroup's first instructions wait for every argument line
+// they touch, and each further line costs a fixed fraction of a microsecond per launch.  Line 0
+// is all a 1x1 stride-1 convolution without split-K reads; line 1 adds what the general
+// addressing needs; split-K, the first convolution and the fused forms read on.
+struct alignas(64) ConvArgs {
+    // ---- line 0
     const void *x;      // NHWC [B][H][W][Cin]
     const void *w;      // packed [Cout][K], k = (r*kwp + s)*Cin + c
     const float *bias;  // [Cout]
     const void *res;    // NHWC like y, or nullptr
     void *y;            // NHWC [B][Ho][Wo][Cout]
+    int32_t M, K;
+    int32_t Cout, Cin;
+    int32_t relu;
+    int32_t nb;         // output tiles of this convolution = workgroups along x (set by the launch code)
+    // ---- line 1
+    int32_t B, H, W, Ho, Wo;
+    int32_t kh, kw, stride, pad;
+    FastDiv wo_div, ho_div;  // for m -> (image, row, column)
+    int32_t kwp;
+    // ---- line 2
+    int32_t khp;        // filter rows in the packed weights (first convolution: may be padded to 8)
+    int32_t split_k, ktiles_per_split;
+    int32_t relu2;
     float *partial;     // split-K: [split][M][Cout] fp32, else nullptr
     int32_t *counters;  // split-K: one arrival counter per output tile, zero between launches
-    int32_t B, H, W, Cin, Ho, Wo, Cout;
-    int32_t kh, kw, kwp, stride, pad;
-    int32_t khp;        // filter rows in the packed weights (first convolution: may be padded to 8)
-    int32_t M, K;
-    int32_t relu;
-    int32_t split_k, ktiles_per_split;
-    FastDiv wo_div, ho_div;  // for m -> (image, row, column)
     // Fused second layer (launch_conv_fused only): a 1x1 stride-1 convolution over this one's
     // output, y = act2(res + bias2 + W2 * act(bias + W * x)).  `res`, `y` then belong to the second
     // layer ([M][Cout2]); the first layer's output is never stored.
     const void *w2;      // packed [Cout2][Cout]
     const float *bias2;  // [Cout2]
-    int32_t Cout2, relu2;
+    int32_t Cout2;
     // Optional projection shortcut computed in the same launch instead of read as `res`:
     // res[m][:] = biasd + Wd * x2[m][:], x2 = [M][Cout] pixels aligned with the output (a 1x1
     // stride-1 projection of a tensor with Cout channels).  wd == nullptr: `res` is read.
@@ -66,6 +78,7 @@ struct ConvArgs {
     const void *wd;      // packed [Cout2][Cout]
     const float *biasd;  // [Cout2]
 };
+static_assert(offsetof(ConvArgs, B) == 64 && offsetof(ConvArgs, khp) == 128 && sizeof(ConvArgs) == 256, "argument lines");
 
 struct CastArgs {
     const float *x;  // NCHW fp32 [B][C][H][W]

@@ -123,7 +123,7 @@ static __device__ __forceinline__ bool splitk_exchange(f32x16 (&acc)[TM][TN], co
     __syncthreads();  // ... and so have those of the whole workgroup
     if (threadIdx.x == 0) {
         const int ticket = __hip_atomic_fetch_add(&a.counters[tile_id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = ticket == (int)gridDim.y - 1;
+        const int last = ticket == a.split_k - 1;
         if (last) __hip_atomic_store(&a.counters[tile_id], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
         s_last = last;
     }
@@ -136,7 +136,7 @@ static __device__ __forceinline__ bool splitk_exchange(f32x16 (&acc)[TM][TN], co
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    for (int z = 0; z < (int)gridDim.y; ++z) {
+    for (int z = 0; z < a.split_k; ++z) {
         const __amdgpu_buffer_rsrc_t rp = make_rsrc(a.partial + (size_t)z * a.M * a.Cout, mn * 4u);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {

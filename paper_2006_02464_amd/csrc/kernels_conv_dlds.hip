@@ -137,7 +137,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 
     const int ktiles = a.K / BK;
     const int kt0 = SPLITK ? blockIdx.y * a.ktiles_per_split : 0;
-    const int kt1 = min(ktiles, kt0 + a.ktiles_per_split);
+    const int kt1 = SPLITK ? min(ktiles, kt0 + a.ktiles_per_split) : ktiles;  // no split: the whole K
     const int nsteps = kt1 - kt0;
     int kt = kt0;  // the slice being computed
 
@@ -602,7 +602,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
-    conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, gridDim.x);
+    conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, a.nb);
 }
 
 // Two independent convolutions that read the same tensor (the first 1x1 of a bottleneck and the
@@ -611,11 +611,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
 // one set-up latency and one tail instead of two.
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int KG>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_pair_kernel(const ConvArgs a0, const ConvArgs a1) {
-    const int nb0 = ((a0.M + BM - 1) / BM) * ((a0.Cout + BN - 1) / BN);
+    const int nb0 = a0.nb;
     if ((int)blockIdx.x < nb0)
         conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a0, blockIdx.x, nb0);
     else
-        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a1, blockIdx.x - nb0, gridDim.x - nb0);
+        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a1, blockIdx.x - nb0, a1.nb);
 }
 
 // LDS stages per tile: 4 where that still lets two workgroups share a CU's 160 KiB, else 3.
@@ -625,7 +625,10 @@ struct RingDepth {
 };
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK, int KG = 1>
-static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a, hipStream_t s) {
+static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a_in, hipStream_t s) {
+    ConvArgs a = a_in;
+    a.nb = (int)grid.x;
+    if (!SPLITK && a.ktiles_per_split != a.K / BK) return hipErrorInvalidValue;  // the kernel walks the whole K
     constexpr int NS = RingDepth<BM, BN, BK>::value;
     constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
     static_assert(NS * stage_bytes <= 160 * 1024, "ring does not fit the LDS");
@@ -709,7 +712,9 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
 }
 
 template <typename T, int BM, int BN, int MODE, int KG>
-static hipError_t launch_fused_one(const ConvArgs &a, hipStream_t s) {
+static hipError_t launch_fused_one(const ConvArgs &a_in, hipStream_t s) {
+    ConvArgs a = a_in;
+    a.nb = (a.M + BM - 1) / BM;
     constexpr int NS = RingDepth<BM, BN, 64>::value;
     constexpr size_t ring = (size_t)NS * (BM + BN) * 64 * 2;
     auto kern = conv_dlds_kernel<T, BM, BN, 2, 2, 64, NS, MODE, false, true, KG>;
@@ -764,7 +769,8 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
 }
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int KG>
-static hipError_t launch_pair_one(const ConvArgs &a0, const ConvArgs &a1, hipStream_t s) {
+static hipError_t launch_pair_one(const ConvArgs &a0_in, const ConvArgs &a1_in, hipStream_t s) {
+    ConvArgs a0 = a0_in, a1 = a1_in;
     constexpr int NS = RingDepth<BM, BN, BK>::value;
     constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
     auto kern = conv_dlds_pair_kernel<T, BM, BN, WARPS_M, WARPS_N, BK, NS, KG>;
@@ -772,6 +778,8 @@ static hipError_t launch_pair_one(const ConvArgs &a0, const ConvArgs &a1, hipStr
     if (attr != hipSuccess) return attr;
     const size_t used = std::max((size_t)std::min(NS, std::max(a0.ktiles_per_split, a1.ktiles_per_split)) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
     const unsigned nb0 = ((a0.M + BM - 1) / BM) * ((a0.Cout + BN - 1) / BN), nb1 = ((a1.M + BM - 1) / BM) * ((a1.Cout + BN - 1) / BN);
+    a0.nb = (int)nb0;
+    a1.nb = (int)nb1;
     kern<<<dim3(nb0 + nb1, 1, 1), 64 * WARPS_M * WARPS_N * KG, used, s>>>(a0, a1);
     return hipGetLastError();
 }
