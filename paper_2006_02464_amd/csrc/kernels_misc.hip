@@ -207,6 +207,50 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SoftmaxArgs a) {
     for (int j = tid; j < a.D; j += 256) a.p[(size_t)row * a.D + j] = expf(z[j] - m) * inv;
 }
 
+// The same for rows of at most 256 * PER values: a thread keeps its values j = tid, tid + 256, ... in
+// registers, so a row is read once and every exponential computed once.  Same formula, same order of
+// every sum as softmax_kernel: the results are identical.
+template <int PER>
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const SoftmaxArgs a) {
+    __shared__ float red_m[4], red_s[4];
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *z = a.z + (size_t)row * a.D;
+    float v[PER];
+    float m = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int j = tid + e * 256;
+        v[e] = j < a.D ? z[j] : -INFINITY;
+        m = fmaxf(m, v[e]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) red_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int j = tid + e * 256;
+        if (j < a.D) {
+            v[e] = expf(v[e] - m);
+            s += v[e];
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) red_s[wave] = s;
+    __syncthreads();
+    s = (red_s[0] + red_s[1]) + (red_s[2] + red_s[3]);
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int j = tid + e * 256;
+        if (j < a.D) a.p[(size_t)row * a.D + j] = v[e] * inv;
+    }
+}
+
 // ---- LOAD: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp], zero padded ---------
 // 16-bit elements are moved as raw bits, so one kernel serves fp16 and bf16.  With `permute`,
 // row i of every group of 32 output channels receives channel sigma(i) of that group,
@@ -299,7 +343,12 @@ hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s) {
 
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s) {
     if (a.B < 1 || a.D < 1) return hipErrorInvalidValue;
-    softmax_kernel<<<dim3(a.B), 256, 0, s>>>(a);
+    if (a.D <= 256 * 4)
+        softmax_rows_kernel<4><<<dim3(a.B), 256, 0, s>>>(a);
+    else if (a.D <= 256 * 16)
+        softmax_rows_kernel<16><<<dim3(a.B), 256, 0, s>>>(a);
+    else
+        softmax_kernel<<<dim3(a.B), 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
