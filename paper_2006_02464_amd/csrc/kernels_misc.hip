@@ -63,6 +63,48 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
     *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + i * 8) = *reinterpret_cast<const uint4 *>(out);
 }
 
+// The same for a window of KS x KS known at compile time and fewer than 2^31 elements: the KS*KS
+// loads of a thread do not depend on each other and are requested together (out-of-range taps read
+// a clamped, valid address and are not counted), and the index arithmetic is 32-bit.
+template <typename T, int KS>
+__global__ __launch_bounds__(256) void maxpool_window_kernel(const PoolArgs a) {
+    const unsigned c8 = (unsigned)a.C / 8u;
+    const unsigned total = (unsigned)a.B * a.Ho * a.Wo * c8;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    const unsigned cg = i % c8;
+    unsigned t = i / c8;
+    const int q = (int)(t % (unsigned)a.Wo);
+    t /= (unsigned)a.Wo;
+    const int p = (int)(t % (unsigned)a.Ho);
+    const unsigned n = t / (unsigned)a.Ho;
+    const T *xg = static_cast<const T *>(a.x) + (size_t)n * a.H * a.W * a.C + cg * 8u;
+    uint4 raw[KS * KS];
+    bool ok[KS * KS];
+#pragma unroll
+    for (int r = 0; r < KS; ++r)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
+            ok[r * KS + s] = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const unsigned ihc = (unsigned)min(max(ih, 0), a.H - 1), iwc = (unsigned)min(max(iw, 0), a.W - 1);
+            raw[r * KS + s] = *reinterpret_cast<const uint4 *>(xg + (ihc * (unsigned)a.W + iwc) * (unsigned)a.C);
+        }
+    float m[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < KS * KS; ++k) {
+        const T *v = reinterpret_cast<const T *>(&raw[k]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = ok[k] ? fmaxf(m[e], to_f32(v[e])) : m[e];
+    }
+    T out[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (T)m[e];  // exact: the max is one of the inputs
+    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + (size_t)i * 8) = *reinterpret_cast<const uint4 *>(out);
+}
+
 // ---- global average pool: NHWC [B][H*W][C] -> fp32 [B][C] -------------------------------
 // One wave per (sample, 64 channels): lane = (part, group) with group = lane%8 owning 8
 // channels and part = lane/8 taking pixels part, part+8, ...; the 8 parts are then summed with
@@ -323,6 +365,12 @@ hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s) {
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
     if (a.C % 8 != 0 || a.B < 1) return hipErrorInvalidValue;
     const size_t total = (size_t)a.B * a.Ho * a.Wo * (a.C / 8);
+    const bool small = total * 8 < (1ull << 31) && (size_t)a.H * a.W * a.C < (1ull << 31) && a.H > 0 && a.W > 0;
+    if (a.k == 3 && small) {
+        if (dt == DT_F16) maxpool_window_kernel<f16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
+        else maxpool_window_kernel<bf16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
+        return hipGetLastError();
+    }
     CW_DISPATCH(dt, maxpool_kernel, dim3(blocks_for(total, 256)), 256, s, a);
     return hipGetLastError();
 }
