@@ -12,20 +12,22 @@ static __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 // coalesced across the wave along W), zeros in the border; one 8-byte write either way.
 template <typename T>
 __global__ __launch_bounds__(256) void cast_input_kernel(const CastArgs a) {
-    const size_t hwp = (size_t)a.Hp * a.Wp;
-    const size_t total = (size_t)a.B * hwp;
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // 32-bit index arithmetic: the launch code checks that the padded output has fewer than 2^31 pixels
+    const unsigned hwp = (unsigned)a.Hp * a.Wp;
+    const unsigned total = (unsigned)a.B * hwp;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
     if (i >= total) return;
-    const size_t n = i / hwp, pp = i - n * hwp;
-    const int ih = (int)(pp / a.Wp) - a.pad, iw = (int)(pp % a.Wp) - a.pad;
+    const unsigned n = i / hwp, pp = i - n * hwp;
+    const unsigned row = pp / (unsigned)a.Wp;
+    const int ih = (int)row - a.pad, iw = (int)(pp - row * (unsigned)a.Wp) - a.pad;
     T v[4] = {(T)0.f, (T)0.f, (T)0.f, (T)0.f};
     if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W) {
         const size_t hw = (size_t)a.H * a.W, p = (size_t)ih * a.W + iw;
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-            if (c < a.C) v[c] = (T)a.x[(n * a.C + c) * hw + p];
+            if (c < a.C) v[c] = (T)a.x[((size_t)n * a.C + c) * hw + p];
     }
-    *reinterpret_cast<uint2 *>(static_cast<T *>(a.y) + i * 4) = *reinterpret_cast<const uint2 *>(v);
+    *reinterpret_cast<uint2 *>(static_cast<T *>(a.y) + (size_t)i * 4) = *reinterpret_cast<const uint2 *>(v);
 }
 
 // ---- max pool k x k, stride, pad (padded taps ignored); one thread = 8 channels ---------
@@ -117,12 +119,19 @@ __global__ __launch_bounds__(64) void gavgpool_kernel(const PoolArgs a) {
     const int hw = a.H * a.W;
     float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const T *xg = static_cast<const T *>(a.x) + (size_t)n * hw * a.C + cb + cg * 8;
-#pragma unroll 4
-    for (int p = part; p < hw; p += 8) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(xg + (size_t)p * a.C);
-        const T *v = reinterpret_cast<const T *>(&raw);
+    // rounds of 8 pixels per lane, their loads requested together (a 7x7 map is one round); a pixel
+    // past the end reads the last one and is not added
+    for (int p0 = part; p0 < hw; p0 += 64) {
+        uint4 raw[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s[e] += to_f32(v[e]);
+        for (int u = 0; u < 8; ++u) raw[u] = *reinterpret_cast<const uint4 *>(xg + (size_t)min(p0 + 8 * u, hw - 1) * a.C);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const T *v = reinterpret_cast<const T *>(&raw[u]);
+            const bool live = p0 + 8 * u < hw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += live ? to_f32(v[e]) : 0.f;
+        }
     }
 #pragma unroll
     for (int off = 8; off < 64; off <<= 1)
@@ -358,6 +367,7 @@ static inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + pe
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s) {
     if (a.C < 1 || a.C > 4 || a.B < 1 || a.pad < 0 || a.Hp != a.H + 2 * a.pad || a.Wp < a.W + 2 * a.pad) return hipErrorInvalidValue;
     const size_t total = (size_t)a.B * a.Hp * a.Wp;
+    if (total >= (1ull << 31)) return hipErrorInvalidValue;
     CW_DISPATCH(dt, cast_input_kernel, dim3(blocks_for(total, 256)), 256, s, a);
     return hipGetLastError();
 }
