@@ -220,6 +220,40 @@ def test_small_custom_net_narrow_channels_and_odd_stride_stem(worker):
     worker.ctx.unload_weights(mid)
 
 
+@pytest.mark.parametrize("classes", [1500, 5000])
+def test_pool_and_softmax_shapes_off_the_resnet_path(worker, classes):
+    """A 2x2 max pool (the general window kernel, not the unrolled 3x3 one), a 5x5 average-pool
+    map, and heads of 1500 and 5000 classes (softmax with 16 values per thread in registers, and
+    the looping kernel for rows beyond 4096).  Every layer teacher-forced against the oracle."""
+    O = T.Op
+    ops = [
+        O(T.CONV, 3, 64, 3, 3, 1, 1, 1, -1, -1),             # 0
+        O(T.MAXPOOL, 64, 64, 2, 2, 2, 0, 0, -1, 0),          # 1  2x2 stride 2, no padding
+        O(T.CONV, 64, 256, 3, 3, 2, 1, 1, -1, 1),            # 2
+        O(T.GAVGPOOL, 256, 256, 0, 0, 1, 0, 0, -1, 2),       # 3
+        O(T.FC, 256, classes, 1, 1, 1, 0, 0, -1, 3),         # 4
+        O(T.SOFTMAX, classes, classes, 0, 0, 1, 0, 0, -1, 4),  # 5
+    ]
+    gain = [1.0, 1.0, 0.05]                                   # small logits: softmax not one-hot
+    case = Case(ops, 20, seed=11, dist="uniform", weight_gain=gain)
+    worker.ctx.set_debug_keep(True)
+    try:
+        mid = worker.ctx.model_define(case.ops, 3, 20, 20, batch_sizes=(1, 3))
+    finally:
+        worker.ctx.set_debug_keep(False)
+    worker.load(mid, case.blob)
+    for batch in (3, 1):
+        x = case.images(0, batch)
+        probs, logits, _ = worker.infer(mid, x, classes=classes)
+        outs, _, gpu = check_all_ops(worker, case, mid, batch, x)
+        check_head(case, gpu[-1], logits, probs)
+        assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+        assert probs.max() < 0.999                           # not one-hot: the sum over the row matters
+        assert np.abs(probs - N.softmax(logits)).max() <= 1e-6
+        assert np.abs(probs.sum(axis=1) - 1).max() <= 1e-5
+    worker.ctx.unload_weights(mid)
+
+
 # ---------------------------------------------------------------- bf16
 def test_resnet18_bf16(worker):
     case = Case(T.resnet(18), 64, seed=2, dtype="bf16", dist="uniform")
