@@ -601,8 +601,17 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 }
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
-__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const ConvArgs a) {
-    conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, a.nb);
+__global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const void *x, const void *w, const void *res, void *y,
+                                                                                 int M, int K, int Cout, int Cin, int nb, int relu,
+                                                                                 const ConvArgs rest) {
+    // The ten leading arguments (14 dwords, all the user SGPRs there are beside the argument
+    // pointer) repeat fields of `rest`: this file is compiled with kernel-argument preloading, so
+    // they are in SGPRs when a wave starts and the first address arithmetic does not wait for a
+    // load of the argument block.  Everything else is read from `rest` when it is needed.
+    ConvArgs a = rest;
+    a.x = x; a.w = w; a.res = res; a.y = y;
+    a.M = M; a.K = K; a.Cout = Cout; a.Cin = Cin; a.nb = nb; a.relu = relu;
+    conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, nb);
 }
 
 // Two independent convolutions that read the same tensor (the first 1x1 of a bottleneck and the
@@ -640,7 +649,7 @@ static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a_in, hipStre
     // a K walk shorter than the ring only ever touches its first stages (the wave groups' exchange
     // at the end needs its own room)
     const size_t used = std::max((size_t)std::min(NS, a.ktiles_per_split) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
-    kern<<<grid, block, used, s>>>(a);
+    kern<<<grid, block, used, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout, a.Cin, a.nb, a.relu, a);
     return hipGetLastError();
 }
 
@@ -725,7 +734,7 @@ static hipError_t launch_fused_one(const ConvArgs &a_in, hipStream_t s) {
                                                  (int)(bias_off + (BN + kFusedMaxCout2) * 4));
     if (attr != hipSuccess) return attr;
     if (a.Cout2 % fused_chunk(BN, KG) != 0) return hipErrorInvalidValue;
-    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a);
+    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout, a.Cin, a.nb, a.relu, a);
     return hipGetLastError();
 }
 
