@@ -17,11 +17,12 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-result",
 ]
-# The direct-to-LDS convolution kernel takes its hottest arguments as leading scalars; with this
-# option the hardware has them in SGPRs when a wave starts (14 dwords: every user SGPR beside the
-# argument pointer).  The compiler keeps a prologue that loads them the ordinary way for firmware
+# The direct-to-LDS convolution kernel takes its hottest arguments as leading scalars, the small
+# kernels all of theirs; with this option the hardware has them in SGPRs when a wave starts (at most
+# 14 dwords: every user SGPR beside the argument pointer).  The compiler keeps a prologue that loads them the ordinary way for firmware
 # without the feature.
-EXTRA_FLAGS = {"kernels_conv_dlds.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
+EXTRA_FLAGS = {"kernels_conv_dlds.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"],
+               "kernels_misc.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=11"]}
 
 
 def _run(cmd, verbose):

@@ -4,6 +4,8 @@
 
 namespace cw {
 
+// The kernels of EXEC take their arguments as scalars, not as a struct: this file is compiled with
+// kernel-argument preloading, so up to 14 dwords of them are in SGPRs when a wave starts.
 template <typename T>
 static __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 
@@ -11,7 +13,8 @@ static __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 // One thread per pixel of the padded output: inside the image C strided 4-byte reads (each
 // coalesced across the wave along W), zeros in the border; one 8-byte write either way.
 template <typename T>
-__global__ __launch_bounds__(256) void cast_input_kernel(const CastArgs a) {
+__global__ __launch_bounds__(256) void cast_input_kernel(const float *x, void *y, int B, int C, int H, int W, int pad, int Hp, int Wp) {
+    const CastArgs a{x, y, B, C, H, W, pad, Hp, Wp};
     // 32-bit index arithmetic: the launch code checks that the padded output has fewer than 2^31 pixels
     const unsigned hwp = (unsigned)a.Hp * a.Wp;
     const unsigned total = (unsigned)a.B * hwp;
@@ -69,7 +72,8 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
 // loads of a thread do not depend on each other and are requested together (out-of-range taps read
 // a clamped, valid address and are not counted), and the index arithmetic is 32-bit.
 template <typename T, int KS>
-__global__ __launch_bounds__(256) void maxpool_window_kernel(const PoolArgs a) {
+__global__ __launch_bounds__(256) void maxpool_window_kernel(const void *x, void *y, int B, int H, int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+    const PoolArgs a{x, y, B, H, W, C, Ho, Wo, k, stride, pad};
     const unsigned c8 = (unsigned)a.C / 8u;
     const unsigned total = (unsigned)a.B * a.Ho * a.Wo * c8;
     const unsigned i = blockIdx.x * 256u + threadIdx.x;
@@ -112,7 +116,8 @@ __global__ __launch_bounds__(256) void maxpool_window_kernel(const PoolArgs a) {
 // channels and part = lane/8 taking pixels part, part+8, ...; the 8 parts are then summed with
 // three xor-shuffles in a fixed order.  8 lanes read one pixel's 128 contiguous bytes.
 template <typename T>
-__global__ __launch_bounds__(64) void gavgpool_kernel(const PoolArgs a) {
+__global__ __launch_bounds__(64) void gavgpool_kernel(const void *x, void *y, int B, int H, int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+    const PoolArgs a{x, y, B, H, W, C, Ho, Wo, k, stride, pad};
     const int groups = a.C / 64;
     const int n = blockIdx.x / groups, cb = (blockIdx.x - n * groups) * 64;
     const int lane = threadIdx.x, cg = lane & 7, part = lane >> 3;
@@ -171,7 +176,8 @@ struct FcMfma<bf16> {
 };
 
 template <typename T>
-__global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const FcArgs a) {
+__global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const float *f, const void *w, const float *bias, float *z, int B, int In, int Out) {
+    const FcArgs a{f, w, bias, z, B, In, Out};
     __shared__ float part[kFcWaves][16][17];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
@@ -262,7 +268,8 @@ __global__ __launch_bounds__(256) void softmax_kernel(const SoftmaxArgs a) {
 // registers, so a row is read once and every exponential computed once.  Same formula, same order of
 // every sum as softmax_kernel: the results are identical.
 template <int PER>
-__global__ __launch_bounds__(256) void softmax_rows_kernel(const SoftmaxArgs a) {
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const float *z_in, float *p_out, int B, int D) {
+    const SoftmaxArgs a{z_in, p_out, B, D};
     __shared__ float red_m[4], red_s[4];
     const int row = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -368,7 +375,7 @@ hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s) {
     if (a.C < 1 || a.C > 4 || a.B < 1 || a.pad < 0 || a.Hp != a.H + 2 * a.pad || a.Wp < a.W + 2 * a.pad) return hipErrorInvalidValue;
     const size_t total = (size_t)a.B * a.Hp * a.Wp;
     if (total >= (1ull << 31)) return hipErrorInvalidValue;
-    CW_DISPATCH(dt, cast_input_kernel, dim3(blocks_for(total, 256)), 256, s, a);
+    CW_DISPATCH(dt, cast_input_kernel, dim3(blocks_for(total, 256)), 256, s, a.x, a.y, a.B, a.C, a.H, a.W, a.pad, a.Hp, a.Wp);
     return hipGetLastError();
 }
 
@@ -377,8 +384,8 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
     const size_t total = (size_t)a.B * a.Ho * a.Wo * (a.C / 8);
     const bool small = total * 8 < (1ull << 31) && (size_t)a.H * a.W * a.C < (1ull << 31) && a.H > 0 && a.W > 0;
     if (a.k == 3 && small) {
-        if (dt == DT_F16) maxpool_window_kernel<f16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
-        else maxpool_window_kernel<bf16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
+        if (dt == DT_F16) maxpool_window_kernel<f16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
+        else maxpool_window_kernel<bf16, 3><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
         return hipGetLastError();
     }
     CW_DISPATCH(dt, maxpool_kernel, dim3(blocks_for(total, 256)), 256, s, a);
@@ -388,23 +395,23 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s) {
     if (a.C % 8 != 0 || a.B < 1) return hipErrorInvalidValue;
     if (a.C % 64 != 0) return hipErrorInvalidValue;
-    CW_DISPATCH(dt, gavgpool_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64, s, a);
+    CW_DISPATCH(dt, gavgpool_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64, s, a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
     return hipGetLastError();
 }
 
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s) {
     if (a.In % (32 * kFcWaves) != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
     const dim3 grid(blocks_for(a.Out, 16), blocks_for(a.B, 16));
-    CW_DISPATCH(dt, fc_kernel, grid, 64 * kFcWaves, s, a);
+    CW_DISPATCH(dt, fc_kernel, grid, 64 * kFcWaves, s, a.f, a.w, a.bias, a.z, a.B, a.In, a.Out);
     return hipGetLastError();
 }
 
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s) {
     if (a.B < 1 || a.D < 1) return hipErrorInvalidValue;
     if (a.D <= 256 * 4)
-        softmax_rows_kernel<4><<<dim3(a.B), 256, 0, s>>>(a);
+        softmax_rows_kernel<4><<<dim3(a.B), 256, 0, s>>>(a.z, a.p, a.B, a.D);
     else if (a.D <= 256 * 16)
-        softmax_rows_kernel<16><<<dim3(a.B), 256, 0, s>>>(a);
+        softmax_rows_kernel<16><<<dim3(a.B), 256, 0, s>>>(a.z, a.p, a.B, a.D);
     else
         softmax_kernel<<<dim3(a.B), 256, 0, s>>>(a);
     return hipGetLastError();
