@@ -25,7 +25,7 @@ BATCHES = (1, 2, 4, 8, 16)
 # HBM-side bytes of the 53 conv launches of one batch-16 EXEC, from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised in profiles/exec_resnet50_b16_hbm_traffic.txt (scaled by a 256 MiB copy).
 # Counters cannot be read from inside this process, so the figure is carried here.
-CONV_TRAFFIC_BYTES_B16 = 1109.4e6
+CONV_TRAFFIC_BYTES_B16 = 1109.7e6
 
 
 def cpu_baseline(seed, log):
