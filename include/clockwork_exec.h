@@ -20,7 +20,11 @@
  *     No exception crosses this boundary.  cw_strerror() names a status;
  *     cw_last_error() gives detail for the last failing call on a context.
  *   - Pointers marked [host] are host memory owned by the caller; the library owns
- *     all device memory.  No call allocates device memory after cw_create().
+ *     all device memory.  The device pools (workspace, IO cache, weight pool, LOAD
+ *     staging) are allocated once, by cw_create(), and nothing is taken from or returned
+ *     to the device allocator afterwards.  Host-side runtime objects are still created
+ *     later: one event per model in cw_model_define(), and one recorded HIP graph per
+ *     (model, batch size) in cw_load_weights() (recording executes nothing).
  *   - `stream` is a raw hipStream_t (passed as void*; NULL = the default stream).
  *     Calls that take a stream only enqueue work; the caller must keep [host]
  *     buffers alive and unmodified until that stream has been synchronised.  Host
@@ -90,9 +94,16 @@ typedef struct {
                                    a multiple of 256, and no weight tensor may be larger */
 } cw_config;
 
-/* Allocates every device buffer the context will ever use.  [host] cfg. */
+/* Section 5.2, "Managing model weights in memory": a worker takes all the device memory it
+ * will use when it starts and manages it itself, so that no allocation happens on the path of
+ * an action.  cw_create makes one allocation per region of cw_config (+ the streams and events
+ * the context needs); cfg [host].  CW_ERR_NO_MEMORY when the device cannot give a region,
+ * CW_ERR_UNSUPPORTED on a GPU other than gfx950, CW_ERR_INVALID for a bad ordinal or page
+ * size.  device == -1 makes a planning-only context: models and plans can be defined and
+ * inspected, every call that would touch a GPU returns CW_ERR_INVALID. */
 int32_t cw_create(cw_ctx **out, const cw_config *cfg);
-/* Waits for all work the context enqueued, then frees everything. */
+/* The worker shuts down: waits for all work the context enqueued, then frees every region,
+ * graph, stream and event.  The handle is invalid afterwards. */
 int32_t cw_destroy(cw_ctx *ctx);
 
 /* ---- models (section 5.1: kernels per batch size + memory metadata) ----------
@@ -134,7 +145,10 @@ size_t cw_model_workspace_bytes(cw_ctx *ctx, int32_t model_id, int32_t batch);
  * `bytes` must equal cw_model_weight_bytes(). */
 int32_t cw_load_weights(cw_ctx *ctx, int32_t model_id, const void *host_blob,
                         size_t bytes, void *stream);
-/* Metadata only; succeeds whether or not the model is resident (section 5.2). */
+/* Metadata only; succeeds whether or not the model is resident (section 5.2).  The pages go
+ * back to the free list at once; an EXEC of the model that is still queued or running keeps
+ * reading them safely, because the next LOAD that takes one of them makes its stream wait for
+ * that EXEC's end before it writes. */
 int32_t cw_unload_weights(cw_ctx *ctx, int32_t model_id);
 /* Free pages of the weight pool: the only memory state a controller needs (section 5.1);
  * in bytes (free pages x page size), and as a count.  cw_model_weight_pages: the pages one
@@ -163,7 +177,10 @@ int32_t cw_exec(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot, void
  * only after these copies have completed.  CW_ERR_NO_INPUT if no EXEC ran. */
 int32_t cw_output(cw_ctx *ctx, int32_t slot, float *host_probs, float *host_logits,
                   void *stream);
-/* Releases a slot without copying anything out. */
+/* Section 5.2, INFER: an action that is rejected after its INPUT (its window passed, its EXEC
+ * failed) must give its IO-cache entry back without an OUTPUT.  Releases the slot without
+ * copying anything out; the memory is reused only after the slot's last EXEC has finished.
+ * Succeeds on a slot that is already free. */
 int32_t cw_release(cw_ctx *ctx, int32_t slot);
 /* On-device duration of the slot's last EXEC (the "timing" field of a result).
  * Blocks until that EXEC has finished. */
@@ -174,91 +191,19 @@ typedef struct {
     uint32_t n;
     float p50_us, p99_us, p999_us, min_us, max_us, mean_us;
 } cw_profile;
-/* Runs `repeats` EXECs of (model, batch) back to back on an internal stream over a
- * zero input, each timed on the device, and stores and returns nearest-rank
- * percentiles.  The EXECs are submitted in bursts of 128; one untimed EXEC leads
- * each burst so that every timed one starts behind queued work.  Synchronous.  samples_us [host] may be NULL, else receives the
- * `repeats` individual durations in microseconds. */
-int32_t cw_profile_measure(cw_ctx *ctx, int32_t model_id, int32_t batch, uint32_t repeats,
-                           cw_profile *out, float *samples_us);
+/* Runs `repeats` EXECs of (model, batch) back to back on an internal stream, each timed on
+ * the device, and stores and returns nearest-rank percentiles.  The EXECs read the input held
+ * by `slot` (an IO slot of this (model, batch) filled by cw_input; it stays the caller's), or,
+ * with slot == -1, a zero-filled input of the library's own.  EXEC time depends slightly on the
+ * operand values through power and clocks, so a profile meant to predict real requests should
+ * be measured over a representative input.  The EXECs are submitted in bursts of 128; one
+ * untimed EXEC leads each burst so that every timed one starts behind queued work.
+ * Synchronous.  samples_us [host] may be NULL, else receives the `repeats` individual
+ * durations in microseconds. */
+int32_t cw_profile_measure(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot,
+                           uint32_t repeats, cw_profile *out, float *samples_us);
 /* Last measured profile; n == 0 if none was measured. */
 int32_t cw_profile_get(cw_ctx *ctx, int32_t model_id, int32_t batch, cw_profile *out);
-
-/* ---- introspection for parity tests and per-layer measurement ----------------
- * Number of kernel launches in the plan of (model, batch); negative on error. */
-int32_t cw_plan_num_launches(cw_ctx *ctx, int32_t model_id, int32_t batch);
-typedef struct {
-    int32_t op_index;      /* which op of the model this launch belongs to (fused launch: the last) */
-    int32_t fused_op;      /* -1, or the op this launch computes first, fused with op_index */
-    int32_t proj_op;       /* -1, or the projection-shortcut op this launch computes as well */
-    int32_t pair_op;       /* -1, or a second, independent convolution over the same input computed by this launch */
-    int32_t kind;          /* internal kernel family id */
-    int32_t grid_x, grid_y, grid_z, block;
-    int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
-    int32_t conv_tile;     /* conv: the tile variant in cw_set_plan_override's numbering; -1 for a fused pair and for other kinds */
-    int32_t wave_groups;   /* conv: groups of waves that split every K slice (1 = none) */
-    int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
-    int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
-    int64_t flops;         /* 2 * MACs */
-    char name[48];
-} cw_launch_info;
-int32_t cw_plan_launch_info(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t index,
-                            cw_launch_info *out);
-/* Runs EXEC like cw_exec but times every launch of the plan with its own pair of
- * events, issuing it `inner` (>= 1) times back to back between them (a launch is
- * idempotent); launch_us [host] receives cw_plan_num_launches() averages, each
- * including the dispatch cost of one launch.  Synchronous. */
-int32_t cw_exec_timed_launches(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot,
-                               int32_t inner, float *launch_us, void *stream);
-/* Copies the output of op `op_index` from the slot's last EXEC to host_out [host]
- * as fp32 NCHW [batch][cout][h][w].  Needs the context to have been created with
- * debug retention (cw_set_debug_keep) before the plan was built; otherwise the
- * workspace region may have been reused: returns CW_ERR_UNSUPPORTED. */
-int32_t cw_debug_read_op(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t op_index,
-                         float *host_out, size_t capacity_floats);
-/* When keep != 0, plans built afterwards give every op output its own workspace
- * region (no reuse) so cw_debug_read_op can read them.  Costs workspace only. */
-int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
-/* EXEC normally replays, for the slot-independent middle of a plan, a HIP graph recorded at
- * LOAD (fewer, cheaper submissions; identical kernels and arguments).  on == 0 makes EXEC
- * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
- * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
-int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..24 =
- * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
- * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
- * instead of 64 (used where cin % 128 == 0, else their 64 form), then tiles whose waves come in
- * 2, 4 or 8 groups that share every K slice (128 wide: 128x64 in 2, 64x64 in 2 and 4, 64x32,
- * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; the first
- * convolution takes a grouped tile's one-group form);
- * pixels x channels per workgroup; -1 = the plan compiler's own choice)
- * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
- * tests can reach every kernel instantiation.  Still fixed at plan time. */
-int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
-/* A convolution with 64 or 128 output channels whose only consumer is a 1x1 stride-1
- * convolution with a residual (the last two layers of a ResNet bottleneck) is planned as ONE
- * launch when the batch gives it enough workgroups: the intermediate tensor then never leaves
- * the chip.  Where the first layer has 128 output channels (and the second a multiple of 128)
- * the launch runs two groups of four waves: they split every K slice of the first layer and
- * the channels of every chunk of the second.  on == 0 plans such pairs as two launches for models defined
- * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
- * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
-int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
-/* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
- * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
- * one launch whose first workgroups compute the one and the rest the other: one dispatch and one
- * set-up latency instead of two.  Both run on one tile shape, so a member's sums may be added up
- * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
- * models defined afterwards; on != 0 restores the default. */
-int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
-/* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
- * The plan compiler takes the tile variant and split-K factor of a convolution from a table
- * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
- * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
- * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
- * kh, stride, conv_tile (0..24 as above), split_k >= 1}; copied.  Shapes in neither table get
- * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
-int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
 
 /* Device ordinal the context was created on (-1: planning only). */
 int32_t cw_context_device(cw_ctx *ctx);
@@ -314,6 +259,10 @@ int32_t cw_worker_next_result(cw_worker *w, cw_result *out, uint64_t timeout_ns)
 int32_t cw_worker_profile(cw_worker *w, int32_t type, int32_t model_id, int32_t batch, uint32_t *n,
                           uint64_t *mean_ns, uint64_t *max_ns);
 
+/* Section 5.2, "Results": a result carries success or an error code.  cw_strerror names a
+ * status (static string, never NULL); cw_last_error gives the detail of the last failing call
+ * on a context (NULL context: of the last failing cw_create on this thread); the string is
+ * owned by the library and valid until the next call on that context. */
 const char *cw_strerror(int32_t status);
 const char *cw_last_error(cw_ctx *ctx);
 

@@ -1,0 +1,101 @@
+/*
+ * clockwork_exec_introspect.h -- plan introspection, per-launch timing, per-layer read-back and
+ * plan-compiler switches of libclockwork_exec.so.
+ *
+ * None of these calls is part of the paper's action model; they exist for the parity tests
+ * (every kernel instantiation must be reachable and every layer comparable with the CPU
+ * oracle), for the tuner that writes the plan table offline, and for the per-launch roofline
+ * report.  A worker serving requests needs only clockwork_exec.h.  Same conventions as there:
+ * int32_t status, [host] pointers owned by the caller, no exception crosses the boundary.
+ * What they expose is the paper's "kernels per batch size" and "memory metadata" of a model
+ * (section 5.1): the fixed launch list of a (model, batch) and where its tensors live.
+ */
+#ifndef CLOCKWORK_EXEC_INTROSPECT_H
+#define CLOCKWORK_EXEC_INTROSPECT_H
+
+#include "clockwork_exec.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Number of kernel launches in the plan of (model, batch); negative on error. */
+int32_t cw_plan_num_launches(cw_ctx *ctx, int32_t model_id, int32_t batch);
+typedef struct {
+    int32_t op_index;      /* which op of the model this launch belongs to (fused launch: the last) */
+    int32_t fused_op;      /* -1, or the op this launch computes first, fused with op_index */
+    int32_t proj_op;       /* -1, or the projection-shortcut op this launch computes as well */
+    int32_t pair_op;       /* -1, or a second, independent convolution over the same input computed by this launch */
+    int32_t kind;          /* internal kernel family id */
+    int32_t grid_x, grid_y, grid_z, block;
+    int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
+    int32_t conv_tile;     /* conv: the tile variant in cw_set_plan_override's numbering; -1 for a fused pair and for other kinds */
+    int32_t wave_groups;   /* conv: groups of waves that split every K slice (1 = none) */
+    int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
+    int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
+    int64_t flops;         /* 2 * MACs */
+    char name[48];
+} cw_launch_info;
+int32_t cw_plan_launch_info(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t index,
+                            cw_launch_info *out);
+/* Runs EXEC like cw_exec but times every launch of the plan with its own pair of
+ * events, issuing it `inner` (>= 1) times back to back between them (a launch is
+ * idempotent); launch_us [host] receives cw_plan_num_launches() averages, each
+ * including the dispatch cost of one launch.  Synchronous. */
+int32_t cw_exec_timed_launches(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot,
+                               int32_t inner, float *launch_us, void *stream);
+/* Copies the output of op `op_index` from the slot's last EXEC to host_out [host]
+ * as fp32 NCHW [batch][cout][h][w].  Needs the context to have been created with
+ * debug retention (cw_set_debug_keep) before the plan was built; otherwise the
+ * workspace region may have been reused: returns CW_ERR_UNSUPPORTED. */
+int32_t cw_debug_read_op(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t op_index,
+                         float *host_out, size_t capacity_floats);
+/* When keep != 0, plans built afterwards give every op output its own workspace
+ * region (no reuse) so cw_debug_read_op can read them.  Costs workspace only. */
+int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
+/* EXEC normally replays, for the slot-independent middle of a plan, a HIP graph recorded at
+ * LOAD (fewer, cheaper submissions; identical kernels and arguments).  on == 0 makes EXEC
+ * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
+ * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
+int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..24 =
+ * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
+ * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
+ * instead of 64 (used where cin % 128 == 0, else their 64 form), then tiles whose waves come in
+ * 2, 4 or 8 groups that share every K slice (128 wide: 128x64 in 2, 64x64 in 2 and 4, 64x32,
+ * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; the first
+ * convolution takes a grouped tile's one-group form);
+ * pixels x channels per workgroup; -1 = the plan compiler's own choice)
+ * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
+ * tests can reach every kernel instantiation.  Still fixed at plan time. */
+int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
+/* A convolution with 64 or 128 output channels whose only consumer is a 1x1 stride-1
+ * convolution with a residual (the last two layers of a ResNet bottleneck) is planned as ONE
+ * launch when the batch gives it enough workgroups: the intermediate tensor then never leaves
+ * the chip.  Where the first layer has 128 output channels (and the second a multiple of 128)
+ * the launch runs two groups of four waves: they split every K slice of the first layer and
+ * the channels of every chunk of the second.  on == 0 plans such pairs as two launches for models defined
+ * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
+ * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
+int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
+/* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
+ * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
+ * one launch whose first workgroups compute the one and the rest the other: one dispatch and one
+ * set-up latency instead of two.  Both run on one tile shape, so a member's sums may be added up
+ * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
+ * models defined afterwards; on != 0 restores the default. */
+int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
+/* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
+ * The plan compiler takes the tile variant and split-K factor of a convolution from a table
+ * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
+ * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
+ * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
+ * kh, stride, conv_tile (0..24 as above), split_k >= 1}; copied.  Shapes in neither table get
+ * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
+int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
+
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLOCKWORK_EXEC_INTROSPECT_H */

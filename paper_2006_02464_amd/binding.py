@@ -86,7 +86,7 @@ SIGNATURES = {
     "cw_output": (c_int32, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]),
     "cw_release": (c_int32, [c_void_p, c_int32]),
     "cw_exec_duration_ns": (c_int32, [c_void_p, c_int32, POINTER(c_uint64)]),
-    "cw_profile_measure": (c_int32, [c_void_p, c_int32, c_int32, c_uint32, POINTER(cw_profile), c_void_p]),
+    "cw_profile_measure": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_uint32, POINTER(cw_profile), c_void_p]),
     "cw_profile_get": (c_int32, [c_void_p, c_int32, c_int32, POINTER(cw_profile)]),
     "cw_plan_num_launches": (c_int32, [c_void_p, c_int32, c_int32]),
     "cw_plan_launch_info": (c_int32, [c_void_p, c_int32, c_int32, c_int32, POINTER(cw_launch_info)]),
@@ -249,10 +249,10 @@ class Context:
         return ns.value
 
     # -- profile
-    def profile_measure(self, model_id, batch, repeats, want_samples=False):
+    def profile_measure(self, model_id, batch, repeats, want_samples=False, slot=-1):
         prof = cw_profile()
         samples = np.empty(repeats, np.float32) if want_samples else None
-        self._check(lib().cw_profile_measure(self._h, model_id, batch, repeats, byref(prof), _ptr(samples)))
+        self._check(lib().cw_profile_measure(self._h, model_id, batch, slot, repeats, byref(prof), _ptr(samples)))
         d = {f: getattr(prof, f) for f, _ in cw_profile._fields_}
         return (d, samples) if want_samples else d
 

@@ -1,5 +1,5 @@
 // C ABI of the worker hot path (see include/clockwork_exec.h for the contract).
-#include "../../include/clockwork_exec.h"
+#include "../../include/clockwork_exec_introspect.h"
 
 #include <algorithm>
 #include <cmath>
@@ -45,6 +45,7 @@ struct ModelRt {
     bool loaded = false;
     std::vector<int32_t> pages;  // pool page of each of the model's weight pages while resident
     hipEvent_t load_done = nullptr;
+    hipEvent_t last_exec_end = nullptr;  // end event of the last EXEC issued on these weights (a slot's event; not owned)
     std::vector<PlanGraph> graphs;  // parallel to m.plans
 };
 
@@ -57,6 +58,7 @@ struct cw_ctx {
     RangeAllocator io_alloc;
     size_t page_bytes = 0;            // weight pool page size
     std::vector<int32_t> free_pages;  // free pages of the weight pool, lowest index last (taken first)
+    std::vector<hipEvent_t> page_guard;  // per page: end event of the last EXEC that may still read it (nullptr: none)
     Slot slots[kMaxSlots];
     std::vector<std::unique_ptr<ModelRt>> models;
     PlanOverride ov;
@@ -113,18 +115,32 @@ Plan *get_plan(ModelRt *m, int32_t batch) {
     return nullptr;
 }
 
-char *resolve(cw_ctx *c, const ModelRt *m, const Slot *s, const Ref &r) {
+// Where the plan's address spaces are for one EXEC: the arena of intermediates and the three
+// per-request buffers (the context's workspace and an IO slot, or the static scratch array and the
+// caller's own device buffers).
+struct Bases {
+    char *workspace = nullptr, *input = nullptr, *logits = nullptr, *probs = nullptr;
+};
+
+Bases bases_of(const cw_ctx *c, const Slot *s) {
+    Bases b;
+    b.workspace = c->workspace;
+    if (s) { b.input = c->io + s->in_off; b.logits = c->io + s->logits_off; b.probs = c->io + s->probs_off; }
+    return b;
+}
+
+char *resolve(cw_ctx *c, const ModelRt *m, const Bases &b, const Ref &r) {
     switch (r.space) {
-        case SP_WORKSPACE: return c->workspace + r.offset;
+        case SP_WORKSPACE: return b.workspace + r.offset;
         case SP_WEIGHTS: return c->pool + (size_t)m->pages[r.offset / c->page_bytes] * c->page_bytes + r.offset % c->page_bytes;
-        case SP_SLOT_INPUT: return c->io + s->in_off;
-        case SP_SLOT_LOGITS: return c->io + s->logits_off;
-        case SP_SLOT_PROBS: return c->io + s->probs_off;
+        case SP_SLOT_INPUT: return b.input;
+        case SP_SLOT_LOGITS: return b.logits;
+        case SP_SLOT_PROBS: return b.probs;
         default: return nullptr;
     }
 }
 
-hipError_t issue(cw_ctx *c, const ModelRt *m, const Slot *s, const Launch &l, hipStream_t st) {
+hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, hipStream_t st) {
     const DType dt = m->m.dtype;
     switch (l.kind) {
         case K_CAST_INPUT: {
@@ -311,7 +327,7 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
         hipGraph_t graph = nullptr;
         CW_HIP(c, hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal));
         hipError_t e = hipSuccess;
-        for (size_t i = best_a; i < best_a + best_n && e == hipSuccess; ++i) e = issue(c, m, nullptr, p.launches[i], c->capture_stream);
+        for (size_t i = best_a; i < best_a + best_n && e == hipSuccess; ++i) e = issue(c, m, bases_of(c, nullptr), p.launches[i], c->capture_stream);
         hipError_t e2 = hipStreamEndCapture(c->capture_stream, &graph);
         if (e != hipSuccess || e2 != hipSuccess) {
             if (graph) (void)hipGraphDestroy(graph);
@@ -330,14 +346,15 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
 // Enqueues the launches of a plan: the recorded graph for its middle part when there is one.
 int32_t enqueue_plan(cw_ctx *c, ModelRt *m, const Plan *p, const Slot *s, hipStream_t st) {
     const size_t pi = (size_t)(p - m->m.plans.data());
-    const PlanGraph *pg = (c->use_graphs && pi < m->graphs.size() && m->graphs[pi].exec) ? &m->graphs[pi] : nullptr;
+    // a graph holds the weight addresses of the placement it was recorded for: replay it only there
+    const PlanGraph *pg = (c->use_graphs && pi < m->graphs.size() && m->graphs[pi].exec && m->graphs[pi].pages == m->pages) ? &m->graphs[pi] : nullptr;
     for (size_t i = 0; i < p->launches.size(); ++i) {
         if (pg && i == pg->first) {
             CW_HIP(c, hipGraphLaunch(pg->exec, st));
             i = pg->last;
             continue;
         }
-        hipError_t e = issue(c, m, s, p->launches[i], st);
+        hipError_t e = issue(c, m, bases_of(c, s), p->launches[i], st);
         if (e != hipSuccess) return hip_fail(c, e, p->launches[i].info.name);
     }
     return CW_OK;
@@ -381,6 +398,7 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
     c->page_bytes = cfg->weight_page_bytes ? cfg->weight_page_bytes : kDefaultPageBytes;
     if (c->page_bytes % 256 != 0) { g_create_err = "weight_page_bytes must be a multiple of 256"; return CW_ERR_INVALID; }
     for (int32_t pg = (int32_t)(cfg->weight_pool_bytes / c->page_bytes) - 1; pg >= 0; --pg) c->free_pages.push_back(pg);
+    c->page_guard.assign(c->free_pages.size(), nullptr);
     if (cfg->device < 0) {  // planning-only: models and plans can be defined and inspected
         *out = c.release();
         return CW_OK;
@@ -568,6 +586,10 @@ int32_t cw_model_weight_pages(cw_ctx *c, int32_t model_id) {
 // Returns a model's pages to the pool; the free list stays sorted so that the lowest page is
 // taken first and placement is a function of the LOAD/UNLOAD history alone.
 static void release_pages(cw_ctx *c, ModelRt *m) {
+    // An EXEC that reads these pages may still be queued or running: whoever writes them next waits
+    // for its end event (UNLOAD itself stays metadata only).
+    for (int32_t pg : m->pages) c->page_guard[pg] = m->last_exec_end;
+    m->last_exec_end = nullptr;
     c->free_pages.insert(c->free_pages.end(), m->pages.begin(), m->pages.end());
     std::sort(c->free_pages.begin(), c->free_pages.end(), std::greater<int32_t>());
     m->pages.clear();
@@ -597,6 +619,17 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     // One staging area: a LOAD waits for the previous LOAD's pack kernels.
     if (c->staging_used && (e = hipStreamWaitEvent(st, c->staging_free, 0)) != hipSuccess) return bail(e, "hipStreamWaitEvent");
     if ((e = hipMemcpyAsync(c->staging, host_blob, bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return bail(e, "hipMemcpyAsync");
+    // The pages may have belonged to a model whose last EXEC has not finished: the pack kernels,
+    // which overwrite them, wait for it on this stream (the copy into the staging area need not).
+    for (int32_t pg : m->pages) {
+        hipEvent_t guard = c->page_guard[pg];
+        if (!guard) continue;
+        const hipError_t q = hipEventQuery(guard);
+        if (q == hipErrorNotReady && (e = hipStreamWaitEvent(st, guard, 0)) != hipSuccess) return bail(e, "hipStreamWaitEvent");
+        if (q != hipSuccess && q != hipErrorNotReady) return bail(q, "hipEventQuery");
+        for (int32_t pg2 : m->pages)
+            if (c->page_guard[pg2] == guard) c->page_guard[pg2] = nullptr;   // waited for (or over) once for all of them
+    }
     auto at = [&](size_t off) { return c->pool + (size_t)m->pages[off / c->page_bytes] * c->page_bytes + off % c->page_bytes; };
     for (const WeightSlot &ws : m->m.wslots) {
         const bool is_conv = m->m.ops[ws.op_index].op == CW_OP_CONV;
@@ -669,6 +702,7 @@ int32_t cw_exec(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, void *
     s->state = SLOT_EXECUTED;
     c->last_exec_stream = st;
     c->last_exec_end = s->exec_end;
+    m->last_exec_end = s->exec_end;
     return CW_OK;
 }
 
@@ -695,7 +729,7 @@ int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32
         for (size_t i = 0; i < cnt; ++i) {
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i], st));
             for (int r = 0; r < inner; ++r) {
-                hipError_t e = issue(c, m, s, p->launches[base + i], st);
+                hipError_t e = issue(c, m, bases_of(c, s), p->launches[base + i], st);
                 if (e != hipSuccess) return hip_fail(c, e, p->launches[base + i].info.name);
             }
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i + 1], st));
@@ -766,7 +800,8 @@ int32_t cw_exec_duration_ns(cw_ctx *c, int32_t slot, uint64_t *ns) {
     return CW_OK;
 }
 
-int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t repeats, cw_profile *out, float *samples_us) {
+int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, uint32_t repeats, cw_profile *out,
+                           float *samples_us) {
     if (!c || !out || repeats == 0) return set_err(c, CW_ERR_INVALID, "null output or zero repeats");
     if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
     ModelRt *m = get_model(c, model_id);
@@ -777,18 +812,31 @@ int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t 
     DeviceGuard g(c->device);
     hipStream_t st = c->internal_stream;
     if (c->last_exec_end) CW_HIP(c, hipEventSynchronize(c->last_exec_end));  // one EXEC at a time
-    int32_t slot = -1;
-    int32_t rc = acquire_slot(c, m, model_id, batch, st, &slot);
-    if (rc != CW_OK) return rc;
+    // The input the EXECs run over: the caller's slot (EXEC time depends a little on the values,
+    // through power and clocks), or a zero-filled one of the library's own.
+    const bool own_slot = slot < 0;
+    hipError_t e = hipSuccess;
+    int32_t rc = CW_OK;
+    if (own_slot) {
+        rc = acquire_slot(c, m, model_id, batch, st, &slot);
+        if (rc != CW_OK) return rc;
+        const size_t in_b = ((size_t)batch * m->m.in_c * m->m.in_h * m->m.in_w * 4 + 255) / 256 * 256;
+        e = launch_fill_zero(c->io + c->slots[slot].in_off, in_b, st);
+        if (e == hipSuccess) e = hipEventRecord(c->slots[slot].input_done, st);
+    } else {
+        if (slot >= kMaxSlots || c->slots[slot].state == SLOT_FREE) return set_err(c, CW_ERR_NO_INPUT, "slot holds no input");
+        if (c->slots[slot].model != model_id) return set_err(c, CW_ERR_NO_INPUT, "slot holds an input for another model");
+        if (c->slots[slot].batch != batch) return set_err(c, CW_ERR_BAD_BATCH, "slot holds an input of another batch size");
+        e = hipStreamWaitEvent(st, c->slots[slot].input_done, 0);
+    }
     Slot &s = c->slots[slot];
-    const size_t in_b = ((size_t)batch * m->m.in_c * m->m.in_h * m->m.in_w * 4 + 255) / 256 * 256;
-    hipError_t e = launch_fill_zero(c->io + s.in_off, in_b, st);
-    if (e == hipSuccess) e = hipEventRecord(s.input_done, st);
     if (e == hipSuccess) e = hipStreamWaitEvent(st, m->load_done, 0);
-    if (e != hipSuccess) { free_slot(c, &s); return hip_fail(c, e, "profile setup"); }
+    if (e != hipSuccess) {
+        if (own_slot) free_slot(c, &s);
+        return hip_fail(c, e, "profile setup");
+    }
     std::vector<float> samples;
     samples.reserve(repeats);
-    rc = CW_OK;
     for (uint32_t done = 0; done < repeats && rc == CW_OK;) {
         const uint32_t cnt = std::min<uint32_t>(kProfileEvents, repeats - done);
         // One untimed EXEC leads every burst: without it the first start event of a burst fires on
@@ -807,7 +855,7 @@ int32_t cw_profile_measure(cw_ctx *c, int32_t model_id, int32_t batch, uint32_t 
         }
         done += cnt;
     }
-    free_slot(c, &s);
+    if (own_slot) free_slot(c, &s);
     if (rc != CW_OK) return rc;
     percentile_profile(samples, &p->profile);
     *out = p->profile;
@@ -852,6 +900,7 @@ int32_t cw_debug_read_op(cw_ctx *c, int32_t model_id, int32_t batch, int32_t op_
     if (!m->m.keep_all) return set_err(c, CW_ERR_UNSUPPORTED, "model was not defined with debug retention");
     if (op_index < 0 || op_index >= (int32_t)m->m.ops.size()) return set_err(c, CW_ERR_INVALID, "bad op index");
     const Ref &r = p->op_out[op_index];
+    if (r.space == SP_NONE) return set_err(c, CW_ERR_UNSUPPORTED, "op is computed inside a fused launch; its output is never stored");
     if (r.space != SP_WORKSPACE) return set_err(c, CW_ERR_UNSUPPORTED, "op output lives in the IO slot; use cw_output");
     const OpShape &sh = m->m.shapes[op_index];
     const size_t count = (size_t)batch * sh.c * sh.h * sh.w;

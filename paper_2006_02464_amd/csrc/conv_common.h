@@ -12,24 +12,6 @@ constexpr unsigned kOob = 0x80000000u;  // byte offset beyond any buffer (buffer
 
 enum ConvMode : int { MODE_CONV = 0, MODE_GEMM = 1, MODE_STEM = 2 };
 
-// Development aid: with -DCW_TRACE one lane per workgroup stamps the shader clock at phase
-// boundaries into a global array (64 stamps per workgroup).  Never compiled into the library.
-#ifdef CW_TRACE
-__device__ long long cw_trace_buf[4096 * 64];
-#define CW_STAMP(slot)                                                                                  \
-    do {                                                                                                \
-        const int sl__ = (slot);                                                                        \
-        if (threadIdx.x == 0 && blockIdx.x < 4096 && sl__ < 60) cw_trace_buf[blockIdx.x * 64 + sl__] = clock64(); \
-    } while (0)
-#define CW_STAMP_END(slot)                                                                              \
-    do {                                                                                                \
-        if (threadIdx.x == 0 && blockIdx.x < 4096) cw_trace_buf[blockIdx.x * 64 + (slot)] = clock64();  \
-    } while (0)
-#else
-#define CW_STAMP(slot) do { } while (0)
-#define CW_STAMP_END(slot) do { } while (0)
-#endif
-
 // n / d for a divisor prepared on the host (round-up multiplier; exact for every 32-bit n).
 static __device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv &d) {
     const unsigned t = __umulhi(d.magic, n);

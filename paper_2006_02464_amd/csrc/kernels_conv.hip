@@ -58,7 +58,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 
     __shared__ __attribute__((aligned(16))) T lds[2 * STAGE];
 
-    CW_STAMP(0);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -238,16 +237,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
 
     // Prologue: slices kt0 .. kt0+PF-1 into the register sets; the first one goes on into LDS
     // stage 0 and its set is refilled with slice kt0+PF.
-    CW_STAMP(1);
 #pragma unroll
     for (int u = 0; u < PF; ++u) load_global(kt0 + u, rxa[u], rwa[u]);
-    CW_STAMP(2);
     store_lds(0, rxa[0], rwa[0]);
     load_global(kt0 + PF, rxa[0], rwa[0]);
     __syncthreads();
-    CW_STAMP(3);
-    int trace_slot = 4;
-    (void)trace_slot;
 
     // Steady state, PF slices per trip, no branches inside.  At the top of step kt the current
     // LDS stage holds slice kt and register set (u+1)%PF holds slice kt+1, requested PF steps
@@ -261,9 +255,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         for (int u = 0; u < PF; ++u) {
             store_lds(cur ^ 1, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
             load_global(kt + u + 1 + PF, rxa[(u + 1) % PF], rwa[(u + 1) % PF]);
-            CW_STAMP(trace_slot++);
             compute(cur);
-            CW_STAMP(trace_slot++);
             __syncthreads();
             cur ^= 1;
         }
@@ -279,7 +271,6 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         }
     }
 
-    CW_STAMP_END(60);
     const EpiPos pos{m0, n0, wm0, wn0, lrow, lhalf};
     if (SPLITK) {
         if (!splitk_exchange<TM, TN>(acc, a, pos, tile_id)) return;
@@ -288,9 +279,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     // arithmetic and the stores
     EpiOperands<TM, TN> eo;
     epilogue_load<TM, TN>(eo, a, pos);
-    CW_STAMP_END(61);
     epilogue_store<T, TM, TN>(acc, eo, a, pos);
-    CW_STAMP_END(62);
 }
 
 TileDim conv_tile_dim(ConvTile t) {

@@ -97,11 +97,6 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
     T *lds = reinterpret_cast<T *>(cw_dyn_lds);
     const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)cw_dyn_lds;
 
-    CW_STAMP(0);
-#ifdef CW_TRACE
-    asm volatile("" ::"s"(a.M), "s"(a.Cin));
-    CW_STAMP(3);
-#endif
     const int tid = threadIdx.x;
     // Fused form: both layers' biases are requested now, with ordinary loads, and go to LDS at the
     // end of the set-up arithmetic below, which covers their latency; no counted load is in
@@ -117,9 +112,6 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             bias2_v[j] = n < a.Cout2 ? a.bias2[n] + (a.wd ? a.biasd[n] : 0.f) : 0.f;
         }
     }
-#ifdef CW_TRACE
-    CW_STAMP_END(59);
-#endif
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = wave / (WARPS_M * WARPS_N);        // K group of this wave
@@ -310,15 +302,8 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             for (int j = 0; j < TN; ++j)
                 qw[j] = *reinterpret_cast<const v8 *>(sW + swz<BK>(wn0 + j * 32 + lrow, kk * 2 + lhalf));
         };
-#ifdef CW_TRACE
-        const bool detail = kt == kt0 + 4;
-        if (detail) CW_STAMP_END(24);
-#endif
 #pragma unroll
         for (int t = 0; t < DEPTH - 1 && t < KK; ++t) fetch(t, fx[t], fw[t]);
-#ifdef CW_TRACE
-        if (detail) CW_STAMP_END(25);
-#endif
 #pragma unroll
         for (int t = 0; t < KK; ++t) {
             if (t + DEPTH - 1 < KK) fetch(t + DEPTH - 1, fx[(t + DEPTH - 1) % DEPTH], fw[(t + DEPTH - 1) % DEPTH]);
@@ -330,9 +315,6 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 #pragma unroll
                 for (int idx = t * LOADS / KK; idx < (t + 1) * LOADS / KK; ++idx) issue_piece(idx);
             }
-#ifdef CW_TRACE
-            if (detail) CW_STAMP_END(26 + t);
-#endif
         }
     };
 
@@ -340,27 +322,21 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
     EpiOperands<TM, TN> eo;
 
     // Prologue: the first min(NS-1, nsteps) slices into stages 0, 1, ...
-    CW_STAMP(1);
     const int ahead = min(NS - 1, nsteps);
 #pragma unroll
     for (int u = 0; u < NS - 1; ++u)
         if (u < ahead) issue(kt0 + u, u);  // uniform
-    CW_STAMP(2);
 
     // Steady state: slice kt sits in stage `cur`; behind it NS-2 more slices are in flight.  After
     // the barrier every wave has finished the MFMAs of slice kt-1, so its stage (the one before
     // `cur` in the ring) takes the loads of slice kt+NS-1, which then fly during NS-1 slices of
     // MFMAs.
     int cur = 0;
-    int trace_slot = 4;
-    (void)trace_slot;
     for (; kt + (NS - 1) < kt1; ++kt) {
         wait_loads_and_barrier<(NS - 2) * LOADS>();
-        CW_STAMP(trace_slot++);
         issue_begin(kt + NS - 1, cur == 0 ? NS - 1 : cur - 1);
         compute(cur, std::true_type{});
         issue_end();
-        CW_STAMP(trace_slot++);
         cur = cur + 1 == NS ? 0 : cur + 1;
     }
     // Tail: the last `ahead` slices, nothing left to load; with r slices still behind the one
@@ -371,10 +347,8 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
         constexpr int u = decltype(behind)::value;  // slices still in flight behind this one
         if (u < kt1 - kt) {                         // uniform
             wait_loads_and_barrier<u * LOADS>();
-            CW_STAMP(trace_slot++);
             if (!SPLITK && !FUSED && u == 0 && kg == 0) epilogue_load<TM, TN>(eo, a, pos);
             compute(cur, std::false_type{});
-            CW_STAMP(trace_slot++);
             cur = cur + 1 == NS ? 0 : cur + 1;
             ++kt;
         }
@@ -413,7 +387,6 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
         }
     }
 
-    CW_STAMP_END(60);
     if constexpr (FUSED) {
         // ---- second layer: y[m][:] = act2(res[m][:] + bias2 + W2 * p[m][:]),  p = act(acc + bias) ----
         // BN == Cout: the tile holds every channel of its BM pixels, so the 1x1 convolution that
@@ -533,12 +506,10 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
                 }
         }
         const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (unsigned)a.M * a.Cout2 * 2u);
-        CW_STAMP_END(61);
         for (int c = 0; c < chunks; ++c) {
             // chunk c has landed (mine: vmcnt; everyone's: barrier); p and the bias are visible;
             // every wave has finished reading the buffer that chunk c+1 is about to overwrite
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
-            CW_STAMP(40 + c);
             if (c + 1 < chunks) issue_chunk(c + 1);
             const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
             const T *sR = sW2 + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
@@ -588,16 +559,13 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
                     }
             }
         }
-        CW_STAMP_END(62);
         return;
     }
     if (SPLITK) {
         if (!splitk_exchange<TM, TN>(acc, a, pos, tile_id)) return;
         epilogue_load<TM, TN>(eo, a, pos);
     }
-    CW_STAMP_END(61);
     epilogue_store<T, TM, TN>(acc, eo, a, pos);
-    CW_STAMP_END(62);
 }
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>

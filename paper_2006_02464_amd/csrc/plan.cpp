@@ -312,7 +312,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
     // convolution with a residual; enough pixels for the launch to fill the GPU.
     std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), fused_kg(n_ops, 1), proj_of(n_ops, -1);
-    if (ov.fuse && !ov.keep_all && ov.tile < 0 && ov.split_k <= 0) {
+    if (ov.fuse && ov.tile < 0 && ov.split_k <= 0) {
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
             if (m.ops[i].input_from >= 0) ++uses[m.ops[i].input_from];

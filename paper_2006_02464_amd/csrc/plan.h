@@ -8,7 +8,7 @@
 #include <string>
 #include <vector>
 
-#include "../../include/clockwork_exec.h"
+#include "../../include/clockwork_exec_introspect.h"
 #include "common.h"
 
 namespace cw {

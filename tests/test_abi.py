@@ -14,9 +14,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _header_symbols():
-    text = open(os.path.join(ROOT, "include", "clockwork_exec.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return set(re.findall(r"\b(cw_[a-z_0-9]+)\s*\(", text))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for h in sorted(os.listdir(inc)):
+        if not h.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(cw_[a-z_0-9]+)\s*\(", text))
+    return names
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -175,7 +181,9 @@ def test_plan_table_rows_take_precedence(ctx):
 
 def test_fusion_of_bottleneck_tail(ctx):
     """At batch 16 the 3x3 + 1x1 tail of every stage-1 and stage-2 bottleneck of ResNet-50 is one
-    launch; with fusion off, with debug retention, or at batch 1 (too few pixels) it is two."""
+    launch; with fusion off or at batch 1 (too few pixels) it is two.  Debug retention keeps the
+    fused plan (so that the fused launches can be compared with the oracle layer by layer): only
+    the intermediate tensor of a fused launch has no place to be read back from."""
     m = ctx.model_define_resnet(50, 224, 224)
     ops = ctx.model_get_ops(m)
     fused = [l for l in ctx.plan(m, 16) if l["fused_op"] >= 0]
@@ -197,7 +205,9 @@ def test_fusion_of_bottleneck_tail(ctx):
     ctx.set_debug_keep(True)
     try:
         m3 = ctx.model_define_resnet(50, 224, 224)
-        assert not [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0]
+        kept = [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0]
+        assert [(l["fused_op"], l["op_index"], l["proj_op"]) for l in kept] == [
+            (l["fused_op"], l["op_index"], l["proj_op"]) for l in fused]
     finally:
         ctx.set_debug_keep(False)
 

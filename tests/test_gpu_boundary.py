@@ -184,6 +184,12 @@ def test_profile_measure(setup):
     slot = ctx.input(mid, 4, x, w.stream)
     per_launch = ctx.exec_timed_launches(mid, 4, slot, w.stream)
     assert len(per_launch) == ctx.plan_num_launches(mid, 4) and (per_launch > 0).all()
+    # a profile over the caller's own input: the slot stays the caller's and keeps its input
+    over_slot = ctx.profile_measure(mid, 4, 64, slot=slot)
+    assert over_slot["n"] == 64 and 0.5 * prof["p50_us"] < over_slot["p50_us"] < 2 * prof["p50_us"]
+    assert _status(ctx.profile_measure, mid, 2, 8, slot=slot) == cw.CW_ERR_BAD_BATCH
+    assert _status(ctx.profile_measure, mid, 4, 8, slot=40) == cw.CW_ERR_NO_INPUT
+    ctx.exec(mid, 4, slot, w.stream)
     ctx.release(slot)
     ctx.unload_weights(mid)
 
@@ -215,3 +221,65 @@ def test_graph_replay_equals_plain_launches(setup):
     assert np.array_equal(w.infer(m2, x)[1], plain)
     ctx.unload_weights(mid)
     ctx.unload_weights(m2)
+
+
+def test_unload_then_load_waits_for_the_exec_in_flight(setup):
+    """UNLOAD hands the pages back at once; a LOAD of another model on another stream takes them
+    while EXECs of the unloaded model are still queued.  Those EXECs must read intact weights: the
+    LOAD's pack kernels wait for the last EXEC that reads the pages."""
+    from gpu_common import TOL, rel_err_per_sample
+    w, case = setup
+    ctx = w.ctx
+    a = ctx.model_define_resnet(18, 64, 64)
+    b = ctx.model_define_resnet(18, 64, 64)
+    other = Case(T.resnet(18), 64, seed=9, dist="uniform")
+    w.load(a, case.blob)
+    x = case.images(0, 16)
+    ref = case.oracle(x)["logits"]
+    hx = torch.from_numpy(x.copy()).pin_memory()
+    blob_b = torch.from_numpy(other.blob.copy()).pin_memory()
+    s2 = torch.cuda.Stream()
+    slot = ctx.input(a, 16, hx, w.stream)
+    for _ in range(40):                       # a few milliseconds of EXECs queued on stream 1
+        ctx.exec(a, 16, slot, w.stream)
+    pages_before = ctx.weight_pages_free()
+    ctx.unload_weights(a)
+    assert ctx.weight_pages_free() == pages_before + ctx.model_weight_pages(a)
+    ctx.load_weights(b, blob_b, s2)           # lowest free pages first: the ones A just gave back
+    probs = torch.empty((16, 1000), dtype=torch.float32).pin_memory()
+    logits = torch.empty((16, 1000), dtype=torch.float32).pin_memory()
+    ctx.output(slot, probs, logits, w.stream)
+    w.stream.synchronize()
+    s2.synchronize()
+    assert rel_err_per_sample(logits.numpy(), ref).max() <= TOL
+    # and B is what was loaded: its own logits against the oracle
+    xb = other.images(0, 2)
+    got = w.infer(b, xb)[1]
+    assert rel_err_per_sample(got, other.oracle(xb)["logits"]).max() <= TOL
+    ctx.unload_weights(b)
+
+
+def test_graph_recorded_for_other_pages_is_not_replayed(setup):
+    """LOAD with graphs on (pages P), graphs off, UNLOAD, LOAD into other pages (no recording),
+    graphs on again: EXEC must not replay the graph that holds the addresses of P."""
+    from gpu_common import TOL, rel_err_per_sample
+    w, case = setup
+    ctx = w.ctx
+    a = ctx.model_define_resnet(18, 64, 64)
+    filler = ctx.model_define_resnet(18, 64, 64)
+    x = case.images(0, 2)
+    ref = case.oracle(x)["logits"]
+    w.load(a, case.blob)                      # graphs recorded for the lowest pages
+    first = w.infer(a, x)[1]
+    ctx.unload_weights(a)
+    try:
+        ctx.set_use_graphs(0)
+        w.load(filler, Case(T.resnet(18), 64, seed=4, dist="uniform").blob)   # takes A's old pages
+        w.load(a, case.blob)                  # lands in other pages; nothing is recorded
+    finally:
+        ctx.set_use_graphs(1)
+    got = w.infer(a, x)[1]
+    assert rel_err_per_sample(got, ref).max() <= TOL
+    assert np.array_equal(got, first)
+    ctx.unload_weights(a)
+    ctx.unload_weights(filler)

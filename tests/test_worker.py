@@ -114,10 +114,12 @@ def test_destroy_with_pending_actions_returns():
 
 @pytest.mark.gpu
 def test_load_and_infer_actions_on_the_gpu():
-    """LOAD, then INFERs with windows, through the executors: results as through the direct calls,
-    EXEC begins inside its window, a late INFER is skipped and its slot comes back."""
+    """LOAD, then INFERs with windows, through the executors: logits within tolerance of the CPU
+    oracle (and bit for bit those of the direct calls, which run the same plan), EXEC begins inside
+    its window, a late INFER is skipped and its slot comes back."""
     import torch
-    from gpu_common import Case
+    from gpu_common import TOL, Case, rel_err_per_sample
+    from oracle import network as N
     from oracle import topology as T
     from paper_2006_02464_amd.runner import Worker
     wk = Worker(workspace_bytes=64 << 20, io_bytes=32 << 20, weight_pool_bytes=64 << 20, load_staging_bytes=32 << 20)
@@ -127,6 +129,7 @@ def test_load_and_infer_actions_on_the_gpu():
     x = case.images(0, 4)
     wk.load(mid, case.blob)
     direct = wk.infer(mid, x)                       # (probs, logits, ns) through the plain calls
+    ref = case.oracle(x)                            # the CPU oracle on the same seeded tensors
     ctx.unload_weights(mid)
     ex = Executors(ctx)
     try:
@@ -155,6 +158,9 @@ def test_load_and_infer_actions_on_the_gpu():
             assert r["status"] == cw.CW_OK
             assert now + (10 + 2 * i) * MS <= r["begin_ns"] <= now + (10 + 2 * i + 50) * MS
             assert 20_000 < r["device_ns"] < 5 * MS and r["end_ns"] - r["begin_ns"] >= r["device_ns"]
+            assert rel_err_per_sample(outs[i][1].numpy(), ref["logits"]).max() <= TOL
+            assert np.array_equal(N.argmax(outs[i][1].numpy()), N.argmax(ref["logits"]))
+            assert np.abs(outs[i][0].numpy() - N.softmax(outs[i][1].numpy())).max() <= 1e-6
             assert np.array_equal(outs[i][1].numpy(), direct[1])      # same plan, same kernels: bit for bit
             assert np.array_equal(outs[i][0].numpy(), direct[0])
         p = ex.profile(CW_ACTION_INFER, mid, 4)
