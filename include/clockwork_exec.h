@@ -190,6 +190,7 @@ int32_t cw_exec_duration_ns(cw_ctx *ctx, int32_t slot, uint64_t *on_device_ns);
 typedef struct {
     uint32_t n;
     float p50_us, p99_us, p999_us, min_us, max_us, mean_us;
+    float p9999_us;   /* nearest rank like the others: the maximum for n < 10000 */
 } cw_profile;
 /* Runs `repeats` EXECs of (model, batch) back to back on an internal stream, each timed on
  * the device, and stores and returns nearest-rank percentiles.  The EXECs read the input held

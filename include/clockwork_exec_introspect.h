@@ -58,13 +58,15 @@ int32_t cw_set_debug_keep(cw_ctx *ctx, int32_t keep);
  * issue every kernel as its own launch instead; on != 0 restores the default.  Takes effect
  * for the next EXEC; graphs are recorded by LOADs issued while the setting is on. */
 int32_t cw_set_use_graphs(cw_ctx *ctx, int32_t on);
-/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..24 =
+/* Test hook: models defined afterwards use conv tile variant `conv_tile` (0..28 =
  * 128x128, 128x64, 64x64, 64x32, 32x64, 32x32, 128x64 on 2 waves, 64x128 on 2 waves,
  * 256x64, 128x128 on 8 waves, then 128x64, 64x64, 64x32, 32x64, 32x32 with K slices of 128
  * instead of 64 (used where cin % 128 == 0, else their 64 form), then tiles whose waves come in
  * 2, 4 or 8 groups that share every K slice (128 wide: 128x64 in 2, 64x64 in 2 and 4, 64x32,
  * 32x64, 32x32 in 4, then 32x32 in 8; 64 wide: 128x64 in 2, 64x64 in 2, 32x32 in 4; the first
- * convolution takes a grouped tile's one-group form);
+ * convolution takes a grouped tile's one-group form); then the tiles for large GEMMs: 256x128,
+ * 128x256 and 256x256 on 8 waves, 256x128 on 4 waves (a convolution with cin % 64 != 0 takes the
+ * largest basic shape below them);
  * pixels x channels per workgroup; -1 = the plan compiler's own choice)
  * and split-K factor `split_k` (0 = own choice) for every convolution, so parity
  * tests can reach every kernel instantiation.  Still fixed at plan time. */
@@ -90,7 +92,7 @@ int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs
  * `n_rows` rows that take precedence over it for models defined afterwards (n_rows == 0
  * removes them).  rows [host]: n_rows x 7 int32 = {M = batch*Ho*Wo, N = cout, K = kh*kw*cin,
- * kh, stride, conv_tile (0..24 as above), split_k >= 1}; copied.  Shapes in neither table get
+ * kh, stride, conv_tile (0..28 as above), split_k >= 1}; copied.  Shapes in neither table get
  * a heuristic choice.  Plans stay a pure function of (model, batch, tables). */
 int32_t cw_set_plan_table(cw_ctx *ctx, const int32_t *rows, int32_t n_rows);
 

@@ -21,7 +21,8 @@ CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32
               "128x64w2": 6, "64x128w2": 7, "256x64": 8, "128x128w8": 9,
               "128x64k128": 10, "64x64k128": 11, "64x32k128": 12, "32x64k128": 13, "32x32k128": 14,
               "128x64k128g2": 15, "64x64k128g2": 16, "64x64k128g4": 17, "64x32k128g4": 18, "32x64k128g4": 19,
-              "32x32k128g4": 20, "32x32k128g8": 21, "128x64g2": 22, "64x64g2": 23, "32x32g4": 24}
+              "32x32k128g4": 20, "32x32k128g8": 21, "128x64g2": 22, "64x64g2": 23, "32x32g4": 24,
+              "256x128w8": 25, "128x256w8": 26, "256x256w8": 27, "256x128": 28}
 
 
 class cw_op(Structure):
@@ -36,7 +37,7 @@ class cw_config(Structure):
 
 class cw_profile(Structure):
     _fields_ = [("n", c_uint32), ("p50_us", c_float), ("p99_us", c_float), ("p999_us", c_float),
-                ("min_us", c_float), ("max_us", c_float), ("mean_us", c_float)]
+                ("min_us", c_float), ("max_us", c_float), ("mean_us", c_float), ("p9999_us", c_float)]
 
 
 class cw_launch_info(Structure):

@@ -244,6 +244,7 @@ void percentile_profile(std::vector<float> v, cw_profile *out) {
     out->p50_us = rank(0.50);
     out->p99_us = rank(0.99);
     out->p999_us = rank(0.999);
+    out->p9999_us = rank(0.9999);
     out->min_us = v.front();
     out->max_us = v.back();
     double s = 0;

@@ -110,12 +110,14 @@ struct SoftmaxArgs {
 // Tile shapes the conv kernel is instantiated for (fixed at plan time per layer).
 // (pixels x channels per workgroup; "wN" = N waves when not 4, each wave then owning 64x64;
 // "k128" = K slices of 128 instead of 64, for Cin % 128 == 0; "gN" = N groups of waves that split
-// every K slice between them and add up at the end)
+// every K slice between them and add up at the end; the last four are for large GEMMs: 8 waves of
+// 64x64 or 64x128 each, and 256x128 on 4 waves of 128x64)
 enum ConvTile : int32_t {
     T128x128 = 0, T128x64, T64x64, T64x32, T32x64, T32x32, T128x64w2, T64x128w2, T256x64, T128x128w8,
     T128x64k128, T64x64k128, T64x32k128, T32x64k128, T32x32k128,
     T128x64k128g2, T64x64k128g2, T64x64k128g4, T64x32k128g4, T32x64k128g4, T32x32k128g4,
-    T32x32k128g8, T128x64g2, T64x64g2, T32x32g4, N_CONV_TILES
+    T32x32k128g8, T128x64g2, T64x64g2, T32x32g4,
+    T256x128w8, T128x256w8, T256x256w8, T256x128, N_CONV_TILES
 };
 struct TileDim {
     int bm, bn, threads, bk, kg;
@@ -125,6 +127,11 @@ TileDim conv_tile_dim(ConvTile t);
 ConvTile conv_tile_k64(ConvTile t);
 // The same tile with one group of waves (split-K needs that).
 ConvTile conv_tile_one_group(ConvTile t);
+// The largest tile of the register-staged kernel that is no larger than t (that kernel has the ten
+// basic shapes only; it serves Cin % 64 != 0 and first convolutions outside the stem form).
+ConvTile conv_tile_staged(ConvTile t);
+// Whether a convolution runs on the direct-to-LDS kernel (else on the register-staged one).
+bool conv_uses_dlds(const ConvArgs &a, bool stem);
 
 // Launchers (kernels_*.hip).  All only enqueue; they return the launch's error state.
 hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hipStream_t s);

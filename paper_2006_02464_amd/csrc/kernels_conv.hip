@@ -308,6 +308,10 @@ TileDim conv_tile_dim(ConvTile t) {
         case T128x64g2: return {128, 64, 512, 64, 2};
         case T64x64g2: return {64, 64, 512, 64, 2};
         case T32x32g4: return {32, 32, 256, 64, 4};
+        case T256x128w8: return {256, 128, 512, 64, 1};
+        case T128x256w8: return {128, 256, 512, 64, 1};
+        case T256x256w8: return {256, 256, 512, 64, 1};
+        case T256x128: return {256, 128, 256, 64, 1};
         default: return {32, 32, 64, 64, 1};
     }
 }
@@ -332,6 +336,16 @@ ConvTile conv_tile_k64(ConvTile t) {
 // The first convolution takes the direct-to-LDS kernel's stem mode when its packed filter has 8
 // rows of 8 taps x 4 channels and its stride is even (16-byte aligned 8-tap windows).
 static bool stem_is_dlds(const ConvArgs &a) { return a.khp == 8 && a.kwp == 8 && a.Cin == 4 && a.stride % 2 == 0 && a.pad == 0; }
+
+ConvTile conv_tile_staged(ConvTile t) {
+    switch (t) {
+        case T256x128w8: case T128x256w8: case T256x256w8: return T128x128w8;
+        case T256x128: return T128x128;
+        default: return conv_tile_one_group(conv_tile_k64(t));
+    }
+}
+
+bool conv_uses_dlds(const ConvArgs &a, bool stem) { return stem ? stem_is_dlds(a) : a.Cin % 64 == 0; }
 
 ConvTile conv_tile_one_group(ConvTile t) {
     switch (t) {
@@ -368,7 +382,7 @@ template <typename T, int BK, int MODE, bool SPLITK>
 static hipError_t launch_conv_t(ConvTile tile, const ConvArgs &a, hipStream_t s) {
     dim3 grid;
     int block;
-    tile = conv_tile_k64(tile);
+    tile = conv_tile_staged(tile);
     conv_grid(tile, a, &grid, &block);
     // K slices in flight in registers: 2 for the tiles with 64x64 per wave (register budget), else 3
     switch (tile) {

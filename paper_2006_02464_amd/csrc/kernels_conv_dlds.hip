@@ -598,7 +598,8 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_pair_ke
 // LDS stages per tile: 4 where that still lets two workgroups share a CU's 160 KiB, else 3.
 template <int BM, int BN, int BK>
 struct RingDepth {
-    static constexpr int value = (BM + BN) * BK * 2 * 4 <= 80 * 1024 ? 4 : 3;
+    static constexpr int stage = (BM + BN) * BK * 2;
+    static constexpr int value = stage * 4 <= 80 * 1024 ? 4 : (stage * 3 <= 160 * 1024 ? 3 : 2);
 };
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK, int KG = 1>
@@ -684,6 +685,10 @@ static hipError_t launch_tile(ConvTile tile, int bk, const ConvArgs &a, hipStrea
         case T32x32g4:
             if constexpr (MODE != MODE_STEM) return launch_one<T, 32, 32, 1, 1, 64, MODE, SPLITK, 4>(grid, block, a, s);
             return hipErrorInvalidValue;
+        case T256x128w8: return launch_one<T, 256, 128, 4, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T128x256w8: return launch_one<T, 128, 256, 2, 4, 64, MODE, SPLITK>(grid, block, a, s);
+        case T256x256w8: return launch_one<T, 256, 256, 4, 2, 64, MODE, SPLITK>(grid, block, a, s);
+        case T256x128: return launch_one<T, 256, 128, 2, 2, 64, MODE, SPLITK>(grid, block, a, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -311,28 +311,34 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const float *z_in, fl
 
 // ---- LOAD: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp], zero padded ---------
 // 16-bit elements are moved as raw bits, so one kernel serves fp16 and bf16.  With `permute`,
+// Workgroups of a LOAD-side launch: at most this many, each striding over its tensor.
+constexpr unsigned kLoadGridCap = 48;
+
 // row i of every group of 32 output channels receives channel sigma(i) of that group,
 //     i = 8g + 4h + k  ->  sigma(i) = 16*(g/2) + 8h + 4*(g%2) + k,
 // the order in which the conv kernel's MFMA accumulators come out as runs of 8 channels.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
                                                            int cout, int cin, int kh, int kw, int khp, int kwp, int cinp,
                                                            int permute) {
+    // A narrow grid that strides over the tensor: LOAD runs beside EXEC (paper section 5.2), and a
+    // launch as wide as the tensor would put its workgroups on every CU the EXEC kernels are using.
     const size_t total = (size_t)cout * khp * kwp * cinp;
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int c = (int)(i % cinp);
-    size_t t = i / cinp;
-    const int s = (int)(t % kwp);
-    t /= kwp;
-    const int r = (int)(t % khp);
-    int k = (int)(t / khp);
-    if (permute) {
-        const int row = k & 31, g = row >> 3, h = (row >> 2) & 1, kk = row & 3;
-        k = (k & ~31) + (g >> 1) * 16 + h * 8 + (g & 1) * 4 + kk;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % cinp);
+        size_t t = i / cinp;
+        const int s = (int)(t % kwp);
+        t /= kwp;
+        const int r = (int)(t % khp);
+        int k = (int)(t / khp);
+        if (permute) {
+            const int row = k & 31, g = row >> 3, h = (row >> 2) & 1, kk = row & 3;
+            k = (k & ~31) + (g >> 1) * 16 + h * 8 + (g & 1) * 4 + kk;
+        }
+        uint16_t v = 0;
+        if (c < cin && s < kw && r < kh) v = src[(((size_t)k * cin + c) * kh + r) * kw + s];
+        dst[i] = v;
     }
-    uint16_t v = 0;
-    if (c < cin && s < kw && r < kh) v = src[(((size_t)k * cin + c) * kh + r) * kw + s];
-    dst[i] = v;
 }
 
 __global__ __launch_bounds__(256) void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, size_t n) {
@@ -421,7 +427,8 @@ hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, in
                                bool permute, hipStream_t s) {
     if (permute && cout % 32 != 0) return hipErrorInvalidValue;
     const size_t total = (size_t)cout * khp * kwp * cinp;
-    pack_weights_kernel<<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const uint16_t *>(src),
+    const unsigned want = blocks_for(total, 256);
+    pack_weights_kernel<<<dim3(want < kLoadGridCap ? want : kLoadGridCap), 256, 0, s>>>(static_cast<const uint16_t *>(src),
                                                                     static_cast<uint16_t *>(dst), cout, cin, kh, kw,
                                                                     khp, kwp, cinp, permute ? 1 : 0);
     return hipGetLastError();

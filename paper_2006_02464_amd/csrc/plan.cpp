@@ -503,6 +503,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 pick_conv_tile(a.M, a.Cout, (int64_t)o.kh * o.kw * o.cin, o.kh, o.stride, a.K / conv_bk(a, l.stem, T64x64), ov,
                                &l.tile, &a.split_k);
                 if (l.stem) l.tile = conv_tile_one_group(l.tile);   // the first convolution's mode has no wave groups
+                if (!conv_uses_dlds(a, l.stem)) l.tile = conv_tile_staged(l.tile);   // the register-staged kernel's shapes
                 if (conv_bk(a, l.stem, l.tile) != conv_tile_dim(l.tile).bk) l.tile = conv_tile_k64(l.tile);  // Cin % 128 != 0
                 const int ktiles = a.K / conv_bk(a, l.stem, l.tile);
                 a.split_k = std::max(1, std::min(a.split_k, ktiles));

@@ -5,8 +5,8 @@
   python -m paper_2006_02464_amd.measure --config 5   64 resident ResNet-50s, Poisson arrivals, mixed batch sizes
   python -m paper_2006_02464_amd.measure --config 6   INFER actions with earliest/latest through the worker's executors
 
-Each prints one JSON object.  All inputs are synthetic (seeded, workload/gen.py); EXEC time does not
-depend on the values.  Durations are on-device (the event pair around every EXEC); the host thread
+Each prints one JSON object.  All inputs are synthetic (seeded, workload/gen.py); EXEC time depends
+on the values only through power and clocks (a few percent), so every profile is taken over seeded images.  Durations are on-device (the event pair around every EXEC); the host thread
 issues INPUT / EXEC / OUTPUT as the worker of the paper does: copies on one stream, EXEC on another,
 one EXEC at a time.
 """
@@ -121,7 +121,7 @@ def config4(args, log):
         ctx.exec(mid, B, slot, ex)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    prof = ctx.profile_measure(mid, B, 1000)
+    prof = ctx.profile_measure(mid, B, 1000, slot=slot)
     plan = ctx.plan(mid, B)
     wk.close()
     return {"config": 4, "workload": "ResNet-152 224x224 bf16 storage (fp16 overflows with these weights), batch 16",
@@ -135,20 +135,29 @@ def config5(args, log):
     import torch
     from .runner import Worker, pinned_like
     from workload import gen
-    n_models, batches, distinct = 64, (1, 2, 4, 8, 16), 8
+    n_models, batches = 64, (1, 2, 4, 8, 16)
     wk = Worker(workspace_bytes=512 << 20, io_bytes=1 << 30, weight_pool_bytes=4 << 30, load_staging_bytes=256 << 20)
     ctx, ex = wk.ctx, wk.stream
     cp = torch.cuda.Stream()
     mids = [ctx.model_define_resnet(50, 224, 224, "fp16") for _ in range(n_models)]
-    blobs = [pinned_like(resnet_blob(ctx, mids[0], s, "fp16")) for s in range(distinct)]
+    # 64 independently seeded weight sets (seeds 0..63), drawn on a few host threads
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        blobs = list(pool.map(lambda s: resnet_blob(ctx, mids[0], s, "fp16"), range(n_models)))
     for k, m in enumerate(mids):
-        ctx.load_weights(m, blobs[k % distinct], ex)
-    ex.synchronize()
+        staged = pinned_like(blobs[k])
+        ctx.load_weights(m, staged, ex)
+        ex.synchronize()
+        blobs[k] = None
     log("64 models resident, %.2f GB of the weight pool in use" % (((4 << 30) - ctx.weight_pool_free()) / 1e9))
     xs = {b: pinned_like(gen.images(0, 0, b, 3, 224, 224, "normal", "fp16")) for b in batches}
     probs = torch.empty((16, 1000), dtype=torch.float32, pin_memory=True)
     # capacity of the mix from the per-batch profile of one model
-    p50 = {b: ctx.profile_measure(mids[0], b, 200)["p50_us"] for b in batches}
+    p50 = {}
+    for b in batches:
+        s_b = ctx.input(mids[0], b, xs[b], ex)
+        p50[b] = ctx.profile_measure(mids[0], b, 200, slot=s_b)["p50_us"]
+        ctx.release(s_b)
     mean_exec_us = float(np.mean(list(p50.values())))
     lam = args.load / (mean_exec_us * 1e-6)                     # requests per second
     # seeded arrivals and request mix (counter-based generator of the workload module)
@@ -185,10 +194,10 @@ def config5(args, log):
     wall = time.perf_counter() - t0
     wk.close()
     images = int(bsel.sum())
-    return {"config": 5, "workload": "%d ResNet-50 fp16 weight sets resident (%d distinct seeds, each model its own "
-                                     "copy in the pool), %d requests, Poisson arrivals at %.0f req/s = %.2f x capacity of "
+    return {"config": 5, "workload": "%d ResNet-50 fp16 weight sets resident (independently seeded, seeds 0..%d), "
+                                     "%d requests, Poisson arrivals at %.0f req/s = %.2f x capacity of "
                                      "the mix, model ~U{0..63}, batch ~U{1,2,4,8,16}, seed %d"
-                                     % (n_models, distinct, n, lam, args.load, args.seed),
+                                     % (n_models, n_models - 1, n, lam, args.load, args.seed),
             "inferences_per_s": round(images / wall, 1), "requests_per_s": round(n / wall, 1), "wall_s": round(wall, 3),
             "max_host_lateness_ms": round(late * 1e3, 3),
             "single_model_p50_us": {str(b): round(p50[b], 2) for b in batches},
@@ -211,10 +220,12 @@ def config6(args, log):
     blob = pinned_like(resnet_blob(ctx, mid, 0, "fp16"))
     ctx.load_weights(mid, blob, wk.stream)
     wk.stream.synchronize()
-    p50 = ctx.profile_measure(mid, B, 300)["p50_us"]
+    x = pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "fp16"))
+    s_p = ctx.input(mid, B, x, wk.stream)
+    p50 = ctx.profile_measure(mid, B, 300, slot=s_p)["p50_us"]
+    ctx.release(s_p)
     ctx.unload_weights(mid)
     ex = Executors(ctx)
-    x = pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "fp16"))
     probs = [torch.empty((B, 1000), dtype=torch.float32, pin_memory=True) for _ in range(32)]
     now = ex.now_ns()
     ex.submit(-1, CW_ACTION_LOAD, mid, now, now + 10**9, host_in=blob)

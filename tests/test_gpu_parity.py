@@ -161,7 +161,8 @@ def test_resnet18_top1_agreement_2048_samples(worker):
                                   "128x64w2", "64x128w2", "256x64", "128x128w8",
                                   "128x64k128", "64x64k128", "64x32k128", "32x64k128", "32x32k128",
                                   "128x64k128g2", "64x64k128g2", "64x64k128g4", "64x32k128g4", "32x64k128g4",
-                                  "32x32k128g4", "32x32k128g8", "128x64g2", "64x64g2", "32x32g4"])
+                                  "32x32k128g4", "32x32k128g8", "128x64g2", "64x64g2", "32x32g4",
+                                  "256x128w8", "128x256w8", "256x256w8", "256x128"])
 @pytest.mark.parametrize("split_k", [1, 3])
 def test_every_conv_tile_and_split_k(worker, tile, split_k):
     """Forces one tile shape and split-K factor on every convolution of ResNet-18 at 64x64

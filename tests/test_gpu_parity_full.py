@@ -116,10 +116,12 @@ def check_every_launch(worker, case, mid, batch, x):
             scale = np.abs(t).max()
             diff = np.abs(got - t)
             # an element of the intermediate on a rounding boundary may land one storage ulp away
-            # and moves the sums over it by that ulp times a weight: an absolute allowance
-            allow_abs = 3e-4 * scale
+            # and moves the sums over it by that ulp times a weight: an absolute allowance of 0.3
+            # storage ulps of the layer's largest value (3e-4 of it in fp16, 2.3e-3 in bf16)
+            allow_abs = 0.3 * ulp * scale
             worst_fused = max(worst_fused, float(diff.max() / scale))
-            assert (diff <= ulp * np.abs(t) + allow_abs).all(), "fused op %d+%d: max diff %.3e of scale %.3e" % (f, i, diff.max(), scale)
+            bad = diff > ulp * np.abs(t) + allow_abs
+            assert not bad.any(), "fused op %d+%d: %d elements beyond one ulp, max diff %.3e of scale %.3e" % (f, i, int(bad.sum()), diff.max(), scale)
             assert (diff > allow_abs).mean() <= 0.05, "fused op %d+%d: too many elements off by an ulp" % (f, i)
         elif o.op == T.CONV:
             t = conv(o, widx[i], tensor(o.input_from))
@@ -131,7 +133,8 @@ def check_every_launch(worker, case, mid, batch, x):
             scale = np.abs(t).max()
             diff = np.abs(got - t)
             worst_plain = max(worst_plain, float(diff.max() / scale))
-            assert (diff <= ulp * np.abs(t) + 1e-5 * scale).all(), "op %d (%s): teacher-forced max diff %.3e" % (i, o, diff.max())
+            bad = diff > ulp * np.abs(t) + 1e-5 * scale
+            assert not bad.any(), "op %d (%s): %d elements beyond one ulp, teacher-forced max diff %.3e" % (i, o, int(bad.sum()), diff.max())
             assert (diff > 1e-5 * scale).mean() <= 0.02, "op %d: too many elements off by an ulp" % i
         elif o.op == T.MAXPOOL:
             assert np.array_equal(got, N.maxpool2d(tensor(o.input_from), o.kh, o.stride, o.pad)), "op %d: max pool not exact" % i
