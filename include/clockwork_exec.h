@@ -171,6 +171,25 @@ int32_t cw_input(cw_ctx *ctx, int32_t model_id, int32_t batch, const float *host
  * issued on a different stream while one is in flight returns CW_ERR_BUSY; on
  * the same stream EXECs simply run back to back.  EXEC may be repeated on a slot. */
 int32_t cw_exec(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot, void *stream);
+/* EXEC for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same plan, same kernels and same results as cw_exec, but
+ *   - the input, the logits and the probabilities are the caller's own device buffers:
+ *     dev_input_nchw [device] fp32 [batch][in_c][in_h][in_w], dev_logits and dev_probs [device]
+ *     fp32 [batch][classes]; the caller orders their producers and consumers on `stream`;
+ *   - the intermediates (activations, split-K partial sums and arrival counters) live in an array
+ *     built into the library, cw_exec_static_capacity() bytes (64 MiB) per GPU, instead of the
+ *     context's workspace: a plan whose intermediates need more returns CW_ERR_NO_MEMORY (see
+ *     cw_model_workspace_bytes; ResNet-50 and ResNet-152 at 224x224 fit up to batch 16);
+ *   - the call allocates nothing, creates no event or graph and records nothing but kernel
+ *     launches (plus one wait for the model's LOAD if that has not finished yet).
+ * Every call on a GPU uses that GPU's one array, whatever the context: calls that overlap in time
+ * on one GPU (two streams, two contexts) race; on one stream they simply run in order.  The EXEC
+ * is not timed and does not take part in cw_exec's one-at-a-time check.
+ * CW_ERR_NOT_LOADED / CW_ERR_BAD_BATCH / CW_ERR_INVALID as for cw_exec. */
+int32_t cw_exec_static(cw_ctx *ctx, int32_t model_id, int32_t batch, const float *dev_input_nchw,
+                       float *dev_logits, float *dev_probs, void *stream);
+/* Bytes of intermediates a plan may need to run through cw_exec_static. */
+size_t cw_exec_static_capacity(void);
 /* OUTPUT: enqueues the copies of the slot's results to host_probs [host]
  * [batch][classes] and, if not NULL, host_logits [host] [batch][classes] on
  * `stream` (after the slot's EXEC), then releases the slot; its memory is reused

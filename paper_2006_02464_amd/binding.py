@@ -84,6 +84,8 @@ SIGNATURES = {
     "cw_model_weight_pages": (c_int32, [c_void_p, c_int32]),
     "cw_input": (c_int32, [c_void_p, c_int32, c_int32, c_void_p, POINTER(c_int32), c_void_p]),
     "cw_exec": (c_int32, [c_void_p, c_int32, c_int32, c_int32, c_void_p]),
+    "cw_exec_static": (c_int32, [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "cw_exec_static_capacity": (c_size_t, []),
     "cw_output": (c_int32, [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]),
     "cw_release": (c_int32, [c_void_p, c_int32]),
     "cw_exec_duration_ns": (c_int32, [c_void_p, c_int32, POINTER(c_uint64)]),
@@ -237,6 +239,15 @@ class Context:
 
     def exec(self, model_id, batch, slot, stream=None):
         self._check(lib().cw_exec(self._h, model_id, batch, slot, _stream(stream)))
+
+    def exec_static(self, model_id, batch, dev_input, dev_logits, dev_probs, stream=None):
+        """dev_*: device tensors (anything with data_ptr()) or raw device addresses."""
+        self._check(lib().cw_exec_static(self._h, model_id, batch, _ptr(dev_input), _ptr(dev_logits), _ptr(dev_probs),
+                                         _stream(stream)))
+
+    @staticmethod
+    def exec_static_capacity():
+        return lib().cw_exec_static_capacity()
 
     def output(self, slot, host_probs, host_logits=None, stream=None):
         self._check(lib().cw_output(self._h, slot, _ptr(host_probs), _ptr(host_logits), _stream(stream)))

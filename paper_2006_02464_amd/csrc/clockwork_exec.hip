@@ -7,6 +7,7 @@
 #include <cstring>
 #include <functional>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -51,8 +52,38 @@ struct ModelRt {
 
 }  // namespace
 
+// ---- the arena of cw_exec_static: device memory that exists without an allocation --------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's
+// name is only a handle for the runtime; its device address on a GPU is asked for once, with that
+// GPU current, and kept (every GPU has its own copy at its own address).
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.  Asked for once per
+// device (cw_create does it); later calls only read the table.
+hipError_t scratch_address(int device, char **out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<char *>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+}  // namespace
+
 struct cw_ctx {
     int device = -1;       // -1: planning-only context without a GPU
+    char *static_scratch = nullptr;  // this GPU's copy of `scratch`
     cw_config cfg{};
     char *workspace = nullptr, *io = nullptr, *pool = nullptr, *staging = nullptr;
     RangeAllocator io_alloc;
@@ -436,6 +467,11 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
         cleanup();
         return CW_ERR_NO_MEMORY;
     }
+    if ((ce = scratch_address(cfg->device, &p->static_scratch)) != hipSuccess) {
+        g_create_err = std::string("hipGetSymbolAddress of the static arena: ") + hipGetErrorString(ce);
+        cleanup();
+        return CW_ERR_HIP;
+    }
     bool ok = hipStreamCreateWithFlags(&p->internal_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&p->staging_free, hipEventDisableTiming) == hipSuccess;
@@ -706,6 +742,47 @@ int32_t cw_exec(cw_ctx *c, int32_t model_id, int32_t batch, int32_t slot, void *
     m->last_exec_end = s->exec_end;
     return CW_OK;
 }
+
+int32_t cw_exec_static(cw_ctx *c, int32_t model_id, int32_t batch, const float *dev_input_nchw, float *dev_logits,
+                       float *dev_probs, void *stream) {
+    if (!c) return CW_ERR_INVALID;
+    if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
+    ModelRt *m = get_model(c, model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    Plan *p = get_plan(m, batch);
+    if (!p) return set_err(c, CW_ERR_BAD_BATCH, "no plan for this batch size");
+    if (!m->loaded) return set_err(c, CW_ERR_NOT_LOADED, "weights are not resident");
+    if (!dev_input_nchw || !dev_logits || !dev_probs) return set_err(c, CW_ERR_INVALID, "null device buffer");
+    if (p->workspace_bytes > kStaticScratchBytes) {
+        char buf[160];
+        snprintf(buf, sizeof buf, "plan needs %zu bytes of intermediates, the static arena holds %zu", p->workspace_bytes,
+                 kStaticScratchBytes);
+        return set_err(c, CW_ERR_NO_MEMORY, buf);
+    }
+    if (!c->static_scratch) return set_err(c, CW_ERR_HIP, "static arena has no address on this device");
+    DeviceGuard g(c->device);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The weights must have landed.  A LOAD that has completed needs no stream operation at all.
+    const hipError_t q = hipEventQuery(m->load_done);
+    if (q == hipErrorNotReady) CW_HIP(c, hipStreamWaitEvent(st, m->load_done, 0));
+    else if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
+    Bases b;
+    b.workspace = c->static_scratch;
+    b.input = const_cast<char *>(reinterpret_cast<const char *>(dev_input_nchw));
+    b.logits = reinterpret_cast<char *>(dev_logits);
+    b.probs = reinterpret_cast<char *>(dev_probs);
+    // The arena keeps what the last call left: the split-K arrival counters at its start must be
+    // zero (a fill kernel, not a memset, so that the call may be recorded into a graph).
+    hipError_t e = launch_fill_zero(c->static_scratch, kCounterBytes, st);
+    if (e != hipSuccess) return hip_fail(c, e, "clearing the arrival counters");
+    for (const Launch &l : p->launches) {
+        e = issue(c, m, b, l, st);
+        if (e != hipSuccess) return hip_fail(c, e, l.info.name);
+    }
+    return CW_OK;
+}
+
+size_t cw_exec_static_capacity(void) { return kStaticScratchBytes; }
 
 int32_t cw_set_use_graphs(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
