@@ -63,24 +63,36 @@ enum {
     CW_ERR_TIMEOUT = -12        /* cw_worker_next_result: no result within the time given */
 };
 
-enum { CW_OP_CONV = 0, CW_OP_MAXPOOL = 1, CW_OP_GAVGPOOL = 2, CW_OP_FC = 3, CW_OP_SOFTMAX = 4 };
+enum { CW_OP_CONV = 0, CW_OP_MAXPOOL = 1, CW_OP_GAVGPOOL = 2, CW_OP_FC = 3, CW_OP_SOFTMAX = 4, CW_OP_CONCAT = 5 };
+enum { CW_ACT_NONE = 0, CW_ACT_RELU = 1, CW_ACT_HSWISH = 2 };   /* values of cw_op.relu */
 enum { CW_DTYPE_FP16 = 0, CW_DTYPE_BF16 = 1 };
 
 /* One operator of a model.  Ops form a DAG over earlier ops' outputs.
- * CONV:     cross-correlation, kh x kw, `stride`, zero padding `pad`, + bias[cout],
- *           then (if residual_from >= 0) + output of that op, then ReLU if relu != 0.
+ * CONV:     cross-correlation, kh x kw, `stride`, zero padding, + bias[cout], then (if
+ *           residual_from >= 0) + output of that op, then the activation `relu` (CW_ACT_*: none,
+ *           ReLU, or hard swish x * min(max(x + 3, 0), 6) / 6).  A square filter is padded by
+ *           `pad` on every side; a rectangular one (kh != kw, e.g. 1x7 and 7x1) by `pad` rows and
+ *           `pad_w` columns.  groups <= 1: dense; groups == cin == cout: depthwise (one kh x kw
+ *           filter per channel, weights W[cout][1][kh][kw]).
  * MAXPOOL:  kh x kw window, `stride`, `pad`; padded taps are ignored.
  * GAVGPOOL: mean over all spatial positions.
  * FC:       cin -> cout, + bias; its fp32 output is the model's logits.
- * SOFTMAX:  over the cout values of each sample; its output is the probabilities. */
+ * SOFTMAX:  over the cout values of each sample; its output is the probabilities.
+ * CONCAT:   the channels of op input_from followed by those of op residual_from (same spatial
+ *           size; cin = channels of the first, cout = of both).  Where the producers allow it
+ *           they write straight into their channel range of the result and nothing is copied.
+ * The operators beyond the ResNet set serve the other model families of the paper's Table 1
+ * (DenseNet: concatenation; Inception v3: rectangular filters; MobileNet: depthwise, hard swish). */
 typedef struct {
     int32_t op;            /* CW_OP_* */
     int32_t cin, cout;     /* channels in / out (MAXPOOL, GAVGPOOL, SOFTMAX: cin == cout) */
     int32_t kh, kw;        /* filter or window size (0 where unused) */
     int32_t stride, pad;
-    int32_t relu;          /* CONV only */
-    int32_t residual_from; /* CONV only: -1 or index of an earlier op */
+    int32_t relu;          /* CONV only: CW_ACT_* */
+    int32_t residual_from; /* CONV: -1 or index of an earlier op to add; CONCAT: the second source */
     int32_t input_from;    /* -1 = the network input, else index of an earlier op */
+    int32_t pad_w;         /* CONV with kh != kw: padding in width (`pad` is then the padding in height) */
+    int32_t groups;        /* CONV: 0 or 1 = dense, cin = depthwise */
 } cw_op;
 
 typedef struct {

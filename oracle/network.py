@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 import numpy as np
 
 from . import build as _build
-from .topology import CONV, FC, GAVGPOOL, MAXPOOL, SOFTMAX
+from .topology import CONCAT, CONV, FC, GAVGPOOL, MAXPOOL, SOFTMAX, conv_geometry
 
 _LIBS = {}
 
@@ -23,7 +23,8 @@ def _lib(prec):
         _build.build()
         lib = ctypes.CDLL(_build.LIBS[prec][0])
         for name in ("orc_conv2d", "orc_relu", "orc_add", "orc_maxpool2d",
-                     "orc_global_avgpool", "orc_fc", "orc_softmax", "orc_argmax"):
+                     "orc_global_avgpool", "orc_fc", "orc_softmax", "orc_argmax",
+                     "orc_conv2d_grouped", "orc_hswish", "orc_concat_channels"):
             getattr(lib, name).restype = None
         _LIBS[prec] = lib
     return _LIBS[prec]
@@ -51,6 +52,38 @@ def conv2d(x, w, b, stride, pad, prec="f32"):
     wo = (wd + 2 * pad - kw) // stride + 1
     y = np.empty((n, k, ho, wo), dtype=_dt(prec))
     _lib(prec).orc_conv2d(_p(x), _p(w), _p(b), _p(y), n, c, h, wd, k, kh, kw, stride, pad)
+    return y
+
+
+def conv2d_grouped(x, w, b, stride, pad_h, pad_w, groups, prec="f32"):
+    """Grouped convolution, rectangular filter, separate paddings; w is [K][C/groups][kh][kw]."""
+    x, w = _arr(x, prec), _arr(w, prec)
+    b = _arr(b, prec) if b is not None else None
+    n, c, h, wd = x.shape
+    k, cg, kh, kw = w.shape
+    assert c % groups == 0 and k % groups == 0 and cg == c // groups
+    ho = (h + 2 * pad_h - kh) // stride + 1
+    wo = (wd + 2 * pad_w - kw) // stride + 1
+    y = np.empty((n, k, ho, wo), dtype=_dt(prec))
+    _lib(prec).orc_conv2d_grouped(_p(x), _p(w), _p(b), _p(y), n, c, h, wd, k, kh, kw, stride, pad_h, pad_w, groups)
+    return y
+
+
+def hswish(x, prec="f32"):
+    x = _arr(x, prec)
+    y = np.empty_like(x)
+    _lib(prec).orc_hswish(_p(x), _p(y), ctypes.c_size_t(x.size))
+    return y
+
+
+def concat_channels(a, b, prec="f32"):
+    a, b = _arr(a, prec), _arr(b, prec)
+    assert a.shape[0] == b.shape[0] and a.shape[2:] == b.shape[2:]
+    n, ca = a.shape[:2]
+    cb = b.shape[1]
+    hw = int(np.prod(a.shape[2:]))
+    y = np.empty((n, ca + cb) + a.shape[2:], dtype=_dt(prec))
+    _lib(prec).orc_concat_channels(_p(a), _p(b), _p(y), n, ca, cb, hw)
     return y
 
 
@@ -139,13 +172,21 @@ def _forward_one(ops, weights, biases, x, prec, keep, storage=None):
     for o in ops:
         src = x if o.input_from < 0 else outs[o.input_from]
         if o.op == CONV:
-            y = conv2d(src, weights[wi], biases[wi], o.stride, o.pad, prec)
+            pad_h, pad_w, groups = conv_geometry(o)
+            if groups == 1 and o.kh == o.kw:
+                y = conv2d(src, weights[wi], biases[wi], o.stride, o.pad, prec)
+            else:
+                y = conv2d_grouped(src, weights[wi], biases[wi], o.stride, pad_h, pad_w, groups, prec)
             wi += 1
             if o.residual_from >= 0:
                 y = add(y, outs[o.residual_from], prec)
-            if o.relu:
+            if o.relu == 1:
                 y = relu(y, prec)
+            elif o.relu == 2:
+                y = hswish(y, prec)
             y = _round_storage(y, storage)
+        elif o.op == CONCAT:
+            y = concat_channels(src, outs[o.residual_from], prec)
         elif o.op == MAXPOOL:
             y = maxpool2d(src, o.kh, o.stride, o.pad, prec)
         elif o.op == GAVGPOOL:

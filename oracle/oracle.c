@@ -151,3 +151,69 @@ void orc_argmax(const REAL *z, int32_t *idx, int N, int D)
         idx[n] = best;
     }
 }
+
+/* ---- operators of the other model families the paper serves (Table 1: DenseNet, Inception v3,
+ * a MobileNet-v3 pose model; Table 2 lists more).  The paper names the families only; these are
+ * their standard operators, written out as definitions like the ones above. ---- */
+
+/* Grouped cross-correlation with a rectangular filter and separate paddings.
+ * Input channels are split into G equal groups and so are the output channels; output channel k
+ * belongs to group g = k / (K/G) and sees only that group's C/G input channels:
+ *   y[n][k][p][q] = b[k] + sum_{c' < C/G} sum_{r < kh} sum_{s < kw}
+ *                   x[n][g*(C/G) + c'][p*st - ph + r][q*st - pw + s] * w[k][c'][r][s]
+ * with x = 0 outside the image; Ho = floor((H + 2*ph - kh)/st) + 1, Wo likewise with pw, kw.
+ * G = 1 is the dense convolution; G = C = K is a depthwise convolution (one filter per channel);
+ * kh != kw gives the 1x7 / 7x1 filters of Inception.  w is [K][C/G][kh][kw]; b may be NULL. */
+void orc_conv2d_grouped(const REAL *x, const REAL *w, const REAL *b, REAL *y,
+                        int N, int C, int H, int W, int K, int kh, int kw, int st, int ph, int pw, int G)
+{
+    int Ho = (H + 2 * ph - kh) / st + 1;
+    int Wo = (W + 2 * pw - kw) / st + 1;
+    int Cg = C / G, Kg = K / G;
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k) {
+            int g = k / Kg;
+            for (int p = 0; p < Ho; ++p)
+                for (int q = 0; q < Wo; ++q) {
+                    REAL acc = b ? b[k] : (REAL)0;
+                    for (int c = 0; c < Cg; ++c)
+                        for (int r = 0; r < kh; ++r)
+                            for (int s = 0; s < kw; ++s) {
+                                int ih = p * st - ph + r;
+                                int iw = q * st - pw + s;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= W)
+                                    continue;
+                                acc += x[(((size_t)n * C + g * Cg + c) * H + ih) * W + iw] *
+                                       w[(((size_t)k * Cg + c) * kh + r) * kw + s];
+                            }
+                    y[(((size_t)n * K + k) * Ho + p) * Wo + q] = acc;
+                }
+        }
+}
+
+/* hard swish: y = x * min(max(x + 3, 0), 6) / 6  (0 for x <= -3, x for x >= 3) */
+void orc_hswish(const REAL *x, REAL *y, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        REAL t = x[i] + (REAL)3;
+        if (t < (REAL)0)
+            t = (REAL)0;
+        if (t > (REAL)6)
+            t = (REAL)6;
+        y[i] = x[i] * t / (REAL)6;
+    }
+}
+
+/* channel concatenation: y[n][c] = a[n][c] for c < Ca, b[n][c - Ca] for Ca <= c < Ca + Cb;
+ * HW = spatial positions per channel */
+void orc_concat_channels(const REAL *a, const REAL *b, REAL *y, int N, int Ca, int Cb, int HW)
+{
+    for (int n = 0; n < N; ++n) {
+        for (int c = 0; c < Ca; ++c)
+            for (int i = 0; i < HW; ++i)
+                y[((size_t)n * (Ca + Cb) + c) * HW + i] = a[((size_t)n * Ca + c) * HW + i];
+        for (int c = 0; c < Cb; ++c)
+            for (int i = 0; i < HW; ++i)
+                y[((size_t)n * (Ca + Cb) + Ca + c) * HW + i] = b[((size_t)n * Cb + c) * HW + i];
+    }
+}

@@ -14,7 +14,7 @@ CW_OK = 0
 CW_ERR_INVALID, CW_ERR_HIP, CW_ERR_NO_MEMORY, CW_ERR_NOT_LOADED = -1, -2, -3, -4
 CW_ERR_ALREADY_LOADED, CW_ERR_NO_INPUT, CW_ERR_BAD_BATCH, CW_ERR_BUSY = -5, -6, -7, -8
 CW_ERR_UNSUPPORTED, CW_ERR_NO_SLOT, CW_ERR_TOO_LATE, CW_ERR_TIMEOUT = -9, -10, -11, -12
-CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX = 0, 1, 2, 3, 4
+CW_OP_CONV, CW_OP_MAXPOOL, CW_OP_GAVGPOOL, CW_OP_FC, CW_OP_SOFTMAX, CW_OP_CONCAT = 0, 1, 2, 3, 4, 5
 CW_DTYPE_FP16, CW_DTYPE_BF16 = 0, 1
 DTYPES = {"fp16": CW_DTYPE_FP16, "bf16": CW_DTYPE_BF16}
 CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32x32": 5,
@@ -27,7 +27,7 @@ CONV_TILES = {"128x128": 0, "128x64": 1, "64x64": 2, "64x32": 3, "32x64": 4, "32
 
 class cw_op(Structure):
     _fields_ = [(n, c_int32) for n in ("op", "cin", "cout", "kh", "kw", "stride", "pad",
-                                        "relu", "residual_from", "input_from")]
+                                        "relu", "residual_from", "input_from", "pad_w", "groups")]
 
 
 class cw_config(Structure):

@@ -136,8 +136,8 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         OpShape out{o.cout, 1, 1};
         switch (o.op) {
             case CW_OP_CONV: {
-                if (o.kh < 1 || o.kh != o.kw || o.stride < 1 || o.pad < 0)
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs square filter, stride>=1", i);
+                if (o.kh < 1 || o.kh != o.kw || o.stride < 1 || o.pad < 0 || o.groups > 1 || o.relu < 0 || o.relu > 1)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs square filter, stride>=1, one group, ReLU or no activation", i);
                 if (sh + 2 * o.pad < o.kh || sw + 2 * o.pad < o.kw)
                     return fail(err, CW_ERR_INVALID, "op %d: filter larger than padded input", i);
                 if (i == 0) {
