@@ -148,7 +148,7 @@ def mobilenet(num_classes=1000, hswish_from=7, residual=True):
     return _tail(ops, cin, num_classes)
 
 
-def dense_net(num_classes=1000, growth=32, layers=(4, 6), bottleneck=128, stem=64):
+def dense_net(num_classes=1000, growth=32, layers=(6, 12), bottleneck=128, stem=64):
     """Densely connected network in the DenseNet style: 7x7 stride-2 stem and 3x3 max pool, then
     dense blocks in which every layer {1x1 to `bottleneck` channels, 3x3 to `growth` channels}
     reads the concatenation of the block input and all earlier layers' outputs; between blocks a
@@ -171,7 +171,7 @@ def dense_net(num_classes=1000, growth=32, layers=(4, 6), bottleneck=128, stem=6
     return _tail(ops, cin, num_classes)
 
 
-def inception_net(num_classes=1000, width=128, blocks=2):
+def inception_net(num_classes=1000, width=256, blocks=2):
     """Network with the factorised 7x7 branches of Inception v3's 17x17 blocks: a 3x3 stride-2
     stem and a 3x3 stride-2 convolution, then blocks that concatenate a 1x1 branch with a
     {1x1, 1x7, 7x1} branch (both `width` channels wide) and mix the result with a 1x1."""

@@ -229,6 +229,21 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             a.p = reinterpret_cast<float *>(resolve(c, m, s, l.y));
             return launch_softmax(a, st);
         }
+        case K_DWCONV: {
+            DwArgs a = l.dw;
+            a.x = resolve(c, m, s, l.x);
+            a.w = resolve(c, m, s, l.w);
+            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            a.res = resolve(c, m, s, l.res);
+            a.y = resolve(c, m, s, l.y);
+            return launch_dwconv(dt, a, st);
+        }
+        case K_COPY_CHANNELS: {
+            CopyArgs a = l.copy;
+            a.src = resolve(c, m, s, l.x);
+            a.dst = resolve(c, m, s, l.y);
+            return launch_copy_channels(a, st);
+        }
     }
     return hipErrorInvalidValue;
 }
@@ -670,8 +685,11 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     auto at = [&](size_t off) { return c->pool + (size_t)m->pages[off / c->page_bytes] * c->page_bytes + off % c->page_bytes; };
     for (const WeightSlot &ws : m->m.wslots) {
         const bool is_conv = m->m.ops[ws.op_index].op == CW_OP_CONV;
-        e = launch_pack_weights(c->staging + ws.blob_w_off, at(ws.packed_w_off), ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
-                                ws.kwp, ws.cinp, is_conv, st);
+        if (ws.depthwise)
+            e = launch_pack_depthwise(c->staging + ws.blob_w_off, at(ws.packed_w_off), ws.cout, ws.kh, ws.kw, st);
+        else
+            e = launch_pack_weights(c->staging + ws.blob_w_off, at(ws.packed_w_off), ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
+                                    ws.kwp, ws.cinp, is_conv, st);
         if (e != hipSuccess) return bail(e, "pack_weights");
         e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
                             reinterpret_cast<float *>(at(ws.packed_b_off)), ws.cout, st);
@@ -992,7 +1010,7 @@ int32_t cw_debug_read_op(cw_ctx *c, int32_t model_id, int32_t batch, int32_t op_
     // The conversion needs count*4 bytes of scratch: the LOAD staging area is idle after the sync.
     if (count * 4 > c->cfg.load_staging_bytes) return set_err(c, CW_ERR_NO_MEMORY, "staging area too small for read-back");
     hipError_t e = launch_nhwc_to_nchw_f32(m->m.dtype, c->workspace + r.offset, reinterpret_cast<float *>(c->staging), batch,
-                                           sh.c, sh.h, sh.w, c->internal_stream);
+                                           sh.c, sh.h, sh.w, p->op_ld[op_index], c->internal_stream);
     if (e != hipSuccess) return hip_fail(c, e, "nhwc_to_nchw");
     CW_HIP(c, hipStreamSynchronize(c->internal_stream));
     CW_HIP(c, hipMemcpy(host_out, c->staging, count * 4, hipMemcpyDeviceToHost));

@@ -20,7 +20,12 @@ enum Kind : int32_t {
     K_GAVGPOOL = 4,
     K_FC = 5,
     K_SOFTMAX = 6,
+    K_DWCONV = 7,      // depthwise convolution (one filter per channel), fused epilogue
+    K_COPY_CHANNELS = 8,  // a tensor into a channel range of a wider one (CONCAT sources that cannot write there themselves)
 };
+
+// Activation codes (cw_op.relu, ConvArgs.relu / relu2).
+enum Act : int32_t { ACT_NONE = 0, ACT_RELU = 1, ACT_HSWISH = 2 };
 
 // Division by a run-time constant as multiply + shifts (Granlund-Montgomery round-up method).
 struct FastDiv {
@@ -56,9 +61,11 @@ struct alignas(64) ConvArgs {
     int32_t nb;         // output tiles of this convolution = workgroups along x (set by the launch code)
     // ---- line 1
     int32_t B, H, W, Ho, Wo;
-    int32_t kh, kw, stride, pad;
+    int32_t kh, kw, stride;
+    int32_t pad;        // padding in height | padding in width << 16 (conv_set_pad / conv_pad_h / conv_pad_w)
     FastDiv wo_div, ho_div;  // for m -> (image, row, column)
-    int32_t kwp;
+    int32_t ld;         // elements per pixel in memory: of x | of y << 16 (= Cin | Cout << 16 unless a tensor is
+                        // a channel range of a wider one: CONCAT without copies); res is always dense
     // ---- line 2
     int32_t khp;        // filter rows in the packed weights (first convolution: may be padded to 8)
     int32_t split_k, ktiles_per_split;
@@ -71,6 +78,7 @@ struct alignas(64) ConvArgs {
     const void *w2;      // packed [Cout2][Cout]
     const float *bias2;  // [Cout2]
     int32_t Cout2;
+    int32_t kwp;         // filter columns in the packed weights (first convolution: padded to 8)
     // Optional projection shortcut computed in the same launch instead of read as `res`:
     // res[m][:] = biasd + Wd * x2[m][:], x2 = [M][Cout] pixels aligned with the output (a 1x1
     // stride-1 projection of a tensor with Cout channels).  wd == nullptr: `res` is read.
@@ -79,6 +87,30 @@ struct alignas(64) ConvArgs {
     const float *biasd;  // [Cout2]
 };
 static_assert(offsetof(ConvArgs, B) == 64 && offsetof(ConvArgs, khp) == 128 && sizeof(ConvArgs) == 256, "argument lines");
+__host__ __device__ inline int conv_pad_h(const ConvArgs &a) { return a.pad & 0xffff; }
+__host__ __device__ inline int conv_pad_w(const ConvArgs &a) { return (int)((unsigned)a.pad >> 16); }
+__host__ __device__ inline int conv_ldx(const ConvArgs &a) { return a.ld & 0xffff; }
+__host__ __device__ inline int conv_ldy(const ConvArgs &a) { return (int)((unsigned)a.ld >> 16); }
+inline void conv_set_pad(ConvArgs &a, int pad_h, int pad_w) { a.pad = pad_h | (pad_w << 16); }
+inline void conv_set_ld(ConvArgs &a, int ldx, int ldy) { a.ld = ldx | (ldy << 16); }
+constexpr int kMaxChannels = 32768;  // channel counts and pitches travel in 16 bits
+
+// Depthwise convolution: y[m][c] = act(res[m][c] + bias[c] + sum_{r,s} x[pixel(m) + (r,s)][c] * w[r][s][c]).
+struct DwArgs {
+    const void *x;      // NHWC, ldx elements per pixel
+    const void *w;      // packed [kh][kw][C]
+    const float *bias;  // [C]
+    const void *res;    // dense NHWC like y, or nullptr
+    void *y;            // NHWC, ldy elements per pixel
+    int32_t B, H, W, C, Ho, Wo, kh, kw, stride, pad, act, ldx, ldy;
+};
+
+struct CopyArgs {
+    const void *src;    // [pixels][ld_src], the first C channels of every pixel are copied
+    void *dst;          // [pixels][ld_dst] (already offset to the destination channel)
+    int32_t pixels, C, ld_src, ld_dst;
+};
+
 
 struct CastArgs {
     const float *x;  // NCHW fp32 [B][C][H][W]
@@ -154,14 +186,18 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
+hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s);
+hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s);   // 2-byte elements, C % 8 == 0
+// LOAD-time re-layout of depthwise weights: canonical W[C][1][kh][kw] -> [kh][kw][C]
+hipError_t launch_pack_depthwise(const void *src, void *dst, int c, int kh, int kw, hipStream_t s);
 // LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout'][khp][kwp][cinp] (zero padded);
 // permute = rows in the conv kernel's MFMA accumulator order (conv weights), else plain (FC).
 hipError_t launch_pack_weights(const void *src, void *dst, int cout, int cin, int kh, int kw,
                                int khp, int kwp, int cinp, bool permute, hipStream_t s);
 hipError_t launch_copy_f32(const float *src, float *dst, size_t n, hipStream_t s);
-// debug read-back: NHWC storage type -> fp32 NCHW
+// debug read-back: NHWC storage type (ld elements per pixel) -> fp32 NCHW
 hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H,
-                                   int W, hipStream_t s);
+                                   int W, int ld, hipStream_t s);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
 
 // K-slice width the conv kernel uses for a shape under a tile: the tile's (128 or 64) when Cin

@@ -181,12 +181,15 @@ static __device__ __forceinline__ void epilogue_load(EpiOperands<TM, TN> &e, con
     }
 }
 
-// + bias, + residual, ReLU, one round-to-nearest-even to the storage type, 16-byte stores.
-template <typename T, int TM, int TN>
-static __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[TM][TN], const EpiOperands<TM, TN> &e, const ConvArgs &a,
-                                                      const EpiPos &p) {
-    const unsigned mn = (unsigned)a.M * a.Cout;
-    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, mn * 2u);
+// + bias, + residual, activation, one round-to-nearest-even to the storage type, 16-byte stores.
+// The activation code is uniform, so the hard-swish arithmetic sits behind a scalar branch and the
+// ReLU / identity form runs the instructions it always ran.
+template <typename T, int TM, int TN, bool HSWISH>
+static __device__ __forceinline__ void epilogue_store_act(const f32x16 (&acc)[TM][TN], const EpiOperands<TM, TN> &e, const ConvArgs &a,
+                                                          const EpiPos &p) {
+    // y may be a channel range of a wider tensor: ldy elements from one pixel to the next
+    const unsigned ldy = (unsigned)conv_ldy(a);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, (((unsigned)a.M - 1u) * ldy + (unsigned)a.Cout) * 2u);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const unsigned m = p.m0 + p.wm0 + i * 32 + p.lrow;
@@ -195,18 +198,26 @@ static __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[TM][TN
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const unsigned n = p.n0 + p.wn0 + j * 32 + q * 16 + p.lhalf * 8;
-                const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * a.Cout + n) * 2u : kOob;
+                const unsigned o = (m < (unsigned)a.M && n < (unsigned)a.Cout) ? (m * ldy + n) * 2u : kOob;
                 const T *r = reinterpret_cast<const T *>(&e.rv[i][j][q]);
                 const float *b = reinterpret_cast<const float *>(&e.bv[j][q][0]);
                 T out[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
                     const float v = acc[i][j][8 * q + k] + b[k] + (float)r[k];
-                    out[k] = (T)(a.relu ? fmaxf(v, 0.f) : v);
+                    if (HSWISH) out[k] = (T)(v * fminf(fmaxf(v + 3.f, 0.f), 6.f) * (1.f / 6.f));
+                    else out[k] = (T)(a.relu ? fmaxf(v, 0.f) : v);
                 }
                 __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
             }
     }
+}
+
+template <typename T, int TM, int TN>
+static __device__ __forceinline__ void epilogue_store(const f32x16 (&acc)[TM][TN], const EpiOperands<TM, TN> &e, const ConvArgs &a,
+                                                      const EpiPos &p) {
+    if (a.relu == ACT_HSWISH) epilogue_store_act<T, TM, TN, true>(acc, e, a, p);
+    else epilogue_store_act<T, TM, TN, false>(acc, e, a, p);
 }
 
 // Workgroups go to the 8 XCDs round-robin; give each XCD a contiguous run of tiles so that

@@ -79,8 +79,11 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
     // The activation buffer is described from D bytes before its start, D = the offset of the
     // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
     // VGPR) + tap/channel offset (uniform, in an SGPR)  is never negative.
-    const unsigned x_bytes = (unsigned)a.B * a.H * a.W * a.Cin * 2u;
-    const unsigned x_shift = MODE == MODE_GEMM ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
+    // x may be the first Cin channels of a wider tensor: ldx elements from one pixel to the next.
+    const unsigned ldx = (unsigned)conv_ldx(a);
+    const int pad_h = conv_pad_h(a), pad_w = conv_pad_w(a);
+    const unsigned x_bytes = (((unsigned)a.B * a.H * a.W - 1u) * ldx + (unsigned)a.Cin) * 2u;
+    const unsigned x_shift = MODE == MODE_GEMM ? 0u : (unsigned)(pad_h * a.W + pad_w) * ldx * 2u;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(static_cast<const char *>(a.x) - x_shift, x_bytes + x_shift);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.w, (unsigned)a.Cout * a.K * 2u);
 
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
         const unsigned m = m0 + cid / CPR;
         unsigned mask = 0, voff = 0;
         if (MODE == MODE_GEMM) {
-            voff = m * (unsigned)a.Cin * 2u + c * 16u;
+            voff = m * ldx * 2u + c * 16u;
             mask = m < (unsigned)a.M ? 1u : 0u;
         } else if (m < (unsigned)a.M) {
             const unsigned t = fast_div(m, a.wo_div);
@@ -105,15 +108,15 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
             const unsigned n = fast_div(t, a.ho_div);
             const int p = t - n * a.Ho;
             const int ihc = p * a.stride, iwc = q * a.stride;
-            voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u + c * 16u;
+            voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * ldx * 2u + c * 16u;
             // filter rows r with 0 <= ihc - pad + r < H
-            const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
+            const int r_lo = max(0, pad_h - ihc), r_hi = min(a.kh, a.H + pad_h - ihc);
             if (MODE == MODE_STEM) {
                 mask = ((1u << r_hi) - 1u) & ~((1u << r_lo) - 1u);
-                if ((unsigned)(iwc - a.pad + 2 * c) < (unsigned)a.W) mask |= 1u << 30;
-                if ((unsigned)(iwc - a.pad + 2 * c + 1) < (unsigned)a.W) mask |= 1u << 31;
+                if ((unsigned)(iwc - pad_w + 2 * c) < (unsigned)a.W) mask |= 1u << 30;
+                if ((unsigned)(iwc - pad_w + 2 * c + 1) < (unsigned)a.W) mask |= 1u << 31;
             } else {
-                const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+                const int s_lo = max(0, pad_w - iwc), s_hi = min(a.kw, a.W + pad_w - iwc);
                 const unsigned cols = ((1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
                 for (int r = r_lo; r < r_hi; ++r) mask |= cols << (r * a.kw);
             }
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N) void conv_igemm_kernel(cons
                 qx[j] = u32x4{t0.x, t0.y, t1.x, t1.y};
             }
         } else {
-            const unsigned soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+            const unsigned soff = MODE == MODE_GEMM ? (unsigned)fc0 * 2u : ((unsigned)(fr * a.W + fs) * ldx + (unsigned)fc0) * 2u;
             const unsigned tbit = !live ? 0u : (MODE == MODE_GEMM ? 1u : (1u << (fr * a.kw + fs)));
 #pragma unroll
             for (int j = 0; j < X_PER; ++j)
@@ -420,8 +423,10 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
     if (a.split_k > 1 && (!a.partial || !a.counters)) return hipErrorInvalidValue;
     if (a.split_k == 1 && a.partial) return hipErrorInvalidValue;
     // buffer descriptors address less than 2 GiB each
-    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
-    if ((long long)a.M * a.Cout * (a.partial ? 4 : 2) >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31))
+    if (conv_ldx(a) < a.Cin || conv_ldy(a) < a.Cout || a.Cin >= kMaxChannels || conv_ldx(a) >= kMaxChannels || conv_ldy(a) >= kMaxChannels)
+        return hipErrorInvalidValue;
+    if ((long long)a.B * a.H * a.W * conv_ldx(a) * 2 + (long long)(conv_pad_h(a) * a.W + conv_pad_w(a)) * conv_ldx(a) * 2 >= (1ll << 31)) return hipErrorInvalidValue;
+    if ((long long)a.M * (a.partial ? a.Cout * 4ll : conv_ldy(a) * 2ll) >= (1ll << 31) || (long long)a.M * conv_ldy(a) * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31))
         return hipErrorInvalidValue;
     // K slices of 64 go global -> LDS directly (kernels_conv_dlds.hip); the stem and Cin % 64 != 0
     // keep the register-staged kernel of this file.

@@ -136,8 +136,11 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
     // The activation buffer is described from D bytes before its start, D = the offset of the
     // top-left tap relative to a filter's centre pixel, so that  centre offset (per thread, in a
     // VGPR) + tap/channel offset (uniform, in an SGPR)  is never negative.
-    const unsigned x_bytes = (unsigned)a.B * a.H * a.W * a.Cin * 2u;
-    const unsigned x_shift = MODE != MODE_CONV ? 0u : (unsigned)(a.pad * a.W + a.pad) * a.Cin * 2u;
+    // x may be the first Cin channels of a wider tensor: ldx elements from one pixel to the next.
+    const unsigned ldx = (unsigned)conv_ldx(a);
+    const int pad_h = conv_pad_h(a), pad_w = conv_pad_w(a);
+    const unsigned x_bytes = (((unsigned)a.B * a.H * a.W - 1u) * ldx + (unsigned)a.Cin) * 2u;
+    const unsigned x_shift = MODE != MODE_CONV ? 0u : (unsigned)(pad_h * a.W + pad_w) * ldx * 2u;
     const u32x4 dx = make_desc(static_cast<const char *>(a.x) - x_shift, x_bytes + x_shift);
     const u32x4 dw = make_desc(a.w, (unsigned)a.Cout * a.K * 2u);
 
@@ -154,7 +157,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             const int row = cid / CPR;
             const int c = (cid % CPR) ^ swz_key<BK>(row);
             const unsigned m = m0 + row;
-            x_voff[j] = m * (unsigned)a.Cin * 2u + c * 16u;
+            x_voff[j] = m * ldx * 2u + c * 16u;
             x_mask[j] = m < (unsigned)a.M ? 1u : 0u;
         }
     } else {
@@ -178,9 +181,9 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
                     mask = 1u;
                 } else {
                     const int ihc = p * a.stride, iwc = q * a.stride;
-                    voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * a.Cin * 2u;
-                    const int r_lo = max(0, a.pad - ihc), r_hi = min(a.kh, a.H + a.pad - ihc);
-                    const int s_lo = max(0, a.pad - iwc), s_hi = min(a.kw, a.W + a.pad - iwc);
+                    voff = (unsigned)((n * a.H + ihc) * a.W + iwc) * ldx * 2u;
+                    const int r_lo = max(0, pad_h - ihc), r_hi = min(a.kh, a.H + pad_h - ihc);
+                    const int s_lo = max(0, pad_w - iwc), s_hi = min(a.kw, a.W + pad_w - iwc);
                     // in-range columns s_lo..s_hi-1 replicated into every in-range filter row r_lo..r_hi-1:
                     // a multiplication by the rows' unit bits (no carries: cols < 2^kw)
                     unsigned row_units = 0;  // bit r*kw for every filter row r
@@ -245,7 +248,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
     auto issue_begin = [&](int kt, int stage) {
         is_soff = MODE == MODE_GEMM   ? (unsigned)fc0 * 2u
                   : MODE == MODE_STEM ? (unsigned)kt * (2u * a.W * 8u)
-                                      : (unsigned)((fr * a.W + fs) * a.Cin + fc0) * 2u;
+                                      : ((unsigned)(fr * a.W + fs) * ldx + (unsigned)fc0) * 2u;
         is_tbit = MODE == MODE_CONV ? (1u << (fr * a.kw + fs)) : 1u;
         is_dst = lds_base + (unsigned)stage * STAGE_BYTES + (unsigned)wave * 1024u;
         is_kb = (unsigned)kt * (BK * 2u);
@@ -500,7 +503,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float v = acc[i][j][8 * q + e] + sBias1[n + e];
-                        out[e] = (T)(a.relu ? fmaxf(v, 0.f) : v);
+                        out[e] = (T)(a.relu ? fmaxf(v, 0.f) : v);   // the fused form is planned for ReLU / no activation only
                     }
                     *reinterpret_cast<u32x4 *>(sP + swz<BN>(wm0 + i * 32 + lrow, n >> 3)) = *reinterpret_cast<const u32x4 *>(out);
                 }
@@ -570,15 +573,18 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(const void *x, const void *w, const void *res, void *y,
-                                                                                 int M, int K, int Cout, int Cin, int nb, int relu,
+                                                                                 int M, int K, int cout_ldy, int cin_ldx, int nb, int relu,
                                                                                  const ConvArgs rest) {
     // The ten leading arguments (14 dwords, all the user SGPRs there are beside the argument
     // pointer) repeat fields of `rest`: this file is compiled with kernel-argument preloading, so
     // they are in SGPRs when a wave starts and the first address arithmetic does not wait for a
     // load of the argument block.  Everything else is read from `rest` when it is needed.
+    // Cout and Cin carry the pixel pitches of y and x in their upper halves, so that the 1x1 form
+    // still needs nothing beyond the preloaded scalars for its addressing.
     ConvArgs a = rest;
     a.x = x; a.w = w; a.res = res; a.y = y;
-    a.M = M; a.K = K; a.Cout = Cout; a.Cin = Cin; a.nb = nb; a.relu = relu;
+    a.M = M; a.K = K; a.Cout = cout_ldy & 0xffff; a.Cin = cin_ldx & 0xffff; a.nb = nb; a.relu = relu;
+    a.ld = (int)(((unsigned)cin_ldx >> 16) | ((unsigned)cout_ldy & 0xffff0000u));
     conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, nb);
 }
 
@@ -618,7 +624,7 @@ static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a_in, hipStre
     // a K walk shorter than the ring only ever touches its first stages (the wave groups' exchange
     // at the end needs its own room)
     const size_t used = std::max((size_t)std::min(NS, a.ktiles_per_split) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
-    kern<<<grid, block, used, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout, a.Cin, a.nb, a.relu, a);
+    kern<<<grid, block, used, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout | (conv_ldy(a) << 16), a.Cin | (conv_ldx(a) << 16), a.nb, a.relu, a);
     return hipGetLastError();
 }
 
@@ -707,7 +713,7 @@ static hipError_t launch_fused_one(const ConvArgs &a_in, hipStream_t s) {
                                                  (int)(bias_off + (BN + kFusedMaxCout2) * 4));
     if (attr != hipSuccess) return attr;
     if (a.Cout2 % fused_chunk(BN, KG) != 0) return hipErrorInvalidValue;
-    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout, a.Cin, a.nb, a.relu, a);
+    kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout | (conv_ldy(a) << 16), a.Cin | (conv_ldx(a) << 16), a.nb, a.relu, a);
     return hipGetLastError();
 }
 
@@ -731,7 +737,8 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
     if (a.wd ? (a.Cout != 64 || !a.x2 || !a.biasd) : !a.res) return hipErrorInvalidValue;
     if (!a.res && !a.wd) return hipErrorInvalidValue;
     if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;
-    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
+    if (conv_ldx(a) != a.Cin || conv_ldy(a) != a.Cout) return hipErrorInvalidValue;   // the fused form takes dense tensors only
+    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(conv_pad_h(a) * a.W + conv_pad_w(a)) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     const bool gemm = a.kh == 1 && a.kw == 1 && a.stride == 1 && a.pad == 0;
 #define CW_FUSED_T(T_, BM_, BN_, KG_) return gemm ? launch_fused_one<T_, BM_, BN_, MODE_GEMM, KG_>(a, s) : launch_fused_one<T_, BM_, BN_, MODE_CONV, KG_>(a, s)
 #define CW_FUSED(BM_, BN_)                                                       \
@@ -777,8 +784,9 @@ bool conv_pair_tile_ok(ConvTile tile) {
 static bool conv_pair_member_ok(const ConvArgs &a, int bk) {
     if (a.Cin % bk != 0 || a.K != a.kh * a.kw * a.Cin || a.kwp != a.kw || a.kh * a.kw > 32 || a.split_k != 1 || a.partial) return false;
     if (a.ktiles_per_split != a.K / bk || a.M <= 0 || a.Cout % 32 != 0) return false;
-    if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(a.pad * a.W + a.pad) * a.Cin * 2 >= (1ll << 31)) return false;
-    return (long long)a.M * a.Cout * 2 < (1ll << 31) && (long long)a.Cout * a.K * 2 < (1ll << 31);
+    if (conv_ldx(a) < a.Cin || conv_ldy(a) < a.Cout) return false;
+    if ((long long)a.B * a.H * a.W * conv_ldx(a) * 2 + (long long)(conv_pad_h(a) * a.W + conv_pad_w(a)) * conv_ldx(a) * 2 >= (1ll << 31)) return false;
+    return (long long)a.M * conv_ldy(a) * 2 < (1ll << 31) && (long long)a.Cout * a.K * 2 < (1ll << 31);
 }
 
 void conv_pair_grid(ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, dim3 *grid, int *block) {

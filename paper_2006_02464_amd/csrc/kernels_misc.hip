@@ -311,6 +311,87 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const float *z_in, fl
 
 // ---- LOAD: canonical W[cout][cin][kh][kw] -> [cout'][kh][kwp][cinp], zero padded ---------
 // 16-bit elements are moved as raw bits, so one kernel serves fp16 and bf16.  With `permute`,
+// ---- depthwise convolution: one kh x kw filter per channel; one thread = 8 channels of one
+// output pixel.  The bytes moved are the bound (one multiply-add per 2 bytes read at 3x3 stride 1);
+// neighbouring threads cover neighbouring channel groups, so every access of a wave is one run of
+// 16-byte pieces, and the taps' overlap between neighbouring pixels is served by the caches.
+// Weights are [kh][kw][C] in the storage type; fp32 accumulation; + bias, + residual, activation,
+// one round-to-nearest-even; x and y may be channel ranges of wider tensors (ldx, ldy).
+static __device__ __forceinline__ float dw_act(float v, int act) {
+    const float r = fmaxf(v, 0.f);
+    const float h = v * fminf(fmaxf(v + 3.f, 0.f), 6.f) * (1.f / 6.f);
+    return act == ACT_RELU ? r : (act == ACT_HSWISH ? h : v);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dwconv_kernel(const DwArgs a) {
+    const unsigned c8 = (unsigned)a.C / 8u;
+    const unsigned total = (unsigned)a.B * a.Ho * a.Wo * c8;   // < 2^31: checked by the launch code
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    const unsigned cg = i % c8;
+    unsigned t = i / c8;            // output pixel m
+    const unsigned m = t;
+    const int q = (int)(t % (unsigned)a.Wo);
+    t /= (unsigned)a.Wo;
+    const int p = (int)(t % (unsigned)a.Ho);
+    const unsigned n = t / (unsigned)a.Ho;
+    float acc[8];
+    {
+        const float4 b0 = *reinterpret_cast<const float4 *>(a.bias + cg * 8u);
+        const float4 b1 = *reinterpret_cast<const float4 *>(a.bias + cg * 8u + 4u);
+        acc[0] = b0.x; acc[1] = b0.y; acc[2] = b0.z; acc[3] = b0.w;
+        acc[4] = b1.x; acc[5] = b1.y; acc[6] = b1.z; acc[7] = b1.w;
+    }
+    const T *x = static_cast<const T *>(a.x);
+    const T *w = static_cast<const T *>(a.w);
+    for (int r = 0; r < a.kh; ++r) {
+        const int ih = p * a.stride - a.pad + r;
+        if ((unsigned)ih >= (unsigned)a.H) continue;
+        for (int s = 0; s < a.kw; ++s) {
+            const int iw = q * a.stride - a.pad + s;
+            if ((unsigned)iw >= (unsigned)a.W) continue;
+            const uint4 xv = *reinterpret_cast<const uint4 *>(x + ((size_t)(n * a.H + ih) * a.W + iw) * a.ldx + cg * 8u);
+            const uint4 wv = *reinterpret_cast<const uint4 *>(w + (size_t)(r * a.kw + s) * a.C + cg * 8u);
+            const T *xe = reinterpret_cast<const T *>(&xv);
+            const T *we = reinterpret_cast<const T *>(&wv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (float)xe[e] * (float)we[e];
+        }
+    }
+    if (a.res) {
+        const uint4 rv = *reinterpret_cast<const uint4 *>(static_cast<const T *>(a.res) + (size_t)m * a.C + cg * 8u);
+        const T *re = reinterpret_cast<const T *>(&rv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (float)re[e];
+    }
+    T out[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (T)dw_act(acc[e], a.act);
+    *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + (size_t)m * a.ldy + cg * 8u) = *reinterpret_cast<const uint4 *>(out);
+}
+
+// ---- a tensor into a channel range of a wider one (2-byte elements, 16 bytes per thread) ----
+__global__ __launch_bounds__(256) void copy_channels_kernel(const CopyArgs a) {
+    const unsigned c8 = (unsigned)a.C / 8u;
+    const unsigned total = (unsigned)a.pixels * c8;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= total) return;
+    const unsigned cg = i % c8, m = i / c8;
+    const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.src) + (size_t)m * a.ld_src + cg * 8u);
+    *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.dst) + (size_t)m * a.ld_dst + cg * 8u) = v;
+}
+
+// LOAD-time re-layout of depthwise weights: canonical W[C][1][kh][kw] -> [kh][kw][C].
+__global__ __launch_bounds__(256) void pack_depthwise_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int C, int taps) {
+    const size_t total = (size_t)C * taps;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % C), t = (int)(i / C);
+        dst[i] = src[(size_t)c * taps + t];
+    }
+}
+
 // Workgroups of a LOAD-side launch: at most this many, each striding over its tensor.
 constexpr unsigned kLoadGridCap = 48;
 
@@ -354,7 +435,7 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *dst, size_t n16) 
 
 template <typename T>
 __global__ __launch_bounds__(256) void nhwc_to_nchw_f32_kernel(const T *__restrict__ src, float *__restrict__ dst,
-                                                               int B, int C, int H, int W) {
+                                                               int B, int C, int H, int W, int ld) {
     const size_t total = (size_t)B * C * H * W;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;  // NCHW index
     if (i >= total) return;
@@ -364,7 +445,7 @@ __global__ __launch_bounds__(256) void nhwc_to_nchw_f32_kernel(const T *__restri
     t /= H;
     const int c = (int)(t % C);
     const int n = (int)(t / C);
-    dst[i] = (float)src[(((size_t)n * H + h) * W + w) * C + c];
+    dst[i] = (float)src[(((size_t)n * H + h) * W + w) * ld + c];
 }
 
 static inline unsigned blocks_for(size_t n, int per) { return (unsigned)((n + per - 1) / per); }
@@ -449,12 +530,41 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H, int W, hipStream_t s) {
+hipError_t launch_nhwc_to_nchw_f32(DType dt, const void *src, float *dst, int B, int C, int H, int W, int ld, hipStream_t s) {
     const size_t total = (size_t)B * C * H * W;
+    if (ld < C) return hipErrorInvalidValue;
     if (dt == DT_F16)
-        nhwc_to_nchw_f32_kernel<f16><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const f16 *>(src), dst, B, C, H, W);
+        nhwc_to_nchw_f32_kernel<f16><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const f16 *>(src), dst, B, C, H, W, ld);
     else
-        nhwc_to_nchw_f32_kernel<bf16><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const bf16 *>(src), dst, B, C, H, W);
+        nhwc_to_nchw_f32_kernel<bf16><<<dim3(blocks_for(total, 256)), 256, 0, s>>>(static_cast<const bf16 *>(src), dst, B, C, H, W, ld);
+    return hipGetLastError();
+}
+
+hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s) {
+    // shapes the kernel's indexing relies on, checked here so that a bad launch is an error
+    if (a.C < 8 || a.C % 8 != 0 || a.ldx < a.C || a.ldy < a.C || a.ldx % 8 != 0 || a.ldy % 8 != 0) return hipErrorInvalidValue;
+    if (a.B < 1 || a.kh < 1 || a.kw < 1 || a.stride < 1 || a.pad < 0 || a.H < 1 || a.W < 1) return hipErrorInvalidValue;
+    if (a.Ho != (a.H + 2 * a.pad - a.kh) / a.stride + 1 || a.Wo != (a.W + 2 * a.pad - a.kw) / a.stride + 1 || a.Ho < 1 || a.Wo < 1) return hipErrorInvalidValue;
+    if (!a.x || !a.w || !a.bias || !a.y) return hipErrorInvalidValue;
+    const size_t total = (size_t)a.B * a.Ho * a.Wo * (a.C / 8);
+    if (total >= (1ull << 31) || (size_t)a.B * a.H * a.W * a.ldx >= (1ull << 31) || (size_t)a.B * a.Ho * a.Wo * a.ldy >= (1ull << 31)) return hipErrorInvalidValue;
+    CW_DISPATCH(dt, dwconv_kernel, dim3(blocks_for(total, 256)), 256, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s) {
+    if (a.C < 8 || a.C % 8 != 0 || a.ld_src < a.C || a.ld_dst < a.C || a.ld_src % 8 != 0 || a.ld_dst % 8 != 0 || a.pixels < 1 || !a.src || !a.dst)
+        return hipErrorInvalidValue;
+    const size_t total = (size_t)a.pixels * (a.C / 8);
+    if (total >= (1ull << 31)) return hipErrorInvalidValue;
+    copy_channels_kernel<<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_depthwise(const void *src, void *dst, int c, int kh, int kw, hipStream_t s) {
+    if (c < 1 || kh < 1 || kw < 1) return hipErrorInvalidValue;
+    const unsigned want = blocks_for((size_t)c * kh * kw, 256);
+    pack_depthwise_kernel<<<dim3(want < kLoadGridCap ? want : kLoadGridCap), 256, 0, s>>>(static_cast<const uint16_t *>(src), static_cast<uint16_t *>(dst), c, kh * kw);
     return hipGetLastError();
 }
 

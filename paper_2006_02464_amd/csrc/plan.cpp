@@ -136,24 +136,29 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         OpShape out{o.cout, 1, 1};
         switch (o.op) {
             case CW_OP_CONV: {
-                if (o.kh < 1 || o.kh != o.kw || o.stride < 1 || o.pad < 0 || o.groups > 1 || o.relu < 0 || o.relu > 1)
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs square filter, stride>=1, one group, ReLU or no activation", i);
-                if (sh + 2 * o.pad < o.kh || sw + 2 * o.pad < o.kw)
+                const bool dw = o.groups > 1;
+                const int pad_h = o.pad, pad_w = o.kh == o.kw ? o.pad : o.pad_w;
+                if (o.kh < 1 || o.kw < 1 || o.stride < 1 || pad_h < 0 || pad_w < 0 || o.relu < 0 || o.relu > 2)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs stride >= 1, padding >= 0 and an activation code 0..2", i);
+                if (dw && (o.groups != o.cin || o.cin != o.cout || o.kh != o.kw || o.cin % 8 != 0 || i == 0))
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: grouped conv must be depthwise (groups == cin == cout, %% 8, square filter)", i);
+                if (sh + 2 * pad_h < o.kh || sw + 2 * pad_w < o.kw)
                     return fail(err, CW_ERR_INVALID, "op %d: filter larger than padded input", i);
                 if (i == 0) {
-                    if (o.cin > 4 || o.kw > 8)
-                        return fail(err, CW_ERR_UNSUPPORTED, "first conv needs cin<=4 and kw<=8");
-                } else if (o.cin % 32 != 0 || o.kh * o.kw > 32) {
-                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs cin %% 32 == 0 and at most 5x5 taps", i);
+                    if (o.cin > 4 || o.kw > 8 || o.kh != o.kw)
+                        return fail(err, CW_ERR_UNSUPPORTED, "first conv needs cin<=4 and a square filter with kw<=8");
+                } else if (!dw && (o.cin % 32 != 0 || o.kh * o.kw > 32)) {
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv needs cin %% 32 == 0 and at most 32 taps", i);
                 }
-                if (o.cout % 32 != 0) return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cout must be a multiple of 32", i);
-                out.h = (sh + 2 * o.pad - o.kh) / o.stride + 1;
-                out.w = (sw + 2 * o.pad - o.kw) / o.stride + 1;
+                if (!dw && o.cout % 32 != 0) return fail(err, CW_ERR_UNSUPPORTED, "op %d: conv cout must be a multiple of 32", i);
+                if (o.cin >= kMaxChannels || o.cout >= kMaxChannels) return fail(err, CW_ERR_UNSUPPORTED, "op %d: too many channels", i);
+                out.h = (sh + 2 * pad_h - o.kh) / o.stride + 1;
+                out.w = (sw + 2 * pad_w - o.kw) / o.stride + 1;
                 if (o.residual_from >= 0) {
                     if (o.residual_from >= i) return fail(err, CW_ERR_INVALID, "op %d: bad residual_from", i);
                     const OpShape &r = m->shapes[o.residual_from];
                     const int rop = ops[o.residual_from].op;
-                    if ((rop != CW_OP_CONV && rop != CW_OP_MAXPOOL) || r.c != out.c || r.h != out.h || r.w != out.w)
+                    if ((rop != CW_OP_CONV && rop != CW_OP_MAXPOOL && rop != CW_OP_CONCAT) || r.c != out.c || r.h != out.h || r.w != out.w)
                         return fail(err, CW_ERR_INVALID, "op %d: residual shape mismatch", i);
                 } else if (o.residual_from != -1) {
                     return fail(err, CW_ERR_INVALID, "op %d: bad residual_from", i);
@@ -168,6 +173,18 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
                 out.h = (sh + 2 * o.pad - o.kh) / o.stride + 1;
                 out.w = (sw + 2 * o.pad - o.kw) / o.stride + 1;
                 break;
+            case CW_OP_CONCAT: {
+                if (i == 0 || o.residual_from < 0 || o.residual_from >= i || o.input_from < 0)
+                    return fail(err, CW_ERR_INVALID, "op %d: CONCAT needs two earlier ops", i);
+                const OpShape &b = m->shapes[o.residual_from];
+                const int bop = ops[o.residual_from].op;
+                if (bop != CW_OP_CONV && bop != CW_OP_MAXPOOL && bop != CW_OP_CONCAT)
+                    return fail(err, CW_ERR_UNSUPPORTED, "op %d: CONCAT needs spatial inputs", i);
+                if (b.h != sh || b.w != sw || o.cout != sc + b.c) return fail(err, CW_ERR_INVALID, "op %d: CONCAT shape mismatch", i);
+                if (sc % 8 != 0 || b.c % 8 != 0 || o.cout >= kMaxChannels) return fail(err, CW_ERR_UNSUPPORTED, "op %d: CONCAT needs channel counts %% 8 == 0", i);
+                out.h = sh; out.w = sw;
+                break;
+            }
             case CW_OP_GAVGPOOL:
                 if (i == 0 || o.cout != o.cin || o.cin % 64 != 0)
                     return fail(err, CW_ERR_UNSUPPORTED, "op %d: average pool needs channels %% 64 == 0", i);
@@ -184,23 +201,24 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         }
         if (o.op != CW_OP_FC && o.op != CW_OP_SOFTMAX && o.op != CW_OP_GAVGPOOL && i > 0) {
             const int src = ops[o.input_from].op;
-            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL)
+            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL && src != CW_OP_CONCAT)
                 return fail(err, CW_ERR_UNSUPPORTED, "op %d: spatial op needs a spatial input", i);
         }
         if (o.op == CW_OP_GAVGPOOL) {
             const int src = ops[o.input_from].op;
-            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL)
+            if (src != CW_OP_CONV && src != CW_OP_MAXPOOL && src != CW_OP_CONCAT)
                 return fail(err, CW_ERR_UNSUPPORTED, "op %d: average pool needs a spatial input", i);
         }
         m->shapes[i] = out;
         if (o.op == CW_OP_CONV || o.op == CW_OP_FC) {
             WeightSlot ws{};
             ws.op_index = i;
-            ws.cout = o.cout; ws.cin = o.cin;
+            ws.depthwise = o.op == CW_OP_CONV && o.groups > 1;
+            ws.cout = o.cout; ws.cin = ws.depthwise ? 1 : o.cin;
             ws.kh = o.op == CW_OP_FC ? 1 : o.kh;
             ws.kw = o.op == CW_OP_FC ? 1 : o.kw;
             ws.kwp = (i == 0) ? 8 : ws.kw;
-            ws.cinp = (i == 0) ? 4 : ws.cin;
+            ws.cinp = (i == 0) ? 4 : ws.cin;   // depthwise: [kh][kw][C], as many bytes as the canonical form
             // first convolution: with an even stride and at most 8 filter rows, the rows are padded
             // to 8 so that two of them make one K slice of 64 (see the stem mode of the conv kernel)
             ws.khp = (i == 0 && o.op == CW_OP_CONV && o.stride % 2 == 0 && ws.kh <= 8) ? 8 : ws.kh;
@@ -300,6 +318,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     Plan p;
     p.batch = batch;
     p.op_out.assign(n_ops, Ref{});
+    p.op_ld.assign(n_ops, 0);
+    for (int i = 0; i < n_ops; ++i) p.op_ld[i] = m.shapes[i].c;
 
     // Guard the 32-bit byte offsets of the conv kernel's buffer loads (tensors stay below 2 GiB).
     {
@@ -316,11 +336,12 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
             if (m.ops[i].input_from >= 0) ++uses[m.ops[i].input_from];
-            if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) ++uses[m.ops[i].residual_from];
+            if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0) ++uses[m.ops[i].residual_from];
         }
         for (int i = 1; i + 1 < n_ops; ++i) {
             const cw_op &o1 = m.ops[i];
             if (o1.op != CW_OP_CONV || o1.residual_from >= 0 || o1.input_from < 0 || o1.cin % 64 != 0 || uses[i] != 1) continue;
+            if (o1.groups > 1 || o1.relu > 1 || m.ops[o1.input_from].op == CW_OP_CONCAT) continue;   // the fused form: dense layers, ReLU
             if ((o1.cout != 64 && o1.cout != 128) || o1.kh * o1.kw > 32 || o1.kh != o1.kw) continue;
             int j = -1;
             for (int t = i + 1; t <= i + 2 && t < n_ops; ++t)
@@ -328,7 +349,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             if (j < 0) continue;
             const cw_op &o2 = m.ops[j];
             if (o2.kh != 1 || o2.kw != 1 || o2.stride != 1 || o2.pad != 0 || o2.residual_from < 0 || o2.residual_from == i) continue;
-            if (o2.cin != o1.cout || o2.cout % o1.cout != 0 || o2.cout > 1024) continue;
+            if (o2.cin != o1.cout || o2.cout % o1.cout != 0 || o2.cout > 1024 || o2.relu > 1 || o2.groups > 1) continue;
+            if (m.ops[o2.residual_from].op == CW_OP_CONCAT) continue;
             const int64_t M = (int64_t)batch * m.shapes[i].h * m.shapes[i].w;
             const int bm = (o1.cout == 64 && M / 128 >= 256) ? 128 : 64;
             if ((M + bm - 1) / bm < 190) continue;  // measured: below that the two-launch form is faster
@@ -360,10 +382,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (ov.pair && ov.tile < 0 && ov.split_k <= 0) {
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
-                if (a.op != CW_OP_CONV || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
+                if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
                 for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
                     const cw_op &b = m.ops[j];
-                    if (b.op != CW_OP_CONV || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j]) continue;
+                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j]) continue;
                     if (b.residual_from >= i) continue;
                     partner[i] = j; moved[j] = 1;
                     break;
@@ -384,14 +406,73 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     for (int i = 0; i < n_ops; ++i) {
         const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : i];
         if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = std::max(last_use[m.ops[i].input_from], at);
-        if (m.ops[i].op == CW_OP_CONV && m.ops[i].residual_from >= 0) last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
+        if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0)
+            last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
     }
+    // CONCAT without copies: a source that is a convolution (or another CONCAT) whose every other
+    // reader can follow a pixel pitch (a convolution reading it as its input) gets its place inside
+    // the CONCAT's tensor and writes there itself: host[s] = the CONCAT, choff[s] = its first
+    // channel there.  Chains (a CONCAT that is the first source of the next, as in a dense block)
+    // resolve to the last CONCAT's tensor; every member is then a channel range of it with that
+    // tensor's pitch.  Sources that do not qualify are copied in by a launch of their own.
+    std::vector<int> host(n_ops, -1), choff(n_ops, 0);
+    {
+        std::vector<std::vector<int>> readers(n_ops);
+        for (int i = 0; i < n_ops; ++i) {
+            if (m.ops[i].input_from >= 0) readers[m.ops[i].input_from].push_back(i);
+            if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0) readers[m.ops[i].residual_from].push_back(i);
+        }
+        for (int c = 1; c < n_ops; ++c) {
+            if (m.ops[c].op != CW_OP_CONCAT) continue;
+            const int src[2] = {m.ops[c].input_from, m.ops[c].residual_from};
+            const int at[2] = {0, m.shapes[src[0]].c};
+            for (int k = 0; k < 2; ++k) {
+                const int sidx = src[k];
+                if (k == 1 && sidx == src[0]) continue;
+                const cw_op &so = m.ops[sidx];
+                if ((so.op != CW_OP_CONV && so.op != CW_OP_CONCAT) || host[sidx] >= 0 || fuse_into[sidx] >= 0 || fused_first[sidx] >= 0) continue;
+                bool ok = true;
+                for (int u : readers[sidx]) {
+                    if (u == c) continue;
+                    const cw_op &uo = m.ops[u];
+                    if (uo.op == CW_OP_CONCAT) continue;   // that one copies (this source has its host already)
+                    if (uo.op == CW_OP_CONV && uo.input_from == sidx && uo.residual_from != sidx && fuse_into[u] < 0 && fused_first[u] < 0) continue;
+                    ok = false;
+                }
+                if (ok) { host[sidx] = c; choff[sidx] = at[k]; }
+            }
+        }
+    }
+    auto root_of = [&](int i) { while (host[i] >= 0) i = host[i]; return i; };
+    auto offset_in_root = [&](int i) { int o = 0; while (host[i] >= 0) { o += choff[i]; i = host[i]; } return o; };
+    for (int i = 0; i < n_ops; ++i) {   // a hosting tensor lives as long as anything inside it is read
+        const int r = root_of(i);
+        if (r != i) last_use[r] = std::max(last_use[r], std::max(last_use[i], pos[r]));
+    }
+    std::vector<long long> root_off(n_ops, -1);
     std::vector<size_t> out_bytes(n_ops, 0);
     RangeAllocator arena((size_t)1 << 46);
     auto ws_alloc = [&](size_t bytes) {
         size_t off = 0;
         arena.alloc(bytes, &off);
         return off;
+    };
+
+    // Where op i's output goes: a region of its own, or its channel range of the CONCAT tensor
+    // that hosts it (allocated when its first member is planned).
+    auto place_output = [&](int i, size_t dense_bytes) {
+        const int r = root_of(i);
+        if (r == i && root_off[i] < 0) {
+            out_bytes[i] = dense_bytes;
+            p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(dense_bytes)};
+            return;
+        }
+        const OpShape &rs = m.shapes[r];
+        const size_t root_bytes = (size_t)batch * rs.h * rs.w * rs.c * esz;
+        if (root_off[r] < 0) root_off[r] = (long long)ws_alloc(root_bytes);
+        p.op_out[i] = Ref{SP_WORKSPACE, (size_t)root_off[r] + (size_t)offset_in_root(i) * esz};
+        p.op_ld[i] = rs.c;
+        out_bytes[i] = r == i ? root_bytes : 0;   // members are never freed on their own
     };
 
     // the split-K arrival counters live at the very start of the workspace, never reused
@@ -445,7 +526,9 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     l.fused_kg = fused_kg[i];
                     ConvArgs &a = l.conv;
                     a.B = batch; a.H = sin.h; a.W = sin.w; a.Cin = o1.cin; a.Ho = s1.h; a.Wo = s1.w; a.Cout = o1.cout;
-                    a.kh = o1.kh; a.kw = o1.kw; a.kwp = o1.kw; a.khp = o1.kh; a.stride = o1.stride; a.pad = o1.pad;
+                    a.kh = o1.kh; a.kw = o1.kw; a.kwp = o1.kw; a.khp = o1.kh; a.stride = o1.stride;
+                    conv_set_pad(a, o1.pad, o1.kh == o1.kw ? o1.pad : o1.pad_w);
+                    conv_set_ld(a, o1.cin, o1.cout);
                     a.M = batch * s1.h * s1.w;
                     a.K = o1.kh * o1.kw * o1.cin;
                     a.relu = o1.relu;
@@ -485,15 +568,34 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     p.launches.push_back(l);
                     break;
                 }
-                out_bytes[i] = (size_t)batch * os.h * os.w * os.c * esz;
-                p.op_out[i] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[i])};
+                place_output(i, (size_t)batch * os.h * os.w * os.c * esz);
+                if (o.groups > 1) {   // depthwise: its own kernel
+                    Launch l{};
+                    l.kind = K_DWCONV;
+                    l.op_index = i;
+                    l.dw = DwArgs{nullptr, nullptr, nullptr, nullptr, nullptr, batch, sh, sw, o.cin, os.h, os.w, o.kh, o.kw, o.stride, o.pad,
+                                  o.relu, p.op_ld[o.input_from], p.op_ld[i]};
+                    l.x = src;
+                    l.w = Ref{SP_WEIGHTS, ws.packed_w_off};
+                    l.bias = Ref{SP_WEIGHTS, ws.packed_b_off};
+                    l.y = p.op_out[i];
+                    if (o.residual_from >= 0) l.res = p.op_out[o.residual_from];
+                    const int64_t out_b = (int64_t)batch * os.h * os.w * os.c * esz;
+                    l.info.flops = 2 * (int64_t)batch * os.h * os.w * os.c * o.kh * o.kw;
+                    l.info.bytes = (int64_t)batch * sh * sw * sc * esz + (int64_t)o.cout * o.kh * o.kw * esz + o.cout * 4 + out_b + (o.residual_from >= 0 ? out_b : 0);
+                    snprintf(l.info.name, sizeof l.info.name, "dwconv%dx%d_s%d", o.kh, o.kw, o.stride);
+                    p.launches.push_back(l);
+                    break;
+                }
                 Launch l{};
                 l.kind = K_CONV;
                 l.op_index = i;
                 l.stem = (i == 0);
                 ConvArgs &a = l.conv;
                 a.B = batch; a.H = sh; a.W = sw; a.Cin = ws.cinp; a.Ho = os.h; a.Wo = os.w; a.Cout = o.cout;
-                a.kh = o.kh; a.kw = o.kw; a.kwp = ws.kwp; a.khp = ws.khp; a.stride = o.stride; a.pad = o.pad;
+                a.kh = o.kh; a.kw = o.kw; a.kwp = ws.kwp; a.khp = ws.khp; a.stride = o.stride;
+                conv_set_pad(a, o.pad, o.kh == o.kw ? o.pad : o.pad_w);
+                conv_set_ld(a, o.input_from < 0 ? ws.cinp : p.op_ld[o.input_from], p.op_ld[i]);
                 if (o.input_from < 0) { a.H = in_hp; a.W = in_wp; a.pad = 0; }  // the cast already padded the image
                 a.M = batch * os.h * os.w;
                 a.K = ws.khp * ws.kwp * ws.cinp;
@@ -523,7 +625,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 const int64_t real_k = (int64_t)o.kh * o.kw * o.cin;
                 const int64_t in_b = in_pixels * (i == 0 ? 4 : o.cin) * esz;
                 const int64_t w_b = (int64_t)o.cout * real_k * esz + o.cout * 4;
-                const int64_t out_b = (int64_t)out_bytes[i];
+                const int64_t out_b = (int64_t)batch * os.h * os.w * os.c * esz;
                 const int64_t res_b = o.residual_from >= 0 ? out_b : 0;
                 l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = real_k;
                 l.info.flops = 2 * (int64_t)a.M * a.Cout * real_k;
@@ -544,6 +646,25 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     snprintf(l.info.name, sizeof l.info.name, i == 0 ? "stem%dx%d_s%d" : "conv%dx%d_s%d", o.kh, o.kw, o.stride);
                 }
                 p.launches.push_back(l);
+                break;
+            }
+            case CW_OP_CONCAT: {
+                place_output(i, (size_t)batch * os.h * os.w * os.c * esz);
+                const int srcs[2] = {o.input_from, o.residual_from};
+                const int at[2] = {0, m.shapes[o.input_from].c};
+                for (int k = 0; k < 2; ++k) {
+                    const int sidx = srcs[k];
+                    if (host[sidx] == i && !(k == 1 && sidx == srcs[0])) continue;   // it wrote its channels itself
+                    Launch l{};
+                    l.kind = K_COPY_CHANNELS;
+                    l.op_index = i;
+                    l.copy = CopyArgs{nullptr, nullptr, batch * os.h * os.w, m.shapes[sidx].c, p.op_ld[sidx], p.op_ld[i]};
+                    l.x = p.op_out[sidx];
+                    l.y = Ref{SP_WORKSPACE, p.op_out[i].offset + (size_t)at[k] * esz};
+                    l.info.bytes = 2 * (int64_t)batch * os.h * os.w * m.shapes[sidx].c * esz;
+                    snprintf(l.info.name, sizeof l.info.name, "concat_copy");
+                    p.launches.push_back(l);
+                }
                 break;
             }
             case CW_OP_MAXPOOL: {
@@ -670,6 +791,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
             case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; break;
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
+            case K_DWCONV: g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256)); b = 256; break;
+            case K_COPY_CHANNELS: g = dim3((unsigned)(((size_t)l.copy.pixels * (l.copy.C / 8) + 255) / 256)); b = 256; break;
         }
         l.info.op_index = l.op_index;
         if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }

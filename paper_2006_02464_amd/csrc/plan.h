@@ -33,6 +33,8 @@ struct Launch {
     PoolArgs pool{};
     FcArgs fc{};
     SoftmaxArgs sm{};
+    DwArgs dw{};
+    CopyArgs copy{};
     Ref x, w, bias, res, y, partial, counters;
     Ref w2, bias2;         // second layer of a fused launch
     Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
@@ -56,13 +58,16 @@ struct WeightSlot {        // one op that owns weights
     size_t packed_w_off;   // byte offset of packed W inside the model's weight-pool region
     size_t packed_b_off;   // byte offset of the fp32 bias there
     size_t packed_w_bytes;
-    int32_t cout, cin, kh, kw, khp, kwp, cinp;
+    int32_t cout, cin, kh, kw, khp, kwp, cinp;   // cin: input channels per filter (1 for a depthwise convolution)
+    bool depthwise;
 };
 
 struct Plan {
     int32_t batch = 0;
     std::vector<Launch> launches;
     std::vector<Ref> op_out;  // workspace (or slot) location of every op's output
+    std::vector<int32_t> op_ld;  // elements from one pixel of that output to the next (> its channels where it is a
+                                 // channel range of a CONCAT result)
     size_t workspace_bytes = 0;
     cw_profile profile{};
 };

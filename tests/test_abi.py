@@ -135,8 +135,18 @@ def test_model_validation_errors(ctx):
     bad(b, cw.CW_ERR_INVALID)
     b = list(good); b[0] = (C, 8, 64, 7, 7, 2, 3, 1, -1, -1)                  # first conv cin > 4
     bad(b, cw.CW_ERR_UNSUPPORTED, c=8)
-    b = list(good); b[2] = (C, 64, 512, 3, 5, 1, 1, 1, -1, 1)                 # non-square filter
+    b = list(good); b[0] = (C, 3, 64, 7, 5, 2, 3, 1, -1, -1)                  # non-square first conv
     bad(b, cw.CW_ERR_UNSUPPORTED)
+    b = list(good); b[2] = (C, 64, 512, 3, 3, 1, 1, 3, -1, 1)                 # unknown activation code
+    bad(b, cw.CW_ERR_UNSUPPORTED)
+    b = list(good); b[2] = (C, 64, 512, 3, 3, 1, 1, 1, -1, 1, 0, 2)           # grouped but not depthwise
+    bad(b, cw.CW_ERR_UNSUPPORTED)
+    b = list(good); b[2] = (C, 64, 512, 7, 7, 1, 3, 1, -1, 1)                 # 49 taps
+    bad(b, cw.CW_ERR_UNSUPPORTED)
+    b = list(good); b[2] = (5, 64, 512, 0, 0, 1, 0, 0, 1, 1)                  # CONCAT whose channels do not add up
+    bad(b, cw.CW_ERR_INVALID)
+    ok = list(good); ok[2] = (C, 64, 512, 3, 5, 1, 1, 1, -1, 1, 2, 0)         # 3x5, padding (1, 2): same size out
+    assert ctx.model_define(ok, 3, 32, 32) >= 0
     with pytest.raises(cw.CwError) as e:
         ctx.model_define(good, 3, 32, 32, batch_sizes=(0,))
     assert e.value.status == cw.CW_ERR_BAD_BATCH

@@ -1,0 +1,80 @@
+"""GPU parity of the operators beyond the ResNet set (depthwise and rectangular convolution, hard
+swish, CONCAT written in place) on the MobileNet-, DenseNet- and Inception-style operator lists:
+every layer teacher forced against the CPU oracle, logits within the per-sample tolerance."""
+import numpy as np
+import pytest
+
+from gpu_common import TOL, Case, rel_err_per_sample
+from oracle import network as N
+from oracle import topology as T
+from test_gpu_parity_full import _head, check_every_launch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def worker():
+    from paper_2006_02464_amd.runner import Worker
+    w = Worker(workspace_bytes=2 << 30, io_bytes=256 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=256 << 20)
+    yield w
+    w.close()
+
+
+FAMILIES = {
+    "mobilenet": (lambda: T.mobilenet(), 96),
+    "dense": (lambda: T.dense_net(), 64),
+    "inception": (lambda: T.inception_net(), 72),
+}
+
+
+@pytest.mark.parametrize("family", sorted(FAMILIES))
+@pytest.mark.parametrize("dtype,batch", [("fp16", 3), ("bf16", 16)])
+def test_family_every_layer(worker, family, dtype, batch):
+    make, hw = FAMILIES[family]
+    case = Case(make(), hw, seed=21, dtype=dtype, dist="normal")
+    ctx = worker.ctx
+    ctx.set_debug_keep(True)
+    try:
+        mid = ctx.model_define(case.ops, 3, hw, hw, batch_sizes=(batch,), dtype=dtype)
+    finally:
+        ctx.set_debug_keep(False)
+    plan = ctx.plan(mid, batch)
+    kinds = {l["name"].split("_")[0].rstrip("0123456789x") for l in plan}
+    if family == "mobilenet":
+        assert sum(l["name"].startswith("dwconv") for l in plan) == 13
+    if family == "dense":     # 18 CONCATs, only the two block inputs (max-pool outputs) are copied in
+        assert sum(l["name"] == "concat_copy" for l in plan) == 2
+    if family == "inception":  # both CONCATs are written in place; 1x7 and 7x1 run on the main kernel
+        assert not any(l["name"] == "concat_copy" for l in plan)
+        assert sum(l["name"].startswith(("conv1x7", "conv7x1")) for l in plan) == 4
+    worker.load(mid, case.blob)
+    x = case.images(0, batch)
+    probs, logits, ns = worker.infer(mid, x)
+    assert np.isfinite(logits).all()
+    wp, wf, nf, gpu = check_every_launch(worker, case, mid, batch, x)
+    feat = [v for i, v in gpu.items() if case.ops[i].op == T.GAVGPOOL][0]
+    _head(case, feat, logits, probs)
+    ref = case.oracle(x)["logits"]
+    err = rel_err_per_sample(logits, ref)
+    print("%s %s b%d: %d launches, exec %.1f us, max rel err %.3e, worst teacher-forced diff / scale %.2e" % (
+        family, dtype, batch, len(plan), ns / 1e3, err.max(), wp), kinds)
+    assert err.max() <= TOL
+    ctx.unload_weights(mid)
+
+
+def test_mobilenet_224_batch16_and_small_batches(worker):
+    """The depthwise family at its real size: 224x224, batch 16 and re-cut at batch 1 and 4."""
+    case = Case(T.mobilenet(), 224, seed=0, dist="normal")
+    ctx = worker.ctx
+    mid = ctx.model_define(case.ops, 3, 224, 224)
+    worker.load(mid, case.blob)
+    x = case.images(0, 16)
+    ref = case.oracle(x)["logits"]
+    for batch in (16, 4, 1):
+        got = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 16, batch)])
+        err = rel_err_per_sample(got, ref)
+        print("mobilenet 224 b%d: max rel err %.3e, top-1 equal on %d of 16" % (batch, err.max(), int((N.argmax(got) == N.argmax(ref)).sum())))
+        assert err.max() <= TOL
+    p = ctx.profile_measure(mid, 16, 200)
+    print("mobilenet 224 b16 EXEC p50 %.1f us" % p["p50_us"])
+    ctx.unload_weights(mid)

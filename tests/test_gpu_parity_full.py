@@ -72,7 +72,7 @@ def check_every_launch(worker, case, mid, batch, x):
             k += 1
     last_use = {}
     for i, o in enumerate(ops):
-        for src in (o.input_from, o.residual_from if o.op == T.CONV else -1):
+        for src in (o.input_from, o.residual_from if o.op in (T.CONV, T.CONCAT) else -1):
             if src >= 0:
                 last_use[src] = i
     for j, (f, d) in fused.items():          # a fused launch reads its members' inputs when op j runs
@@ -86,7 +86,13 @@ def check_every_launch(worker, case, mid, batch, x):
         return x if i < 0 else gpu[i]
 
     def conv(o, wi, src):
-        return _per_sample(lambda s: N.conv2d(s, case.w[wi], case.b[wi], o.stride, o.pad), src)
+        ph, pw, groups = T.conv_geometry(o)
+        if groups == 1 and o.kh == o.kw:
+            return _per_sample(lambda s: N.conv2d(s, case.w[wi], case.b[wi], o.stride, o.pad), src)
+        return _per_sample(lambda s: N.conv2d_grouped(s, case.w[wi], case.b[wi], o.stride, ph, pw, groups), src)
+
+    def act(o, t):
+        return N.relu(t) if o.relu == 1 else (N.hswish(t) if o.relu == 2 else t)
 
     worst_plain = worst_fused = 0.0
     for i, (o, (c, h, w)) in enumerate(zip(ops, shapes)):
@@ -127,15 +133,15 @@ def check_every_launch(worker, case, mid, batch, x):
             t = conv(o, widx[i], tensor(o.input_from))
             if o.residual_from >= 0:
                 t = N.add(t, tensor(o.residual_from))
-            if o.relu:
-                t = N.relu(t)
-            t = gen.quantize(t, case.dtype)
+            t = gen.quantize(act(o, t), case.dtype)
             scale = np.abs(t).max()
             diff = np.abs(got - t)
             worst_plain = max(worst_plain, float(diff.max() / scale))
             bad = diff > ulp * np.abs(t) + 1e-5 * scale
             assert not bad.any(), "op %d (%s): %d elements beyond one ulp, teacher-forced max diff %.3e" % (i, o, int(bad.sum()), diff.max())
             assert (diff > 1e-5 * scale).mean() <= 0.02, "op %d: too many elements off by an ulp" % i
+        elif o.op == T.CONCAT:
+            assert np.array_equal(got, N.concat_channels(tensor(o.input_from), tensor(o.residual_from))), "op %d: concat not exact" % i
         elif o.op == T.MAXPOOL:
             assert np.array_equal(got, N.maxpool2d(tensor(o.input_from), o.kh, o.stride, o.pad)), "op %d: max pool not exact" % i
         elif o.op == T.GAVGPOOL:

@@ -178,7 +178,7 @@ def test_dense_and_inception_lists_are_consistent():
             if o.op == T.CONV and o.residual_from >= 0:
                 assert sh[o.residual_from] == (c, h, w)
     d = T.dense_net()
-    assert sum(o.op == T.CONCAT for o in d) == 10 and T.shapes(d, 224, 224)[-4] == (288, 28, 28)
+    assert sum(o.op == T.CONCAT for o in d) == 18 and T.shapes(d, 224, 224)[-4] == (512, 28, 28)
 
 
 def _tiny_case(ops, hw, seed):
