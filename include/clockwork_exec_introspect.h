@@ -87,6 +87,16 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
  * models defined afterwards; on != 0 restores the default. */
 int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
+/* Winograd F(2x2, 3x3) (the paper's model zoo holds Winograd-compiled ResNets: Table 2).  on != 0:
+ * models defined afterwards run every 3x3 stride-1 padding-1 convolution with cin % 64 == 0 as an
+ * input transform, 16 GEMMs [tiles x cin] x [cin x cout] in one batched launch of the convolution
+ * kernel, and an output transform with the fused epilogue: 2.25 times fewer multiply-adds, at the
+ * price of two more launches, transformed tensors four times the size of the input and output, and
+ * one more rounding to the storage type of the transformed input, weights and products.  LOAD
+ * stores the transformed weights (16/9 of the 3x3 filter's bytes) beside the packed ones.  Such
+ * convolutions are then neither fused with a following 1x1 nor paired.  on == 0 (default): the
+ * direct kernel.  Applies to models defined afterwards. */
+int32_t cw_set_winograd(cw_ctx *ctx, int32_t on);
 /* Plan table (section 5.1: the kernels of a model are fixed per batch size ahead of time).
  * The plan compiler takes the tile variant and split-K factor of a convolution from a table
  * keyed by its GEMM shape; the library has one built in for the ResNets.  This call installs

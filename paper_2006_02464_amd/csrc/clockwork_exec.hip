@@ -238,6 +238,15 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             a.y = resolve(c, m, s, l.y);
             return launch_dwconv(dt, a, st);
         }
+        case K_WINO_INPUT:
+        case K_WINO_OUTPUT: {
+            WinoArgs a = l.wino;
+            a.x = resolve(c, m, s, l.x);
+            a.y = resolve(c, m, s, l.y);
+            a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            a.res = resolve(c, m, s, l.res);
+            return l.kind == K_WINO_INPUT ? launch_wino_input(dt, a, st) : launch_wino_output(dt, a, st);
+        }
         case K_COPY_CHANNELS: {
             CopyArgs a = l.copy;
             a.src = resolve(c, m, s, l.x);
@@ -556,6 +565,12 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     return CW_OK;
 }
 
+int32_t cw_set_winograd(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.winograd = on != 0;
+    return CW_OK;
+}
+
 int32_t cw_set_pair_launches(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     c->ov.pair = on != 0;
@@ -579,7 +594,7 @@ int32_t cw_model_define(cw_ctx *c, const cw_op *ops, int32_t n_ops, int32_t in_c
     if (!c || !ops || !batch_sizes || n_batch < 1 || !model_id) return set_err(c, CW_ERR_INVALID, "null or empty argument");
     std::unique_ptr<ModelRt> m(new ModelRt);
     std::string err;
-    int32_t rc = model_init(&m->m, ops, n_ops, in_c, in_h, in_w, dtype, c->page_bytes, &err);
+    int32_t rc = model_init(&m->m, ops, n_ops, in_c, in_h, in_w, dtype, c->page_bytes, c->ov.winograd, &err);
     if (rc != CW_OK) return set_err(c, rc, err);
     m->m.keep_all = c->ov.keep_all;
     for (int i = 0; i < n_batch; ++i) {
@@ -691,6 +706,10 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
             e = launch_pack_weights(c->staging + ws.blob_w_off, at(ws.packed_w_off), ws.cout, ws.cin, ws.kh, ws.kw, ws.khp,
                                     ws.kwp, ws.cinp, is_conv, st);
         if (e != hipSuccess) return bail(e, "pack_weights");
+        if (ws.wino_bytes) {
+            e = launch_pack_winograd(m->m.dtype, c->staging + ws.blob_w_off, at(ws.wino_w_off), ws.cout, ws.cin, st);
+            if (e != hipSuccess) return bail(e, "pack_winograd");
+        }
         e = launch_copy_f32(reinterpret_cast<const float *>(c->staging + ws.blob_b_off),
                             reinterpret_cast<float *>(at(ws.packed_b_off)), ws.cout, st);
         if (e != hipSuccess) return bail(e, "copy bias");

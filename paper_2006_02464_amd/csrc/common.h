@@ -22,6 +22,8 @@ enum Kind : int32_t {
     K_SOFTMAX = 6,
     K_DWCONV = 7,      // depthwise convolution (one filter per channel), fused epilogue
     K_COPY_CHANNELS = 8,  // a tensor into a channel range of a wider one (CONCAT sources that cannot write there themselves)
+    K_WINO_INPUT = 9,   // Winograd F(2x2, 3x3): input tiles -> 16 transformed matrices
+    K_WINO_OUTPUT = 10, // ... 16 product matrices -> 2x2 output tiles, fused epilogue
 };
 
 // Activation codes (cw_op.relu, ConvArgs.relu / relu2).
@@ -85,6 +87,12 @@ struct alignas(64) ConvArgs {
     const void *x2;      // NHWC [M][Cout]
     const void *wd;      // packed [Cout2][Cout]
     const float *biasd;  // [Cout2]
+    // Batched form (1x1 stride-1 addressing, no split-K): nz > 1 runs nz independent GEMMs of this
+    // shape in one launch; workgroups with blockIdx.z = z take x, w and y advanced by z times these
+    // byte strides (bias and res are not used then).  Read only by z > 0.
+    int32_t nz;
+    int32_t zs_pad_;
+    long long zs_x, zs_w, zs_y;
 };
 static_assert(offsetof(ConvArgs, B) == 64 && offsetof(ConvArgs, khp) == 128 && sizeof(ConvArgs) == 256, "argument lines");
 __host__ __device__ inline int conv_pad_h(const ConvArgs &a) { return a.pad & 0xffff; }
@@ -103,6 +111,18 @@ struct DwArgs {
     const void *res;    // dense NHWC like y, or nullptr
     void *y;            // NHWC, ldy elements per pixel
     int32_t B, H, W, C, Ho, Wo, kh, kw, stride, pad, act, ldx, ldy;
+};
+
+// Winograd F(2x2, 3x3) for a 3x3 stride-1 pad-1 convolution.  Output pixels are cut into 2x2 tiles,
+// th x tw per image (th = ceil(Ho/2), tw = ceil(Wo/2)), tiles = B*th*tw.  The input transform writes
+// V[16][tiles][C]; after 16 GEMMs with the transformed weights U[16][Cout][C] (one batched launch
+// of the convolution kernel), the output transform reads Mx[16][tiles][Cout] and writes y.
+struct WinoArgs {
+    const void *x;      // input transform: NHWC activations (ldx elements per pixel); output transform: Mx
+    void *y;            // input transform: V; output transform: NHWC result (dense)
+    const float *bias;  // output transform: [Cout]
+    const void *res;    // output transform: dense NHWC like y, or nullptr
+    int32_t B, H, W, C, th, tw, ldx, act;   // H, W: image size (= output size); C: channels of the tensor being transformed
 };
 
 struct CopyArgs {
@@ -188,6 +208,11 @@ hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s);
 hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s);   // 2-byte elements, C % 8 == 0
+hipError_t launch_wino_input(DType dt, const WinoArgs &a, hipStream_t s);
+hipError_t launch_wino_output(DType dt, const WinoArgs &a, hipStream_t s);
+// LOAD-time: canonical W[cout][cin][3][3] -> U[16][cout'][cin] = G g G^T per (cout, cin), rows in the
+// conv kernel's accumulator order, computed in fp32 and rounded once to the storage type
+hipError_t launch_pack_winograd(DType dt, const void *src, void *dst, int cout, int cin, hipStream_t s);
 // LOAD-time re-layout of depthwise weights: canonical W[C][1][kh][kw] -> [kh][kw][C]
 hipError_t launch_pack_depthwise(const void *src, void *dst, int c, int kh, int kw, hipStream_t s);
 // LOAD-time re-layout: canonical W[cout][cin][kh][kw] -> [cout'][khp][kwp][cinp] (zero padded);

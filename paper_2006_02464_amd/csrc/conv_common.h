@@ -156,16 +156,18 @@ template <int TM, int TN>
 static __device__ __forceinline__ void epilogue_load(EpiOperands<TM, TN> &e, const ConvArgs &a, const EpiPos &p) {
     const unsigned mn = (unsigned)a.M * a.Cout;
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(a.res ? a.res : a.y, mn * 2u);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(a.bias, (unsigned)a.Cout * 4u);
+    // without a bias (the batched form) every bias load is out of range and returns zeros
+    const bool has_bias = a.bias != nullptr;
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(has_bias ? static_cast<const void *>(a.bias) : a.y, (unsigned)a.Cout * 4u);
     const bool has_res = a.res != nullptr;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const unsigned n = p.n0 + p.wn0 + j * 32 + q * 16 + p.lhalf * 8;
-            const unsigned o = n < (unsigned)a.Cout ? n * 4u : kOob;
+            const unsigned o = (has_bias && n < (unsigned)a.Cout) ? n * 4u : kOob;
             e.bv[j][q][0] = __builtin_amdgcn_raw_buffer_load_b128(rb, o, 0, 0);
-            e.bv[j][q][1] = __builtin_amdgcn_raw_buffer_load_b128(rb, o + 16u, 0, 0);
+            e.bv[j][q][1] = __builtin_amdgcn_raw_buffer_load_b128(rb, has_bias ? o + 16u : kOob, 0, 0);
         }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {

@@ -377,7 +377,7 @@ static bool conv_is_gemm(const ConvArgs &a, bool stem) {
 void conv_grid(ConvTile tile, const ConvArgs &a, dim3 *grid, int *block) {
     const TileDim d = conv_tile_dim(tile);
     const unsigned tm = (a.M + d.bm - 1) / d.bm, tn = (a.Cout + d.bn - 1) / d.bn;
-    *grid = dim3(tm * tn, a.split_k, 1);
+    *grid = dim3(tm * tn, a.split_k, a.nz > 1 ? a.nz : 1);
     *block = d.threads;
 }
 
@@ -421,6 +421,8 @@ hipError_t launch_conv(DType dt, ConvTile tile, bool stem, const ConvArgs &a, hi
     if (stem ? a.kh > 30 : a.kh * a.kw > 32) return hipErrorInvalidValue;  // tap masks are 32 bits
     if ((long long)a.split_k * a.ktiles_per_split < a.K / bk) return hipErrorInvalidValue;
     if (a.split_k > 1 && (!a.partial || !a.counters)) return hipErrorInvalidValue;
+    if (a.nz > 1 && (stem || !conv_is_gemm(a, stem) || a.split_k != 1 || a.bias || a.res)) return hipErrorInvalidValue;   // batched: 1x1 form only
+    if (a.nz <= 1 && !a.bias) return hipErrorInvalidValue;
     if (a.split_k == 1 && a.partial) return hipErrorInvalidValue;
     // buffer descriptors address less than 2 GiB each
     if (conv_ldx(a) < a.Cin || conv_ldy(a) < a.Cout || a.Cin >= kMaxChannels || conv_ldx(a) >= kMaxChannels || conv_ldy(a) >= kMaxChannels)

@@ -585,6 +585,14 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
     a.x = x; a.w = w; a.res = res; a.y = y;
     a.M = M; a.K = K; a.Cout = cout_ldy & 0xffff; a.Cin = cin_ldx & 0xffff; a.nb = nb; a.relu = relu;
     a.ld = (int)(((unsigned)cin_ldx >> 16) | ((unsigned)cout_ldy & 0xffff0000u));
+    if constexpr (MODE == MODE_GEMM && !SPLITK && !FUSED) {
+        // batched form: one GEMM per blockIdx.z, operands advanced by the strides in the last argument line
+        if (blockIdx.z != 0) {
+            a.x = static_cast<const char *>(x) + (long long)blockIdx.z * rest.zs_x;
+            a.w = static_cast<const char *>(w) + (long long)blockIdx.z * rest.zs_w;
+            a.y = static_cast<char *>(y) + (long long)blockIdx.z * rest.zs_y;
+        }
+    }
     conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE, SPLITK, FUSED, KG>(a, blockIdx.x, nb);
 }
 
@@ -613,6 +621,8 @@ static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a_in, hipStre
     ConvArgs a = a_in;
     a.nb = (int)grid.x;
     if (!SPLITK && a.ktiles_per_split != a.K / BK) return hipErrorInvalidValue;  // the kernel walks the whole K
+    if (a.nz > 1 && (MODE != MODE_GEMM || SPLITK || a.bias || a.res || grid.z != (unsigned)a.nz)) return hipErrorInvalidValue;
+    if (a.nz <= 1 && grid.z != 1) return hipErrorInvalidValue;
     constexpr int NS = RingDepth<BM, BN, BK>::value;
     constexpr size_t stage_bytes = (size_t)(BM + BN) * BK * 2;
     static_assert(NS * stage_bytes <= 160 * 1024, "ring does not fit the LDS");

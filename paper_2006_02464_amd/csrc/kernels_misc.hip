@@ -392,6 +392,173 @@ __global__ __launch_bounds__(256) void pack_depthwise_kernel(const uint16_t *__r
     }
 }
 
+// ---- Winograd F(2x2, 3x3) transforms (3x3 stride-1 pad-1 convolution) ------------------------
+//   Y = A^T [ (G g G^T) .* (B^T d B) ] A,  d = 4x4 input patch of a 2x2 output tile,
+//   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1],
+//   A^T = [1 1 1 0; 0 1 -1 -1].
+// The element-wise product summed over input channels is 16 GEMMs [tiles x C] x [C x Cout], which
+// run on the convolution kernel (batched 1x1 form).  The transforms are bandwidth-bound: one thread
+// handles 8 channels of one tile, all accesses are 16-byte pieces contiguous across a wave.
+template <typename T>
+__global__ __launch_bounds__(256) void wino_input_kernel(const WinoArgs a) {
+    const unsigned c8 = (unsigned)a.C / 8u;
+    const unsigned tiles = (unsigned)a.B * a.th * a.tw;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= tiles * c8) return;
+    const unsigned cg = i % c8, t = i / c8;
+    const int tj = (int)(t % (unsigned)a.tw);
+    const int ti = (int)((t / (unsigned)a.tw) % (unsigned)a.th);
+    const unsigned n = t / ((unsigned)a.tw * a.th);
+    const T *x = static_cast<const T *>(a.x);
+    float d[4][4][8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int ih = 2 * ti - 1 + r;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int iw = 2 * tj - 1 + s;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+                v = *reinterpret_cast<const uint4 *>(x + ((size_t)(n * a.H + ih) * a.W + iw) * a.ldx + cg * 8u);
+            const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) d[r][s][k] = (float)e[k];
+        }
+    }
+    T *V = static_cast<T *>(a.y);
+    const size_t plane = (size_t)tiles * a.C;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float u[4][4];   // B^T d
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u[0][s] = d[0][s][k] - d[2][s][k];
+            u[1][s] = d[1][s][k] + d[2][s][k];
+            u[2][s] = d[2][s][k] - d[1][s][k];
+            u[3][s] = d[1][s][k] - d[3][s][k];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {   // (B^T d) B, back into d
+            d[r][0][k] = u[r][0] - u[r][2];
+            d[r][1][k] = u[r][1] + u[r][2];
+            d[r][2][k] = u[r][2] - u[r][1];
+            d[r][3][k] = u[r][1] - u[r][3];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            T out[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) out[k] = (T)d[r][s][k];
+            *reinterpret_cast<uint4 *>(V + (size_t)(r * 4 + s) * plane + (size_t)t * a.C + cg * 8u) = *reinterpret_cast<const uint4 *>(out);
+        }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void wino_output_kernel(const WinoArgs a) {
+    const unsigned c8 = (unsigned)a.C / 8u;
+    const unsigned tiles = (unsigned)a.B * a.th * a.tw;
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= tiles * c8) return;
+    const unsigned cg = i % c8, t = i / c8;
+    const int tj = (int)(t % (unsigned)a.tw);
+    const int ti = (int)((t / (unsigned)a.tw) % (unsigned)a.th);
+    const unsigned n = t / ((unsigned)a.tw * a.th);
+    const T *M = static_cast<const T *>(a.x);
+    const size_t plane = (size_t)tiles * a.C;
+    float mm[4][4][8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(M + (size_t)(r * 4 + s) * plane + (size_t)t * a.C + cg * 8u);
+            const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) mm[r][s][k] = (float)e[k];
+        }
+    float bias[8];
+    {
+        const float4 b0 = *reinterpret_cast<const float4 *>(a.bias + cg * 8u);
+        const float4 b1 = *reinterpret_cast<const float4 *>(a.bias + cg * 8u + 4u);
+        bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+        bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+    }
+    float y[2][2][8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float u[2][4];   // A^T m
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u[0][s] = mm[0][s][k] + mm[1][s][k] + mm[2][s][k];
+            u[1][s] = mm[1][s][k] - mm[2][s][k] - mm[3][s][k];
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            y[r][0][k] = u[r][0] + u[r][1] + u[r][2] + bias[k];
+            y[r][1][k] = u[r][1] - u[r][2] - u[r][3] + bias[k];
+        }
+    }
+    T *Y = static_cast<T *>(a.y);
+    const T *R = static_cast<const T *>(a.res);
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int oh = 2 * ti + r, ow = 2 * tj + s;
+            if (oh >= a.H || ow >= a.W) continue;
+            const size_t at = ((size_t)(n * a.H + oh) * a.W + ow) * a.C + cg * 8u;
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = y[r][s][k];
+            if (R) {
+                const uint4 rv = *reinterpret_cast<const uint4 *>(R + at);
+                const T *re = reinterpret_cast<const T *>(&rv);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] += (float)re[k];
+            }
+            T out[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) out[k] = (T)dw_act(v[k], a.act);
+            *reinterpret_cast<uint4 *>(Y + at) = *reinterpret_cast<const uint4 *>(out);
+        }
+}
+
+// LOAD-time: W[cout][cin][3][3] -> U[16][cout'][cin], U = G g G^T in fp32, one rounding to T.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_winograd_kernel(const T *__restrict__ src, T *__restrict__ dst, int cout, int cin) {
+    const size_t total = (size_t)cout * cin;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % cin);
+        const int kp = (int)(i / cin);   // row of the packed matrix
+        const int row = kp & 31, g = row >> 3, h = (row >> 2) & 1, kk = row & 3;
+        const int k = (kp & ~31) + (g >> 1) * 16 + h * 8 + (g & 1) * 4 + kk;   // the channel that row holds
+        float w[3][3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) w[r][s] = (float)src[(((size_t)k * cin + c) * 3 + r) * 3 + s];
+        float gg[4][3];   // G g
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            gg[0][s] = w[0][s];
+            gg[1][s] = 0.5f * (w[0][s] + w[1][s] + w[2][s]);
+            gg[2][s] = 0.5f * (w[0][s] - w[1][s] + w[2][s]);
+            gg[3][s] = w[2][s];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float u0 = gg[r][0], u1 = 0.5f * (gg[r][0] + gg[r][1] + gg[r][2]), u2 = 0.5f * (gg[r][0] - gg[r][1] + gg[r][2]), u3 = gg[r][2];
+            dst[(size_t)(r * 4 + 0) * total + i] = (T)u0;
+            dst[(size_t)(r * 4 + 1) * total + i] = (T)u1;
+            dst[(size_t)(r * 4 + 2) * total + i] = (T)u2;
+            dst[(size_t)(r * 4 + 3) * total + i] = (T)u3;
+        }
+    }
+}
+
 // Workgroups of a LOAD-side launch: at most this many, each striding over its tensor.
 constexpr unsigned kLoadGridCap = 48;
 
@@ -558,6 +725,40 @@ hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s) {
     const size_t total = (size_t)a.pixels * (a.C / 8);
     if (total >= (1ull << 31)) return hipErrorInvalidValue;
     copy_channels_kernel<<<dim3(blocks_for(total, 256)), 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+static hipError_t wino_check(const WinoArgs &a, bool input) {
+    if (a.B < 1 || a.H < 1 || a.W < 1 || a.C < 8 || a.C % 8 != 0 || !a.x || !a.y) return hipErrorInvalidValue;
+    if (a.th != (a.H + 1) / 2 || a.tw != (a.W + 1) / 2) return hipErrorInvalidValue;
+    if (input ? (a.ldx < a.C || a.ldx % 8 != 0) : !a.bias) return hipErrorInvalidValue;
+    const size_t tiles = (size_t)a.B * a.th * a.tw;
+    if (16 * tiles * a.C >= (1ull << 31) || (size_t)a.B * a.H * a.W * (input ? a.ldx : a.C) >= (1ull << 31)) return hipErrorInvalidValue;
+    return hipSuccess;
+}
+
+hipError_t launch_wino_input(DType dt, const WinoArgs &a, hipStream_t s) {
+    const hipError_t e = wino_check(a, true);
+    if (e != hipSuccess) return e;
+    const size_t total = (size_t)a.B * a.th * a.tw * (a.C / 8);
+    CW_DISPATCH(dt, wino_input_kernel, dim3(blocks_for(total, 256)), 256, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_wino_output(DType dt, const WinoArgs &a, hipStream_t s) {
+    const hipError_t e = wino_check(a, false);
+    if (e != hipSuccess) return e;
+    const size_t total = (size_t)a.B * a.th * a.tw * (a.C / 8);
+    CW_DISPATCH(dt, wino_output_kernel, dim3(blocks_for(total, 256)), 256, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_winograd(DType dt, const void *src, void *dst, int cout, int cin, hipStream_t s) {
+    if (cout < 32 || cout % 32 != 0 || cin < 1) return hipErrorInvalidValue;
+    const unsigned want = blocks_for((size_t)cout * cin, 256);
+    const dim3 grid(want < kLoadGridCap ? want : kLoadGridCap);
+    if (dt == DT_F16) pack_winograd_kernel<f16><<<grid, 256, 0, s>>>(static_cast<const f16 *>(src), static_cast<f16 *>(dst), cout, cin);
+    else pack_winograd_kernel<bf16><<<grid, 256, 0, s>>>(static_cast<const bf16 *>(src), static_cast<bf16 *>(dst), cout, cin);
     return hipGetLastError();
 }
 

@@ -109,8 +109,14 @@ static int32_t fail(std::string *err, int32_t code, const char *fmt, int a = 0, 
     return code;
 }
 
+// A convolution the Winograd F(2x2, 3x3) path takes: 3x3, stride 1, padding 1, dense, Cin % 64 == 0.
+static bool wino_eligible(const cw_op &o, int index) {
+    return index > 0 && o.op == CW_OP_CONV && o.kh == 3 && o.kw == 3 && o.stride == 1 && o.pad == 1 && o.groups <= 1 && o.cin % 64 == 0 &&
+           o.cout % 32 == 0;
+}
+
 int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
-                   int32_t dtype, size_t page_bytes, std::string *err) {
+                   int32_t dtype, size_t page_bytes, bool winograd, std::string *err) {
     if (!ops || n_ops < 3) return fail(err, CW_ERR_INVALID, "need at least 3 ops");
     if (dtype != CW_DTYPE_FP16 && dtype != CW_DTYPE_BF16) return fail(err, CW_ERR_INVALID, "bad dtype %d", dtype);
     if (in_c < 1 || in_h < 1 || in_w < 1) return fail(err, CW_ERR_INVALID, "bad input size");
@@ -118,6 +124,7 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
     m->shapes.assign(n_ops, OpShape{0, 0, 0});
     m->in_c = in_c; m->in_h = in_h; m->in_w = in_w;
     m->dtype = (DType)dtype;
+    m->winograd = winograd;
     m->wslots.clear();
     m->op_wslot.assign(n_ops, -1);
     if (ops[n_ops - 2].op != CW_OP_FC || ops[n_ops - 1].op != CW_OP_SOFTMAX)
@@ -251,6 +258,10 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
         ws.packed_w_off = place(ws.packed_w_bytes);
     }
     for (WeightSlot &ws : m->wslots) ws.packed_b_off = place((size_t)ws.cout * 4);
+    for (WeightSlot &ws : m->wslots) {
+        ws.wino_bytes = (winograd && wino_eligible(ops[ws.op_index], ws.op_index)) ? (size_t)16 * ws.cout * ws.cin * 2 : 0;
+        ws.wino_w_off = ws.wino_bytes ? place(ws.wino_bytes) : 0;
+    }
     if (too_big) return fail(err, CW_ERR_UNSUPPORTED, "a weight tensor is larger than a weight page (%d bytes)", (int)page_bytes);
     m->blob_bytes = blob_b;
     m->packed_bytes = packed;
@@ -342,6 +353,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             const cw_op &o1 = m.ops[i];
             if (o1.op != CW_OP_CONV || o1.residual_from >= 0 || o1.input_from < 0 || o1.cin % 64 != 0 || uses[i] != 1) continue;
             if (o1.groups > 1 || o1.relu > 1 || m.ops[o1.input_from].op == CW_OP_CONCAT) continue;   // the fused form: dense layers, ReLU
+            if (m.winograd && wino_eligible(o1, i)) continue;
             if ((o1.cout != 64 && o1.cout != 128) || o1.kh * o1.kw > 32 || o1.kh != o1.kw) continue;
             int j = -1;
             for (int t = i + 1; t <= i + 2 && t < n_ops; ++t)
@@ -383,10 +395,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
                 if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
+                if (m.winograd && wino_eligible(a, i)) continue;
                 for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
                     const cw_op &b = m.ops[j];
                     if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j]) continue;
-                    if (b.residual_from >= i) continue;
+                    if (b.residual_from >= i || (m.winograd && wino_eligible(b, j))) continue;
                     partner[i] = j; moved[j] = 1;
                     break;
                 }
@@ -431,6 +444,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 if (k == 1 && sidx == src[0]) continue;
                 const cw_op &so = m.ops[sidx];
                 if ((so.op != CW_OP_CONV && so.op != CW_OP_CONCAT) || host[sidx] >= 0 || fuse_into[sidx] >= 0 || fused_first[sidx] >= 0) continue;
+                if (m.winograd && wino_eligible(so, sidx)) continue;   // its output transform writes dense tensors only
                 bool ok = true;
                 for (int u : readers[sidx]) {
                     if (u == c) continue;
@@ -506,6 +520,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (o.input_from < 0) { sc = 4; sh = m.in_h; sw = m.in_w; src = Ref{SP_WORKSPACE, cast_off}; }  // logical size; see below
         else { sc = m.shapes[o.input_from].c; sh = m.shapes[o.input_from].h; sw = m.shapes[o.input_from].w; src = p.op_out[o.input_from]; }
         size_t partial_off = 0, partial_bytes = 0;
+        size_t tmp_off[2] = {0, 0}, tmp_bytes[2] = {0, 0};   // Winograd: transformed input and products
 
         switch (o.op) {
             case CW_OP_CONV: {
@@ -585,6 +600,66 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     l.info.bytes = (int64_t)batch * sh * sw * sc * esz + (int64_t)o.cout * o.kh * o.kw * esz + o.cout * 4 + out_b + (o.residual_from >= 0 ? out_b : 0);
                     snprintf(l.info.name, sizeof l.info.name, "dwconv%dx%d_s%d", o.kh, o.kw, o.stride);
                     p.launches.push_back(l);
+                    break;
+                }
+                if (m.winograd && ws.wino_bytes && ov.tile < 0 && ov.split_k <= 0) {
+                    // Winograd F(2x2, 3x3): input transform, 16 GEMMs [tiles x Cin] x [Cin x Cout] as one
+                    // batched launch of the convolution kernel, output transform with the fused epilogue.
+                    const int th = (os.h + 1) / 2, tw = (os.w + 1) / 2;
+                    const int64_t tiles = (int64_t)batch * th * tw;
+                    tmp_bytes[0] = (size_t)16 * tiles * o.cin * esz;
+                    tmp_bytes[1] = (size_t)16 * tiles * o.cout * esz;
+                    tmp_off[0] = ws_alloc(tmp_bytes[0]);
+                    tmp_off[1] = ws_alloc(tmp_bytes[1]);
+                    Launch li{};
+                    li.kind = K_WINO_INPUT;
+                    li.op_index = i;
+                    li.wino = WinoArgs{nullptr, nullptr, nullptr, nullptr, batch, sh, sw, o.cin, th, tw, p.op_ld[o.input_from], 0};
+                    li.x = src;
+                    li.y = Ref{SP_WORKSPACE, tmp_off[0]};
+                    li.info.bytes = (int64_t)batch * sh * sw * o.cin * esz + (int64_t)tmp_bytes[0];
+                    snprintf(li.info.name, sizeof li.info.name, "winograd_input");
+                    p.launches.push_back(li);
+                    Launch lg{};
+                    lg.kind = K_CONV;
+                    lg.op_index = i;
+                    ConvArgs &g = lg.conv;
+                    g.B = 1; g.H = 1; g.W = (int32_t)tiles; g.Ho = 1; g.Wo = (int32_t)tiles; g.Cin = o.cin; g.Cout = o.cout;
+                    g.kh = 1; g.kw = 1; g.kwp = 1; g.khp = 1; g.stride = 1; g.pad = 0;
+                    conv_set_ld(g, o.cin, o.cout);
+                    g.M = (int32_t)tiles; g.K = o.cin; g.relu = 0;
+                    g.wo_div = make_fast_div((uint32_t)tiles);
+                    g.ho_div = make_fast_div(1);
+                    lg.tile = tiles >= 4096 ? (o.cin % 128 == 0 ? T128x64k128 : T128x64) : (o.cin % 128 == 0 ? T64x64k128 : T64x64);
+                    g.split_k = 1;
+                    g.ktiles_per_split = g.K / conv_bk(g, false, lg.tile);
+                    g.nz = 16;
+                    g.zs_x = (long long)tiles * o.cin * esz;
+                    g.zs_w = (long long)o.cout * o.cin * esz;
+                    g.zs_y = (long long)tiles * o.cout * esz;
+                    lg.x = Ref{SP_WORKSPACE, tmp_off[0]};
+                    lg.w = Ref{SP_WEIGHTS, ws.wino_w_off};
+                    lg.y = Ref{SP_WORKSPACE, tmp_off[1]};
+                    const TileDim tdg = conv_tile_dim(lg.tile);
+                    lg.info.gemm_m = tiles; lg.info.gemm_n = o.cout; lg.info.gemm_k = o.cin;
+                    lg.info.flops = 2 * 16 * tiles * o.cout * o.cin;
+                    lg.info.bytes = (int64_t)tmp_bytes[0] + (int64_t)ws.wino_bytes + (int64_t)tmp_bytes[1];
+                    lg.info.tile_m = tdg.bm; lg.info.tile_n = tdg.bn; lg.info.tile_k = conv_bk(g, false, lg.tile); lg.info.split_k = 1;
+                    lg.info.conv_tile = lg.tile; lg.info.wave_groups = tdg.kg;
+                    snprintf(lg.info.name, sizeof lg.info.name, "winograd_16gemms");
+                    p.launches.push_back(lg);
+                    Launch lo{};
+                    lo.kind = K_WINO_OUTPUT;
+                    lo.op_index = i;
+                    lo.wino = WinoArgs{nullptr, nullptr, nullptr, nullptr, batch, os.h, os.w, o.cout, th, tw, 0, o.relu};
+                    lo.x = Ref{SP_WORKSPACE, tmp_off[1]};
+                    lo.y = p.op_out[i];
+                    lo.bias = Ref{SP_WEIGHTS, ws.packed_b_off};
+                    if (o.residual_from >= 0) lo.res = p.op_out[o.residual_from];
+                    const int64_t out_bw = (int64_t)batch * os.h * os.w * os.c * esz;
+                    lo.info.bytes = (int64_t)tmp_bytes[1] + out_bw + (o.residual_from >= 0 ? out_bw : 0) + o.cout * 4;
+                    snprintf(lo.info.name, sizeof lo.info.name, "winograd_output");
+                    p.launches.push_back(lo);
                     break;
                 }
                 Launch l{};
@@ -726,6 +801,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
 
         if (partial_bytes) arena.free(partial_off, partial_bytes);
+        for (int k = 0; k < 2; ++k)
+            if (tmp_bytes[k]) arena.free(tmp_off[k], tmp_bytes[k]);
         if (!ov.keep_all) {
             if (i == 0) arena.free(cast_off, cast_bytes);
             for (int j = 0; j < n_ops; ++j) {
@@ -793,6 +870,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
             case K_DWCONV: g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256)); b = 256; break;
             case K_COPY_CHANNELS: g = dim3((unsigned)(((size_t)l.copy.pixels * (l.copy.C / 8) + 255) / 256)); b = 256; break;
+            case K_WINO_INPUT:
+            case K_WINO_OUTPUT: g = dim3((unsigned)(((size_t)l.wino.B * l.wino.th * l.wino.tw * (l.wino.C / 8) + 255) / 256)); b = 256; break;
         }
         l.info.op_index = l.op_index;
         if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }

@@ -35,6 +35,7 @@ struct Launch {
     SoftmaxArgs sm{};
     DwArgs dw{};
     CopyArgs copy{};
+    WinoArgs wino{};
     Ref x, w, bias, res, y, partial, counters;
     Ref w2, bias2;         // second layer of a fused launch
     Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
@@ -60,6 +61,8 @@ struct WeightSlot {        // one op that owns weights
     size_t packed_w_bytes;
     int32_t cout, cin, kh, kw, khp, kwp, cinp;   // cin: input channels per filter (1 for a depthwise convolution)
     bool depthwise;
+    size_t wino_w_off;     // Winograd-transformed weights U[16][cout][cin] (0 bytes: none)
+    size_t wino_bytes;
 };
 
 struct Plan {
@@ -83,6 +86,7 @@ struct PlanOverride {
     bool keep_all = false; // no workspace reuse (debug read-back)
     int32_t fuse = 1;      // two-layer launches: 0 = none, 1 = yes, 2 = yes but never with two wave groups
     bool pair = true;      // two convolutions over one tensor as one launch
+    bool winograd = false; // 3x3 stride-1 pad-1 convolutions through Winograd F(2x2, 3x3)
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 
@@ -100,12 +104,13 @@ struct Model {
     int32_t n_pages = 0;       // pages a LOAD takes
     std::vector<Plan> plans;
     bool keep_all = false;
+    bool winograd = false;     // eligible convolutions carry transformed weights and are planned as Winograd launches
 };
 
 // Validates the op list and fills shapes, weight slots and sizes.  Returns CW_OK or an error
 // with a message in *err.
 int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int32_t in_h, int32_t in_w,
-                   int32_t dtype, size_t page_bytes, std::string *err);
+                   int32_t dtype, size_t page_bytes, bool winograd, std::string *err);
 // Compiles the plan of one batch size.
 int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err);
 // Operator list of ResNet-18/50/152.
