@@ -87,6 +87,18 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
  * models defined afterwards; on != 0 restores the default. */
 int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
+/* Resident launches (section 4.4: one EXEC at a time owns the whole GPU).  on != 0: plans of batch
+ * sizes that are multiples of 8, compiled for models defined afterwards, run every run of plain
+ * convolution layers as ONE launch of 256 workgroups that stay on their CUs: the batch is cut into
+ * 8 partitions of batch/8 images, partition p is computed by the 32 workgroups on XCD p, and a
+ * layer starts when the layers it reads have signalled completion through flags in the workspace
+ * header, so the layers of a partition meet in one L2 and no dispatch, cache write-back or
+ * invalidate separates them.  Such plans fuse and pair nothing, give every tensor its own
+ * workspace region, and need the GPU to itself: every wait is bounded, and when one gives up (or a
+ * workgroup finds itself on another XCD than its partition's) the EXEC still ends and
+ * cw_exec_duration_ns reports CW_ERR_HIP.  CW_ERR_UNSUPPORTED on a device without 256 compute units
+ * in 8 XCDs.  on == 0 (default): one launch per layer. */
+int32_t cw_set_resident(cw_ctx *ctx, int32_t on);
 /* Winograd F(2x2, 3x3) (the paper's model zoo holds Winograd-compiled ResNets: Table 2).  on != 0:
  * models defined afterwards run every 3x3 stride-1 padding-1 convolution with cin % 64 == 0 as an
  * input transform, 16 GEMMs [tiles x cin] x [cin x cout] in one batched launch of the convolution

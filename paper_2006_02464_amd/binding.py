@@ -101,6 +101,7 @@ SIGNATURES = {
     "cw_set_fusion": (c_int32, [c_void_p, c_int32]),
     "cw_set_pair_launches": (c_int32, [c_void_p, c_int32]),
     "cw_set_winograd": (c_int32, [c_void_p, c_int32]),
+    "cw_set_resident": (c_int32, [c_void_p, c_int32]),
     "cw_set_use_graphs": (c_int32, [c_void_p, c_int32]),
     "cw_strerror": (c_char_p, [c_int32]),
     "cw_last_error": (c_char_p, [c_void_p]),
@@ -311,6 +312,9 @@ class Context:
 
     def set_pair_launches(self, on):
         self._check(lib().cw_set_pair_launches(self._h, int(on)))
+
+    def set_resident(self, on):
+        self._check(lib().cw_set_resident(self._h, int(on)))
 
     def set_winograd(self, on):
         self._check(lib().cw_set_winograd(self._h, int(on)))

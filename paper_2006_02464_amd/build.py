@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libclockwork_exec.so")
-SOURCES = ["clockwork_exec.hip", "plan.cpp", "kernels_conv.hip", "kernels_conv_dlds.hip", "kernels_misc.hip", "worker.hip"]
+SOURCES = ["clockwork_exec.hip", "plan.cpp", "kernels_conv.hip", "kernels_conv_dlds.hip", "kernels_resident.hip", "kernels_misc.hip", "worker.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fno-gpu-rdc",

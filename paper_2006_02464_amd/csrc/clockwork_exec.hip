@@ -48,6 +48,7 @@ struct ModelRt {
     hipEvent_t load_done = nullptr;
     hipEvent_t last_exec_end = nullptr;  // end event of the last EXEC issued on these weights (a slot's event; not owned)
     std::vector<PlanGraph> graphs;  // parallel to m.plans
+    std::vector<std::vector<ResLayer>> res_programs;  // host copies of the resident programs uploaded by the last LOAD
 };
 
 }  // namespace
@@ -102,6 +103,8 @@ struct cw_ctx {
     // one EXEC at a time: remember where the last one went
     hipStream_t last_exec_stream = nullptr;
     hipEvent_t last_exec_end = nullptr;
+    unsigned *res_error = nullptr;   // pinned host word a resident launch raises when it gives up (see kernels_resident.hip)
+    bool resident_capable = true;    // 256 CUs in 8 XCDs (planning-only contexts: assumed)
     std::string err;
 };
 
@@ -237,6 +240,18 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             a.res = resolve(c, m, s, l.res);
             a.y = resolve(c, m, s, l.y);
             return launch_dwconv(dt, a, st);
+        }
+        case K_RESIDENT: {
+            ResidentArgs a{};
+            a.layers = reinterpret_cast<const ResLayer *>(resolve(c, m, s, l.w));
+            a.n_layers = (int32_t)l.members.size();
+            a.workspace = s.workspace;
+            a.flags = reinterpret_cast<unsigned *>(s.workspace + kCounterBytes + kResidentFlagsOff);
+            a.flags_per_part = l.res_flags_per_part;
+            a.epoch = reinterpret_cast<unsigned *>(s.workspace + kCounterBytes);
+            a.error = c->res_error;
+            a.spin_limit = 1u << 20;   // about a second of polling before a wait gives up
+            return launch_resident(dt, a, st);
         }
         case K_WINO_INPUT:
         case K_WINO_OUTPUT: {
@@ -486,8 +501,8 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
         return CW_ERR_NO_MEMORY;
     }
     // split-K arrival counters must start at zero; every launch leaves them at zero again
-    if (cfg->workspace_bytes < kCounterBytes || hipMemset(p->workspace, 0, kCounterBytes) != hipSuccess) {
-        g_create_err = "workspace smaller than the split-K counter area, or hipMemset failed";
+    if (cfg->workspace_bytes < kCounterBytes + kResidentBytes || hipMemset(p->workspace, 0, kCounterBytes + kResidentBytes) != hipSuccess) {
+        g_create_err = "workspace smaller than its header (split-K counters, resident-launch flags), or hipMemset failed";
         cleanup();
         return CW_ERR_NO_MEMORY;
     }
@@ -496,6 +511,13 @@ int32_t cw_create(cw_ctx **out, const cw_config *cfg) {
         cleanup();
         return CW_ERR_HIP;
     }
+    p->resident_capable = prop.multiProcessorCount == kResPartitions * kResGroupsPerPartition;
+    if (hipHostMalloc(reinterpret_cast<void **>(&p->res_error), 64, hipHostMallocDefault) != hipSuccess) {
+        g_create_err = "hipHostMalloc of the resident-launch error word failed";
+        cleanup();
+        return CW_ERR_HIP;
+    }
+    *p->res_error = 0u;
     bool ok = hipStreamCreateWithFlags(&p->internal_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&p->staging_free, hipEventDisableTiming) == hipSuccess;
@@ -535,6 +557,7 @@ int32_t cw_destroy(cw_ctx *c) {
             if (e) (void)hipEventDestroy(e);
         if (c->staging_free) (void)hipEventDestroy(c->staging_free);
         if (c->internal_stream) (void)hipStreamDestroy(c->internal_stream);
+        if (c->res_error) (void)hipHostFree(c->res_error);
         if (c->workspace) (void)hipFree(c->workspace);
         if (c->io) (void)hipFree(c->io);
         if (c->pool) (void)hipFree(c->pool);
@@ -562,6 +585,13 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "fusion mode must be 0, 1 or 2");
     c->ov.fuse = on;
+    return CW_OK;
+}
+
+int32_t cw_set_resident(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    if (on && !c->resident_capable) return set_err(c, CW_ERR_UNSUPPORTED, "resident launches need 256 compute units in 8 XCDs");
+    c->ov.resident = on != 0;
     return CW_OK;
 }
 
@@ -606,6 +636,15 @@ int32_t cw_model_define(cw_ctx *c, const cw_op *ops, int32_t n_ops, int32_t in_c
             return set_err(c, CW_ERR_NO_MEMORY, "plan needs more workspace than the context has");
         m->m.plans.push_back(std::move(p));
     }
+    // resident programs live beside the model's packed weights (written at LOAD, when the weights'
+    // addresses are known)
+    for (Plan &p : m->m.plans)
+        for (Launch &l : p.launches)
+            if (l.kind == K_RESIDENT) {
+                const size_t bytes = l.members.size() * sizeof(ResLayer);
+                if (bytes > m->m.page_bytes) return set_err(c, CW_ERR_UNSUPPORTED, "a resident program is larger than a weight page");
+                l.w = Ref{SP_WEIGHTS, model_reserve(&m->m, bytes)};
+            }
     if (c->device >= 0) {
         DeviceGuard g(c->device);
         CW_HIP(c, hipEventCreateWithFlags(&m->load_done, hipEventDisableTiming));
@@ -714,6 +753,37 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
                             reinterpret_cast<float *>(at(ws.packed_b_off)), ws.cout, st);
         if (e != hipSuccess) return bail(e, "copy bias");
     }
+    // resident programs: every member's arguments with the weights' addresses of this placement;
+    // activations stay workspace offsets (res + 1, so that 0 means none)
+    m->res_programs.clear();
+    for (const Plan &p : m->m.plans)
+        for (const Launch &l : p.launches) {
+            if (l.kind != K_RESIDENT) continue;
+            std::vector<ResLayer> prog(l.members.size());
+            for (size_t k = 0; k < l.members.size(); ++k) {
+                const Launch &ml = l.members[k];
+                ResLayer &r = prog[k];
+                r = ResLayer{};
+                r.a = ml.conv;
+                r.a.x = reinterpret_cast<const void *>(ml.x.offset);
+                r.a.y = reinterpret_cast<void *>(ml.y.offset);
+                r.a.res = ml.res.space == SP_WORKSPACE ? reinterpret_cast<const void *>(ml.res.offset + 1) : nullptr;
+                r.a.w = at(ml.w.offset);
+                r.a.bias = reinterpret_cast<const float *>(at(ml.bias.offset));
+                r.a.partial = nullptr; r.a.counters = nullptr;
+                r.ps_x = ml.res_ps_x; r.ps_y = ml.res_ps_y; r.ps_res = ml.res_ps_res;
+                r.variant = ml.res_variant; r.tiles = ml.res_tiles;
+                r.dep[0] = ml.res_dep[0]; r.dep[1] = ml.res_dep[1];
+                r.flag_base = ml.res_flag_base;
+                if (ml.x.space != SP_WORKSPACE || ml.y.space != SP_WORKSPACE || !resident_layer_ok(r, c->cfg.workspace_bytes) ||
+                    r.dep[0] >= (int)k || r.dep[1] >= (int)k || r.flag_base + r.tiles > l.res_flags_per_part)
+                    return bail(hipErrorInvalidValue, "resident program does not fit the kernel's assumptions");
+            }
+            m->res_programs.push_back(std::move(prog));
+            const std::vector<ResLayer> &keep = m->res_programs.back();
+            if ((e = hipMemcpyAsync(at(l.w.offset), keep.data(), keep.size() * sizeof(ResLayer), hipMemcpyHostToDevice, st)) != hipSuccess)
+                return bail(e, "hipMemcpyAsync of a resident program");
+        }
     if ((e = hipEventRecord(c->staging_free, st)) != hipSuccess) return bail(e, "hipEventRecord");
     c->staging_used = true;
     if ((e = hipEventRecord(m->load_done, st)) != hipSuccess) return bail(e, "hipEventRecord");
@@ -912,6 +982,9 @@ int32_t cw_exec_duration_ns(cw_ctx *c, int32_t slot, uint64_t *ns) {
     float ms = 0.f;
     CW_HIP(c, hipEventElapsedTime(&ms, s.exec_start, s.exec_end));
     *ns = (uint64_t)((double)ms * 1e6 + 0.5);
+    if (c->res_error && *reinterpret_cast<volatile unsigned *>(c->res_error) != 0u)
+        return set_err(c, CW_ERR_HIP, *c->res_error == 2u ? "a resident launch found a workgroup on an unexpected XCD: results are invalid"
+                                                          : "a resident launch gave up waiting for a layer: results are invalid");
     return CW_OK;
 }
 

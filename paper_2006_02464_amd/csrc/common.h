@@ -24,6 +24,7 @@ enum Kind : int32_t {
     K_COPY_CHANNELS = 8,  // a tensor into a channel range of a wider one (CONCAT sources that cannot write there themselves)
     K_WINO_INPUT = 9,   // Winograd F(2x2, 3x3): input tiles -> 16 transformed matrices
     K_WINO_OUTPUT = 10, // ... 16 product matrices -> 2x2 output tiles, fused epilogue
+    K_RESIDENT = 11,    // a run of convolution layers as one launch of resident workgroups (kernels_resident.hip)
 };
 
 // Activation codes (cw_op.relu, ConvArgs.relu / relu2).
@@ -125,6 +126,55 @@ struct WinoArgs {
     int32_t B, H, W, C, th, tw, ldx, act;   // H, W: image size (= output size); C: channels of the tensor being transformed
 };
 
+// ---- resident multi-layer launch ---------------------------------------------------------------
+// A run of consecutive convolution layers executed by ONE launch of 256 workgroups that stay on
+// their CUs: the batch is cut into 8 partitions of B/8 images, partition p is computed by the 32
+// workgroups that run on XCD p, and a layer's tiles start as soon as the tiles of the layers it reads
+// (same partition, hence same XCD and same L2) have signalled completion through per-tile flags.
+// Tile shapes the resident kernel holds (all on 4 waves, so that one workgroup can run any of them):
+enum ResVariant : int32_t {
+    RV_128x128 = 0, RV_128x64, RV_64x64, RV_128x64k128, RV_64x64k128, RV_32x32k128g4, RV_32x32g4, N_RES_VARIANTS
+};
+struct ResVariantDim { int bm, bn, bk; };
+inline ResVariantDim res_variant_dim(int v) {
+    switch (v) {
+        case RV_128x128: return {128, 128, 64};
+        case RV_128x64: return {128, 64, 64};
+        case RV_64x64: return {64, 64, 64};
+        case RV_128x64k128: return {128, 64, 128};
+        case RV_64x64k128: return {64, 64, 128};
+        case RV_32x32k128g4: return {32, 32, 128};
+        default: return {32, 32, 64};
+    }
+}
+// One layer of the program (device memory).  a.x, a.res and a.y hold byte offsets into the workspace
+// of the tensors' first image, a.w and a.bias device addresses; partition p adds p * ps_*.
+struct alignas(64) ResLayer {
+    ConvArgs a;
+    long long ps_x, ps_y, ps_res;
+    int32_t variant;     // ResVariant; the addressing mode follows from the shape (1x1 stride 1: plain matrix)
+    int32_t tiles;       // per partition
+    int32_t dep[2];      // program indices of the layers that produce this layer's input and residual, or -1
+    int32_t flag_base;   // this layer's first completion flag within a partition's flags
+    int32_t pad_[3];
+};
+constexpr int kResPartitions = 8;          // = XCDs of the device
+constexpr int kResGroupsPerPartition = 32; // workgroups per partition = CUs per XCD
+// Workspace header behind the split-K counters: [epoch word at 0, abort word at byte 128 (holds the epoch of an
+// abandoned launch), unused up to 256 B][completion flags]
+constexpr size_t kResidentBytes = (size_t)1 << 20;
+constexpr size_t kResidentFlagsOff = 256;
+struct ResidentArgs {
+    const ResLayer *layers;   // device
+    int32_t n_layers;
+    char *workspace;          // base the layers' activation offsets are relative to
+    unsigned *flags;          // [kResPartitions][flags_per_part]
+    int32_t flags_per_part;
+    unsigned *epoch;          // flags equal to *epoch + 1 mean "done in this launch"
+    unsigned *error;          // host-visible word: set when a wait times out or a workgroup is on the wrong XCD
+    unsigned spin_limit;
+};
+
 struct CopyArgs {
     const void *src;    // [pixels][ld_src], the first C channels of every pixel are copied
     void *dst;          // [pixels][ld_dst] (already offset to the destination channel)
@@ -208,6 +258,10 @@ hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s);
 hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s);   // 2-byte elements, C % 8 == 0
+hipError_t launch_resident(DType dt, const ResidentArgs &a, hipStream_t s);   // + the epoch bump behind it
+// Host-side check of one program layer against what the resident kernel assumes (shapes, sizes,
+// tile counts); ws_bytes = size of the workspace its offsets must stay inside.
+bool resident_layer_ok(const ResLayer &l, size_t ws_bytes);
 hipError_t launch_wino_input(DType dt, const WinoArgs &a, hipStream_t s);
 hipError_t launch_wino_output(DType dt, const WinoArgs &a, hipStream_t s);
 // LOAD-time: canonical W[cout][cin][3][3] -> U[16][cout'][cin] = G g G^T per (cout, cin), rows in the

@@ -270,6 +270,33 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
     return CW_OK;
 }
 
+size_t model_reserve(Model *m, size_t bytes) {
+    size_t packed = m->packed_bytes;
+    if (packed % m->page_bytes + bytes > m->page_bytes) packed = align_up(packed, m->page_bytes);
+    const size_t at = packed;
+    m->packed_bytes = align_up(packed + bytes, 256);
+    m->n_pages = (int32_t)((m->packed_bytes + m->page_bytes - 1) / m->page_bytes);
+    return at;
+}
+
+// Tile shape of a layer inside a resident run: 32 workgroups share the partition's tiles in rounds,
+// a tile costs about max(load-path clocks, matrix-core clocks) per K element plus a fixed part.
+static int pick_res_variant(int64_t M, int64_t N, int64_t K, int32_t cin) {
+    int best = RV_64x64;
+    double best_cost = 1e30;
+    for (int v = 0; v < N_RES_VARIANTS; ++v) {
+        const ResVariantDim d = res_variant_dim(v);
+        if (cin % d.bk != 0 || (d.bn > N && d.bn > 32)) continue;
+        const int64_t tiles = ((M + d.bm - 1) / d.bm) * ((N + d.bn - 1) / d.bn);
+        const int64_t rounds = (tiles + kResGroupsPerPartition - 1) / kResGroupsPerPartition;
+        const double load_clk = (double)(d.bm + d.bn) * 2.0 / 64.0;       // bytes per K element over 64 B/clock
+        const double mfma_clk = (double)d.bm * d.bn * 2.0 / 4096.0 * (d.bm <= 32 ? 2.0 : 1.0);   // small wave tiles issue at about half rate
+        const double cost = (double)rounds * ((double)K * std::max(load_clk, mfma_clk) * 1.4 + 2500.0);
+        if (cost < best_cost) { best_cost = cost; best = v; }
+    }
+    return best;
+}
+
 // ---------------------------------------------------------------- tile choice
 // A measured shape takes its tile and split from the table.  Otherwise: the largest tile that
 // still gives every CU at least one workgroup; below that, a 64x64 (or narrower) tile with K
@@ -342,8 +369,12 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // Pairs planned as one launch: op i = a convolution with 64 or 128 output channels (Cin % 64
     // == 0, activation, no residual) whose only consumer is op j = i+1 or i+2, a 1x1 stride-1
     // convolution with a residual; enough pixels for the launch to fill the GPU.
+    // Resident runs: plain convolution launches only (the layers meet in the XCD's L2 anyway), every
+    // tensor in a region of its own (a tensor is written once per launch, so no cache holds an old copy).
+    const bool resident = ov.resident && batch % kResPartitions == 0 && ov.tile < 0 && ov.split_k <= 0 && !m.winograd;
+    const bool no_reuse = ov.keep_all || resident;
     std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), fused_kg(n_ops, 1), proj_of(n_ops, -1);
-    if (ov.fuse && ov.tile < 0 && ov.split_k <= 0) {
+    if (ov.fuse && !resident && ov.tile < 0 && ov.split_k <= 0) {
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
             if (m.ops[i].input_from >= 0) ++uses[m.ops[i].input_from];
@@ -391,7 +422,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     {
         std::vector<char> moved(n_ops, 0);
         std::vector<int> partner(n_ops, -1);
-        if (ov.pair && ov.tile < 0 && ov.split_k <= 0) {
+        if (ov.pair && !resident && ov.tile < 0 && ov.split_k <= 0) {
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
                 if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
@@ -489,8 +520,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         out_bytes[i] = r == i ? root_bytes : 0;   // members are never freed on their own
     };
 
-    // the split-K arrival counters live at the very start of the workspace, never reused
+    // the split-K arrival counters live at the very start of the workspace, never reused; behind
+    // them the epoch word and completion flags of resident launches
     (void)ws_alloc(kCounterBytes);
+    (void)ws_alloc(kResidentBytes);
 
     // input cast: fp32 NCHW in the IO slot -> NHWC4 in the workspace, inside a zero border as wide
     // as the first convolution's padding (that convolution then runs unpadded over the larger image)
@@ -803,7 +836,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         if (partial_bytes) arena.free(partial_off, partial_bytes);
         for (int k = 0; k < 2; ++k)
             if (tmp_bytes[k]) arena.free(tmp_off[k], tmp_bytes[k]);
-        if (!ov.keep_all) {
+        if (!no_reuse) {
             if (i == 0) arena.free(cast_off, cast_bytes);
             for (int j = 0; j < n_ops; ++j) {
                 if (pos[j] > t) continue;
@@ -820,7 +853,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // (in a ResNet: the first 1x1 of a block and the projection shortcut beside it) become one
     // launch on one tile shape: that of the one with more work, if the pair kernel has it and the
     // other is at least a tile wide.
-    if (ov.pair && ov.tile < 0 && ov.split_k <= 0) {
+    if (ov.pair && !resident && ov.tile < 0 && ov.split_k <= 0) {
         for (size_t i = 0; i + 1 < p.launches.size(); ++i) {
             Launch &l0 = p.launches[i], &l1 = p.launches[i + 1];
             if (l0.kind != K_CONV || l1.kind != K_CONV || l0.stem || l1.stem || l0.fused_bm > 0 || l1.fused_bm > 0) continue;
@@ -853,6 +886,72 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             p.launches.erase(p.launches.begin() + i + 1);
         }
     }
+    // Resident runs: every maximal run of two or more plain convolution launches (direct-to-LDS
+    // kernel, whole K per workgroup) becomes one launch whose members keep partition 0's arguments.
+    if (resident) {
+        auto eligible = [&](const Launch &l) {
+            return l.kind == K_CONV && !l.stem && l.fused_bm == 0 && l.pair_op < 0 && l.conv.nz <= 1 && l.conv.Cin % 64 == 0 &&
+                   l.conv.kwp == l.conv.kw && l.conv.khp == l.conv.kh;
+        };
+        std::vector<Launch> out;
+        for (size_t i = 0; i < p.launches.size();) {
+            size_t j = i;
+            while (j < p.launches.size() && eligible(p.launches[j])) ++j;
+            if (j - i < 2) {
+                for (size_t k = i; k < std::max(j, i + 1); ++k) out.push_back(p.launches[k]);
+                i = std::max(j, i + 1);
+                continue;
+            }
+            Launch r{};
+            r.kind = K_RESIDENT;
+            r.op_index = p.launches[j - 1].op_index;
+            std::vector<int> member_of(n_ops, -1);
+            int flag_base = 0;
+            for (size_t k = i; k < j; ++k) {
+                Launch mlaunch = p.launches[k];
+                const cw_op &o = m.ops[mlaunch.op_index];
+                ConvArgs &a = mlaunch.conv;
+                a.B = batch / kResPartitions;
+                a.M = a.B * a.Ho * a.Wo;
+                const int v = pick_res_variant(a.M, a.Cout, a.K, a.Cin);
+                const ResVariantDim d = res_variant_dim(v);
+                a.split_k = 1;
+                a.ktiles_per_split = a.K / d.bk;
+                mlaunch.partial = Ref{};
+                mlaunch.counters = Ref{};
+                mlaunch.res_variant = v;
+                mlaunch.res_tiles = ((a.M + d.bm - 1) / d.bm) * ((a.Cout + d.bn - 1) / d.bn);
+                mlaunch.res_ps_x = (long long)a.B * a.H * a.W * conv_ldx(a) * (long long)esz;
+                mlaunch.res_ps_y = (long long)a.M * conv_ldy(a) * (long long)esz;
+                mlaunch.res_ps_res = (long long)a.M * a.Cout * (long long)esz;
+                mlaunch.res_dep[0] = o.input_from >= 0 ? member_of[o.input_from] : -1;
+                mlaunch.res_dep[1] = o.residual_from >= 0 ? member_of[o.residual_from] : -1;
+                mlaunch.res_flag_base = flag_base;
+                flag_base += mlaunch.res_tiles;
+                mlaunch.info.tile_m = d.bm; mlaunch.info.tile_n = d.bn; mlaunch.info.tile_k = d.bk; mlaunch.info.split_k = 1;
+                member_of[mlaunch.op_index] = (int)r.members.size();
+                r.info.flops += mlaunch.info.flops;
+                r.info.bytes += (int64_t)a.M * kResPartitions * 0 + mlaunch.info.bytes;
+                r.members.push_back(mlaunch);
+            }
+            r.res_flags_per_part = flag_base;
+            if ((size_t)kResPartitions * flag_base * 4 > kResidentBytes - kResidentFlagsOff)
+                return fail(err, CW_ERR_NO_MEMORY, "batch %d: a resident run needs more completion flags than the workspace header holds", batch);
+            // split-K members counted their partial sums; a resident member walks the whole K itself
+            r.info.bytes = 0;
+            for (const Launch &ml : r.members) {
+                const cw_op &o = m.ops[ml.op_index];
+                const ConvArgs &a = ml.conv;
+                const int64_t Mfull = (int64_t)a.M * kResPartitions;
+                const int64_t in_pixels = (o.kh == 1 && o.stride > 1) ? Mfull : (int64_t)batch * a.H * a.W;
+                r.info.bytes += in_pixels * o.cin * (int64_t)esz + (int64_t)o.cout * a.K * (int64_t)esz + o.cout * 4 + Mfull * o.cout * (int64_t)esz * (o.residual_from >= 0 ? 2 : 1);
+            }
+            snprintf(r.info.name, sizeof r.info.name, "resident_%dconvs", (int)r.members.size());
+            out.push_back(r);
+            i = j;
+        }
+        p.launches.swap(out);
+    }
     // grid/block of every launch, for introspection
     for (Launch &l : p.launches) {
         dim3 g(1, 1, 1);
@@ -870,6 +969,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
             case K_DWCONV: g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256)); b = 256; break;
             case K_COPY_CHANNELS: g = dim3((unsigned)(((size_t)l.copy.pixels * (l.copy.C / 8) + 255) / 256)); b = 256; break;
+            case K_RESIDENT: g = dim3(kResPartitions * kResGroupsPerPartition); b = 256; break;
             case K_WINO_INPUT:
             case K_WINO_OUTPUT: g = dim3((unsigned)(((size_t)l.wino.B * l.wino.th * l.wino.tw * (l.wino.C / 8) + 255) / 256)); b = 256; break;
         }

@@ -46,6 +46,13 @@ struct Launch {
     Ref w0, bias0, res0, y0;
     int64_t in_bytes = 0;  // algorithmic bytes of the input tensor (counted once in a pair)
     cw_launch_info info{};
+    // K_RESIDENT: the convolution layers of the run, each with partition 0's arguments (conv), its
+    // tile shape (res_variant), tiles per partition and the members it waits for; `w` of the
+    // resident launch itself points at the program's place in the model's weight pages.
+    std::vector<Launch> members;
+    int32_t res_variant = 0, res_tiles = 0, res_dep[2] = {-1, -1}, res_flag_base = 0;
+    long long res_ps_x = 0, res_ps_y = 0, res_ps_res = 0;
+    int32_t res_flags_per_part = 0;
 };
 
 struct OpShape {
@@ -87,6 +94,7 @@ struct PlanOverride {
     int32_t fuse = 1;      // two-layer launches: 0 = none, 1 = yes, 2 = yes but never with two wave groups
     bool pair = true;      // two convolutions over one tensor as one launch
     bool winograd = false; // 3x3 stride-1 pad-1 convolutions through Winograd F(2x2, 3x3)
+    bool resident = false; // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0)
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 
@@ -113,6 +121,8 @@ int32_t model_init(Model *m, const cw_op *ops, int32_t n_ops, int32_t in_c, int3
                    int32_t dtype, size_t page_bytes, bool winograd, std::string *err);
 // Compiles the plan of one batch size.
 int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err);
+// Appends `bytes` to the model's packed layout (same page rule as the weights); returns the offset.
+size_t model_reserve(Model *m, size_t bytes);
 // Operator list of ResNet-18/50/152.
 bool resnet_ops(int32_t depth, std::vector<cw_op> *ops);
 

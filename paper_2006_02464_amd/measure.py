@@ -4,6 +4,8 @@
   python -m paper_2006_02464_amd.measure --config 4   ResNet-152, bf16, batch 16: throughput and latency
   python -m paper_2006_02464_amd.measure --config 5   64 resident ResNet-50s, Poisson arrivals, mixed batch sizes
   python -m paper_2006_02464_amd.measure --config 6   INFER actions with earliest/latest through the worker's executors
+  python -m paper_2006_02464_amd.measure --config 7   the other Table-1 families (MobileNet-, DenseNet-, Inception-style
+                                                      operator lists): EXEC latency and every launch against its roofline
 
 Each prints one JSON object.  All inputs are synthetic (seeded, workload/gen.py); EXEC time depends
 on the values only through power and clocks (a few percent), so every profile is taken over seeded images.  Durations are on-device (the event pair around every EXEC); the host thread
@@ -207,13 +209,17 @@ def config5(args, log):
 def config6(args, log):
     """A schedule of INFER actions as a controller would send it (paper sections 4.4, 5.2): one ResNet-50,
     batch 16, action i may begin at t0 + i * period with period = 1.15 x the measured EXEC p50 and must
-    have begun 1 ms later.  Reports how punctually EXEC begins, what the executors add around the
-    on-device time, and how many actions the window rejected."""
+    have begun 1 ms later.  Beside them a second ResNet-50 is unloaded and loaded again every 100 INFERs
+    (the controller's LOAD / UNLOAD actions, which section 5.2 runs next to EXEC).  Reports how
+    punctually EXEC begins (all actions, and those whose window overlaps a LOAD), what the executors
+    add around the on-device time, how long a LOAD occupies its executor, and how many actions the
+    window rejected."""
     import torch
-    from .binding import CW_ACTION_INFER, CW_ACTION_LOAD, Executors
+    from .binding import CW_ACTION_INFER, CW_ACTION_LOAD, CW_ACTION_UNLOAD, Executors
     from .runner import Worker, pinned_like
     from workload import gen
     B, n = 16, args.requests if args.requests != 10000 else 2000
+    every = 100
     wk = Worker(workspace_bytes=512 << 20, io_bytes=512 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20)
     ctx = wk.ctx
     mid = ctx.model_define_resnet(50, 224, 224, "fp16")
@@ -225,6 +231,22 @@ def config6(args, log):
     p50 = ctx.profile_measure(mid, B, 300, slot=s_p)["p50_us"]
     ctx.release(s_p)
     ctx.unload_weights(mid)
+    other = ctx.model_define_resnet(50, 224, 224, "fp16")
+    blob2 = pinned_like(resnet_blob(ctx, other, 1, "fp16"))
+    # How long the LOAD call itself keeps the context (it only enqueues the copies and pack kernels
+    # and records the plans' graphs; the executors issue nothing else meanwhile): first LOAD, LOAD
+    # into the same pages again, LOAD into other pages.
+    import time
+    call_ms = []
+    for k in range(3):
+        if k == 2:
+            ctx.load_weights(mid, blob, wk.stream)           # takes the lowest pages, so `other` lands elsewhere
+        t_a = time.perf_counter()
+        ctx.load_weights(other, blob2, wk.stream)
+        call_ms.append(round((time.perf_counter() - t_a) * 1e3, 3))
+        wk.stream.synchronize()
+        ctx.unload_weights(other)
+    ctx.unload_weights(mid)
     ex = Executors(ctx)
     probs = [torch.empty((B, 1000), dtype=torch.float32, pin_memory=True) for _ in range(32)]
     now = ex.now_ns()
@@ -232,25 +254,49 @@ def config6(args, log):
     load = ex.next_result(10.0)
     period = int(p50 * 1.15 * 1e3)
     t0 = ex.now_ns() + 20_000_000
-    res, sent = [], 0
-    while len(res) < n:
+    res, loads, unloads, sent, side, side_out = [], [], [], 0, 0, 0
+    LOAD_ID, UNLOAD_ID = 1 << 20, 1 << 21
+    while len(res) < n or side_out:
         while sent < n and sent - len(res) < 24:                 # a controller keeps a short queue ahead
+            if sent % every == every // 2:                        # the other model goes out and comes back in
+                at = t0 + sent * period
+                if side:
+                    ex.submit(UNLOAD_ID + side, CW_ACTION_UNLOAD, other, at, at + 50_000_000)
+                    side_out += 1
+                ex.submit(LOAD_ID + side, CW_ACTION_LOAD, other, at + (100_000 if side else 0), at + 50_000_000, host_in=blob2)
+                side, side_out = side + 1, side_out + 1
             ex.submit(sent, CW_ACTION_INFER, mid, t0 + sent * period, t0 + sent * period + 1_000_000, batch=B, host_in=x,
                       host_probs=probs[sent % 32])
             sent += 1
         r = ex.next_result(10.0)
         assert r is not None
-        res.append(r)
+        if r["id"] >= UNLOAD_ID:
+            unloads.append(r); side_out -= 1
+        elif r["id"] >= LOAD_ID:
+            loads.append(r); side_out -= 1
+        else:
+            res.append(r)
     ex.destroy()
     wk.close()
     ok = [r for r in res if r["status"] == 0]
     late = [(r["begin_ns"] - (t0 + r["id"] * period)) / 1e3 for r in ok]
+    spans = [(l["begin_ns"], l["end_ns"] + int(l["device_ns"])) for l in loads if l["status"] == 0]
+    beside = [(r["begin_ns"] - (t0 + r["id"] * period)) / 1e3 for r in ok
+              if any(a - period <= t0 + r["id"] * period <= b for a, b in spans)]
+    dev_beside = [r["device_ns"] / 1e3 for r in ok if any(a - period <= t0 + r["id"] * period <= b for a, b in spans)]
     over = [((r["end_ns"] - r["begin_ns"]) - r["device_ns"]) / 1e3 for r in ok]
     dev = [r["device_ns"] / 1e3 for r in ok]
     span = (max(r["end_ns"] for r in res) - t0) / 1e9
     return {"config": 6, "workload": "ResNet-50 fp16 batch 16: %d INFER actions through the executors, action i may begin at "
                                      "t0 + i x %.1f us (1.15 x EXEC p50 of %.1f us), window 1 ms" % (n, period / 1e3, p50),
             "load_action": {"status": load["status"], "host_ms": round((load["end_ns"] - load["begin_ns"]) / 1e6, 3), "device_ms": round(load["device_ns"] / 1e6, 3)},
+            "load_call_host_ms": {"first": call_ms[0], "same_pages_again": call_ms[1], "other_pages": call_ms[2]},
+            "side_actions": {"loads": len(loads), "loads_ok": sum(l["status"] == 0 for l in loads), "unloads_ok": sum(u["status"] == 0 for u in unloads),
+                             "load_host_ms": summary([(l["end_ns"] - l["begin_ns"]) / 1e6 for l in loads]) if loads else None,
+                             "load_device_ms": summary([l["device_ns"] / 1e6 for l in loads]) if loads else None,
+                             "infer_beside_a_load": len(beside),
+                             "begin_after_earliest_us_beside_a_load": {"p50": round(pct(beside, 0.5), 1), "p99": round(pct(beside, 0.99), 1), "max": round(max(beside), 1)} if beside else None,
+                             "exec_device_us_beside_a_load": summary(dev_beside) if dev_beside else None},
             "executed": len(ok), "rejected_too_late": sum(r["status"] == -11 for r in res),
             "begin_after_earliest_us": {"p50": round(pct(late, 0.5), 1), "p99": round(pct(late, 0.99), 1), "max": round(max(late), 1)},
             "exec_device_us": summary(dev),
@@ -258,9 +304,118 @@ def config6(args, log):
             "inferences_per_s": round(B * len(ok) / span, 1)}
 
 
+# The operator lists of the other families, written out here for the library (the test suite holds
+# its own copies on the oracle's side): (op, cin, cout, kh, kw, stride, pad, act, residual_from,
+# input_from, pad_w, groups); op 0 conv, 1 max pool, 2 global average pool, 3 FC, 4 softmax, 5 concat.
+def _tail(ops, cin, classes=1000):
+    ops.append((2, cin, cin, 0, 0, 1, 0, 0, -1, len(ops) - 1, 0, 0))
+    ops.append((3, cin, classes, 1, 1, 1, 0, 0, -1, len(ops) - 1, 0, 0))
+    ops.append((4, classes, classes, 0, 0, 1, 0, 0, -1, len(ops) - 1, 0, 0))
+    return ops
+
+
+def mobilenet_ops():
+    cfg = [(64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2)] + [(512, 1)] * 5 + [(1024, 2), (1024, 1)]
+    ops, cin = [(0, 3, 32, 3, 3, 2, 1, 1, -1, -1, 0, 0)], 32
+    for i, (cout, stride) in enumerate(cfg):
+        act, block_in = (2 if i >= 7 else 1), len(ops) - 1
+        ops.append((0, cin, cin, 3, 3, stride, 1, act, -1, block_in, 0, cin))
+        ops.append((0, cin, cout, 1, 1, 1, 0, act, block_in if (stride == 1 and cin == cout) else -1, len(ops) - 1, 0, 0))
+        cin = cout
+    return _tail(ops, cin)
+
+
+def dense_ops(layers=(6, 12), growth=32, bottleneck=128, stem=64):
+    ops = [(0, 3, stem, 7, 7, 2, 3, 1, -1, -1, 0, 0), (1, stem, stem, 3, 3, 2, 1, 0, -1, 0, 0, 0)]
+    cin = stem
+    for b, n in enumerate(layers):
+        cur = len(ops) - 1
+        for _ in range(n):
+            ops.append((0, cin, bottleneck, 1, 1, 1, 0, 1, -1, cur, 0, 0))
+            ops.append((0, bottleneck, growth, 3, 3, 1, 1, 1, -1, len(ops) - 1, 0, 0))
+            ops.append((5, cin, cin + growth, 0, 0, 1, 0, 0, len(ops) - 1, cur, 0, 0))
+            cur, cin = len(ops) - 1, cin + growth
+        if b + 1 < len(layers):
+            ops.append((0, cin, cin // 2, 1, 1, 1, 0, 1, -1, cur, 0, 0))
+            cin //= 2
+            ops.append((1, cin, cin, 2, 2, 2, 0, 0, -1, len(ops) - 1, 0, 0))
+    return _tail(ops, cin)
+
+
+def inception_ops(width=256, blocks=2):
+    ops = [(0, 3, 32, 3, 3, 2, 1, 1, -1, -1, 0, 0), (0, 32, width, 3, 3, 2, 1, 1, -1, 0, 0, 0)]
+    for _ in range(blocks):
+        x = len(ops) - 1
+        ops.append((0, width, width, 1, 1, 1, 0, 1, -1, x, 0, 0))
+        a = len(ops) - 1
+        ops.append((0, width, width, 1, 1, 1, 0, 1, -1, x, 0, 0))
+        ops.append((0, width, width, 1, 7, 1, 0, 1, -1, len(ops) - 1, 3, 0))
+        ops.append((0, width, width, 7, 1, 1, 3, 1, -1, len(ops) - 1, 0, 0))
+        ops.append((5, width, 2 * width, 0, 0, 1, 0, 0, len(ops) - 1, a, 0, 0))
+        ops.append((0, 2 * width, width, 1, 1, 1, 0, 1, x, len(ops) - 1, 0, 0))
+    return _tail(ops, width)
+
+
+def config7(args, log):
+    """EXEC latency per batch size and the per-launch table at batch 16 of the three other families."""
+    from .runner import Worker, pinned_like
+    from workload import gen
+    wk = Worker(workspace_bytes=1 << 30, io_bytes=256 << 20, weight_pool_bytes=512 << 20, load_staging_bytes=128 << 20)
+    ctx, ex = wk.ctx, wk.stream
+    out = {"config": 7, "families": {}}
+    tables = []
+    for name, ops, hw in (("mobilenet", mobilenet_ops(), 224), ("densenet-style", dense_ops(), 224), ("inception-style", inception_ops(), 224)):
+        mid = ctx.model_define(ops, 3, hw, hw)
+        shapes = [(o[2], o[1] // max(1, o[11]), o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
+        w, b = gen.model_tensors(shapes, 0, "fp16")
+        ctx.load_weights(mid, pinned_like(gen.pack_blob(w, b, "fp16")), ex)
+        ex.synchronize()
+        fam = {"params": int(sum(int(np.prod(s)) + s[0] for s in shapes)), "exec": {}}
+        for B in (1, 4, 16):
+            slot = ctx.input(mid, B, pinned_like(gen.images(0, 0, B, 3, hw, hw, "normal", "fp16")), ex)
+            ctx.profile_measure(mid, B, 50, slot=slot)
+            p = ctx.profile_measure(mid, B, 1000, slot=slot)
+            fam["exec"][str(B)] = {"p50_us": round(p["p50_us"], 2), "p999_over_p50": round(p["p999_us"] / p["p50_us"], 4),
+                                   "inferences_per_s": round(B / (p["p50_us"] * 1e-6), 1), "launches": ctx.plan_num_launches(mid, B)}
+            if B == 16:
+                plan = ctx.plan(mid, B)
+                ctx.set_use_graphs(0)
+                whole = []
+                for _ in range(60):
+                    ctx.exec(mid, B, slot, ex)
+                    whole.append(ctx.exec_duration_ns(slot) / 1e3)
+                raw = np.median(np.stack([ctx.exec_timed_launches(mid, B, slot, ex, inner=1) for _ in range(60)]), axis=0)
+                ctx.set_use_graphs(1)
+                over = (float(raw.sum()) - float(np.median(whole[10:]))) / len(plan)
+                us = raw - over
+                groups = {}
+                for l, u in zip(plan, us):
+                    key = l["name"].split("_s")[0] if l["name"].startswith(("dwconv", "conv")) else l["name"]
+                    g = groups.setdefault(key, [0, 0.0, 0, 0])
+                    g[0] += 1; g[1] += float(u); g[2] += l["bytes"]; g[3] += l["flops"]
+                fam["by_kernel_b16"] = {k: {"launches": v[0], "us": round(v[1], 1), "GBps": round(v[2] / (v[1] * 1e-6) / 1e9, 0),
+                                            "TFLOPs": round(v[3] / (v[1] * 1e-6) / 1e12, 1), "frac_of_8TBps": round(v[2] / (v[1] * 1e-6) / 8e12, 3)}
+                                        for k, v in groups.items()}
+                tables.append("== %s, %dx%d, batch 16: every launch (us net of %.2f us event overhead)" % (name, hw, hw, over))
+                tables.append("%-26s %9s %6s %6s %8s %8s %8s %8s" % ("launch", "M", "N", "K", "MB", "us", "GB/s", "TFLOP/s"))
+                for l, u in zip(plan, us):
+                    tables.append("%-26s %9d %6d %6d %8.2f %8.2f %8.0f %8.1f" % (l["name"], l["gemm_m"], l["gemm_n"], l["gemm_k"], l["bytes"] / 1e6, u,
+                                                                                   l["bytes"] / (u * 1e-6) / 1e9, l["flops"] / (u * 1e-6) / 1e12))
+            ctx.release(slot)
+        ctx.unload_weights(mid)
+        out["families"][name] = fam
+        log("%s: %s" % (name, fam["exec"]))
+    wk.close()
+    if args.table_out:
+        with open(args.table_out, "w") as f:
+            f.write("\n".join(tables) + "\n")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5, 6))
+    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5, 6, 7))
+    ap.add_argument("--table-out", default="", help="config 7: write the per-launch tables here")
     ap.add_argument("--execs", type=int, default=2000)
     ap.add_argument("--loads-per-round", type=int, default=6, help="config 3: LOADs queued per 20 EXECs")
     ap.add_argument("--requests", type=int, default=10000)
@@ -280,7 +435,7 @@ def main():
             make(self, **kw)
             self.ctx.set_use_graphs(args.graphs)
         runner.Worker.__init__ = patched
-    out = {3: config3, 4: config4, 5: config5, 6: config6}[args.config](args, log)
+    out = {3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[args.config](args, log)
     print(json.dumps(out), flush=True)
 
 
