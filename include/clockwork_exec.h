@@ -157,6 +157,27 @@ size_t cw_model_workspace_bytes(cw_ctx *ctx, int32_t model_id, int32_t batch);
  * `bytes` must equal cw_model_weight_bytes(). */
 int32_t cw_load_weights(cw_ctx *ctx, int32_t model_id, const void *host_blob,
                         size_t bytes, void *stream);
+/* The same LOAD in steps, for a caller whose threads share one context under a lock of their
+ * own (the worker's executors, section 5.2: LOAD runs beside EXEC), so that the lock is held
+ * only while work is enqueued:
+ *   cw_load_weights_begin    takes the pages and enqueues the copy and the re-layout on `stream`;
+ *                            the model counts as resident from here on (an EXEC waits for the
+ *                            copy on its own stream) and runs with plain launches until the end
+ *                            step.  Serialise with the other calls on the context.
+ *   cw_load_weights_record   records the plans' HIP graphs for the pages taken.  Host work of a few
+ *                            milliseconds, nothing executes.  May run while other threads call
+ *                            into the same context; only one recording at a time per context.
+ *   cw_load_weights_end      installs the recorded graphs (nothing if the model has been unloaded
+ *                            meanwhile).  Serialise with the other calls on the context.
+ *   cw_load_weights_release  destroys `pending` and the graphs the new ones displaced.  Needs no
+ *                            serialisation.  Always call it once for a `pending` that begin returned.
+ * cw_load_weights() is these four in a row.  `*pending` is NULL when begin fails. */
+typedef struct cw_load_pending cw_load_pending;
+int32_t cw_load_weights_begin(cw_ctx *ctx, int32_t model_id, const void *host_blob, size_t bytes,
+                              void *stream, cw_load_pending **pending);
+int32_t cw_load_weights_record(cw_ctx *ctx, cw_load_pending *pending);
+int32_t cw_load_weights_end(cw_ctx *ctx, cw_load_pending *pending);
+void    cw_load_weights_release(cw_load_pending *pending);
 /* Metadata only; succeeds whether or not the model is resident (section 5.2).  The pages go
  * back to the free list at once; an EXEC of the model that is still queued or running keeps
  * reading them safely, because the next LOAD that takes one of them makes its stream wait for

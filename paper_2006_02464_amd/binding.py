@@ -71,6 +71,10 @@ SIGNATURES = {
     "cw_model_weight_bytes": (c_size_t, [c_void_p, c_int32]),
     "cw_model_workspace_bytes": (c_size_t, [c_void_p, c_int32, c_int32]),
     "cw_load_weights": (c_int32, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p]),
+    "cw_load_weights_begin": (c_int32, [c_void_p, c_int32, c_void_p, c_size_t, c_void_p, POINTER(c_void_p)]),
+    "cw_load_weights_record": (c_int32, [c_void_p, c_void_p]),
+    "cw_load_weights_end": (c_int32, [c_void_p, c_void_p]),
+    "cw_load_weights_release": (None, [c_void_p]),
     "cw_unload_weights": (c_int32, [c_void_p, c_int32]),
     "cw_weight_pool_free": (c_size_t, [c_void_p]),
     "cw_weight_pages_free": (c_int32, [c_void_p]),
@@ -220,6 +224,22 @@ class Context:
     def load_weights(self, model_id, host_blob, stream=None):
         nbytes = host_blob.nbytes if isinstance(host_blob, np.ndarray) else host_blob.numel() * host_blob.element_size()
         self._check(lib().cw_load_weights(self._h, model_id, _ptr(host_blob), nbytes, _stream(stream)))
+
+    def load_weights_begin(self, model_id, host_blob, stream=None):
+        """First step of a LOAD in steps; returns the handle the other three steps take."""
+        nbytes = host_blob.nbytes if isinstance(host_blob, np.ndarray) else host_blob.numel() * host_blob.element_size()
+        pending = c_void_p()
+        self._check(lib().cw_load_weights_begin(self._h, model_id, _ptr(host_blob), nbytes, _stream(stream), ctypes.byref(pending)))
+        return pending
+
+    def load_weights_record(self, pending):
+        self._check(lib().cw_load_weights_record(self._h, pending))
+
+    def load_weights_end(self, pending):
+        self._check(lib().cw_load_weights_end(self._h, pending))
+
+    def load_weights_release(self, pending):
+        lib().cw_load_weights_release(pending)
 
     def unload_weights(self, model_id):
         self._check(lib().cw_unload_weights(self._h, model_id))

@@ -38,8 +38,19 @@ struct Slot {
 struct PlanGraph {
     hipGraphExec_t exec = nullptr;
     size_t first = 0, last = 0;  // launches [first, last] are inside the graph
-    std::vector<int32_t> pages;  // weight placement the graph was captured for
 };
+
+// The graphs of a model's plans for one placement of its weights.  A model keeps the sets of the
+// last few placements it had: coming back into pages it has been in before needs no recording,
+// and no graph is destroyed while the worker runs unless a model moves through more than
+// kMaxGraphSets placements (destroying one was measured at about a millisecond, during which other
+// threads' launches stall).
+struct GraphSet {
+    std::vector<int32_t> pages;    // weight placement the graphs were captured for
+    std::vector<PlanGraph> plans;  // parallel to m.plans
+    uint64_t last_used = 0;        // LOAD counter value when it was last the active set
+};
+constexpr size_t kMaxGraphSets = 8;
 
 struct ModelRt {
     Model m;
@@ -47,7 +58,8 @@ struct ModelRt {
     std::vector<int32_t> pages;  // pool page of each of the model's weight pages while resident
     hipEvent_t load_done = nullptr;
     hipEvent_t last_exec_end = nullptr;  // end event of the last EXEC issued on these weights (a slot's event; not owned)
-    std::vector<PlanGraph> graphs;  // parallel to m.plans
+    std::vector<GraphSet> graph_sets;  // at most kMaxGraphSets
+    int active_set = -1;               // the set recorded for `pages`, if there is one
     std::vector<std::vector<ResLayer>> res_programs;  // host copies of the resident programs uploaded by the last LOAD
 };
 
@@ -82,6 +94,16 @@ hipError_t scratch_address(int device, char **out) {
 }
 }  // namespace
 
+// A LOAD between its begin and its end: the placement it took and the graphs recorded for it.
+struct cw_load_pending {
+    int32_t model_id = -1;
+    std::vector<int32_t> pages;     // the model's pages as the LOAD took them
+    std::vector<char> want;         // per plan: record a graph for this placement
+    std::vector<PlanGraph> graphs;  // recorded, then (after the end) the ones to destroy
+    int32_t status = CW_OK;
+    std::string err;
+};
+
 struct cw_ctx {
     int device = -1;       // -1: planning-only context without a GPU
     char *static_scratch = nullptr;  // this GPU's copy of `scratch`
@@ -97,6 +119,7 @@ struct cw_ctx {
     hipStream_t internal_stream = nullptr;
     hipStream_t capture_stream = nullptr;  // only ever used to record graphs
     bool use_graphs = true;
+    uint64_t load_counter = 0;             // orders the graph sets of a model by last use
     hipEvent_t staging_free = nullptr;  // last LOAD's pack kernels are done with the staging area
     bool staging_used = false;
     hipEvent_t prof_ev[2 * kProfileEvents] = {};
@@ -154,11 +177,13 @@ Plan *get_plan(ModelRt *m, int32_t batch) {
 // caller's own device buffers).
 struct Bases {
     char *workspace = nullptr, *input = nullptr, *logits = nullptr, *probs = nullptr;
+    const int32_t *pages = nullptr;  // pool page of each of the model's weight pages
 };
 
-Bases bases_of(const cw_ctx *c, const Slot *s) {
+Bases bases_of(const cw_ctx *c, const ModelRt *m, const Slot *s) {
     Bases b;
     b.workspace = c->workspace;
+    b.pages = m->pages.data();
     if (s) { b.input = c->io + s->in_off; b.logits = c->io + s->logits_off; b.probs = c->io + s->probs_off; }
     return b;
 }
@@ -166,7 +191,7 @@ Bases bases_of(const cw_ctx *c, const Slot *s) {
 char *resolve(cw_ctx *c, const ModelRt *m, const Bases &b, const Ref &r) {
     switch (r.space) {
         case SP_WORKSPACE: return b.workspace + r.offset;
-        case SP_WEIGHTS: return c->pool + (size_t)m->pages[r.offset / c->page_bytes] * c->page_bytes + r.offset % c->page_bytes;
+        case SP_WEIGHTS: return c->pool + (size_t)b.pages[r.offset / c->page_bytes] * c->page_bytes + r.offset % c->page_bytes;
         case SP_SLOT_INPUT: return b.input;
         case SP_SLOT_LOGITS: return b.logits;
         case SP_SLOT_PROBS: return b.probs;
@@ -372,20 +397,31 @@ bool slot_free(const Launch &l) {
     return true;
 }
 
-void destroy_graphs(ModelRt *m) {
-    for (PlanGraph &g : m->graphs)
+void destroy_graphs(std::vector<PlanGraph> &graphs) {
+    for (PlanGraph &g : graphs)
         if (g.exec) { (void)hipGraphExecDestroy(g.exec); g.exec = nullptr; }
 }
 
-// Records the slot-independent run of launches of every plan into a graph.  Host work only:
-// nothing executes.  Called at LOAD, when the weights' place in the pool is known.
-int32_t build_graphs(cw_ctx *c, ModelRt *m) {
-    m->graphs.resize(m->m.plans.size());
+// Records the slot-independent run of launches of every plan for which `want[pi]` is set into a
+// graph whose kernel arguments hold the weight addresses of the placement `pages`.  Host work only:
+// nothing executes.  Reads the context's constants, the model's plans (fixed once it is defined)
+// and its own arguments, nothing else: it may run beside other calls on the same context, one
+// recording at a time (there is one capture stream).
+int32_t record_graphs(cw_ctx *c, const ModelRt *m, const std::vector<int32_t> &pages, const std::vector<char> &want,
+                      std::vector<PlanGraph> *out, std::string *err) {
+    out->clear();
+    out->resize(m->m.plans.size());
+    Bases b;
+    b.workspace = c->workspace;
+    b.pages = pages.data();
+    auto fail = [&](hipError_t e, const char *what) {
+        *err = std::string(what) + ": " + hipGetErrorString(e);
+        return CW_ERR_HIP;
+    };
     for (size_t pi = 0; pi < m->m.plans.size(); ++pi) {
+        if (!want[pi]) continue;
         const Plan &p = m->m.plans[pi];
-        PlanGraph &pg = m->graphs[pi];
-        if (pg.exec && pg.pages == m->pages) continue;  // still valid from an earlier LOAD into the same pages
-        if (pg.exec) { (void)hipGraphExecDestroy(pg.exec); pg.exec = nullptr; }
+        PlanGraph &pg = (*out)[pi];
         // longest run of slot-independent launches
         size_t best_a = 0, best_n = 0, a = 0;
         for (size_t i = 0; i <= p.launches.size(); ++i) {
@@ -396,20 +432,19 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
         }
         if (best_n < 2) continue;
         hipGraph_t graph = nullptr;
-        CW_HIP(c, hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal));
-        hipError_t e = hipSuccess;
-        for (size_t i = best_a; i < best_a + best_n && e == hipSuccess; ++i) e = issue(c, m, bases_of(c, nullptr), p.launches[i], c->capture_stream);
+        hipError_t e = hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e != hipSuccess) return fail(e, "hipStreamBeginCapture");
+        for (size_t i = best_a; i < best_a + best_n && e == hipSuccess; ++i) e = issue(c, m, b, p.launches[i], c->capture_stream);
         hipError_t e2 = hipStreamEndCapture(c->capture_stream, &graph);
         if (e != hipSuccess || e2 != hipSuccess) {
             if (graph) (void)hipGraphDestroy(graph);
-            return hip_fail(c, e != hipSuccess ? e : e2, "graph capture");
+            return fail(e != hipSuccess ? e : e2, "graph capture");
         }
         e = hipGraphInstantiate(&pg.exec, graph, nullptr, nullptr, 0);
         (void)hipGraphDestroy(graph);
-        if (e != hipSuccess) { pg.exec = nullptr; return hip_fail(c, e, "hipGraphInstantiate"); }
+        if (e != hipSuccess) { pg.exec = nullptr; return fail(e, "hipGraphInstantiate"); }
         pg.first = best_a;
         pg.last = best_a + best_n - 1;
-        pg.pages = m->pages;
     }
     return CW_OK;
 }
@@ -418,14 +453,15 @@ int32_t build_graphs(cw_ctx *c, ModelRt *m) {
 int32_t enqueue_plan(cw_ctx *c, ModelRt *m, const Plan *p, const Slot *s, hipStream_t st) {
     const size_t pi = (size_t)(p - m->m.plans.data());
     // a graph holds the weight addresses of the placement it was recorded for: replay it only there
-    const PlanGraph *pg = (c->use_graphs && pi < m->graphs.size() && m->graphs[pi].exec && m->graphs[pi].pages == m->pages) ? &m->graphs[pi] : nullptr;
+    const GraphSet *gs = (c->use_graphs && m->active_set >= 0) ? &m->graph_sets[m->active_set] : nullptr;
+    const PlanGraph *pg = (gs && pi < gs->plans.size() && gs->plans[pi].exec) ? &gs->plans[pi] : nullptr;
     for (size_t i = 0; i < p->launches.size(); ++i) {
         if (pg && i == pg->first) {
             CW_HIP(c, hipGraphLaunch(pg->exec, st));
             i = pg->last;
             continue;
         }
-        hipError_t e = issue(c, m, bases_of(c, s), p->launches[i], st);
+        hipError_t e = issue(c, m, bases_of(c, m, s), p->launches[i], st);
         if (e != hipSuccess) return hip_fail(c, e, p->launches[i].info.name);
     }
     return CW_OK;
@@ -543,7 +579,8 @@ int32_t cw_destroy(cw_ctx *c) {
         DeviceGuard g(c->device);
         (void)hipDeviceSynchronize();
         for (auto &m : c->models) {
-            if (m) destroy_graphs(m.get());
+            if (m)
+                for (GraphSet &gs : m->graph_sets) destroy_graphs(gs.plans);
             if (m && m->load_done) (void)hipEventDestroy(m->load_done);
         }
         if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
@@ -699,10 +736,12 @@ static void release_pages(cw_ctx *c, ModelRt *m) {
     c->free_pages.insert(c->free_pages.end(), m->pages.begin(), m->pages.end());
     std::sort(c->free_pages.begin(), c->free_pages.end(), std::greater<int32_t>());
     m->pages.clear();
+    m->active_set = -1;
 }
 
-int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size_t bytes, void *stream) {
-    if (!c) return CW_ERR_INVALID;
+int32_t cw_load_weights_begin(cw_ctx *c, int32_t model_id, const void *host_blob, size_t bytes, void *stream, cw_load_pending **pending) {
+    if (!c || !pending) return CW_ERR_INVALID;
+    *pending = nullptr;
     if (c->device < 0) return set_err(c, CW_ERR_INVALID, "planning-only context has no device");
     ModelRt *m = get_model(c, model_id);
     if (!m || !host_blob) return set_err(c, CW_ERR_INVALID, "unknown model id or null blob");
@@ -788,13 +827,74 @@ int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size
     c->staging_used = true;
     if ((e = hipEventRecord(m->load_done, st)) != hipSuccess) return bail(e, "hipEventRecord");
     m->loaded = true;
-    if (c->use_graphs) {
-        const int32_t rc = build_graphs(c, m);
-        if (rc != CW_OK) {  // LOAD stays valid; EXEC falls back to plain launches for this model
-            destroy_graphs(m);
-            m->graphs.clear();
+    // What is left is host work: the graphs of the plans that have none for this placement.
+    cw_load_pending *pd = new cw_load_pending;
+    pd->model_id = model_id;
+    pd->pages = m->pages;
+    pd->want.assign(m->m.plans.size(), 0);
+    m->active_set = -1;
+    for (size_t k = 0; k < m->graph_sets.size(); ++k)
+        if (m->graph_sets[k].pages == m->pages) { m->active_set = (int)k; m->graph_sets[k].last_used = ++c->load_counter; }
+    if (c->use_graphs)
+        for (size_t pi = 0; pi < m->m.plans.size(); ++pi)
+            pd->want[pi] = !(m->active_set >= 0 && m->graph_sets[m->active_set].plans[pi].exec);
+    *pending = pd;
+    return CW_OK;
+}
+
+int32_t cw_load_weights_record(cw_ctx *c, cw_load_pending *pd) {
+    if (!c || !pd) return CW_ERR_INVALID;
+    const ModelRt *m = get_model(c, pd->model_id);
+    if (!m) return CW_ERR_INVALID;
+    DeviceGuard g(c->device);
+    pd->status = record_graphs(c, m, pd->pages, pd->want, &pd->graphs, &pd->err);
+    return pd->status;
+}
+
+int32_t cw_load_weights_end(cw_ctx *c, cw_load_pending *pd) {
+    if (!c || !pd) return CW_ERR_INVALID;
+    ModelRt *m = get_model(c, pd->model_id);
+    if (!m) return set_err(c, CW_ERR_INVALID, "unknown model id");
+    if (pd->status != CW_OK) return set_err(c, pd->status, pd->err);  // LOAD stays valid; EXEC issues plain launches
+    if (!m->loaded || m->pages != pd->pages) return CW_OK;            // unloaded meanwhile: the graphs are of no use
+    bool any = false;
+    for (const PlanGraph &g : pd->graphs) any = any || g.exec;
+    if (!any) return CW_OK;
+    if (m->active_set < 0) {
+        if (m->graph_sets.size() >= kMaxGraphSets) {  // the placement used longest ago makes room; `pd` takes its graphs along
+            size_t old = 0;
+            for (size_t k = 1; k < m->graph_sets.size(); ++k)
+                if (m->graph_sets[k].last_used < m->graph_sets[old].last_used) old = k;
+            for (PlanGraph &g : m->graph_sets[old].plans)
+                if (g.exec) pd->graphs.push_back(g);
+            m->graph_sets.erase(m->graph_sets.begin() + old);
         }
+        GraphSet gs;
+        gs.pages = pd->pages;
+        gs.plans.resize(m->m.plans.size());
+        gs.last_used = ++c->load_counter;
+        m->graph_sets.push_back(std::move(gs));
+        m->active_set = (int)m->graph_sets.size() - 1;
     }
+    GraphSet &gs = m->graph_sets[m->active_set];
+    for (size_t pi = 0; pi < gs.plans.size(); ++pi)
+        if (pd->graphs[pi].exec && !gs.plans[pi].exec) { gs.plans[pi] = pd->graphs[pi]; pd->graphs[pi].exec = nullptr; }
+    return CW_OK;
+}
+
+void cw_load_weights_release(cw_load_pending *pd) {
+    if (!pd) return;
+    destroy_graphs(pd->graphs);
+    delete pd;
+}
+
+int32_t cw_load_weights(cw_ctx *c, int32_t model_id, const void *host_blob, size_t bytes, void *stream) {
+    cw_load_pending *pd = nullptr;
+    int32_t rc = cw_load_weights_begin(c, model_id, host_blob, bytes, stream, &pd);
+    if (rc != CW_OK) return rc;
+    (void)cw_load_weights_record(c, pd);
+    (void)cw_load_weights_end(c, pd);   // a recording that failed leaves the LOAD valid: EXEC then issues plain launches
+    cw_load_weights_release(pd);
     return CW_OK;
 }
 
@@ -875,6 +975,7 @@ int32_t cw_exec_static(cw_ctx *c, int32_t model_id, int32_t batch, const float *
     else if (q != hipSuccess) return hip_fail(c, q, "hipEventQuery");
     Bases b;
     b.workspace = c->static_scratch;
+    b.pages = m->pages.data();
     b.input = const_cast<char *>(reinterpret_cast<const char *>(dev_input_nchw));
     b.logits = reinterpret_cast<char *>(dev_logits);
     b.probs = reinterpret_cast<char *>(dev_probs);
@@ -914,7 +1015,7 @@ int32_t cw_exec_timed_launches(cw_ctx *c, int32_t model_id, int32_t batch, int32
         for (size_t i = 0; i < cnt; ++i) {
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i], st));
             for (int r = 0; r < inner; ++r) {
-                hipError_t e = issue(c, m, bases_of(c, s), p->launches[base + i], st);
+                hipError_t e = issue(c, m, bases_of(c, m, s), p->launches[base + i], st);
                 if (e != hipSuccess) return hip_fail(c, e, p->launches[base + i].info.name);
             }
             CW_HIP(c, hipEventRecord(c->prof_ev[2 * i + 1], st));

@@ -135,6 +135,19 @@ int32_t sync_stream(cw_worker *w, int ex) {
     return hipStreamSynchronize(w->stream[ex]) == hipSuccess ? CW_OK : CW_ERR_HIP;
 }
 
+// LOAD waits for milliseconds and nothing waits for it to the microsecond: it sleeps between
+// polls.  (A thread blocked in hipStreamSynchronize for the length of a LOAD was measured to make
+// the EXEC executor's launches, issued meanwhile, late by tens of microseconds.)
+int32_t nap_stream(cw_worker *w, int ex) {
+    if (w->device < 0) return CW_OK;
+    for (;;) {
+        const hipError_t e = hipStreamQuery(w->stream[ex]);
+        if (e == hipSuccess) return CW_OK;
+        if (e != hipErrorNotReady) return CW_ERR_HIP;
+        std::this_thread::sleep_for(std::chrono::microseconds(100));
+    }
+}
+
 // The EXEC executor polls instead of sleeping in the driver: it owns its core, and the wake-up
 // of a blocking wait (tens of microseconds) would be idle GPU time between two EXECs.
 int32_t spin_stream(cw_worker *w, int ex) {
@@ -152,14 +165,26 @@ void run_load(cw_worker *w) {
     while (take(w, EX_LOAD, true, &it)) {
         it.begin_ns = now_ns();
         if (it.begin_ns > it.a.latest_ns) { post(w, it, CW_ERR_TOO_LATE, it.begin_ns); continue; }
+        // The context is held only while the copies and pack kernels are enqueued and while the
+        // recorded graphs are installed; the recording itself (milliseconds of host work) runs
+        // beside the other executors, and the action's result is posted when all of it is done.
         int32_t rc;
+        cw_load_pending *pending = nullptr;
         {
             std::lock_guard<std::mutex> g(w->ctx_mu);
             if (w->device >= 0) (void)hipEventRecord(w->load_ev[0], w->stream[EX_LOAD]);
-            rc = cw_load_weights(w->ctx, it.a.model_id, it.a.host_in, it.a.host_in_bytes, w->stream[EX_LOAD]);
+            rc = cw_load_weights_begin(w->ctx, it.a.model_id, it.a.host_in, it.a.host_in_bytes, w->stream[EX_LOAD], &pending);
             if (w->device >= 0) (void)hipEventRecord(w->load_ev[1], w->stream[EX_LOAD]);
         }
-        if (rc == CW_OK) rc = sync_stream(w, EX_LOAD);
+        if (rc == CW_OK) {
+            (void)cw_load_weights_record(w->ctx, pending);
+            {
+                std::lock_guard<std::mutex> g(w->ctx_mu);
+                (void)cw_load_weights_end(w->ctx, pending);   // without graphs EXEC issues plain launches
+            }
+            cw_load_weights_release(pending);
+            rc = nap_stream(w, EX_LOAD);
+        }
         if (rc == CW_OK && w->device >= 0) {
             float ms = 0.f;
             if (hipEventElapsedTime(&ms, w->load_ev[0], w->load_ev[1]) == hipSuccess) it.device_ns = (uint64_t)((double)ms * 1e6 + 0.5);

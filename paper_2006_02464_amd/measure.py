@@ -284,6 +284,9 @@ def config6(args, log):
     beside = [(r["begin_ns"] - (t0 + r["id"] * period)) / 1e3 for r in ok
               if any(a - period <= t0 + r["id"] * period <= b for a, b in spans)]
     dev_beside = [r["device_ns"] / 1e3 for r in ok if any(a - period <= t0 + r["id"] * period <= b for a, b in spans)]
+    # the EXECs around the first three LOADs: (begin of EXEC minus begin of LOAD in us, on-device us)
+    around = [[(round((r["begin_ns"] - a) / 1e3), round(r["device_ns"] / 1e3, 1)) for r in sorted(ok, key=lambda r: r["begin_ns"])
+               if a - 2 * period <= r["begin_ns"] <= b + 2 * period] for a, b in spans[1:4]]
     over = [((r["end_ns"] - r["begin_ns"]) - r["device_ns"]) / 1e3 for r in ok]
     dev = [r["device_ns"] / 1e3 for r in ok]
     span = (max(r["end_ns"] for r in res) - t0) / 1e9
@@ -292,11 +295,14 @@ def config6(args, log):
             "load_action": {"status": load["status"], "host_ms": round((load["end_ns"] - load["begin_ns"]) / 1e6, 3), "device_ms": round(load["device_ns"] / 1e6, 3)},
             "load_call_host_ms": {"first": call_ms[0], "same_pages_again": call_ms[1], "other_pages": call_ms[2]},
             "side_actions": {"loads": len(loads), "loads_ok": sum(l["status"] == 0 for l in loads), "unloads_ok": sum(u["status"] == 0 for u in unloads),
-                             "load_host_ms": summary([(l["end_ns"] - l["begin_ns"]) / 1e6 for l in loads]) if loads else None,
-                             "load_device_ms": summary([l["device_ns"] / 1e6 for l in loads]) if loads else None,
+                             "load_host_ms": {"p50": round(pct([(l["end_ns"] - l["begin_ns"]) / 1e6 for l in loads], 0.5), 3),
+                                              "max": round(max((l["end_ns"] - l["begin_ns"]) / 1e6 for l in loads), 3)} if loads else None,
+                             "load_device_ms": {"p50": round(pct([l["device_ns"] / 1e6 for l in loads], 0.5), 3),
+                                                "max": round(max(l["device_ns"] / 1e6 for l in loads), 3)} if loads else None,
                              "infer_beside_a_load": len(beside),
                              "begin_after_earliest_us_beside_a_load": {"p50": round(pct(beside, 0.5), 1), "p99": round(pct(beside, 0.99), 1), "max": round(max(beside), 1)} if beside else None,
-                             "exec_device_us_beside_a_load": summary(dev_beside) if dev_beside else None},
+                             "exec_device_us_beside_a_load": summary(dev_beside) if dev_beside else None,
+                             "execs_around_three_loads_offset_us_and_device_us": around},
             "executed": len(ok), "rejected_too_late": sum(r["status"] == -11 for r in res),
             "begin_after_earliest_us": {"p50": round(pct(late, 0.5), 1), "p99": round(pct(late, 0.99), 1), "max": round(max(late), 1)},
             "exec_device_us": summary(dev),

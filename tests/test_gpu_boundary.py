@@ -223,6 +223,43 @@ def test_graph_replay_equals_plain_launches(setup):
     ctx.unload_weights(m2)
 
 
+def test_load_in_steps(setup):
+    """LOAD as the executors issue it: an EXEC between the begin and the end step runs plain
+    launches, one after the end step replays the graphs; both give what a one-call LOAD gives.
+    Graphs recorded for a placement the model has left meanwhile are dropped."""
+    w, case = setup
+    ctx = w.ctx
+    x = case.images(0, 4)
+    ref = ctx.model_define_resnet(18, 64, 64)
+    w.load(ref, case.blob)
+    want = w.infer(ref, x)[1]
+    ctx.unload_weights(ref)
+    mid = ctx.model_define_resnet(18, 64, 64)
+    from paper_2006_02464_amd.runner import pinned_like
+    blob = pinned_like(case.blob)
+    pd = ctx.load_weights_begin(mid, blob, w.stream)
+    assert np.array_equal(w.infer(mid, x)[1], want)
+    ctx.load_weights_record(pd)
+    assert np.array_equal(w.infer(mid, x)[1], want)
+    ctx.load_weights_end(pd)
+    ctx.load_weights_release(pd)
+    for _ in range(3):
+        assert np.array_equal(w.infer(mid, x)[1], want)
+    # unloaded (and loaded elsewhere) between record and end: the recorded graphs must not be used
+    ctx.unload_weights(mid)
+    pd = ctx.load_weights_begin(mid, blob, w.stream)     # pages 0..3 again
+    ctx.load_weights_record(pd)
+    ctx.unload_weights(mid)
+    w.load(ref, case.blob)                               # takes pages 0..3
+    w.load(mid, case.blob)                               # pages 4..7
+    ctx.load_weights_end(pd)
+    ctx.load_weights_release(pd)
+    assert np.array_equal(w.infer(mid, x)[1], want)
+    assert np.array_equal(w.infer(ref, x)[1], want)
+    ctx.unload_weights(mid)
+    ctx.unload_weights(ref)
+
+
 def test_unload_then_load_waits_for_the_exec_in_flight(setup):
     """UNLOAD hands the pages back at once; a LOAD of another model on another stream takes them
     while EXECs of the unloaded model are still queued.  Those EXECs must read intact weights: the
