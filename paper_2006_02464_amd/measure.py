@@ -4,6 +4,8 @@
   python -m paper_2006_02464_amd.measure --config 4   ResNet-152, bf16, batch 16: throughput and latency
   python -m paper_2006_02464_amd.measure --config 5   64 resident ResNet-50s, Poisson arrivals, mixed batch sizes
   python -m paper_2006_02464_amd.measure --config 6   INFER actions with earliest/latest through the worker's executors
+  python -m paper_2006_02464_amd.measure --config 8   ResNet-50 EXEC under each plan option (fusion, pair launches, graphs,
+                                                      Winograd, resident multi-layer launch) against the default plan
   python -m paper_2006_02464_amd.measure --config 7   the other Table-1 families (MobileNet-, DenseNet-, Inception-style
                                                       operator lists): EXEC latency and every launch against its roofline
 
@@ -418,9 +420,48 @@ def config7(args, log):
     return out
 
 
+def config8(args, log):
+    """The same ResNet-50, the same seeded images, one plan option changed at a time: launches per
+    EXEC and the on-device EXEC p50 at batch 1 and 16 (1000 EXECs each), all in one process on one GPU."""
+    from .runner import Worker, pinned_like
+    from workload import gen
+    wk = Worker(workspace_bytes=1 << 30, io_bytes=256 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20)
+    ctx, ex = wk.ctx, wk.stream
+    variants = [("default plan", None, None), ("fused 3x3+1x1 launches off", ctx.set_fusion, 1), ("pair launches off", ctx.set_pair_launches, 1),
+                ("plain launches instead of graph replay", None, None), ("Winograd F(2x2,3x3) for the 3x3 stride-1 layers", ctx.set_winograd, 0),
+                ("resident multi-layer launches", ctx.set_resident, 0), ("default plan again", None, None)]
+    blob, rows = None, []
+    for name, setter, default in variants:
+        if setter is not None:
+            setter(1 - default)
+        try:
+            mid = ctx.model_define_resnet(50, 224, 224, "fp16")
+        finally:
+            if setter is not None:
+                setter(default)
+        if blob is None:
+            blob = pinned_like(resnet_blob(ctx, mid, 0, "fp16"))
+        graphs = 0 if name.startswith("plain launches") else 1
+        ctx.set_use_graphs(graphs)
+        ctx.load_weights(mid, blob, ex)
+        row = {"variant": name}
+        for B in (1, 16):
+            slot = ctx.input(mid, B, pinned_like(gen.images(0, 0, B, 3, 224, 224, "normal", "fp16")), ex)
+            ctx.profile_measure(mid, B, 50, slot=slot)
+            p = ctx.profile_measure(mid, B, 1000, slot=slot)
+            row["b%d" % B] = {"launches": ctx.plan_num_launches(mid, B), "p50_us": round(p["p50_us"], 1), "p999_over_p50": round(p["p999_us"] / p["p50_us"], 4)}
+            ctx.release(slot)
+        ctx.set_use_graphs(1)
+        ctx.unload_weights(mid)
+        rows.append(row)
+        log(str(row))
+    wk.close()
+    return {"config": 8, "workload": "ResNet-50 224x224 fp16, 1000 EXECs per cell", "variants": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5, 6, 7))
+    ap.add_argument("--config", type=int, required=True, choices=(3, 4, 5, 6, 7, 8))
     ap.add_argument("--table-out", default="", help="config 7: write the per-launch tables here")
     ap.add_argument("--execs", type=int, default=2000)
     ap.add_argument("--loads-per-round", type=int, default=6, help="config 3: LOADs queued per 20 EXECs")
@@ -441,7 +482,7 @@ def main():
             make(self, **kw)
             self.ctx.set_use_graphs(args.graphs)
         runner.Worker.__init__ = patched
-    out = {3: config3, 4: config4, 5: config5, 6: config6, 7: config7}[args.config](args, log)
+    out = {3: config3, 4: config4, 5: config5, 6: config6, 7: config7, 8: config8}[args.config](args, log)
     print(json.dumps(out), flush=True)
 
 
