@@ -91,6 +91,8 @@ def main():
                     help="profiling runs: only the timed EXECs and the per-launch pass at --batch "
                          "(no per-batch latency profile, no extra configurations, no CPU baseline)")
     ap.add_argument("--no-graphs", action="store_true", help="issue every kernel as its own launch")
+    ap.add_argument("--panels", action="store_true",
+                    help="plan the tile numbering in channel panels (cw_set_panels; for the traffic counter runs)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one device-to-device copy kernel of this many MiB (scale for HBM counters)")
     args = ap.parse_args()
@@ -121,6 +123,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.panels:
+        ctx.set_panels(1)
     mid = ctx.model_define_resnet(50, 224, 224, "fp16")
     ops = ctx.model_get_ops(mid)
     shapes = [(o[2], o[1], o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]

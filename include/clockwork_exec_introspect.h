@@ -31,6 +31,8 @@ typedef struct {
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
     int32_t conv_tile;     /* conv: the tile variant in cw_set_plan_override's numbering; -1 for a fused pair and for other kinds */
     int32_t wave_groups;   /* conv: groups of waves that split every K slice (1 = none) */
+    int32_t panels;        /* conv: channel panels of the tile numbering (1 = row by row; see cw_set_panels); a pair
+                              launch: of op_index's convolution in the low byte, of pair_op's in the next */
     int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
     int64_t bytes;         /* algorithmic HBM bytes: inputs + weights + outputs, once each */
     int64_t flops;         /* 2 * MACs */
@@ -87,6 +89,16 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
  * models defined afterwards; on != 0 restores the default. */
 int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
+/* Tile numbering.  A launch's workgroups go to the chip's 8 XCDs in turn, and each XCD has an L2 of
+ * its own; by default a convolution's output tiles are numbered row by row, so that an XCD
+ * computes an eighth of the pixels and reads all the weights.  on != 0: for models defined
+ * afterwards the plan numbers the tiles of each launch in 1, 2, 4 or 8 panels of channel tiles (an
+ * XCD then reads that fraction of the weights and more of the pixels), whichever moves the fewest
+ * bytes into the L2s.  Measured on ResNet-50 at batch 16: a third less traffic between the L2s and
+ * the memory side over the convolution launches, and no launch faster for it (the repeats are
+ * served by the last-level cache), which is why it is off by default.  Results do not depend on
+ * it.  on == 0 restores the default. */
+int32_t cw_set_panels(cw_ctx *ctx, int32_t on);
 /* Resident launches (section 4.4: one EXEC at a time owns the whole GPU).  on != 0: plans of batch
  * sizes that are multiples of 8, compiled for models defined afterwards, run every run of plain
  * convolution layers as ONE launch of 256 workgroups that stay on their CUs: the batch is cut into

@@ -625,6 +625,12 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     return CW_OK;
 }
 
+int32_t cw_set_panels(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.panels = on != 0;
+    return CW_OK;
+}
+
 int32_t cw_set_resident(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on && !c->resident_capable) return set_err(c, CW_ERR_UNSUPPORTED, "resident launches need 256 compute units in 8 XCDs");

@@ -92,10 +92,21 @@ struct alignas(64) ConvArgs {
     // shape in one launch; workgroups with blockIdx.z = z take x, w and y advanced by z times these
     // byte strides (bias and res are not used then).  Read only by z > 0.
     int32_t nz;
-    int32_t zs_pad_;
+    int32_t panel_log2;  // host side only: tile numbering of this launch (conv_pack_nb); the kernel gets it inside its tile count
     long long zs_x, zs_w, zs_y;
 };
 static_assert(offsetof(ConvArgs, B) == 64 && offsetof(ConvArgs, khp) == 128 && sizeof(ConvArgs) == 256, "argument lines");
+// Tile numbering.  A launch's workgroups go to the 8 XCDs in turn and each XCD keeps a contiguous run
+// of tile numbers, so the numbering decides what an XCD's L2 has to fetch.  Numbering 0 walks the
+// tiles row by row (all channel tiles of a block of pixels, then the next pixels): every XCD reads
+// an eighth of the pixels and all the weights.  Numbering p > 0 cuts the channel tiles into 2^p
+// panels and walks panel after panel: an XCD reads 1/2^p of the weights and 2^p/8 of the pixels,
+// which is less traffic where the weights outweigh the activations (small M, long K).  The kernel
+// receives  tiles | p << 28  as its tile count (a preloaded scalar: no argument load is waited for).
+constexpr int kPanelShift = 28;
+__host__ __device__ inline int conv_pack_nb(int tiles, int panel_log2) { return tiles | (panel_log2 << kPanelShift); }
+__host__ __device__ inline int conv_nb_tiles(int nb) { return nb & ((1 << kPanelShift) - 1); }
+__host__ __device__ inline int conv_nb_panel(int nb) { return (int)((unsigned)nb >> kPanelShift); }
 __host__ __device__ inline int conv_pad_h(const ConvArgs &a) { return a.pad & 0xffff; }
 __host__ __device__ inline int conv_pad_w(const ConvArgs &a) { return (int)((unsigned)a.pad >> 16); }
 __host__ __device__ inline int conv_ldx(const ConvArgs &a) { return a.ld & 0xffff; }

@@ -79,7 +79,9 @@ constexpr int kFusedMaxCout2 = 1024;
 // the convolution (a launch may hold two convolutions, see conv_dlds_pair_kernel).
 // RAW: bid is the tile index itself (the caller has chosen which tile this workgroup computes).
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int MODE, bool SPLITK, bool FUSED = false, int KG = 1, bool RAW = false>
-static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const int bid, const int nb) {
+static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const int bid, const int nb_packed) {
+    // nb_packed: the convolution's tile count with its tile numbering in the top bits (conv_pack_nb)
+    const int nb = conv_nb_tiles(nb_packed), panel = conv_nb_panel(nb_packed);
     static_assert(BK == 64 || BK == 128, "K slices of 64 or 128");
     static_assert(KG == 1 || ((BK / 16) % KG == 0 && (!FUSED || KG == 2)), "K groups: whole steps per group");
     static_assert(!FUSED || (!SPLITK && MODE != MODE_STEM && (BN == 64 || BN == 128)), "fused form: whole first layer in one tile");
@@ -127,8 +129,18 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
 
     const int tile_id = RAW ? bid : xcd_tile_id(bid, nb);
     const int tiles_n = a.Cout / BN + (a.Cout % BN != 0);
-    const int tile_m = tile_id / tiles_n;
-    const int tile_n = tile_id - tile_m * tiles_n;
+    int tile_m, tile_n;
+    if (RAW || FUSED || panel == 0) {   // uniform
+        tile_m = tile_id / tiles_n;
+        tile_n = tile_id - tile_m * tiles_n;
+    } else {
+        // panel after panel of tiles_n >> panel channel tiles, row by row inside a panel
+        const int pw = tiles_n >> panel;
+        const int per = ((a.M + BM - 1) / BM) * pw;
+        const int p = tile_id / per, r = tile_id - p * per;
+        tile_m = r / pw;
+        tile_n = p * pw + (r - tile_m * pw);
+    }
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     const int ktiles = a.K / BK;

@@ -35,17 +35,26 @@ __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_kernel(
 // one set-up latency and one tail instead of two.
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int NS, int KG>
 __global__ __launch_bounds__(64 * WARPS_M * WARPS_N * KG) void conv_dlds_pair_kernel(const ConvArgs a0, const ConvArgs a1) {
-    const int nb0 = a0.nb;
+    const int nb0 = conv_nb_tiles(a0.nb);
     if ((int)blockIdx.x < nb0)
-        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a0, blockIdx.x, nb0);
+        conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a0, blockIdx.x, a0.nb);
     else
         conv_dlds_body<T, BM, BN, WARPS_M, WARPS_N, BK, NS, MODE_CONV, false, false, KG>(a1, blockIdx.x - nb0, a1.nb);
+}
+
+// A tile numbering in 2^p panels needs the channel tiles to divide evenly, and the tile count must
+// leave the bits above kPanelShift free.
+static bool conv_panel_ok(const ConvArgs &a, int bn, unsigned tiles) {
+    if (tiles >= (1u << kPanelShift) || a.panel_log2 < 0 || a.panel_log2 > 3) return false;
+    const int tiles_n = (a.Cout + bn - 1) / bn;
+    return a.panel_log2 == 0 || tiles_n % (1 << a.panel_log2) == 0;
 }
 
 template <typename T, int BM, int BN, int WARPS_M, int WARPS_N, int BK, int MODE, bool SPLITK, int KG = 1>
 static hipError_t launch_one(dim3 grid, int block, const ConvArgs &a_in, hipStream_t s) {
     ConvArgs a = a_in;
-    a.nb = (int)grid.x;
+    if (!conv_panel_ok(a, BN, grid.x)) return hipErrorInvalidValue;
+    a.nb = conv_pack_nb((int)grid.x, a.panel_log2);
     if (!SPLITK && a.ktiles_per_split != a.K / BK) return hipErrorInvalidValue;  // the kernel walks the whole K
     if (a.nz > 1 && (MODE != MODE_GEMM || SPLITK || a.bias || a.res || grid.z != (unsigned)a.nz)) return hipErrorInvalidValue;
     if (a.nz <= 1 && grid.z != 1) return hipErrorInvalidValue;
@@ -203,8 +212,9 @@ static hipError_t launch_pair_one(const ConvArgs &a0_in, const ConvArgs &a1_in, 
     if (attr != hipSuccess) return attr;
     const size_t used = std::max((size_t)std::min(NS, std::max(a0.ktiles_per_split, a1.ktiles_per_split)) * stage_bytes, (size_t)(KG - 1) * BM * BN * 4);
     const unsigned nb0 = ((a0.M + BM - 1) / BM) * ((a0.Cout + BN - 1) / BN), nb1 = ((a1.M + BM - 1) / BM) * ((a1.Cout + BN - 1) / BN);
-    a0.nb = (int)nb0;
-    a1.nb = (int)nb1;
+    if (!conv_panel_ok(a0, BN, nb0) || !conv_panel_ok(a1, BN, nb1)) return hipErrorInvalidValue;
+    a0.nb = conv_pack_nb((int)nb0, a0.panel_log2);
+    a1.nb = conv_pack_nb((int)nb1, a1.panel_log2);
     kern<<<dim3(nb0 + nb1, 1, 1), 64 * WARPS_M * WARPS_N * KG, used, s>>>(a0, a1);
     return hipGetLastError();
 }

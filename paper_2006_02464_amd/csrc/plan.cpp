@@ -348,6 +348,20 @@ static void pick_conv_tile(int64_t M, int64_t N, int64_t K, int32_t kh, int32_t 
     *split = std::max(1, s);
 }
 
+// Tile numbering of a convolution launch (see conv_pack_nb): with 2^p channel panels each of the 8
+// XCDs fetches 1/2^p of the weights and 2^p/8 of the input pixels, 8 * w_bytes / 2^p + in_bytes * 2^p
+// in all; p = the count with the fewest bytes among those that divide the channel tiles evenly.
+static int choose_panel(int cout, int bn, int64_t w_bytes, int64_t in_bytes) {
+    const int tiles_n = (cout + bn - 1) / bn;
+    int best = 0;
+    int64_t best_cost = 8 * w_bytes + in_bytes;
+    for (int p = 1; p <= 3 && tiles_n % (1 << p) == 0; ++p) {
+        const int64_t cost = 8 * w_bytes / (1 << p) + in_bytes * (1 << p);
+        if (cost < best_cost) { best_cost = cost; best = p; }
+    }
+    return best;
+}
+
 // ---------------------------------------------------------------- plan_build
 int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *out, std::string *err) {
     if (batch < 1 || batch > 4096) return fail(err, CW_ERR_BAD_BATCH, "batch %d out of range", batch);
@@ -740,6 +754,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 const TileDim td = conv_tile_dim(l.tile);
                 l.info.tile_m = td.bm; l.info.tile_n = td.bn; l.info.tile_k = conv_bk(a, l.stem, l.tile); l.info.split_k = a.split_k;
                 l.info.conv_tile = l.tile; l.info.wave_groups = td.kg;
+                a.panel_log2 = (ov.panels && !l.stem && conv_uses_dlds(a, false)) ? choose_panel(a.Cout, td.bn, w_b, in_b) : 0;
+                l.info.panels = 1 << a.panel_log2;
                 if (a.split_k > 1) {
                     partial_bytes = (size_t)a.split_k * a.M * a.Cout * 4;
                     partial_off = ws_alloc(partial_bytes);
@@ -875,6 +891,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             l.conv0 = l0.conv;
             l.conv0.ktiles_per_split = l.conv0.K / d.bk;
             l.conv.ktiles_per_split = l.conv.K / d.bk;
+            // both members run on the pair's tile shape: their tile numbering is chosen for it
+            l.conv0.panel_log2 = ov.panels ? choose_panel(l.conv0.Cout, d.bn, (int64_t)l.conv0.Cout * l.conv0.K * 2, l0.in_bytes) : 0;
+            l.conv.panel_log2 = ov.panels ? choose_panel(l.conv.Cout, d.bn, (int64_t)l.conv.Cout * l.conv.K * 2, l1.in_bytes) : 0;
+            l.info.panels = (1 << l.conv.panel_log2) | ((1 << l.conv0.panel_log2) << 8);
             l.w0 = l0.w; l.bias0 = l0.bias; l.res0 = l0.res; l.y0 = l0.y;
             l.info.flops = l0.info.flops + l1.info.flops;
             l.info.bytes = l0.info.bytes + l1.info.bytes - std::min(l0.in_bytes, l1.in_bytes);   // the shared input once

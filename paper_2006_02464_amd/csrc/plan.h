@@ -95,6 +95,7 @@ struct PlanOverride {
     bool pair = true;      // two convolutions over one tensor as one launch
     bool winograd = false; // 3x3 stride-1 pad-1 convolutions through Winograd F(2x2, 3x3)
     bool resident = false; // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0)
+    bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };
 

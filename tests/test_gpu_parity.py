@@ -146,6 +146,12 @@ def test_resnet18_top1_agreement_2048_samples(worker):
           "mismatches among them %d; (gap, err) of mismatches %s" % (
               1 - len(mism) / n, len(mism), n, err.max(), int(clear.sum()), int((a != b)[clear].sum()),
               [(float(gaps[i]), float(abs_err[i])) for i in mism]))
+    from test_gpu_parity_full import _report
+    _report("resnet18_64_2048", {"samples": n, "top1_agreement": 1 - len(mism) / n, "mismatches": [
+        {"sample": int(i), "oracle_top2_gap": float(gaps[i]), "abs_err": float(abs_err[i])} for i in mism],
+        "max_rel_err": float(err.max()), "well_separated_samples": int(clear.sum()),
+        "mismatches_among_well_separated": int((a != b)[clear].sum()), "oracle_linf_median": float(np.median(np.abs(ref).max(axis=1))),
+        "distinct_top1_classes": int(len(set(b.tolist())))})
     assert all(gaps[i] <= 2 * abs_err[i] for i in mism)      # only near-ties may flip
     assert (a != b)[clear].sum() <= clear.sum() // 1000
     assert len(mism) <= 0.005 * n
@@ -170,11 +176,13 @@ def test_every_conv_tile_and_split_k(worker, tile, split_k):
     case = Case(T.resnet(18), 64, seed=1, dist="uniform")
     worker.ctx.set_plan_override(tile, split_k)
     worker.ctx.set_debug_keep(True)
+    worker.ctx.set_panels(split_k == 3)     # the split-K half of the cases also numbers its tiles in channel panels
     try:
         mid = worker.ctx.model_define(case.ops, 3, 64, 64, batch_sizes=(3,))
     finally:
         worker.ctx.set_plan_override(-1, 0)
         worker.ctx.set_debug_keep(False)
+        worker.ctx.set_panels(0)
     worker.load(mid, case.blob)
     x = case.images(0, 3)
     probs, logits, _ = worker.infer(mid, x)
@@ -383,6 +391,34 @@ def test_resnet50_pair_launches_change_nothing(worker, r50):
         d = rel_err_per_sample(out["paired"], out["single"]).max()
         print("batch %d: paired vs single launches max rel diff %.3e" % (batch, d))
         assert d <= 5e-3
+
+
+def test_resnet50_panel_numbering_changes_nothing(worker, r50):
+    """Numbering a launch's tiles in channel panels only changes which workgroup computes which
+    tile: the logits are bit-identical to the default plan's, at batch 16 (panels of 2, 4 and 8 in
+    stages 3-4, pair launches included) and at batch 1 (split-K launches included)."""
+    case, x, ref = r50
+    ctx = worker.ctx
+    rows = ctx.model_define_resnet(50, 224, 224)
+    ctx.set_panels(1)
+    try:
+        panels = ctx.model_define_resnet(50, 224, 224)
+    finally:
+        ctx.set_panels(0)
+    for batch in (16, 1):
+        n = 16 if batch == 16 else 4
+        assert all(max(l["panels"] & 255, l["panels"] >> 8) <= 1 for l in ctx.plan(rows, batch))
+        seen = {l["panels"] & 255 for l in ctx.plan(panels, batch)} | {l["panels"] >> 8 for l in ctx.plan(panels, batch)}
+        assert {2, 4, 8} <= seen
+        if batch == 1:
+            assert any((l["panels"] & 255) > 1 and l["split_k"] > 1 for l in ctx.plan(panels, batch))
+        out = {}
+        for name, mid in (("rows", rows), ("panels", panels)):
+            worker.load(mid, case.blob)
+            out[name] = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, n, batch)])
+            ctx.unload_weights(mid)
+        assert rel_err_per_sample(out["panels"], ref[:n]).max() <= TOL
+        assert np.array_equal(out["panels"], out["rows"])
 
 
 @pytest.mark.parametrize("batch", [1, 2, 4, 8])
