@@ -89,6 +89,13 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * in another order than on its own tile (results agree to rounding).  on == 0 plans them as two launches for
  * models defined afterwards; on != 0 restores the default. */
 int32_t cw_set_pair_launches(cw_ctx *ctx, int32_t on);
+/* FC and SOFTMAX as one launch (up to batch 16 and 1024 classes), for models defined afterwards:
+ * the FC's K is split over several workgroups per 16 outputs and the workgroup that completes the
+ * last outputs computes the probabilities.  Off by default: the arrival tickets and the trips
+ * through memory between the phases cost more than the second launch they save (ResNet-50 head:
+ * 16.0 us against 11.8 us as two launches at batch 16, 9.8 against 9.8 at batch 1).  on == 0
+ * restores the default, two launches. */
+int32_t cw_set_fc_softmax(cw_ctx *ctx, int32_t on);
 /* Tile numbering.  A launch's workgroups go to the chip's 8 XCDs in turn, and each XCD has an L2 of
  * its own; by default a convolution's output tiles are numbered row by row, so that an XCD
  * computes an eighth of the pixels and reads all the weights.  on != 0: for models defined

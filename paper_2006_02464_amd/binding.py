@@ -105,6 +105,7 @@ SIGNATURES = {
     "cw_set_fusion": (c_int32, [c_void_p, c_int32]),
     "cw_set_pair_launches": (c_int32, [c_void_p, c_int32]),
     "cw_set_panels": (c_int32, [c_void_p, c_int32]),
+    "cw_set_fc_softmax": (c_int32, [c_void_p, c_int32]),
     "cw_set_winograd": (c_int32, [c_void_p, c_int32]),
     "cw_set_resident": (c_int32, [c_void_p, c_int32]),
     "cw_set_use_graphs": (c_int32, [c_void_p, c_int32]),
@@ -333,6 +334,9 @@ class Context:
 
     def set_pair_launches(self, on):
         self._check(lib().cw_set_pair_launches(self._h, int(on)))
+
+    def set_fc_softmax(self, on):
+        self._check(lib().cw_set_fc_softmax(self._h, int(on)))
 
     def set_panels(self, on):
         self._check(lib().cw_set_panels(self._h, int(on)))

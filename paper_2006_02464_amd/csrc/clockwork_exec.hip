@@ -249,6 +249,11 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             a.w = resolve(c, m, s, l.w);
             a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
             a.z = reinterpret_cast<float *>(resolve(c, m, s, l.y));
+            if (l.probs.space == SP_SLOT_PROBS) {
+                a.p = reinterpret_cast<float *>(resolve(c, m, s, l.probs));
+                a.partial = reinterpret_cast<float *>(resolve(c, m, s, l.partial));
+                a.counters = reinterpret_cast<int32_t *>(resolve(c, m, s, l.counters));
+            }
             return launch_fc(dt, a, st);
         }
         case K_SOFTMAX: {
@@ -392,7 +397,7 @@ void free_slot(cw_ctx *c, Slot *s) {
 
 
 bool slot_free(const Launch &l) {
-    for (const Ref *r : {&l.x, &l.w, &l.bias, &l.res, &l.y, &l.partial, &l.counters})
+    for (const Ref *r : {&l.x, &l.w, &l.bias, &l.res, &l.y, &l.partial, &l.counters, &l.probs})
         if (r->space == SP_SLOT_INPUT || r->space == SP_SLOT_LOGITS || r->space == SP_SLOT_PROBS) return false;
     return true;
 }
@@ -622,6 +627,12 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "fusion mode must be 0, 1 or 2");
     c->ov.fuse = on;
+    return CW_OK;
+}
+
+int32_t cw_set_fc_softmax(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.fc_softmax = on != 0;
     return CW_OK;
 }
 

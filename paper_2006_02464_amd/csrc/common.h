@@ -212,7 +212,15 @@ struct FcArgs {
     const float *bias;
     float *z;        // [B][Out]
     int32_t B, In, Out;
+    // FC and softmax in one launch (p != nullptr; B <= 16, Out <= 1024): K is split over split_k
+    // workgroups per 16 outputs, which meet through `partial` and arrival counters like the
+    // convolution's split-K; the workgroup that finishes the last 16 outputs computes p = softmax(z).
+    float *p;           // [B][Out] probabilities, or nullptr: logits only (the unfused kernel)
+    float *partial;     // [split_k][16][Out] fp32 (split_k > 1)
+    int32_t *counters;  // ceil(Out/16) + 1 arrival counters, zero between launches
+    int32_t split_k;    // 1, 2 or 4; In % (128 * split_k) == 0
 };
+constexpr int kFcSoftmaxMaxBatch = 16, kFcSoftmaxMaxOut = 1024;
 
 struct SoftmaxArgs {
     const float *z;

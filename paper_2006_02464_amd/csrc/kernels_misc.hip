@@ -239,6 +239,137 @@ __global__ __launch_bounds__(64 * kFcWaves) void fc_kernel(const float *f, const
     }
 }
 
+// FC and softmax as one launch, for at most 16 samples and 1024 classes.  Grid (16-output tiles,
+// K splits): a workgroup of 4 waves computes a 16 x 16 partial tile over In / split_k of K (each wave
+// a quarter of that, chunks as above).  The splits of a tile meet like the convolution's split-K:
+// partial tiles go to memory with device-scope stores, a ticket per tile makes the last arrival add
+// them in split order, so the logits do not depend on arrival order.  A second ticket over the
+// tiles makes the workgroup that completes the last tile compute the softmax of every row (wave w
+// takes rows w, w+4, ...: a row is 16 values per lane, max and sum by wave shuffles; the same
+// formula as the stand-alone kernels), so no second launch and no second pass over the logits.
+// Workgroups sit on different XCDs: everything another workgroup reads travels device-scope.
+constexpr int kFcsWaves = 4;
+template <typename T>
+__global__ __launch_bounds__(64 * kFcsWaves) void fc_softmax_kernel(const float *f, const void *w, const float *bias, float *z, float *p,
+                                                                    float *partial, int *counters, int B, int In, int Out, int S) {
+    __shared__ float part[kFcsWaves][16][17];
+    __shared__ int s_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int j = blockIdx.x * 16 + r;   // output row this lane feeds
+    const bool j_ok = j < Out, n_ok = r < B;
+    const T *wrow = static_cast<const T *>(w) + (size_t)(j_ok ? j : 0) * In;
+    const float *frow = f + (size_t)(n_ok ? r : 0) * In;
+    fc_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int kq = In / (kFcsWaves * S);  // K range of this wave (a multiple of 32)
+    const int k_begin = ((int)blockIdx.y * kFcsWaves + wave) * kq, k_end = k_begin + kq;
+    for (int k0 = k_begin + g * 8; k0 < k_end; k0 += 128) {
+        uint4 wraw[4];
+        float4 f0[4], f1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + 32 * u;
+            const bool live = k < k_end;  // uniform per wave
+            const int kc = live ? k : k0;
+            wraw[u] = *reinterpret_cast<const uint4 *>(wrow + kc);
+            f0[u] = *reinterpret_cast<const float4 *>(frow + kc);
+            f1[u] = *reinterpret_cast<const float4 *>(frow + kc + 4);
+            if (!j_ok || !live) wraw[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (!n_ok) { f0[u] = make_float4(0.f, 0.f, 0.f, 0.f); f1[u] = f0[u]; }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float fv[8] = {f0[u].x, f0[u].y, f0[u].z, f0[u].w, f1[u].x, f1[u].y, f1[u].z, f1[u].w};
+            typename FcMfma<T>::v8 hi, lo;   // fp32 feature = storage-type head + rounding remainder, as in fc_kernel
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                hi[e] = (typename FcMfma<T>::elem)fv[e];
+                lo[e] = (typename FcMfma<T>::elem)(fv[e] - (float)hi[e]);
+            }
+            const typename FcMfma<T>::v8 wv = *reinterpret_cast<const typename FcMfma<T>::v8 *>(&wraw[u]);
+            acc = FcMfma<T>::mma(wv, hi, acc);
+            acc = FcMfma<T>::mma(wv, lo, acc);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) part[wave][4 * g + e][r] = acc[e];
+    __syncthreads();
+    const int t = threadIdx.x;           // 256 threads = 16 outputs x 16 samples
+    const int oj = t >> 4, on = t & 15;
+    const int jj = blockIdx.x * 16 + oj;
+    const bool live = jj < Out && on < B;
+    float v = (part[0][oj][on] + part[1][oj][on]) + (part[2][oj][on] + part[3][oj][on]);
+    if (S > 1) {
+        if (live) __hip_atomic_store(&partial[((size_t)blockIdx.y * 16 + on) * Out + jj], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0);   // this thread's partial sum has been written
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();                 // ... and so have the workgroup's
+        if (t == 0) {
+            const int ticket = __hip_atomic_fetch_add(&counters[blockIdx.x], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = ticket == S - 1;
+            if (last) __hip_atomic_store(&counters[blockIdx.x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+            s_last = last;
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        v = 0.f;
+        if (live)
+            for (int s = 0; s < S; ++s)
+                v += __hip_atomic_load(&partial[((size_t)s * 16 + on) * Out + jj], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (live) __hip_atomic_store(&z[(size_t)on * Out + jj], v + bias[jj], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // ---- the workgroup that completes the last tile turns the logits into probabilities
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (t == 0) {
+        int *all = counters + gridDim.x;
+        const int ticket = __hip_atomic_fetch_add(all, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = ticket == (int)gridDim.x - 1;
+        if (last) __hip_atomic_store(all, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    constexpr int PER = kFcSoftmaxMaxOut / 64, ROWS = kFcSoftmaxMaxBatch / kFcsWaves;
+    float vals[ROWS][PER];
+#pragma unroll
+    for (int q = 0; q < ROWS; ++q) {
+        const int row = wave + kFcsWaves * q;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int c = lane + 64 * e;
+            vals[q][e] = (row < B && c < Out) ? __hip_atomic_load(&z[(size_t)row * Out + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < ROWS; ++q) {
+        const int row = wave + kFcsWaves * q;
+        if (row >= B) continue;   // uniform per wave
+        float m = vals[q][0];
+#pragma unroll
+        for (int e = 1; e < PER; ++e) m = fmaxf(m, vals[q][e]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            vals[q][e] = expf(vals[q][e] - m);   // classes past Out: exp(-inf) = 0
+            sum += vals[q][e];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        const float inv = 1.f / sum;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int c = lane + 64 * e;
+            if (c < Out) p[(size_t)row * Out + c] = vals[q][e] * inv;
+        }
+    }
+}
+
 // ---- softmax over D values per row; one workgroup of 256 per row, wavefront reductions ---
 __global__ __launch_bounds__(256) void softmax_kernel(const SoftmaxArgs a) {
     __shared__ float red[4];
@@ -656,6 +787,15 @@ hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s) {
+    if (a.p) {   // FC + softmax in one launch
+        const int S = a.split_k;
+        if (a.B < 1 || a.B > kFcSoftmaxMaxBatch || a.Out < 1 || a.Out > kFcSoftmaxMaxOut || (S != 1 && S != 2 && S != 4) ||
+            a.In % (32 * kFcsWaves * S) != 0 || !a.counters || (S > 1 && !a.partial))
+            return hipErrorInvalidValue;
+        CW_DISPATCH(dt, fc_softmax_kernel, dim3(blocks_for(a.Out, 16), S), 64 * kFcsWaves, s, a.f, a.w, a.bias, a.z, a.p, a.partial,
+                    a.counters, a.B, a.In, a.Out, S);
+        return hipGetLastError();
+    }
     if (a.In % (32 * kFcWaves) != 0 || a.B < 1 || a.Out < 1) return hipErrorInvalidValue;
     const dim3 grid(blocks_for(a.Out, 16), blocks_for(a.B, 16));
     CW_DISPATCH(dt, fc_kernel, grid, 64 * kFcWaves, s, a.f, a.w, a.bias, a.z, a.B, a.In, a.Out);

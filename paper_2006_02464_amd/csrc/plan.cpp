@@ -832,11 +832,30 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 l.info.flops = 2 * (int64_t)batch * o.cout * o.cin;
                 l.info.bytes = (int64_t)batch * o.cin * 4 + (int64_t)o.cout * o.cin * esz + o.cout * 4 + (int64_t)batch * o.cout * 4;
                 snprintf(l.info.name, sizeof l.info.name, "fc");
+                // The softmax that follows (model_init has checked that it does) runs in the same
+                // launch where the finishing workgroup can hold every row in registers.
+                if (ov.fc_softmax && batch <= kFcSoftmaxMaxBatch && o.cout <= kFcSoftmaxMaxOut) {
+                    l.fc.split_k = o.cin % 512 == 0 ? 4 : 2;   // cin % 256 == 0 holds for every FC
+                    partial_bytes = (size_t)l.fc.split_k * 16 * o.cout * 4;
+                    partial_off = ws_alloc(partial_bytes);
+                    l.partial = Ref{SP_WORKSPACE, partial_off};
+                    l.counters = Ref{SP_WORKSPACE, 0};
+                    l.probs = Ref{SP_SLOT_PROBS, 0};
+                    l.info.split_k = l.fc.split_k;
+                }
                 p.launches.push_back(l);
                 break;
             }
             case CW_OP_SOFTMAX: {
                 p.op_out[i] = Ref{SP_SLOT_PROBS, 0};
+                if (!p.launches.empty() && p.launches.back().kind == K_FC && p.launches.back().probs.space == SP_SLOT_PROBS) {
+                    Launch &lf = p.launches.back();   // computed by the FC's launch
+                    lf.info.fused_op = lf.op_index;
+                    lf.op_index = i;
+                    lf.info.bytes += (int64_t)batch * o.cout * 4;   // the probabilities; the logits are not read back from HBM
+                    snprintf(lf.info.name, sizeof lf.info.name, "fc+softmax");
+                    break;
+                }
                 Launch l{};
                 l.kind = K_SOFTMAX;
                 l.op_index = i;
@@ -985,7 +1004,10 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
-            case K_FC: g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; break;
+            case K_FC:
+                if (l.probs.space == SP_SLOT_PROBS) { g = dim3((l.fc.Out + 15) / 16, l.fc.split_k); b = 256; }
+                else { g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; }
+                break;
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
             case K_DWCONV: g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256)); b = 256; break;
             case K_COPY_CHANNELS: g = dim3((unsigned)(((size_t)l.copy.pixels * (l.copy.C / 8) + 255) / 256)); b = 256; break;
@@ -994,7 +1016,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case K_WINO_OUTPUT: g = dim3((unsigned)(((size_t)l.wino.B * l.wino.th * l.wino.tw * (l.wino.C / 8) + 255) / 256)); b = 256; break;
         }
         l.info.op_index = l.op_index;
-        if (l.fused_bm <= 0) { l.info.fused_op = -1; l.info.proj_op = -1; }
+        const bool fc_sm = l.kind == K_FC && l.probs.space == SP_SLOT_PROBS;   // fused_op = the FC, set where the softmax joined it
+        if (l.fused_bm <= 0) { if (!fc_sm) l.info.fused_op = -1; l.info.proj_op = -1; }
         l.info.pair_op = l.pair_op;
         l.info.kind = l.kind;
         if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }

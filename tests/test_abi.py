@@ -196,7 +196,7 @@ def test_fusion_of_bottleneck_tail(ctx):
     the intermediate tensor of a fused launch has no place to be read back from."""
     m = ctx.model_define_resnet(50, 224, 224)
     ops = ctx.model_get_ops(m)
-    fused = [l for l in ctx.plan(m, 16) if l["fused_op"] >= 0]
+    fused = [l for l in ctx.plan(m, 16) if l["fused_op"] >= 0 and l["kind"] == 1]
     assert len(fused) == 7
     assert [l["proj_op"] >= 0 for l in fused] == [True] + [False] * 6   # the stride-1 projection of the first block
     proj = ops[fused[0]["proj_op"]]
@@ -205,17 +205,17 @@ def test_fusion_of_bottleneck_tail(ctx):
         first, second = ops[l["fused_op"]], ops[l["op_index"]]
         assert first[3] == 3 and second[3] == 1 and second[1] == first[2] and first[2] in (64, 128)
         assert l["grid_x"] == -(-l["gemm_m"] // l["tile_m"]) and l["grid_y"] == 1 and l["split_k"] == 1
-    assert not [l for l in ctx.plan(m, 1) if l["fused_op"] >= 0]
+    assert not [l for l in ctx.plan(m, 1) if l["fused_op"] >= 0 and l["kind"] == 1]
     ctx.set_fusion(0)
     try:
         m2 = ctx.model_define_resnet(50, 224, 224)
-        assert not [l for l in ctx.plan(m2, 16) if l["fused_op"] >= 0]
+        assert not [l for l in ctx.plan(m2, 16) if l["fused_op"] >= 0 and l["kind"] == 1]
     finally:
         ctx.set_fusion(1)
     ctx.set_debug_keep(True)
     try:
         m3 = ctx.model_define_resnet(50, 224, 224)
-        kept = [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0]
+        kept = [l for l in ctx.plan(m3, 16) if l["fused_op"] >= 0 and l["kind"] == 1]
         assert [(l["fused_op"], l["op_index"], l["proj_op"]) for l in kept] == [
             (l["fused_op"], l["op_index"], l["proj_op"]) for l in fused]
     finally:

@@ -263,6 +263,51 @@ def test_pool_and_softmax_shapes_off_the_resnet_path(worker, classes):
     worker.ctx.unload_weights(mid)
 
 
+@pytest.mark.parametrize("feat,classes,dtype", [(256, 1000, "fp16"), (768, 10, "fp16"), (512, 1024, "bf16"), (1024, 37, "fp16")])
+def test_fc_and_softmax_in_one_launch(worker, feat, classes, dtype):
+    """FC + softmax as one launch (K split over 2 or 4 workgroups per 16 outputs, softmax by the
+    workgroup that finishes last) against the oracle on moderate logits, against the two-launch
+    plan, at batch 1, 5 and 16, and bit-identical over 100 EXECs (arrival order must not matter).
+    256 and 768 features: two splits; 512 and 1024: four.  10 and 37 classes: ragged output tiles."""
+    O = T.Op
+    ops = [
+        O(T.CONV, 3, 64, 3, 3, 2, 1, 1, -1, -1),
+        O(T.CONV, 64, feat, 3, 3, 2, 1, 1, -1, 0),
+        O(T.GAVGPOOL, feat, feat, 0, 0, 1, 0, 0, -1, 1),
+        O(T.FC, feat, classes, 1, 1, 1, 0, 0, -1, 2),
+        O(T.SOFTMAX, classes, classes, 0, 0, 1, 0, 0, -1, 3),
+    ]
+    case = Case(ops, 16, seed=13, dtype=dtype, dist="uniform", weight_gain=[1.0, 1.0, 0.05])
+    ctx = worker.ctx
+    ctx.set_debug_keep(True)
+    try:
+        two = ctx.model_define(case.ops, 3, 16, 16, batch_sizes=(1, 5, 16), dtype=dtype)
+        ctx.set_fc_softmax(1)
+        one = ctx.model_define(case.ops, 3, 16, 16, batch_sizes=(1, 5, 16), dtype=dtype)
+    finally:
+        ctx.set_debug_keep(False)
+        ctx.set_fc_softmax(0)
+    for batch in (16, 5, 1):
+        p1, p2 = ctx.plan(one, batch), ctx.plan(two, batch)
+        assert [l["name"] for l in p1][-1] == "fc+softmax" and p1[-1]["split_k"] == (4 if feat % 512 == 0 else 2)
+        assert [l["name"] for l in p2][-2:] == ["fc", "softmax"] and len(p1) == len(p2) - 1
+        x = case.images(0, batch)
+        worker.load(two, case.blob)
+        probs2, logits2, _ = worker.infer(two, x, classes=classes)
+        ctx.unload_weights(two)
+        worker.load(one, case.blob)
+        probs, logits, _ = worker.infer(one, x, classes=classes)
+        outs, _, gpu = check_all_ops(worker, case, one, batch, x)
+        check_head(case, gpu[-1], logits, probs)
+        assert probs.max() < 0.999 and np.abs(probs.sum(axis=1) - 1).max() <= 1e-5
+        assert np.abs(logits - logits2).max() <= 1e-5 * np.abs(logits2).max()
+        assert np.abs(probs - probs2).max() <= 1e-6
+        for _ in range(100 if batch == 16 else 10):
+            pr, lg, _ = worker.infer(one, x, classes=classes)
+            assert np.array_equal(lg, logits) and np.array_equal(pr, probs)
+        ctx.unload_weights(one)
+
+
 # ---------------------------------------------------------------- bf16
 def test_resnet18_bf16(worker):
     case = Case(T.resnet(18), 64, seed=2, dtype="bf16", dist="uniform")
@@ -347,11 +392,11 @@ def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
     finally:
         ctx.set_fusion(1)
     for batch in (16, 8):
-        blocks = {name: sorted({l["block"] for l in ctx.plan(mid, batch) if l["fused_op"] >= 0})
+        blocks = {name: sorted({l["block"] for l in ctx.plan(mid, batch) if l["fused_op"] >= 0 and l["kind"] == 1})
                   for name, mid in (("fused", fused), ("fused1", fused1), ("plain", plain))}
         # two groups of four waves for the 128-channel pairs (stage 2, fused at batch 16 only), one group for the 64-channel ones
         assert blocks == {"fused": [256, 512] if batch == 16 else [256], "fused1": [256], "plain": []}
-        n_fused = sum(l["fused_op"] >= 0 for l in ctx.plan(fused, batch))
+        n_fused = sum(l["fused_op"] >= 0 and l["kind"] == 1 for l in ctx.plan(fused, batch))
         out = {}
         for name, mid in (("fused", fused), ("fused1", fused1), ("plain", plain)):
             worker.load(mid, case.blob)

@@ -63,7 +63,7 @@ def check_every_launch(worker, case, mid, batch, x):
     ops = case.ops
     shapes = T.shapes(ops, case.hw, case.hw)
     plan = ctx.plan(mid, batch)
-    fused = {l["op_index"]: (l["fused_op"], l["proj_op"]) for l in plan if l["fused_op"] >= 0}
+    fused = {l["op_index"]: (l["fused_op"], l["proj_op"]) for l in plan if l["fused_op"] >= 0 and l["kind"] == 1}
     unstored = {f for f, _ in fused.values()} | {d for _, d in fused.values() if d >= 0}
     widx, k = {}, 0
     for i, o in enumerate(ops):
