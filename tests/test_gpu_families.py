@@ -78,3 +78,39 @@ def test_mobilenet_224_batch16_and_small_batches(worker):
     p = ctx.profile_measure(mid, 16, 200)
     print("mobilenet 224 b16 EXEC p50 %.1f us" % p["p50_us"])
     ctx.unload_weights(mid)
+
+
+def test_depthwise_shapes_off_the_mobilenet_path(worker):
+    """Depthwise filters MobileNet does not have (5x5 padding 2 with hard swish, 3x3 without padding,
+    3x3 stride 3) and 3x3 ones on odd map widths (19, 10, 8, 3 columns), one with a residual: every
+    layer against the oracle."""
+    O = T.Op
+    ops = [
+        O(T.CONV, 3, 64, 3, 3, 1, 1, 1, -1, -1),                 # 0   19x19
+        O(T.CONV, 64, 64, 5, 5, 1, 2, 2, -1, 0, 0, 64),           # 1   5x5 depthwise, hard swish
+        O(T.CONV, 64, 64, 3, 3, 1, 1, 1, 0, 1, 0, 64),            # 2   19 columns, residual
+        O(T.CONV, 64, 64, 3, 3, 2, 1, 0, -1, 2, 0, 64),           # 3   stride 2 -> 10x10
+        O(T.CONV, 64, 64, 3, 3, 1, 0, 1, -1, 3, 0, 64),           # 4   no padding -> 8x8
+        O(T.CONV, 64, 64, 3, 3, 1, 1, 1, -1, 4, 0, 64),           # 5
+        O(T.CONV, 64, 64, 3, 3, 3, 1, 1, -1, 5, 0, 64),           # 6   stride 3 -> 3x3
+        O(T.CONV, 64, 256, 1, 1, 1, 0, 1, -1, 6),                 # 7
+        O(T.GAVGPOOL, 256, 256, 0, 0, 1, 0, 0, -1, 7),
+        O(T.FC, 256, 100, 1, 1, 1, 0, 0, -1, 8),
+        O(T.SOFTMAX, 100, 100, 0, 0, 1, 0, 0, -1, 9),
+    ]
+    for dtype, batch in (("fp16", 5), ("bf16", 2)):
+        case = Case(ops, 19, seed=31, dtype=dtype, dist="normal")
+        ctx = worker.ctx
+        ctx.set_debug_keep(True)
+        try:
+            mid = ctx.model_define(case.ops, 3, 19, 19, batch_sizes=(batch,), dtype=dtype)
+        finally:
+            ctx.set_debug_keep(False)
+        assert sum(l["name"].startswith("dwconv") for l in ctx.plan(mid, batch)) == 6
+        worker.load(mid, case.blob)
+        x = case.images(0, batch)
+        probs, logits, ns = worker.infer(mid, x, classes=100)
+        wp, wf, nf, gpu = check_every_launch(worker, case, mid, batch, x)
+        ref = case.oracle(x)["logits"]
+        assert rel_err_per_sample(logits, ref).max() <= TOL
+        ctx.unload_weights(mid)
