@@ -31,6 +31,8 @@ typedef struct {
     int32_t tile_m, tile_n, tile_k, split_k; /* conv: pixels x channels per workgroup, K slice */
     int32_t conv_tile;     /* conv: the tile variant in cw_set_plan_override's numbering; -1 for a fused pair and for other kinds */
     int32_t wave_groups;   /* conv: groups of waves that split every K slice (1 = none) */
+    int32_t next_op;       /* -1, or the 1x1 convolution over op_index's output that a fused launch computes as well (its
+                              output is stored like op_index's) */
     int32_t panels;        /* conv: channel panels of the tile numbering (1 = row by row; see cw_set_panels); a pair
                               launch: of op_index's convolution in the low byte, of pair_op's in the next */
     int64_t gemm_m, gemm_n, gemm_k; /* 0 for non-GEMM launches */
@@ -82,6 +84,10 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
  * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
  * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
 int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
+/* A fused launch (see above) may also compute the 1x1 stride-1 convolution that reads its output:
+ * the next bottleneck's reduce, whose input then never comes back from memory.  on == 0 plans that
+ * convolution as a launch of its own for models defined afterwards; on != 0 restores the default. */
+int32_t cw_set_fusion_third(cw_ctx *ctx, int32_t on);
 /* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
  * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
  * one launch whose first workgroups compute the one and the rest the other: one dispatch and one

@@ -43,7 +43,7 @@ class cw_profile(Structure):
 class cw_launch_info(Structure):
     _fields_ = [("op_index", c_int32), ("fused_op", c_int32), ("proj_op", c_int32), ("pair_op", c_int32), ("kind", c_int32), ("grid_x", c_int32), ("grid_y", c_int32),
                 ("grid_z", c_int32), ("block", c_int32), ("tile_m", c_int32), ("tile_n", c_int32),
-                ("tile_k", c_int32), ("split_k", c_int32), ("conv_tile", c_int32), ("wave_groups", c_int32), ("panels", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
+                ("tile_k", c_int32), ("split_k", c_int32), ("conv_tile", c_int32), ("wave_groups", c_int32), ("next_op", c_int32), ("panels", c_int32), ("gemm_m", c_int64), ("gemm_n", c_int64), ("gemm_k", c_int64),
                 ("bytes", c_int64), ("flops", c_int64), ("name", c_char * 48)]
 
 
@@ -105,6 +105,7 @@ SIGNATURES = {
     "cw_set_fusion": (c_int32, [c_void_p, c_int32]),
     "cw_set_pair_launches": (c_int32, [c_void_p, c_int32]),
     "cw_set_panels": (c_int32, [c_void_p, c_int32]),
+    "cw_set_fusion_third": (c_int32, [c_void_p, c_int32]),
     "cw_set_fc_softmax": (c_int32, [c_void_p, c_int32]),
     "cw_set_winograd": (c_int32, [c_void_p, c_int32]),
     "cw_set_resident": (c_int32, [c_void_p, c_int32]),
@@ -337,6 +338,9 @@ class Context:
 
     def set_fc_softmax(self, on):
         self._check(lib().cw_set_fc_softmax(self._h, int(on)))
+
+    def set_fusion_third(self, on):
+        self._check(lib().cw_set_fusion_third(self._h, int(on)))
 
     def set_panels(self, on):
         self._check(lib().cw_set_panels(self._h, int(on)))

@@ -223,6 +223,9 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
                 a.x2 = resolve(c, m, s, l.x2);
                 a.wd = resolve(c, m, s, l.wd);
                 a.biasd = reinterpret_cast<const float *>(resolve(c, m, s, l.biasd));
+                a.w3 = resolve(c, m, s, l.w3);
+                a.bias3 = reinterpret_cast<const float *>(resolve(c, m, s, l.bias3));
+                a.y3 = resolve(c, m, s, l.y3);
                 return launch_conv_fused(dt, l.fused_bm, l.fused_kg, a, st);
             }
             if (l.pair_op >= 0) {
@@ -397,7 +400,7 @@ void free_slot(cw_ctx *c, Slot *s) {
 
 
 bool slot_free(const Launch &l) {
-    for (const Ref *r : {&l.x, &l.w, &l.bias, &l.res, &l.y, &l.partial, &l.counters, &l.probs})
+    for (const Ref *r : {&l.x, &l.w, &l.bias, &l.res, &l.y, &l.partial, &l.counters, &l.probs, &l.y3})
         if (r->space == SP_SLOT_INPUT || r->space == SP_SLOT_LOGITS || r->space == SP_SLOT_PROBS) return false;
     return true;
 }
@@ -627,6 +630,12 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "fusion mode must be 0, 1 or 2");
     c->ov.fuse = on;
+    return CW_OK;
+}
+
+int32_t cw_set_fusion_third(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.fuse_third = on != 0;
     return CW_OK;
 }
 

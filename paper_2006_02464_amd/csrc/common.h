@@ -93,7 +93,14 @@ struct alignas(64) ConvArgs {
     // byte strides (bias and res are not used then).  Read only by z > 0.
     int32_t nz;
     int32_t panel_log2;  // host side only: tile numbering of this launch (conv_pack_nb); the kernel gets it inside its tile count
-    long long zs_x, zs_w, zs_y;
+    union {
+        struct { long long zs_x, zs_w, zs_y; };
+        // Fused form only (never batched): a third layer, the 1x1 stride-1 convolution that reads the
+        // second layer's output (the next bottleneck's reduce), y3 = act3(bias3 + W3 * y), Cout3 = Cout.
+        // y is still stored (it is the next block's shortcut); y3 is stored besides.  w3 == nullptr: none.
+        struct { const void *w3; const float *bias3; void *y3; };
+    };
+    int32_t relu3;
 };
 static_assert(offsetof(ConvArgs, B) == 64 && offsetof(ConvArgs, khp) == 128 && sizeof(ConvArgs) == 256, "argument lines");
 // Tile numbering.  A launch's workgroups go to the 8 XCDs in turn and each XCD keeps a contiguous run

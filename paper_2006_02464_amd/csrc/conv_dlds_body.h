@@ -59,13 +59,14 @@ static __device__ __forceinline__ u32x4 make_desc(const void *p, unsigned bytes)
 extern __shared__ __attribute__((aligned(16))) unsigned char cw_dyn_lds[];
 
 // LDS bytes of the fused second layer (see the end of the kernel): the first layer's tile, two
-// buffers of {a chunk of W2, the matching residual tile}.  Both layers' biases sit behind
-// whichever is larger, this or the ring, from the start of the kernel.
+// buffers of {a chunk of W2, the matching residual tile}, and one chunk of a third layer's weights.
+// The layers' biases sit behind whichever is larger, this or the ring, from the start of the kernel.
 constexpr int fused_chunk(int bn, int kg) { return kg > 1 ? 128 : (bn == 128 ? 64 : bn); }   // second-layer channels per chunk
 constexpr unsigned fused_lds_bytes(int bm, int bn, int kg) {
     const int p = bm * bn * 2, w2 = fused_chunk(bn, kg) * bn * 2, r = bm * fused_chunk(bn, kg) * 2;
     // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile (as large as p)
-    const int plain = 2 * (w2 + r), proj = bn == 64 ? 4 * w2 + p : 0;
+    const int w3 = bn * fused_chunk(bn, kg) * 2;   // third layer: Cout3 = bn output rows x a chunk of its K
+    const int plain = 2 * (w2 + r) + w3, proj = bn == 64 ? 4 * w2 + p : 0;
     return (unsigned)(p + (plain > proj ? plain : proj));
 }
 constexpr int kFusedMaxCout2 = 1024;
@@ -109,9 +110,10 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
     // flight yet at that point (visible to every wave after the first barrier).
     constexpr unsigned BIAS_OFF = FUSED ? (NS * STAGE_BYTES > fused_lds_bytes(BM, BN, KG) ? NS * STAGE_BYTES : fused_lds_bytes(BM, BN, KG)) : 0u;
     constexpr int B2_PER = FUSED ? (kFusedMaxCout2 + NT - 1) / NT : 1;
-    float bias1_v = 0.f, bias2_v[B2_PER];
+    float bias1_v = 0.f, bias2_v[B2_PER], bias3_v = 0.f;
     if constexpr (FUSED) {
         if (tid < BN) bias1_v = a.bias[tid];
+        if (tid < BN && a.w3) bias3_v = a.bias3[tid];
 #pragma unroll
         for (int j = 0; j < B2_PER; ++j) {
             const int n = tid + j * NT;
@@ -241,6 +243,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             const int n = tid + j * NT;
             if (n < a.Cout2) sb[BN + n] = bias2_v[j];
         }
+        if (tid < BN && a.w3) sb[BN + a.Cout2 + tid] = bias3_v;
     }
 
     // (r, s, c0) of the next K slice to load: k0 = kt*BK = (r*kw + s)*Cin + c0.
@@ -428,7 +431,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
         constexpr int ST = TM * TN2 * 2;                           // stores per thread per chunk
         constexpr unsigned P_BYTES = BM * BN * 2u, W2_BYTES = BN2 * BN * 2u, R_BYTES = BM * BN2 * 2u;
         constexpr unsigned BUF_BYTES = W2_BYTES + R_BYTES;
-        static_assert(BIAS_OFF + (BN + kFusedMaxCout2) * 4 <= 160 * 1024, "second layer does not fit the LDS");
+        static_assert(BIAS_OFF + (BN + kFusedMaxCout2 + BN) * 4 <= 160 * 1024, "second layer does not fit the LDS");
         T *sP = lds;
         const float *sBias1 = reinterpret_cast<const float *>(cw_dyn_lds + BIAS_OFF);
         const float *sBias = sBias1 + BN;
@@ -461,6 +464,39 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             x2_voff[j] = m < (unsigned)a.M ? (m * (unsigned)BN + c * 8) * 2u : kOob;
         }
         constexpr unsigned XB_OFF = P_BYTES + 4 * W2_BYTES;   // x2 tile, projection form only
+        // Third layer (a.w3; never together with the projection form; Cout3 = BN): y3 = act3(bias3 + W3 * y).
+        // Its K is the second layer's Cout2, walked in the same chunks: once a chunk of y is final
+        // (rounded to the storage type, as it is stored), the threads write it back over the residual
+        // tile they have just read, element for element, which is then the chunk's activation operand;
+        // W3[:, chunk] comes into a buffer of its own while the chunk's second-layer MFMAs run.  The
+        // waves keep the first layer's channel split; acc3 lives across the chunks.
+        constexpr bool THIRD_OK = BN / (WARPS_N * KG) >= 32;   // every wave gets whole 32-channel tiles of the third layer
+        const bool third = THIRD_OK && a.w3 != nullptr;        // uniform
+        constexpr int W3_PER = BN * CR2 / NT;
+        static_assert(BN * CR2 % NT == 0, "tile/threads mismatch");
+        constexpr unsigned W3_OFF = P_BYTES + 2 * BUF_BYTES;
+        constexpr int TN3 = THIRD_OK ? BN / (WARPS_N * KG) / 32 : 1;
+        static_assert(TN3 <= TN, "third-layer wave tile");
+        const int wn3 = (kg * WARPS_N + wq % WARPS_N) * (BN / (WARPS_N * KG));
+        const u32x4 dw3 = make_desc(third ? a.w3 : a.w2, (unsigned)BN * a.Cout2 * 2u);
+        unsigned w3_voff[W3_PER];
+#pragma unroll
+        for (int j = 0; j < W3_PER; ++j) {
+            const int cid = tid + j * NT, row = cid / CR2, c = (cid % CR2) ^ swz_key<BN2>(row);
+            w3_voff[j] = (unsigned)(row * a.Cout2 + c * 8) * 2u;
+        }
+        auto issue_w3 = [&](int c) {
+            const unsigned dst = lds_base + W3_OFF + (unsigned)wave * 1024u;
+#pragma unroll
+            for (int j = 0; j < W3_PER; ++j) load_to_lds(dw3, w3_voff[j], (unsigned)c * (BN2 * 2u), dst + j * (NT * 16));
+        };
+        f32x16 acc3[TM][TN3];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN3; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc3[i][j][e] = 0.f;
         auto buf_off = [&](int c) { return P_BYTES + (unsigned)(c & 1) * (proj ? 2 * W2_BYTES : BUF_BYTES); };
         auto issue_chunk = [&](int c) {
             const unsigned dst = lds_base + buf_off(c) + (unsigned)wave * 1024u;
@@ -529,9 +565,10 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             // chunk c has landed (mine: vmcnt; everyone's: barrier); p and the bias are visible;
             // every wave has finished reading the buffer that chunk c+1 is about to overwrite
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
+            if (third) issue_w3(c);   // ahead of the next chunk's loads: it is awaited first
             if (c + 1 < chunks) issue_chunk(c + 1);
             const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
-            const T *sR = sW2 + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
+            T *sR = reinterpret_cast<T *>(cw_dyn_lds + buf_off(c)) + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
             const T *sXb = reinterpret_cast<const T *>(cw_dyn_lds + XB_OFF);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -575,6 +612,47 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
                         }
                         const unsigned o = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + (unsigned)(c * BN2 + nl)) * 2u : kOob;
                         __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
+                        if (third) *reinterpret_cast<u32x4 *>(sR + swz<BN2>(wm0 + i * 32 + lrow, nl >> 3)) = *reinterpret_cast<const u32x4 *>(out);
+                    }
+            }
+            if (third) {
+                // The chunk of y is in LDS (everyone's: barrier) and W3[:, chunk] has landed: younger than
+                // it are only the next chunk's loads and this chunk's stores.
+                if (c + 1 < chunks) wait_lds_loads_and_barrier<W2_PER + R_PER + ST>(); else wait_lds_loads_and_barrier<ST>();
+                const T *sW3 = reinterpret_cast<const T *>(cw_dyn_lds + W3_OFF);
+#pragma unroll
+                for (int kk = 0; kk < BN2 / 16; ++kk) {
+                    v8 px[TM], pw[TN3];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sR + swz<BN2>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+                    for (int j = 0; j < TN3; ++j) pw[j] = *reinterpret_cast<const v8 *>(sW3 + swz<BN2>(wn3 + j * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN3; ++j) acc3[i][j] = Mfma<T>::mma(pw[j], px[i], acc3[i][j]);
+                }
+            }
+        }
+        if (third) {
+            const float *sBias3 = sBias + a.Cout2;
+            const __amdgpu_buffer_rsrc_t ry3 = make_rsrc(a.y3, (unsigned)a.M * BN * 2u);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const unsigned m = m0 + wm0 + i * 32 + lrow;
+#pragma unroll
+                for (int j = 0; j < TN3; ++j)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int n = wn3 + j * 32 + q * 16 + lhalf * 8;
+                        T out[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float v = acc3[i][j][8 * q + e] + sBias3[n + e];
+                            out[e] = (T)(a.relu3 ? fmaxf(v, 0.f) : v);
+                        }
+                        const unsigned o = m < (unsigned)a.M ? (m * (unsigned)BN + (unsigned)n) * 2u : kOob;
+                        __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry3, o, 0, 0);
                     }
             }
         }

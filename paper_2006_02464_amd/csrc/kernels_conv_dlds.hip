@@ -152,12 +152,13 @@ static hipError_t launch_fused_one(const ConvArgs &a_in, hipStream_t s) {
     constexpr size_t ring = (size_t)NS * (BM + BN) * 64 * 2;
     auto kern = conv_dlds_kernel<T, BM, BN, 2, 2, 64, NS, MODE, false, true, KG>;
     constexpr size_t bias_off = std::max<size_t>(ring, fused_lds_bytes(BM, BN, KG));
-    static_assert(bias_off + (BN + kFusedMaxCout2) * 4 <= 160 * 1024, "fused form does not fit the LDS");
-    const size_t need = bias_off + (size_t)(BN + a.Cout2) * 4;
+    static_assert(bias_off + (BN + kFusedMaxCout2 + BN) * 4 <= 160 * 1024, "fused form does not fit the LDS");
+    const size_t need = bias_off + (size_t)(BN + a.Cout2 + (a.w3 ? BN : 0)) * 4;
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 (int)(bias_off + (BN + kFusedMaxCout2) * 4));
+                                                 (int)(bias_off + (BN + kFusedMaxCout2 + BN) * 4));
     if (attr != hipSuccess) return attr;
     if (a.Cout2 % fused_chunk(BN, KG) != 0) return hipErrorInvalidValue;
+    if (a.w3 && BN / (2 * KG) < 32) return hipErrorInvalidValue;   // the third layer needs whole 32-channel tiles per wave
     kern<<<dim3((a.M + BM - 1) / BM, 1, 1), 256 * KG, need, s>>>(a.x, a.w, a.res, a.y, a.M, a.K, a.Cout | (conv_ldy(a) << 16), a.Cin | (conv_ldx(a) << 16), a.nb, a.relu, a);
     return hipGetLastError();
 }
@@ -181,6 +182,10 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
     if (!a.w2 || !a.bias2) return hipErrorInvalidValue;
     if (a.wd ? (a.Cout != 64 || !a.x2 || !a.biasd) : !a.res) return hipErrorInvalidValue;
     if (!a.res && !a.wd) return hipErrorInvalidValue;
+    // third layer: over the second layer's output, as many channels as the first layer has; not with the projection form
+    if (a.w3 && (a.wd || !a.bias3 || !a.y3 || (long long)a.M * a.Cout * 2 >= (1ll << 31) || (long long)a.Cout * a.Cout2 * 2 >= (1ll << 31)))
+        return hipErrorInvalidValue;
+    if (a.nz > 1) return hipErrorInvalidValue;   // the batched form's strides share their place with the third layer's pointers
     if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;
     if (conv_ldx(a) != a.Cin || conv_ldy(a) != a.Cout) return hipErrorInvalidValue;   // the fused form takes dense tensors only
     if ((long long)a.B * a.H * a.W * a.Cin * 2 + (long long)(conv_pad_h(a) * a.W + conv_pad_w(a)) * a.Cin * 2 >= (1ll << 31)) return hipErrorInvalidValue;

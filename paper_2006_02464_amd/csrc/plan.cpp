@@ -388,6 +388,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     const bool resident = ov.resident && batch % kResPartitions == 0 && ov.tile < 0 && ov.split_k <= 0 && !m.winograd;
     const bool no_reuse = ov.keep_all || resident;
     std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), fused_kg(n_ops, 1), proj_of(n_ops, -1);
+    std::vector<int> third_of(n_ops, -1), in_third(n_ops, -1);   // fused launch of op j also computes op third_of[j]; in_third[k] = j
     if (ov.fuse && !resident && ov.tile < 0 && ov.split_k <= 0) {
         std::vector<int> uses(n_ops, 0);
         for (int i = 0; i < n_ops; ++i) {
@@ -427,6 +428,28 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 fuse_into[d] = j;
             }
         }
+        // Third layer: the 1x1 stride-1 convolution that is the only one to read op j's output as its
+        // input (the next bottleneck's reduce; the output's other reader is that block's shortcut), with
+        // as many output channels as op i.  Not with the in-launch projection (its LDS is taken).
+        if (ov.fuse_third) {
+            std::vector<int> in_readers(n_ops, 0);
+            for (int i = 0; i < n_ops; ++i)
+                if (m.ops[i].op == CW_OP_CONV && m.ops[i].input_from >= 0) ++in_readers[m.ops[i].input_from];
+            for (int j = 0; j + 1 < n_ops; ++j) {
+                if (fused_first[j] < 0 || proj_of[j] >= 0 || in_readers[j] != 1) continue;
+                const int k = j + 1;
+                const cw_op &o3 = m.ops[k];
+                if (o3.op != CW_OP_CONV || o3.input_from != j || o3.kh != 1 || o3.kw != 1 || o3.stride != 1 || o3.pad != 0) continue;
+                if (o3.residual_from >= 0 || o3.relu > 1 || o3.groups > 1 || o3.cin != m.ops[j].cout || o3.cout != m.ops[fused_first[j]].cout) continue;
+                if (fuse_into[k] >= 0 || fused_first[k] >= 0) continue;
+                bool concat_reader = false;   // its output must be a dense tensor of its own
+                for (int r = k + 1; r < n_ops; ++r)
+                    if (m.ops[r].op == CW_OP_CONCAT && (m.ops[r].input_from == k || m.ops[r].residual_from == k)) concat_reader = true;
+                if (concat_reader) continue;
+                third_of[j] = k;
+                in_third[k] = j;
+            }
+        }
     }
     // Order in which the ops are planned and launched: op order, except that a convolution j which
     // reads the same tensor as an earlier convolution i and depends on nothing after i (a ResNet
@@ -440,10 +463,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
                 if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
+                if (in_third[i] >= 0) continue;
                 if (m.winograd && wino_eligible(a, i)) continue;
                 for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
                     const cw_op &b = m.ops[j];
-                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j]) continue;
+                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j] || in_third[j] >= 0) continue;
                     if (b.residual_from >= i || (m.winograd && wino_eligible(b, j))) continue;
                     partner[i] = j; moved[j] = 1;
                     break;
@@ -462,7 +486,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // fused launch reads its inputs when that launch runs.
     std::vector<int> last_use(n_ops, -1);
     for (int i = 0; i < n_ops; ++i) {
-        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : i];
+        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : (in_third[i] >= 0 ? in_third[i] : i)];
         if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = std::max(last_use[m.ops[i].input_from], at);
         if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0)
             last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
@@ -573,6 +597,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             case CW_OP_CONV: {
                 const WeightSlot &ws = m.wslots[m.op_wslot[i]];
                 if (fuse_into[i] >= 0) break;  // computed inside the launch of op fuse_into[i]; its output is never stored
+                if (in_third[i] >= 0) break;   // computed, and its output placed, by the fused launch of op in_third[i]
                 if (fused_first[i] >= 0) {
                     const int f = fused_first[i];
                     const cw_op &o1 = m.ops[f];
@@ -624,6 +649,24 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                         l.res = p.op_out[o.residual_from];
                         l.info.bytes += (int64_t)out_bytes[i];   // the residual tensor
                         snprintf(l.info.name, sizeof l.info.name, "conv%dx%d_s%d+1x1", o1.kh, o1.kw, o1.stride);
+                    }
+                    l.info.next_op = -1;
+                    if (third_of[i] >= 0) {
+                        const int k = third_of[i];
+                        const cw_op &o3 = m.ops[k];
+                        const WeightSlot &ws3 = m.wslots[m.op_wslot[k]];
+                        out_bytes[k] = (size_t)batch * os.h * os.w * o3.cout * esz;
+                        p.op_out[k] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[k])};
+                        p.op_ld[k] = o3.cout;
+                        a.relu3 = o3.relu;
+                        l.w3 = Ref{SP_WEIGHTS, ws3.packed_w_off};
+                        l.bias3 = Ref{SP_WEIGHTS, ws3.packed_b_off};
+                        l.y3 = p.op_out[k];
+                        l.info.next_op = k;
+                        l.info.flops += 2 * (int64_t)a.M * o3.cout * o3.cin;
+                        l.info.bytes += (int64_t)o3.cout * o3.cin * esz + o3.cout * 4 + (int64_t)out_bytes[k];   // its input never leaves the chip
+                        const size_t len = strlen(l.info.name);
+                        snprintf(l.info.name + len, sizeof l.info.name - len, "+1x1");
                     }
                     l.info.tile_m = l.fused_bm; l.info.tile_n = a.Cout; l.info.tile_k = 64; l.info.split_k = 1;
                     l.info.conv_tile = -1; l.info.wave_groups = l.fused_kg;
@@ -1017,7 +1060,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
         l.info.op_index = l.op_index;
         const bool fc_sm = l.kind == K_FC && l.probs.space == SP_SLOT_PROBS;   // fused_op = the FC, set where the softmax joined it
-        if (l.fused_bm <= 0) { if (!fc_sm) l.info.fused_op = -1; l.info.proj_op = -1; }
+        if (l.fused_bm <= 0) { if (!fc_sm) l.info.fused_op = -1; l.info.proj_op = -1; l.info.next_op = -1; }
         l.info.pair_op = l.pair_op;
         l.info.kind = l.kind;
         if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }

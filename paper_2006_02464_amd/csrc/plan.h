@@ -39,6 +39,7 @@ struct Launch {
     Ref x, w, bias, res, y, partial, counters;
     Ref probs;             // FC + softmax in one launch: the softmax's output
     Ref w2, bias2;         // second layer of a fused launch
+    Ref w3, bias3, y3;     // its third layer (the next block's 1x1 reduce), when there is one
     Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
     // A pair launch (pair_op >= 0): a second, independent convolution over the same input tensor runs
     // in this launch's first workgroups; its arguments and tensors:
@@ -96,6 +97,7 @@ struct PlanOverride {
     bool pair = true;      // two convolutions over one tensor as one launch
     bool winograd = false; // 3x3 stride-1 pad-1 convolutions through Winograd F(2x2, 3x3)
     bool resident = false; // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0)
+    bool fuse_third = true; // the next block's 1x1 reduce inside a fused 3x3 + 1x1 launch
     bool fc_softmax = false; // FC and softmax as one launch (batch <= 16, at most 1024 classes)
     bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table

@@ -65,9 +65,10 @@ def test_plan_is_fixed_and_covers_every_op(ctx):
         plan = ctx.plan(m, b)
         assert plan == ctx.plan(m2, b)                      # pure function of (model, batch)
         ops_hit = ({l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0} |
-                   {l["proj_op"] for l in plan if l["proj_op"] >= 0} | {l["pair_op"] for l in plan if l["pair_op"] >= 0})
+                   {l["proj_op"] for l in plan if l["proj_op"] >= 0} | {l["pair_op"] for l in plan if l["pair_op"] >= 0} |
+                   {l["next_op"] for l in plan if l["next_op"] >= 0})
         assert ops_hit == set(range(57))                    # a fused launch covers two or three ops, a pair launch two
-        assert len(plan) == 58 - sum((l["fused_op"] >= 0) + (l["proj_op"] >= 0) + (l["pair_op"] >= 0) for l in plan)
+        assert len(plan) == 58 - sum((l["fused_op"] >= 0) + (l["proj_op"] >= 0) + (l["pair_op"] >= 0) + (l["next_op"] >= 0) for l in plan)
         flops = sum(l["flops"] for l in plan)
         assert flops == 2 * b * T.mac_count(T.resnet(50), 224, 224)
         for l in plan:
