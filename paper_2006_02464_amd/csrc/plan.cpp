@@ -411,7 +411,9 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             if (m.ops[o2.residual_from].op == CW_OP_CONCAT) continue;
             const int64_t M = (int64_t)batch * m.shapes[i].h * m.shapes[i].w;
             const int bm = (o1.cout == 64 && M / 128 >= 256) ? 128 : 64;
-            if ((M + bm - 1) / bm < 190) continue;  // measured: below that the two-launch form is faster
+            // measured on ResNet-50 (batch 1..16, thresholds 190, 96, 48 workgroups): 96 is as fast as 190 or 1 us
+            // faster with up to 7 launches fewer; at 48 the batch-4 EXEC loses 10 us
+            if ((M + bm - 1) / bm < 96) continue;
             fuse_into[i] = j; fused_first[j] = i; fused_bm[j] = bm;
             // two wave groups pay off where one workgroup per CU is all the launch has anyway (the 128-channel form)
             fused_kg[j] = (ov.fuse == 1 && o1.cout == 128 && conv_fused_ok(bm, 2, o1.cout, o2.cout)) ? 2 : 1;

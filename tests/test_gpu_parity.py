@@ -42,9 +42,18 @@ def check_all_ops(worker, case, mid, batch, x, teacher=True):
     worst = 0.0
     gpu = []
     wi = 0
+    plan = worker.ctx.plan(mid, batch)
+    # the first layer of a fused launch, and a projection computed inside one, are never stored
+    unstored = ({l["fused_op"] for l in plan if l["kind"] == 1 and l["fused_op"] >= 0} |
+                {l["proj_op"] for l in plan if l["kind"] == 1 and l["proj_op"] >= 0})
     for i, (o, (c, h, w)) in enumerate(zip(case.ops, shapes)):
         if o.op in (T.FC, T.SOFTMAX):
             break
+        if i in unstored:
+            assert not teacher, "teacher forcing needs every tensor"
+            gpu.append(None)
+            wi += o.op == T.CONV
+            continue
         shape = (batch, c) if o.op == T.GAVGPOOL else (batch, c, h, w)
         got = worker.ctx.debug_read_op(mid, batch, i, shape)
         gpu.append(got)
@@ -394,8 +403,8 @@ def test_resnet50_fused_and_unfused_plans_agree(worker, r50):
     for batch in (16, 8):
         blocks = {name: sorted({l["block"] for l in ctx.plan(mid, batch) if l["fused_op"] >= 0 and l["kind"] == 1})
                   for name, mid in (("fused", fused), ("fused1", fused1), ("plain", plain))}
-        # two groups of four waves for the 128-channel pairs (stage 2, fused at batch 16 only), one group for the 64-channel ones
-        assert blocks == {"fused": [256, 512] if batch == 16 else [256], "fused1": [256], "plain": []}
+        # two groups of four waves for the 128-channel pairs (stage 2), one group for the 64-channel ones
+        assert blocks == {"fused": [256, 512], "fused1": [256], "plain": []}
         n_fused = sum(l["fused_op"] >= 0 and l["kind"] == 1 for l in ctx.plan(fused, batch))
         out = {}
         for name, mid in (("fused", fused), ("fused1", fused1), ("plain", plain)):
