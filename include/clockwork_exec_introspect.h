@@ -122,7 +122,9 @@ int32_t cw_set_panels(cw_ctx *ctx, int32_t on);
  * workspace region, and need the GPU to itself: every wait is bounded, and when one gives up (or a
  * workgroup finds itself on another XCD than its partition's) the EXEC still ends and
  * cw_exec_duration_ns reports CW_ERR_HIP.  CW_ERR_UNSUPPORTED on a device without 256 compute units
- * in 8 XCDs.  on == 0 (default): one launch per layer. */
+ * in 8 XCDs.  on == 2: only the layers of at most 4096 pixels per batch (the later stages) run that
+ * way; the earlier ones keep their fused and pair launches.  on == 0 (default): one launch per
+ * layer.  Other values: CW_ERR_INVALID. */
 int32_t cw_set_resident(cw_ctx *ctx, int32_t on);
 /* Winograd F(2x2, 3x3) (the paper's model zoo holds Winograd-compiled ResNets: Table 2).  on != 0:
  * models defined afterwards run every 3x3 stride-1 padding-1 convolution with cin % 64 == 0 as an

@@ -654,7 +654,8 @@ int32_t cw_set_panels(cw_ctx *c, int32_t on) {
 int32_t cw_set_resident(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on && !c->resident_capable) return set_err(c, CW_ERR_UNSUPPORTED, "resident launches need 256 compute units in 8 XCDs");
-    c->ov.resident = on != 0;
+    if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "resident mode must be 0, 1 or 2");
+    c->ov.resident = on;
     return CW_OK;
 }
 

@@ -385,8 +385,9 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // convolution with a residual; enough pixels for the launch to fill the GPU.
     // Resident runs: plain convolution launches only (the layers meet in the XCD's L2 anyway), every
     // tensor in a region of its own (a tensor is written once per launch, so no cache holds an old copy).
-    const bool resident = ov.resident && batch % kResPartitions == 0 && ov.tile < 0 && ov.split_k <= 0 && !m.winograd;
-    const bool no_reuse = ov.keep_all || resident;
+    const int res_mode = (ov.resident && batch % kResPartitions == 0 && ov.tile < 0 && ov.split_k <= 0 && !m.winograd) ? ov.resident : 0;
+    const bool resident = res_mode == 1;   // every run: plain launches only
+    const bool no_reuse = ov.keep_all || res_mode != 0;
     std::vector<int> fuse_into(n_ops, -1), fused_first(n_ops, -1), fused_bm(n_ops, 0), fused_kg(n_ops, 1), proj_of(n_ops, -1);
     std::vector<int> third_of(n_ops, -1), in_third(n_ops, -1);   // fused launch of op j also computes op third_of[j]; in_third[k] = j
     if (ov.fuse && !resident && ov.tile < 0 && ov.split_k <= 0) {
@@ -972,10 +973,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     }
     // Resident runs: every maximal run of two or more plain convolution launches (direct-to-LDS
     // kernel, whole K per workgroup) becomes one launch whose members keep partition 0's arguments.
-    if (resident) {
+    if (res_mode) {
+        constexpr int kResidentLateM = 4096;
         auto eligible = [&](const Launch &l) {
             return l.kind == K_CONV && !l.stem && l.fused_bm == 0 && l.pair_op < 0 && l.conv.nz <= 1 && l.conv.Cin % 64 == 0 &&
-                   l.conv.kwp == l.conv.kw && l.conv.khp == l.conv.kh;
+                   l.conv.kwp == l.conv.kw && l.conv.khp == l.conv.kh && (res_mode == 1 || l.conv.M <= kResidentLateM);
         };
         std::vector<Launch> out;
         for (size_t i = 0; i < p.launches.size();) {

@@ -96,7 +96,9 @@ struct PlanOverride {
     int32_t fuse = 1;      // two-layer launches: 0 = none, 1 = yes, 2 = yes but never with two wave groups
     bool pair = true;      // two convolutions over one tensor as one launch
     bool winograd = false; // 3x3 stride-1 pad-1 convolutions through Winograd F(2x2, 3x3)
-    bool resident = false; // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0)
+    int32_t resident = 0;  // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0): 1 = every
+                           // run (no fused or pair launches then), 2 = only layers of at most kResidentLateM pixels,
+                           // beside the fused and pair launches of the earlier stages
     bool fuse_third = true; // the next block's 1x1 reduce inside a fused 3x3 + 1x1 launch
     bool fc_softmax = false; // FC and softmax as one launch (batch <= 16, at most 1024 classes)
     bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s

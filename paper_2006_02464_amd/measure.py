@@ -432,10 +432,13 @@ def config8(args, log):
                 ("FC and softmax as one launch", ctx.set_fc_softmax, 0),
                 ("tile numbering in channel panels where they move fewer bytes", ctx.set_panels, 0),
                 ("plain launches instead of graph replay", None, None), ("Winograd F(2x2,3x3) for the 3x3 stride-1 layers", ctx.set_winograd, 0),
-                ("resident multi-layer launches", ctx.set_resident, 0), ("default plan again", None, None)]
+                ("resident multi-layer launches", ctx.set_resident, 0), ("resident launches for the later stages only", "resident2", 0), ("default plan again", None, None)]
     blob, rows = None, []
     for name, setter, default in variants:
-        if setter is not None:
+        if setter == "resident2":
+            ctx.set_resident(2)
+            setter = ctx.set_resident
+        elif setter is not None:
             setter(1 - default)
         try:
             mid = ctx.model_define_resnet(50, 224, 224, "fp16")

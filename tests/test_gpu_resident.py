@@ -23,9 +23,9 @@ def worker():
     w.close()
 
 
-def _define(worker, ops, hw, batches, dtype="fp16", keep=False):
+def _define(worker, ops, hw, batches, dtype="fp16", keep=False, mode=1):
     ctx = worker.ctx
-    ctx.set_resident(1)
+    ctx.set_resident(mode)
     ctx.set_debug_keep(keep)
     try:
         return ctx.model_define(ops, 3, hw, hw, batch_sizes=batches, dtype=dtype)
@@ -77,6 +77,26 @@ def test_resident_resnet50_every_layer_and_logits(worker, dtype):
         print("resident resnet50 %s b%d: exec %.1f us, max rel err %.3e, worst teacher-forced diff / scale %.2e" % (dtype, batch, ns / 1e3, err.max(), wp))
         assert np.isfinite(got).all() and err.max() <= TOL
         assert np.array_equal(N.argmax(got), N.argmax(ref))
+    worker.ctx.unload_weights(mid)
+
+
+def test_resident_later_stages_beside_fused_and_pair_launches(worker):
+    """Mode 2: stages 3 and 4 of ResNet-50 as two resident launches, stages 1 and 2 as the fused
+    and pair launches of the default plan; every layer teacher forced, logits against the oracle."""
+    case = Case(T.resnet(50), 224, seed=0, dist="normal")
+    mid = _define(worker, case.ops, 224, (16, 8), keep=True, mode=2)
+    plan = worker.ctx.plan(mid, 16)
+    assert [l["name"] for l in plan if l["kind"] == 11] == ["resident_17convs", "resident_8convs"]
+    assert sum(l["fused_op"] >= 0 and l["kind"] == 1 for l in plan) == 7 and sum(l["pair_op"] >= 0 for l in plan) == 3
+    worker.load(mid, case.blob)
+    x = case.images(0, 16)
+    ref = np.load(os.path.join(GOLDEN, "resnet50_fp16_seed0_images0-1023_logits.npy"))[:16]
+    for batch in (16, 8):
+        got = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 16, batch)])
+        wp, wf, nf, gpu = check_every_launch(worker, case, mid, batch, x[16 - batch:])
+        err = rel_err_per_sample(got, ref)
+        print("resident (later stages) resnet50 b%d: %d launches, max rel err %.3e" % (batch, len(worker.ctx.plan(mid, batch)), err.max()))
+        assert err.max() <= TOL
     worker.ctx.unload_weights(mid)
 
 
