@@ -86,7 +86,9 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
 int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
 /* A fused launch (see above) may also compute the 1x1 stride-1 convolution that reads its output:
  * the next bottleneck's reduce, whose input then never comes back from memory.  on == 0 plans that
- * convolution as a launch of its own for models defined afterwards; on != 0 restores the default. */
+ * convolution as a launch of its own for models defined afterwards; on == 2 does so only where
+ * the fused launch also computes a projection shortcut; on == 1 restores the default; other
+ * values: CW_ERR_INVALID. */
 int32_t cw_set_fusion_third(cw_ctx *ctx, int32_t on);
 /* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
  * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as

@@ -635,7 +635,8 @@ int32_t cw_set_fusion(cw_ctx *c, int32_t on) {
 
 int32_t cw_set_fusion_third(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
-    c->ov.fuse_third = on != 0;
+    if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "mode must be 0, 1 or 2");
+    c->ov.fuse_third = on;
     return CW_OK;
 }
 

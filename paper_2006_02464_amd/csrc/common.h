@@ -98,6 +98,7 @@ struct alignas(64) ConvArgs {
         // Fused form only (never batched): a third layer, the 1x1 stride-1 convolution that reads the
         // second layer's output (the next bottleneck's reduce), y3 = act3(bias3 + W3 * y), Cout3 = Cout.
         // y is still stored (it is the next block's shortcut); y3 is stored besides.  w3 == nullptr: none.
+        // Together with the in-launch projection (wd) only in the one-group form.
         struct { const void *w3; const float *bias3; void *y3; };
     };
     int32_t relu3;

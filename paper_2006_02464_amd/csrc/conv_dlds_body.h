@@ -66,7 +66,7 @@ constexpr unsigned fused_lds_bytes(int bm, int bn, int kg) {
     const int p = bm * bn * 2, w2 = fused_chunk(bn, kg) * bn * 2, r = bm * fused_chunk(bn, kg) * 2;
     // with a projection (64-channel form only): 2 x {W2, Wd chunk} + the x2 tile (as large as p)
     const int w3 = bn * fused_chunk(bn, kg) * 2;   // third layer: Cout3 = bn output rows x a chunk of its K
-    const int plain = 2 * (w2 + r) + w3, proj = bn == 64 ? 4 * w2 + p : 0;
+    const int plain = 2 * (w2 + r) + w3, proj = bn == 64 ? 4 * w2 + p + w3 : 0;
     return (unsigned)(p + (plain > proj ? plain : proj));
 }
 constexpr int kFusedMaxCout2 = 1024;
@@ -464,7 +464,7 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             x2_voff[j] = m < (unsigned)a.M ? (m * (unsigned)BN + c * 8) * 2u : kOob;
         }
         constexpr unsigned XB_OFF = P_BYTES + 4 * W2_BYTES;   // x2 tile, projection form only
-        // Third layer (a.w3; never together with the projection form; Cout3 = BN): y3 = act3(bias3 + W3 * y).
+        // Third layer (a.w3; Cout3 = BN): y3 = act3(bias3 + W3 * y).
         // Its K is the second layer's Cout2, walked in the same chunks: once a chunk of y is final
         // (rounded to the storage type, as it is stored), the threads write it back over the residual
         // tile they have just read, element for element, which is then the chunk's activation operand;
@@ -474,7 +474,9 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
         const bool third = THIRD_OK && a.w3 != nullptr;        // uniform
         constexpr int W3_PER = BN * CR2 / NT;
         static_assert(BN * CR2 % NT == 0, "tile/threads mismatch");
-        constexpr unsigned W3_OFF = P_BYTES + 2 * BUF_BYTES;
+        // behind the chunk buffers and, in the 64-channel form (which may carry a projection), the x2 tile
+        constexpr unsigned W3_OFF = (BN == 64 && XB_OFF + P_BYTES > P_BYTES + 2 * BUF_BYTES) ? XB_OFF + P_BYTES : P_BYTES + 2 * BUF_BYTES;
+        static_assert(W3_OFF + BN * BN2 * 2u <= fused_lds_bytes(BM, BN, KG), "third layer's weights do not fit the LDS plan");
         constexpr int TN3 = THIRD_OK ? BN / (WARPS_N * KG) / 32 : 1;
         static_assert(TN3 <= TN, "third-layer wave tile");
         const int wn3 = (kg * WARPS_N + wq % WARPS_N) * (BN / (WARPS_N * KG));
@@ -497,7 +499,11 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             for (int j = 0; j < TN3; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc3[i][j][e] = 0.f;
-        auto buf_off = [&](int c) { return P_BYTES + (unsigned)(c & 1) * (proj ? 2 * W2_BYTES : BUF_BYTES); };
+        // Third layer together with the projection: there is no residual tile to write the chunk of y over,
+        // so it goes to the room of the second {W2, Wd} buffer, and the chunks' weights come through
+        // the first buffer alone, requested as soon as every wave has finished the chunk's products.
+        const bool single = third && proj;
+        auto buf_off = [&](int c) { return P_BYTES + (single ? 0u : (unsigned)(c & 1)) * (proj ? 2 * W2_BYTES : BUF_BYTES); };
         auto issue_chunk = [&](int c) {
             const unsigned dst = lds_base + buf_off(c) + (unsigned)wave * 1024u;
 #pragma unroll
@@ -566,9 +572,10 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             // every wave has finished reading the buffer that chunk c+1 is about to overwrite
             if (c == 0) wait_lds_loads_and_barrier<0>(); else wait_lds_loads_and_barrier<ST>();
             if (third) issue_w3(c);   // ahead of the next chunk's loads: it is awaited first
-            if (c + 1 < chunks) issue_chunk(c + 1);
+            if (!single && c + 1 < chunks) issue_chunk(c + 1);
             const T *sW2 = reinterpret_cast<const T *>(cw_dyn_lds + buf_off(c));
             T *sR = reinterpret_cast<T *>(cw_dyn_lds + buf_off(c)) + BN2 * BN;  // residual tile, or Wd[chunk] in projection form
+            T *sQ = proj ? reinterpret_cast<T *>(cw_dyn_lds + P_BYTES + 2 * W2_BYTES) : sR;   // the chunk of y as the third layer's operand
             const T *sXb = reinterpret_cast<const T *>(cw_dyn_lds + XB_OFF);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -592,6 +599,12 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
             };
             product(sP, sW2);
             if (proj) product(sXb, sR);
+            if (single) {
+                // every wave is done with the one weight buffer (only LDS reads are awaited: older than
+                // the third layer's weights there are at most the last chunk's stores)
+                wait_lds_loads_and_barrier<ST + W3_PER>();
+                if (c + 1 < chunks) issue_chunk(c + 1);
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const unsigned m = m0 + wm0 + i * 32 + lrow;
@@ -612,19 +625,21 @@ static __device__ __forceinline__ void conv_dlds_body(const ConvArgs &a, const i
                         }
                         const unsigned o = m < (unsigned)a.M ? (m * (unsigned)a.Cout2 + (unsigned)(c * BN2 + nl)) * 2u : kOob;
                         __builtin_amdgcn_raw_buffer_store_b128(*reinterpret_cast<const u32x4 *>(out), ry, o, 0, 0);
-                        if (third) *reinterpret_cast<u32x4 *>(sR + swz<BN2>(wm0 + i * 32 + lrow, nl >> 3)) = *reinterpret_cast<const u32x4 *>(out);
+                        if (third) *reinterpret_cast<u32x4 *>(sQ + swz<BN2>(wm0 + i * 32 + lrow, nl >> 3)) = *reinterpret_cast<const u32x4 *>(out);
                     }
             }
             if (third) {
                 // The chunk of y is in LDS (everyone's: barrier) and W3[:, chunk] has landed: younger than
                 // it are only the next chunk's loads and this chunk's stores.
-                if (c + 1 < chunks) wait_lds_loads_and_barrier<W2_PER + R_PER + ST>(); else wait_lds_loads_and_barrier<ST>();
+                if (c + 1 >= chunks) wait_lds_loads_and_barrier<ST>();
+                else if (proj) wait_lds_loads_and_barrier<2 * W2_PER + ST>();
+                else wait_lds_loads_and_barrier<W2_PER + R_PER + ST>();
                 const T *sW3 = reinterpret_cast<const T *>(cw_dyn_lds + W3_OFF);
 #pragma unroll
                 for (int kk = 0; kk < BN2 / 16; ++kk) {
                     v8 px[TM], pw[TN3];
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sR + swz<BN2>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
+                    for (int i = 0; i < TM; ++i) px[i] = *reinterpret_cast<const v8 *>(sQ + swz<BN2>(wm0 + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
                     for (int j = 0; j < TN3; ++j) pw[j] = *reinterpret_cast<const v8 *>(sW3 + swz<BN2>(wn3 + j * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll

@@ -182,8 +182,9 @@ hipError_t launch_conv_fused(DType dt, int bm, int kg, const ConvArgs &a, hipStr
     if (!a.w2 || !a.bias2) return hipErrorInvalidValue;
     if (a.wd ? (a.Cout != 64 || !a.x2 || !a.biasd) : !a.res) return hipErrorInvalidValue;
     if (!a.res && !a.wd) return hipErrorInvalidValue;
-    // third layer: over the second layer's output, as many channels as the first layer has; not with the projection form
-    if (a.w3 && (a.wd || !a.bias3 || !a.y3 || (long long)a.M * a.Cout * 2 >= (1ll << 31) || (long long)a.Cout * a.Cout2 * 2 >= (1ll << 31)))
+    // third layer: over the second layer's output, as many channels as the first layer has; with the projection
+    // form only as one wave group (the 64-channel form is planned that way)
+    if (a.w3 && ((a.wd && kg != 1) || !a.bias3 || !a.y3 || (long long)a.M * a.Cout * 2 >= (1ll << 31) || (long long)a.Cout * a.Cout2 * 2 >= (1ll << 31)))
         return hipErrorInvalidValue;
     if (a.nz > 1) return hipErrorInvalidValue;   // the batched form's strides share their place with the third layer's pointers
     if (a.kh * a.kw > 32 || (long long)a.M * a.Cout2 * 2 >= (1ll << 31) || (long long)a.Cout * a.K * 2 >= (1ll << 31)) return hipErrorInvalidValue;

@@ -433,13 +433,13 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
         // Third layer: the 1x1 stride-1 convolution that is the only one to read op j's output as its
         // input (the next bottleneck's reduce; the output's other reader is that block's shortcut), with
-        // as many output channels as op i.  Not with the in-launch projection (its LDS is taken).
+        // as many output channels as op i.
         if (ov.fuse_third) {
             std::vector<int> in_readers(n_ops, 0);
             for (int i = 0; i < n_ops; ++i)
                 if (m.ops[i].op == CW_OP_CONV && m.ops[i].input_from >= 0) ++in_readers[m.ops[i].input_from];
             for (int j = 0; j + 1 < n_ops; ++j) {
-                if (fused_first[j] < 0 || proj_of[j] >= 0 || in_readers[j] != 1) continue;
+                if (fused_first[j] < 0 || in_readers[j] != 1 || (proj_of[j] >= 0 && (fused_kg[j] != 1 || ov.fuse_third == 2))) continue;
                 const int k = j + 1;
                 const cw_op &o3 = m.ops[k];
                 if (o3.op != CW_OP_CONV || o3.input_from != j || o3.kh != 1 || o3.kw != 1 || o3.stride != 1 || o3.pad != 0) continue;

@@ -99,7 +99,8 @@ struct PlanOverride {
     int32_t resident = 0;  // runs of convolution layers as one launch of resident workgroups (batch % 8 == 0): 1 = every
                            // run (no fused or pair launches then), 2 = only layers of at most kResidentLateM pixels,
                            // beside the fused and pair launches of the earlier stages
-    bool fuse_third = true; // the next block's 1x1 reduce inside a fused 3x3 + 1x1 launch
+    int32_t fuse_third = 1; // the next block's 1x1 reduce inside a fused 3x3 + 1x1 launch: 0 = never, 1 = yes, 2 = yes, but
+                            // not in a launch that also computes a projection shortcut
     bool fc_softmax = false; // FC and softmax as one launch (batch <= 16, at most 1024 classes)
     bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table

@@ -207,19 +207,19 @@ def test_fusion_of_bottleneck_tail(ctx):
         assert first[3] == 3 and second[3] == 1 and second[1] == first[2] and first[2] in (64, 128)
         assert l["grid_x"] == -(-l["gemm_m"] // l["tile_m"]) and l["grid_y"] == 1 and l["split_k"] == 1
     assert not [l for l in ctx.plan(m, 1) if l["fused_op"] >= 0 and l["kind"] == 1]
-    # the next block's 1x1 reduce rides along where the launch does not also compute a projection
+    # the next block's 1x1 reduce rides along, also in the launch that computes the first block's projection
     third = [l for l in fused if l["next_op"] >= 0]
-    assert len(third) == 4 and all(l["proj_op"] < 0 for l in third)
+    assert len(third) == 5 and [l["proj_op"] >= 0 for l in third] == [True] + [False] * 4
     for l in third:
         nxt, second, first = ops[l["next_op"]], ops[l["op_index"]], ops[l["fused_op"]]
         assert l["next_op"] == l["op_index"] + 1 and nxt[9] == l["op_index"] and nxt[3] == 1 and nxt[5] == 1
-        assert nxt[1] == second[2] and nxt[2] == first[2] and l["name"].endswith("+1x1+1x1")
+        assert nxt[1] == second[2] and nxt[2] == first[2] and l["name"].endswith("+1x1+proj+1x1" if l["proj_op"] >= 0 else "+1x1+1x1")
     assert not any(l["op_index"] in {t["next_op"] for t in third} for l in ctx.plan(m, 16))   # no launch of their own
     ctx.set_fusion_third(0)
     try:
         m4 = ctx.model_define_resnet(50, 224, 224)
         assert not [l for l in ctx.plan(m4, 16) if l["next_op"] >= 0]
-        assert len(ctx.plan(m4, 16)) == len(ctx.plan(m, 16)) + 4
+        assert len(ctx.plan(m4, 16)) == len(ctx.plan(m, 16)) + 5
     finally:
         ctx.set_fusion_third(1)
     ctx.set_fusion(0)
