@@ -68,6 +68,15 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
     *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + i * 8) = *reinterpret_cast<const uint4 *>(out);
 }
 
+// Workgroups go to the 8 XCDs in turn.  Kernels whose neighbouring workgroups read overlapping
+// windows number their blocks so that each XCD computes one contiguous eighth of the output, and
+// the overlap is found in that XCD's L2 instead of being fetched once per XCD.
+static __device__ __forceinline__ unsigned xcd_block(unsigned bid, unsigned nb) {
+    const unsigned xcd = bid & 7u, idx = bid >> 3;
+    const unsigned per = nb >> 3, rem = nb & 7u;
+    return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
 // The same for a window of KS x KS known at compile time and fewer than 2^31 elements: the KS*KS
 // loads of a thread do not depend on each other and are requested together (out-of-range taps read
 // a clamped, valid address and are not counted), and the index arithmetic is 32-bit.
@@ -76,7 +85,7 @@ __global__ __launch_bounds__(256) void maxpool_window_kernel(const void *x, void
     const PoolArgs a{x, y, B, H, W, C, Ho, Wo, k, stride, pad};
     const unsigned c8 = (unsigned)a.C / 8u;
     const unsigned total = (unsigned)a.B * a.Ho * a.Wo * c8;
-    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    const unsigned i = xcd_block(blockIdx.x, gridDim.x) * 256u + threadIdx.x;
     if (i >= total) return;
     const unsigned cg = i % c8;
     unsigned t = i / c8;
@@ -458,7 +467,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void dwconv_kernel(const DwArgs a) {
     const unsigned c8 = (unsigned)a.C / 8u;
     const unsigned total = (unsigned)a.B * a.Ho * a.Wo * c8;   // < 2^31: checked by the launch code
-    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    const unsigned i = xcd_block(blockIdx.x, gridDim.x) * 256u + threadIdx.x;
     if (i >= total) return;
     const unsigned cg = i % c8;
     unsigned t = i / c8;            // output pixel m
