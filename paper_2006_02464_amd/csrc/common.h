@@ -123,6 +123,8 @@ inline void conv_set_pad(ConvArgs &a, int pad_h, int pad_w) { a.pad = pad_h | (p
 inline void conv_set_ld(ConvArgs &a, int ldx, int ldy) { a.ld = ldx | (ldy << 16); }
 constexpr int kMaxChannels = 32768;  // channel counts and pitches travel in 16 bits
 
+// Maps of at least this many pixels are averaged by the 16-wave kernel (one wave per 64 channels below).
+constexpr int kGapWideFrom = 256;
 // Depthwise convolution: y[m][c] = act(res[m][c] + bias[c] + sum_{r,s} x[pixel(m) + (r,s)][c] * w[r][s][c]).
 struct DwArgs {
     const void *x;      // NHWC, ldx elements per pixel

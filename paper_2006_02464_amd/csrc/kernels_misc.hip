@@ -159,6 +159,50 @@ __global__ __launch_bounds__(64) void gavgpool_kernel(const void *x, void *y, in
     }
 }
 
+// The same for large maps (hundreds of pixels and more: the DenseNet- and Inception-style lists pool
+// 28x28 and 56x56 maps): kGapWaves waves per (sample, 64 channels); wave w takes the rounds w,
+// w + kGapWaves, ... of 64 pixels; the waves' sums meet in LDS and are added in wave order.
+constexpr int kGapWaves = 16;
+template <typename T>
+__global__ __launch_bounds__(64 * kGapWaves) void gavgpool_wide_kernel(const void *x, void *y, int B, int H, int W, int C, int Ho, int Wo, int k, int stride, int pad) {
+    const PoolArgs a{x, y, B, H, W, C, Ho, Wo, k, stride, pad};
+    __shared__ float red[kGapWaves][8][8];
+    const int groups = a.C / 64;
+    const int n = blockIdx.x / groups, cb = (blockIdx.x - n * groups) * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, cg = lane & 7, part = lane >> 3;
+    const int hw = a.H * a.W;
+    float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const T *xg = static_cast<const T *>(a.x) + (size_t)n * hw * a.C + cb + cg * 8;
+    for (int p0 = part + 64 * wave; p0 < hw; p0 += 64 * kGapWaves) {
+        uint4 raw[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) raw[u] = *reinterpret_cast<const uint4 *>(xg + (size_t)min(p0 + 8 * u, hw - 1) * a.C);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const T *v = reinterpret_cast<const T *>(&raw[u]);
+            const bool live = p0 + 8 * u < hw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += live ? to_f32(v[e]) : 0.f;
+        }
+    }
+#pragma unroll
+    for (int off = 8; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += __shfl_xor(s[e], off, 64);
+    if (part == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[wave][cg][e] = s[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {   // 8 channel groups x 8 channels
+        const int g = threadIdx.x >> 3, e = threadIdx.x & 7;
+        float t = red[0][g][e];
+#pragma unroll
+        for (int w = 1; w < kGapWaves; ++w) t += red[w][g][e];
+        static_cast<float *>(a.y)[(size_t)n * a.C + cb + g * 8 + e] = t * (1.f / (float)hw);
+    }
+}
+
 // ---- FC: z[n][j] = bias[j] + sum_i f[n][i] * W[j][i], fp32 features, fp32 result ---------
 // A workgroup computes 16 outputs x 16 samples on the matrix cores (v_mfma_f32_16x16x32 in the
 // storage type: 16 output rows x 16 sample columns x 32 k per instruction).  Its 8 waves split K;
@@ -791,7 +835,10 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s) {
     if (a.C % 8 != 0 || a.B < 1) return hipErrorInvalidValue;
     if (a.C % 64 != 0) return hipErrorInvalidValue;
-    CW_DISPATCH(dt, gavgpool_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64, s, a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
+    if (a.H * a.W >= kGapWideFrom)
+        CW_DISPATCH(dt, gavgpool_wide_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64 * kGapWaves, s, a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
+    else
+        CW_DISPATCH(dt, gavgpool_kernel, dim3((unsigned)(a.B * (a.C / 64))), 64, s, a.x, a.y, a.B, a.H, a.W, a.C, a.Ho, a.Wo, a.k, a.stride, a.pad);
     return hipGetLastError();
 }
 

@@ -1050,7 +1050,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
             case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
-            case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = 64; break;
+            case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = l.pool.H * l.pool.W >= kGapWideFrom ? 1024 : 64; break;
             case K_FC:
                 if (l.probs.space == SP_SLOT_PROBS) { g = dim3((l.fc.Out + 15) / 16, l.fc.split_k); b = 256; }
                 else { g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; }
