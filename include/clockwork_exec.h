@@ -210,7 +210,7 @@ int32_t cw_exec(cw_ctx *ctx, int32_t model_id, int32_t batch, int32_t slot, void
  *     dev_input_nchw [device] fp32 [batch][in_c][in_h][in_w], dev_logits and dev_probs [device]
  *     fp32 [batch][classes]; the caller orders their producers and consumers on `stream`;
  *   - the intermediates (activations, split-K partial sums and arrival counters) live in an array
- *     built into the library, cw_exec_static_capacity() bytes (64 MiB) per GPU, instead of the
+ *     built into the library, cw_exec_static_capacity() bytes (80 MiB) per GPU, instead of the
  *     context's workspace: a plan whose intermediates need more returns CW_ERR_NO_MEMORY (see
  *     cw_model_workspace_bytes; ResNet-50 and ResNet-152 at 224x224 fit up to batch 16);
  *   - the call allocates nothing, creates no event or graph and records nothing but kernel

@@ -69,7 +69,7 @@ struct ModelRt {
 // One array per GPU the library runs on, held until the process ends.  In host code the array's
 // name is only a handle for the runtime; its device address on a GPU is asked for once, with that
 // GPU current, and kept (every GPU has its own copy at its own address).
-constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)80 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {

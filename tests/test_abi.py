@@ -58,6 +58,17 @@ def test_resnet_op_lists_match_the_oracle_topology(ctx, depth, hw):
     assert ctx.model_weight_bytes(m) == gen.blob_bytes(T.weight_shapes(T.resnet(depth)))
 
 
+def test_resnet_plans_fit_the_static_arena(ctx):
+    """cw_exec_static keeps a plan's intermediates in an array built into the library: the plans of
+    the metric's models must fit it at every batch size."""
+    from paper_2006_02464_amd import binding
+    cap = binding.lib().cw_exec_static_capacity()
+    for depth, dtype in ((50, "fp16"), (152, "bf16")):
+        m = ctx.model_define_resnet(depth, 224, 224, dtype)
+        for b in (1, 2, 4, 8, 16):
+            assert ctx.model_workspace_bytes(m, b) <= cap, (depth, b)
+
+
 def test_plan_is_fixed_and_covers_every_op(ctx):
     m = ctx.model_define_resnet(50, 224, 224)
     m2 = ctx.model_define_resnet(50, 224, 224)

@@ -27,7 +27,7 @@ def test_exec_static_matches_exec_on_two_calls_in_a_row():
     wk = Worker(workspace_bytes=512 << 20, io_bytes=64 << 20, weight_pool_bytes=256 << 20, load_staging_bytes=64 << 20)
     try:
         ctx = wk.ctx
-        assert ctx.exec_static_capacity() == 64 << 20
+        assert ctx.exec_static_capacity() == 80 << 20
         # ResNet-50 at 224x224: batch 4, then batch 1 (split-K launches: partial sums and arrival
         # counters in the arena), then a ResNet-18 at 64x64 over the arena the others left behind
         r50 = Case(T.resnet(50), 224, seed=0, dist="normal")
@@ -42,6 +42,12 @@ def test_exec_static_matches_exec_on_two_calls_in_a_row():
             probs_s, logits_s = _static_infer(wk, m50, xs)
             assert np.array_equal(logits_s, logits_e) and np.array_equal(probs_s, probs_e)
             assert rel_err_per_sample(logits_s, ref[first:first + count]).max() <= TOL
+        # the largest plan of the metric's model (fused launches with their third layer): 68.6 MiB of the arena
+        x16 = r50.images(0, 16)
+        probs_e, logits_e, _ = wk.infer(m50, x16)
+        probs_s, logits_s = _static_infer(wk, m50, x16)
+        assert np.array_equal(logits_s, logits_e) and np.array_equal(probs_s, probs_e)
+        assert np.array_equal(logits_s[:4], logits_e[:4]) and rel_err_per_sample(logits_s[:4], ref).max() <= TOL
         r18 = Case(T.resnet(18), 64, seed=0, dist="uniform")
         m18 = ctx.model_define_resnet(18, 64, 64)
         wk.load(m18, r18.blob)
