@@ -38,7 +38,8 @@ def summary(v):
 def resnet_blob(ctx, mid, seed, dtype):
     from workload import gen
     ops = ctx.model_get_ops(mid)
-    shapes = [(o[2], o[1], o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
+    # (cout, cin per group, kh, kw) per convolution, (out, in, 1, 1) per FC
+    shapes = [(o[2], o[1] // max(1, o[11]), o[3], o[4]) if o[0] == 0 else (o[2], o[1], 1, 1) for o in ops if o[0] in (0, 3)]
     w, b = gen.model_tensors(shapes, seed, dtype)
     return gen.pack_blob(w, b, dtype)
 

@@ -9,10 +9,14 @@ pass of coordinate descent per batch size, starting from the library's current
 choice.  The result is written as csrc/plan_table.inc, which the library compiles
 in.  Nothing is tuned when EXEC runs.
 
-  python -m paper_2006_02464_amd.tune [--depth 50] [--hw 224] [--batches 1,2,4,8,16] [--out FILE]
+  python -m paper_2006_02464_amd.tune [--family resnet] [--depth 50] [--hw 224] [--batches 1,2,4,8,16] [--out FILE] [--keep-existing]
+
+The table as compiled in: ResNet-50 first, then `--depth 18 --keep-existing`, then the other
+families' lists (`--family mobilenet|densenet|inception --batches 1,4,16 --keep-existing`).
 """
 import argparse
 import os
+import re
 import sys
 import time
 
@@ -53,13 +57,29 @@ def rows(table):
     return [k + v for k, v in table.items()]
 
 
+def read_table(path):
+    """{(M, N, K, kh, stride): (tile, split)} of a plan_table.inc."""
+    out = {}
+    for line in open(path):
+        m = re.match(r"\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+)\}", line)
+        if m:
+            v = tuple(int(g) for g in m.groups())
+            out[v[:5]] = v[5:]
+    return out
+
+
 class Bench:
-    def __init__(self, depth, hw, reps):
+    def __init__(self, family, depth, hw, reps):
         from .runner import Worker, pinned_like
+        from . import measure
         self.hw, self.reps = hw, reps
         self.wk = Worker(**POOLS)
         ctx = self.wk.ctx
-        mid = ctx.model_define_resnet(depth, hw, hw)
+        if family == "resnet":
+            mid = ctx.model_define_resnet(depth, hw, hw)
+        else:
+            lists = {"mobilenet": measure.mobilenet_ops, "densenet": measure.dense_ops, "inception": measure.inception_ops}
+            mid = ctx.model_define(lists[family](), 3, hw, hw, batch_sizes=(1,))
         self.ops = ctx.model_get_ops(mid)
         # seeded random weights, as every measurement uses: with all-zero operands the matrix cores draw
         # less power, the clocks sit higher and EXEC measures 2-4 % shorter, not equally for every tile
@@ -106,6 +126,8 @@ class Bench:
 
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--family", default="resnet", choices=["resnet", "mobilenet", "densenet", "inception"],
+                    help="resnet (of --depth) or one of measure.py's operator lists of the other families")
     ap.add_argument("--depth", type=int, default=50)
     ap.add_argument("--hw", type=int, default=224)
     ap.add_argument("--batches", default="1,2,4,8,16")
@@ -115,9 +137,10 @@ def main():
     ap.add_argument("--only-suffix", default="", help="only try tiles whose name ends like this")
     ap.add_argument("--verbose", action="store_true", help="print every candidate's time")
     ap.add_argument("--out", default=TABLE)
+    ap.add_argument("--keep-existing", action="store_true", help="rows already in the output file are not replaced")
     args = ap.parse_args()
     from .binding import CONV_TILES
-    b = Bench(args.depth, args.hw, args.reps)
+    b = Bench(args.family, args.depth, args.hw, args.reps)
     final = {}
     for batch in (int(v) for v in args.batches.split(",")):
         t_start = time.time()
@@ -149,8 +172,17 @@ def main():
         final.update(cur)
     b.wk.close()
     names = {v: k for k, v in CONV_TILES.items()}
+    # rows of the table being rewritten whose shapes this run did not visit stay; with --keep-existing
+    # the rows it did visit stay as well and only new shapes are added (a second model's own shapes
+    # without moving the first model's choices)
+    kept = read_table(args.out) if os.path.exists(args.out) else {}
+    for key, val in kept.items():
+        if key not in final or args.keep_existing:
+            final[key] = val
     lines = ["// Generated by paper_2006_02464_amd/tune.py on an MI355X: per GEMM shape the (tile, split-K) under which",
-             "// whole EXECs of ResNet-%d ran fastest.  {M, N, K, kh, stride, tile, split_k}" % args.depth]
+             "// whole EXECs ran fastest.  ResNet-50's shapes first; the shapes that only ResNet-18 or the MobileNet-,",
+             "// DenseNet- and Inception-style lists have were added afterwards without moving those.",
+             "// {M, N, K, kh, stride, tile, split_k}"]
     for key in sorted(final):
         tile, split = final[key]
         lines.append("{%d, %d, %d, %d, %d, %d, %d},  // %s" % (key + (tile, split, names[tile])))
