@@ -12,7 +12,8 @@ in.  Nothing is tuned when EXEC runs.
   python -m paper_2006_02464_amd.tune [--family resnet] [--depth 50] [--hw 224] [--batches 1,2,4,8,16] [--out FILE] [--keep-existing]
 
 The table as compiled in: ResNet-50 first, then `--depth 18 --keep-existing`, then the other
-families' lists (`--family mobilenet|densenet|inception --batches 1,4,16 --keep-existing`).
+families' lists (`--family mobilenet|densenet|inception --batches 1,4,16 --keep-existing`), then a second
+pass over each of those with `--protect-resnet 50` in place of `--keep-existing`.
 """
 import argparse
 import os
@@ -98,6 +99,20 @@ class Bench:
         self.n_models += 1
         return ctx.model_define(self.ops, 3, self.hw, self.hw, batch_sizes=(batch,))
 
+    def resnet_shapes(self, depth, batches=(1, 2, 4, 8, 16)):
+        """Shape keys of every table-driven convolution launch of a ResNet at the given batch sizes."""
+        ctx = self.wk.ctx
+        ctx.set_plan_table([])
+        mid = ctx.model_define_resnet(depth, self.hw, self.hw)
+        ops = ctx.model_get_ops(mid)
+        keys = set()
+        for batch in batches:
+            for l in ctx.plan(mid, batch):
+                if l["kind"] == 1 and l["fused_op"] < 0:
+                    o = ops[l["op_index"]]
+                    keys.add((l["gemm_m"], l["gemm_n"], l["gemm_k"], o[3], o[5]))
+        return keys
+
     def plan_choices(self, batch):
         """{shape key: (tile index, split)} as the library plans this batch size now."""
         mid = self._define(batch, {})
@@ -138,9 +153,11 @@ def main():
     ap.add_argument("--verbose", action="store_true", help="print every candidate's time")
     ap.add_argument("--out", default=TABLE)
     ap.add_argument("--keep-existing", action="store_true", help="rows already in the output file are not replaced")
+    ap.add_argument("--protect-resnet", type=int, default=0, help="shapes that this ResNet depth uses are neither retuned nor replaced")
     args = ap.parse_args()
     from .binding import CONV_TILES
     b = Bench(args.family, args.depth, args.hw, args.reps)
+    protected = b.resnet_shapes(args.protect_resnet) if args.protect_resnet else set()
     final = {}
     for batch in (int(v) for v in args.batches.split(",")):
         t_start = time.time()
@@ -149,7 +166,7 @@ def main():
         print("batch %d: %d shapes, start %.1f us" % (batch, len(cur), t0), flush=True)
         for key in sorted(cur, key=lambda k: -k[0] * k[1] * k[2]):
             best, best_t = cur[key], b.measure(batch, cur)
-            if args.kh and key[3] != args.kh:
+            if (args.kh and key[3] != args.kh) or key in protected:
                 continue
             for tile, s in candidates(*key):
                 if args.only_suffix and not tile.endswith(args.only_suffix):
@@ -177,7 +194,7 @@ def main():
     # without moving the first model's choices)
     kept = read_table(args.out) if os.path.exists(args.out) else {}
     for key, val in kept.items():
-        if key not in final or args.keep_existing:
+        if key not in final or args.keep_existing or key in protected:
             final[key] = val
     lines = ["// Generated by paper_2006_02464_amd/tune.py on an MI355X: per GEMM shape the (tile, split-K) under which",
              "// whole EXECs ran fastest.  ResNet-50's shapes first; the shapes that only ResNet-18 or the MobileNet-,",
