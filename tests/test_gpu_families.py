@@ -80,6 +80,26 @@ def test_mobilenet_224_batch16_and_small_batches(worker):
     ctx.unload_weights(mid)
 
 
+@pytest.mark.parametrize("name", ["resnet18", "dense", "inception"])
+def test_models_with_tuned_shapes_at_224(worker, name):
+    """ResNet-18 and the DenseNet- and Inception-style lists at 224x224, where their convolution shapes
+    have rows of their own in the plan table: batch 16, re-cut at batch 4 and 1, logits against the oracle."""
+    make = {"resnet18": lambda: T.resnet(18), "dense": T.dense_net, "inception": T.inception_net}[name]
+    case = Case(make(), 224, seed=0, dist="normal")
+    ctx = worker.ctx
+    mid = ctx.model_define(case.ops, 3, 224, 224)
+    worker.load(mid, case.blob)
+    x = case.images(0, 16)
+    ref = case.oracle(x)["logits"]
+    for batch in (16, 4, 1):
+        got = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 16, batch)])
+        err = rel_err_per_sample(got, ref)
+        print("%s 224 b%d: %d launches, max rel err %.3e, top-1 equal on %d of 16" % (
+            name, batch, len(ctx.plan(mid, batch)), err.max(), int((N.argmax(got) == N.argmax(ref)).sum())))
+        assert np.isfinite(got).all() and err.max() <= TOL
+    ctx.unload_weights(mid)
+
+
 def test_depthwise_shapes_off_the_mobilenet_path(worker):
     """Depthwise filters MobileNet does not have (5x5 padding 2 with hard swish, 3x3 without padding,
     3x3 stride 3) and 3x3 ones on odd map widths (19, 10, 8, 3 columns), one with a residual: every
