@@ -82,7 +82,8 @@ int32_t cw_set_plan_override(cw_ctx *ctx, int32_t conv_tile, int32_t split_k);
  * the launch runs two groups of four waves: they split every K slice of the first layer and
  * the channels of every chunk of the second.  on == 0 plans such pairs as two launches for models defined
  * afterwards, on == 2 as one launch of a single wave group, on == 1 restores the default;
- * other values: CW_ERR_INVALID.  Plans with debug retention are never fused. */
+ * other values: CW_ERR_INVALID.  Under debug retention the first layer's tensor of such a launch is
+ * the one tensor that cannot be read back (it is never stored). */
 int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
 /* A fused launch (see above) may also compute the 1x1 stride-1 convolution that reads its output:
  * the next bottleneck's reduce, whose input then never comes back from memory.  on == 0 plans that
@@ -90,6 +91,14 @@ int32_t cw_set_fusion(cw_ctx *ctx, int32_t on);
  * the fused launch also computes a projection shortcut; on == 1 restores the default; other
  * values: CW_ERR_INVALID. */
 int32_t cw_set_fusion_third(cw_ctx *ctx, int32_t on);
+/* A 3x3 max pool over 64 channels whose output is the input of a 1x1 stride-1 convolution 64 -> 64
+ * or 128 right behind it (ResNet-50: the first bottleneck's reduce) is planned as ONE launch with that
+ * convolution when the batch gives it enough workgroups: the pooled tile goes through LDS to the
+ * matrix cores and is still written for its other readers; cw_launch_info.fused_op of the max-pool
+ * launch then names the convolution.  Same arithmetic, bit for bit, as the two launches.  on == 0
+ * plans them as two launches for models defined afterwards (also off with cw_set_fusion(0)),
+ * on != 0 restores the default. */
+int32_t cw_set_fusion_pool(cw_ctx *ctx, int32_t on);
 /* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
  * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
  * one launch whose first workgroups compute the one and the rest the other: one dispatch and one

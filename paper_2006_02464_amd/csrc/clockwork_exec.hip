@@ -244,6 +244,13 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             PoolArgs a = l.pool;
             a.x = resolve(c, m, s, l.x);
             a.y = resolve(c, m, s, l.y);
+            if (l.kind == K_MAXPOOL && l.pool_bm > 0) {   // with the 1x1 convolution over the pooled tile
+                ConvArgs cv = l.conv;
+                cv.w = resolve(c, m, s, l.w);
+                cv.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+                cv.y = resolve(c, m, s, l.y2);
+                return launch_maxpool_conv(dt, a, cv, l.pool_bm, st);
+            }
             return l.kind == K_MAXPOOL ? launch_maxpool(dt, a, st) : launch_gavgpool(dt, a, st);
         }
         case K_FC: {
@@ -637,6 +644,12 @@ int32_t cw_set_fusion_third(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     if (on < 0 || on > 2) return set_err(c, CW_ERR_INVALID, "mode must be 0, 1 or 2");
     c->ov.fuse_third = on;
+    return CW_OK;
+}
+
+int32_t cw_set_fusion_pool(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.fuse_pool = on != 0;
     return CW_OK;
 }
 

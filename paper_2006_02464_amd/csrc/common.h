@@ -283,6 +283,9 @@ void conv_pair_grid(ConvTile tile, const ConvArgs &a0, const ConvArgs &a1, dim3 
 hipError_t launch_cast_input(DType dt, const CastArgs &a, hipStream_t s);
 hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s);
 hipError_t launch_gavgpool(DType dt, const PoolArgs &a, hipStream_t s);
+// A 3x3 max pool over 64 channels and the 1x1 stride-1 convolution 64 -> 64 or 128 that reads it, in one launch;
+// c = that convolution's arguments (its x is not read), bm = pooled pixels per workgroup (64 or 128).
+hipError_t launch_maxpool_conv(DType dt, const PoolArgs &a, const ConvArgs &c, int bm, hipStream_t s);
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s);

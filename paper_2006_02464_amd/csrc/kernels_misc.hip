@@ -1,6 +1,7 @@
 // Bandwidth-bound kernels of the EXEC path (input cast, pooling, FC, softmax) and the
 // LOAD-time weight re-layout.  Activations are NHWC in the model's storage type.
 #include "common.h"
+#include "conv_common.h"
 
 namespace cw {
 
@@ -118,6 +119,104 @@ __global__ __launch_bounds__(256) void maxpool_window_kernel(const void *x, void
 #pragma unroll
     for (int e = 0; e < 8; ++e) out[e] = (T)m[e];  // exact: the max is one of the inputs
     *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + (size_t)i * 8) = *reinterpret_cast<const uint4 *>(out);
+}
+
+// ---- max pool and the 1x1 convolution that reads it, in one launch -----------------------
+// A workgroup of 4 waves takes BM pooled pixels x 64 channels: every thread computes BM/32 pieces
+// (pixel, 8 channels) of the pooled tile as the kernel above does, writes them to the pooled tensor
+// (its other readers need it) and into LDS in the convolution kernel's operand layout (128-byte
+// rows, 16-byte chunks swizzled); the N x 64 weights (N = 64 or 128) go to LDS the same way.  After one barrier the
+// waves (2 x 2 over pixels x output channels) run the 64-deep product on the matrix cores, in the
+// same k order as the convolution kernel, and store through its epilogue (bias, activation, one
+// rounding).  The 1x1 convolution then costs no launch of its own and never reads its input from memory.
+template <typename T, int KS, int BM, int N>
+__global__ __launch_bounds__(256) void maxpool_conv1x1_kernel(const PoolArgs a, const ConvArgs c) {
+    constexpr int C = 64;                // channels of the pooled tensor; N = output channels of the convolution
+    constexpr int PIECES = BM * (C / 8) / 256;
+    constexpr int TM = BM / 64, TN = N / 64;
+    typedef typename Mfma<T>::v8 v8;
+    __shared__ __attribute__((aligned(16))) T sX[BM * C];
+    __shared__ __attribute__((aligned(16))) T sW[N * C];
+    const unsigned tid = threadIdx.x;
+    const unsigned m0 = xcd_block(blockIdx.x, gridDim.x) * (unsigned)BM;
+    const unsigned M = (unsigned)a.B * a.Ho * a.Wo;
+    const int lane = tid & 63, wave = tid >> 6;
+    const EpiPos pos{(int)m0, 0, (wave >> 1) * (BM / 2), (wave & 1) * (N / 2), lane & 31, lane >> 5};
+    EpiOperands<TM, TN> eo;
+    epilogue_load<TM, TN>(eo, c, pos);   // the bias, requested beside the window loads
+    uint4 wraw[N * (C / 8) / 256];       // N x 64 weights: row = output channel
+#pragma unroll
+    for (int j = 0; j < N * (C / 8) / 256; ++j) {
+        const unsigned cid = tid + j * 256u;
+        wraw[j] = *reinterpret_cast<const uint4 *>(static_cast<const T *>(c.w) + (cid >> 3) * C + (cid & 7u) * 8u);
+    }
+    uint4 raw[PIECES][KS * KS];
+    bool ok[PIECES][KS * KS];
+#pragma unroll
+    for (int j = 0; j < PIECES; ++j) {
+        const unsigned cid = tid + j * 256u;
+        const unsigned m = min(m0 + (cid >> 3), M - 1u), cg = cid & 7u;   // rows beyond M: a valid pixel, not stored
+        unsigned t = m / (unsigned)a.Wo;
+        const int q = (int)(m - t * (unsigned)a.Wo);
+        const unsigned n = t / (unsigned)a.Ho;
+        const int p = (int)(t - n * (unsigned)a.Ho);
+        const T *xg = static_cast<const T *>(a.x) + (size_t)n * a.H * a.W * C + cg * 8u;
+#pragma unroll
+        for (int r = 0; r < KS; ++r)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int ih = p * a.stride - a.pad + r, iw = q * a.stride - a.pad + s;
+                ok[j][r * KS + s] = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+                const unsigned ihc = (unsigned)min(max(ih, 0), a.H - 1), iwc = (unsigned)min(max(iw, 0), a.W - 1);
+                raw[j][r * KS + s] = *reinterpret_cast<const uint4 *>(xg + (ihc * (unsigned)a.W + iwc) * (unsigned)C);
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < N * (C / 8) / 256; ++j) {
+        const unsigned cid = tid + j * 256u;
+        *reinterpret_cast<uint4 *>(sW + swz<C>((int)(cid >> 3), (int)(cid & 7u))) = wraw[j];
+    }
+#pragma unroll
+    for (int j = 0; j < PIECES; ++j) {
+        const unsigned cid = tid + j * 256u;
+        const unsigned row = cid >> 3, cg = cid & 7u;
+        float mx[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mx[e] = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < KS * KS; ++k) {
+            const T *v = reinterpret_cast<const T *>(&raw[j][k]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mx[e] = ok[j][k] ? fmaxf(mx[e], to_f32(v[e])) : mx[e];
+        }
+        T out[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (T)mx[e];  // exact: the max is one of the inputs
+        const uint4 o = *reinterpret_cast<const uint4 *>(out);
+        if (m0 + row < M) *reinterpret_cast<uint4 *>(static_cast<T *>(a.y) + ((size_t)(m0 + row) * C + cg * 8u)) = o;
+        *reinterpret_cast<uint4 *>(sX + swz<C>((int)row, (int)cg)) = o;   // rows beyond M hold a copy of the last pixel; never stored
+    }
+    __syncthreads();
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < C / 16; ++kk) {
+        v8 fw[TN], fx[TM];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const v8 *>(sW + swz<C>(pos.wn0 + j * 32 + pos.lrow, kk * 2 + pos.lhalf));
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fx[i] = *reinterpret_cast<const v8 *>(sX + swz<C>(pos.wm0 + i * 32 + pos.lrow, kk * 2 + pos.lhalf));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<T>::mma(fw[j], fx[i], acc[i][j]);
+    }
+    epilogue_store<T, TM, TN>(acc, eo, c, pos);
 }
 
 // ---- global average pool: NHWC [B][H*W][C] -> fp32 [B][C] -------------------------------
@@ -829,6 +928,25 @@ hipError_t launch_maxpool(DType dt, const PoolArgs &a, hipStream_t s) {
         return hipGetLastError();
     }
     CW_DISPATCH(dt, maxpool_kernel, dim3(blocks_for(total, 256)), 256, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool_conv(DType dt, const PoolArgs &a, const ConvArgs &c, int bm, hipStream_t s) {
+    const size_t M = (size_t)a.B * a.Ho * a.Wo;
+    if (a.C != 64 || a.k != 3 || a.B < 1 || M * 8 >= (1ull << 31) || (size_t)a.B * a.H * a.W * a.C >= (1ull << 31)) return hipErrorInvalidValue;
+    if (c.Cin != 64 || c.K != 64 || (c.Cout != 64 && c.Cout != 128) || (size_t)c.M != M || c.res || !c.w || !c.bias || !c.y || !a.x || !a.y) return hipErrorInvalidValue;
+    if (conv_ldy(c) < c.Cout || (bm != 64 && bm != 128)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((M + bm - 1) / bm));
+#define CW_POOLCONV(BM_, N_)                                                                  \
+    do {                                                                                      \
+        if (dt == DT_F16) maxpool_conv1x1_kernel<f16, 3, BM_, N_><<<grid, 256, 0, s>>>(a, c); \
+        else maxpool_conv1x1_kernel<bf16, 3, BM_, N_><<<grid, 256, 0, s>>>(a, c);             \
+    } while (0)
+    if (bm == 64 && c.Cout == 64) CW_POOLCONV(64, 64);
+    else if (bm == 64) CW_POOLCONV(64, 128);
+    else if (c.Cout == 64) CW_POOLCONV(128, 64);
+    else CW_POOLCONV(128, 128);
+#undef CW_POOLCONV
     return hipGetLastError();
 }
 

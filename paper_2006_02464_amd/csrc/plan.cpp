@@ -454,6 +454,29 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             }
         }
     }
+    // Max pool + 1x1: a 3x3 max pool over 64 channels whose output is the input of the 1x1 stride-1
+    // convolution 64 -> 64 or 128 right behind it (ResNet-50: the first bottleneck's reduce) computes that
+    // convolution too, from the pooled tile in LDS, where the launch has enough workgroups; the pooled
+    // tensor is still written for its other readers.
+    std::vector<int> pool_conv(n_ops, -1), in_pool(n_ops, -1), pool_bm(n_ops, 0);
+    if (ov.fuse && ov.fuse_pool && !resident && ov.tile < 0 && ov.split_k <= 0) {
+        for (int j = 0; j + 1 < n_ops; ++j) {
+            const cw_op &op = m.ops[j];
+            if (op.op != CW_OP_MAXPOOL || op.kh != 3 || op.kw != 3 || m.shapes[j].c != 64) continue;
+            const int k = j + 1;
+            const cw_op &oc = m.ops[k];
+            if (oc.op != CW_OP_CONV || oc.input_from != j || oc.kh != 1 || oc.kw != 1 || oc.stride != 1 || oc.pad != 0) continue;
+            if (oc.cin != 64 || (oc.cout != 64 && oc.cout != 128) || oc.groups > 1 || oc.residual_from >= 0 || oc.relu > 1) continue;
+            if (fuse_into[k] >= 0 || fused_first[k] >= 0 || in_third[k] >= 0) continue;
+            bool concat_reader = false;   // its output must be a dense tensor of its own
+            for (int r = k + 1; r < n_ops; ++r)
+                if (m.ops[r].op == CW_OP_CONCAT && (m.ops[r].input_from == k || m.ops[r].residual_from == k)) concat_reader = true;
+            if (concat_reader) continue;
+            const int64_t M = (int64_t)batch * m.shapes[j].h * m.shapes[j].w;
+            if (M * 8 >= ((int64_t)1 << 31) || (M + 63) / 64 < 96) continue;   // as for the fused bottleneck tails
+            pool_conv[j] = k; in_pool[k] = j; pool_bm[j] = 64;
+        }
+    }
     // Order in which the ops are planned and launched: op order, except that a convolution j which
     // reads the same tensor as an earlier convolution i and depends on nothing after i (a ResNet
     // block's projection shortcut, i = the block's first 1x1) moves to right behind i, where the two
@@ -466,11 +489,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
                 if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
-                if (in_third[i] >= 0) continue;
+                if (in_third[i] >= 0 || in_pool[i] >= 0) continue;
                 if (m.winograd && wino_eligible(a, i)) continue;
                 for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
                     const cw_op &b = m.ops[j];
-                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j] || in_third[j] >= 0) continue;
+                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j] || in_third[j] >= 0 || in_pool[j] >= 0) continue;
                     if (b.residual_from >= i || (m.winograd && wino_eligible(b, j))) continue;
                     partner[i] = j; moved[j] = 1;
                     break;
@@ -489,7 +512,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // fused launch reads its inputs when that launch runs.
     std::vector<int> last_use(n_ops, -1);
     for (int i = 0; i < n_ops; ++i) {
-        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : (in_third[i] >= 0 ? in_third[i] : i)];
+        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : (in_third[i] >= 0 ? in_third[i] : (in_pool[i] >= 0 ? in_pool[i] : i))];
         if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = std::max(last_use[m.ops[i].input_from], at);
         if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0)
             last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
@@ -601,6 +624,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 const WeightSlot &ws = m.wslots[m.op_wslot[i]];
                 if (fuse_into[i] >= 0) break;  // computed inside the launch of op fuse_into[i]; its output is never stored
                 if (in_third[i] >= 0) break;   // computed, and its output placed, by the fused launch of op in_third[i]
+                if (in_pool[i] >= 0) break;    // likewise by the max-pool launch of op in_pool[i]
                 if (fused_first[i] >= 0) {
                     const int f = fused_first[i];
                     const cw_op &o1 = m.ops[f];
@@ -847,6 +871,33 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 l.x = src; l.y = p.op_out[i];
                 l.info.bytes = (int64_t)batch * sh * sw * sc * esz + (int64_t)out_bytes[i];
                 snprintf(l.info.name, sizeof l.info.name, "maxpool%dx%d_s%d", o.kh, o.kw, o.stride);
+                if (pool_conv[i] >= 0) {
+                    const int k = pool_conv[i];
+                    const cw_op &oc = m.ops[k];
+                    const WeightSlot &wsc = m.wslots[m.op_wslot[k]];
+                    out_bytes[k] = (size_t)batch * os.h * os.w * oc.cout * esz;
+                    p.op_out[k] = Ref{SP_WORKSPACE, ws_alloc(out_bytes[k])};
+                    p.op_ld[k] = oc.cout;
+                    l.pool_bm = pool_bm[i];
+                    ConvArgs &a = l.conv;
+                    a.B = batch; a.H = os.h; a.W = os.w; a.Cin = oc.cin; a.Ho = os.h; a.Wo = os.w; a.Cout = oc.cout;
+                    a.kh = 1; a.kw = 1; a.kwp = 1; a.khp = 1; a.stride = 1;
+                    conv_set_pad(a, 0, 0);
+                    conv_set_ld(a, oc.cin, oc.cout);
+                    a.M = batch * os.h * os.w;
+                    a.K = oc.cin;
+                    a.relu = oc.relu;
+                    a.split_k = 1; a.ktiles_per_split = 1;
+                    l.w = Ref{SP_WEIGHTS, wsc.packed_w_off};
+                    l.bias = Ref{SP_WEIGHTS, wsc.packed_b_off};
+                    l.y2 = p.op_out[k];
+                    l.info.fused_op = k;
+                    l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = a.K;
+                    l.info.flops = 2 * (int64_t)a.M * a.Cout * a.K;
+                    l.info.bytes += (int64_t)oc.cout * oc.cin * esz + oc.cout * 4 + (int64_t)out_bytes[k];   // its input never leaves the chip
+                    const size_t len = strlen(l.info.name);
+                    snprintf(l.info.name + len, sizeof l.info.name - len, "+1x1");
+                }
                 p.launches.push_back(l);
                 break;
             }
@@ -1049,7 +1100,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 else conv_grid(l.tile, l.conv, &g, &b);
                 break;
             case K_CAST_INPUT: g = dim3((unsigned)(((size_t)l.cast.B * l.cast.Hp * l.cast.Wp + 255) / 256)); b = 256; break;
-            case K_MAXPOOL: g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256)); b = 256; break;
+            case K_MAXPOOL:
+                if (l.pool_bm > 0) g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo + l.pool_bm - 1) / l.pool_bm));
+                else g = dim3((unsigned)(((size_t)l.pool.B * l.pool.Ho * l.pool.Wo * (l.pool.C / 8) + 255) / 256));
+                b = 256;
+                break;
             case K_GAVGPOOL: g = dim3((unsigned)(l.pool.B * (l.pool.C / 64))); b = l.pool.H * l.pool.W >= kGapWideFrom ? 1024 : 64; break;
             case K_FC:
                 if (l.probs.space == SP_SLOT_PROBS) { g = dim3((l.fc.Out + 15) / 16, l.fc.split_k); b = 256; }
@@ -1064,7 +1119,8 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         }
         l.info.op_index = l.op_index;
         const bool fc_sm = l.kind == K_FC && l.probs.space == SP_SLOT_PROBS;   // fused_op = the FC, set where the softmax joined it
-        if (l.fused_bm <= 0) { if (!fc_sm) l.info.fused_op = -1; l.info.proj_op = -1; l.info.next_op = -1; }
+        const bool pool_conv1x1 = l.kind == K_MAXPOOL && l.pool_bm > 0;       // fused_op = the 1x1 convolution over the pooled tile
+        if (l.fused_bm <= 0) { if (!fc_sm && !pool_conv1x1) l.info.fused_op = -1; l.info.proj_op = -1; l.info.next_op = -1; }
         l.info.pair_op = l.pair_op;
         l.info.kind = l.kind;
         if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }

@@ -41,6 +41,10 @@ struct Launch {
     Ref w2, bias2;         // second layer of a fused launch
     Ref w3, bias3, y3;     // its third layer (the next block's 1x1 reduce), when there is one
     Ref x2, wd, biasd;     // its projection shortcut, when that is computed in the launch too
+    // K_MAXPOOL with pool_bm > 0: the launch also computes the 1x1 convolution info.fused_op over the pooled tensor
+    // (conv = that convolution's arguments, w / bias its weights, y2 its output; pool_bm pooled pixels per workgroup)
+    int32_t pool_bm = 0;
+    Ref y2;
     // A pair launch (pair_op >= 0): a second, independent convolution over the same input tensor runs
     // in this launch's first workgroups; its arguments and tensors:
     int32_t pair_op = -1;
@@ -102,6 +106,7 @@ struct PlanOverride {
     int32_t fuse_third = 1; // the next block's 1x1 reduce inside a fused 3x3 + 1x1 launch: 0 = never, 1 = yes, 2 = yes, but
                             // not in a launch that also computes a projection shortcut
     bool fc_softmax = false; // FC and softmax as one launch (batch <= 16, at most 1024 classes)
+    bool fuse_pool = true;   // a 3x3 max pool over 64 channels and the 1x1 convolution 64 -> 64 or 128 that reads it as one launch
     bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };

@@ -429,7 +429,8 @@ def config8(args, log):
     wk = Worker(workspace_bytes=1 << 30, io_bytes=256 << 20, weight_pool_bytes=1 << 30, load_staging_bytes=256 << 20)
     ctx, ex = wk.ctx, wk.stream
     variants = [("default plan", None, None), ("fused 3x3+1x1 launches off", ctx.set_fusion, 1),
-                ("next block's 1x1 reduce as a launch of its own", ctx.set_fusion_third, 1), ("pair launches off", ctx.set_pair_launches, 1),
+                ("next block's 1x1 reduce as a launch of its own", ctx.set_fusion_third, 1),
+                ("max pool and the 1x1 behind it as two launches", ctx.set_fusion_pool, 1), ("pair launches off", ctx.set_pair_launches, 1),
                 ("FC and softmax as one launch", ctx.set_fc_softmax, 0),
                 ("tile numbering in channel panels where they move fewer bytes", ctx.set_panels, 0),
                 ("plain launches instead of graph replay", None, None), ("Winograd F(2x2,3x3) for the 3x3 stride-1 layers", ctx.set_winograd, 0),

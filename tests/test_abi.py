@@ -249,6 +249,34 @@ def test_fusion_of_bottleneck_tail(ctx):
         ctx.set_debug_keep(False)
 
 
+def test_max_pool_with_the_1x1_behind_it(ctx):
+    """From batch 2 up the max pool of ResNet-50 also computes the first bottleneck's 1x1 reduce (64 -> 64
+    over the pooled tile); at batch 1 (49 workgroups) and with the option or all fusion off they are two
+    launches; ResNet-18's max pool is followed by a 3x3 and stays alone."""
+    m = ctx.model_define_resnet(50, 224, 224)
+    ops = ctx.model_get_ops(m)
+    assert [len(ctx.plan(m, b)) for b in (1, 2, 4, 8, 16)] == [54, 48, 48, 41, 41]
+    for b in (2, 4, 8, 16):
+        plan = ctx.plan(m, b)
+        pool = [l for l in plan if l["kind"] == 3]
+        assert len(pool) == 1 and pool[0]["op_index"] == 1 and pool[0]["fused_op"] == 2 and pool[0]["name"] == "maxpool3x3_s2+1x1"
+        assert ops[2][0] == 0 and ops[2][3] == 1 and ops[2][1] == 64 and ops[2][2] == 64 and ops[2][9] == 1
+        assert pool[0]["grid_x"] == -(-b * 56 * 56 // 64) and pool[0]["block"] == 256
+        assert (pool[0]["gemm_m"], pool[0]["gemm_n"], pool[0]["gemm_k"]) == (b * 56 * 56, 64, 64) and pool[0]["flops"] == 2 * b * 56 * 56 * 64 * 64
+        assert not [l for l in plan if l["kind"] == 1 and l["op_index"] == 2]      # no launch of its own
+    assert [l["fused_op"] for l in ctx.plan(m, 1) if l["kind"] == 3] == [-1]
+    for setter in (ctx.set_fusion_pool, ctx.set_fusion):
+        setter(0)
+        try:
+            m2 = ctx.model_define_resnet(50, 224, 224)
+            assert [l["fused_op"] for l in ctx.plan(m2, 16) if l["kind"] == 3] == [-1]
+            assert [l for l in ctx.plan(m2, 16) if l["kind"] == 1 and 2 in (l["op_index"], l["pair_op"])]   # a launch of its own, or half of a pair
+        finally:
+            setter(1)
+    m18 = ctx.model_define_resnet(18, 224, 224)
+    assert [l["fused_op"] for l in ctx.plan(m18, 16) if l["kind"] == 3] == [-1]
+
+
 def test_weight_pages():
     """The weight pool is paged (paper section 5.1): page counts per model, the limits, the free count."""
     c = cw.Context(device=-1, weight_pool_bytes=1 << 30)          # default page: 16 MiB

@@ -238,6 +238,42 @@ def test_small_custom_net_narrow_channels_and_odd_stride_stem(worker):
     worker.ctx.unload_weights(mid)
 
 
+@pytest.mark.parametrize("cout,dtype", [(64, "fp16"), (128, "fp16"), (128, "bf16")])
+def test_max_pool_with_the_1x1_behind_it_every_layer(worker, cout, dtype):
+    """The launch that computes a 3x3 max pool over 64 channels and the 1x1 convolution 64 -> 64 or 128
+    behind it: 157 workgroups whose last holds 16 of 64 pixels, the pooled tensor (exact) and the
+    convolution's output (teacher forced) against the oracle; a second convolution reads the pooled tensor too."""
+    O = T.Op
+    ops = [
+        O(T.CONV, 3, 64, 7, 7, 2, 3, 1, -1, -1),           # 0
+        O(T.MAXPOOL, 64, 64, 3, 3, 2, 1, 0, -1, 0),         # 1
+        O(T.CONV, 64, cout, 1, 1, 1, 0, 1, -1, 1),          # 2  computed by the max pool's launch
+        O(T.CONV, 64, 64, 3, 3, 1, 1, 1, -1, 1),            # 3  the pooled tensor's other reader
+        O(T.CONV, cout, 256, 1, 1, 2, 0, 1, -1, 2),         # 4
+        O(T.CONV, 64, 256, 1, 1, 2, 0, 1, 4, 3),            # 5  joins the two
+        O(T.GAVGPOOL, 256, 256, 0, 0, 1, 0, 0, -1, 5),      # 6
+        O(T.FC, 256, 10, 1, 1, 1, 0, 0, -1, 6),             # 7
+        O(T.SOFTMAX, 10, 10, 0, 0, 1, 0, 0, -1, 7),         # 8
+    ]
+    case = Case(ops, 100, seed=9, dtype=dtype, dist="uniform")
+    worker.ctx.set_debug_keep(True)
+    try:
+        mid = worker.ctx.model_define(case.ops, 3, 100, 100, batch_sizes=(16, 2), dtype=dtype)
+    finally:
+        worker.ctx.set_debug_keep(False)
+    pool = [l for l in worker.ctx.plan(mid, 16) if l["kind"] == 3]
+    assert len(pool) == 1 and pool[0]["fused_op"] == 2 and pool[0]["grid_x"] == 157 and pool[0]["gemm_n"] == cout
+    assert [l["fused_op"] for l in worker.ctx.plan(mid, 2) if l["kind"] == 3] == [-1]     # 20 workgroups: two launches
+    worker.load(mid, case.blob)
+    for batch in (16, 2):
+        x = case.images(0, batch)
+        probs, logits, _ = worker.infer(mid, x, classes=10)
+        outs, _, gpu = check_all_ops(worker, case, mid, batch, x)
+        check_head(case, gpu[-1], logits, probs)
+        assert rel_err_per_sample(logits, outs[-2]).max() <= TOL
+    worker.ctx.unload_weights(mid)
+
+
 @pytest.mark.parametrize("classes", [1500, 5000])
 def test_pool_and_softmax_shapes_off_the_resnet_path(worker, classes):
     """A 2x2 max pool (the general window kernel, not the unrolled 3x3 one), a 5x5 average-pool
@@ -445,6 +481,33 @@ def test_resnet50_pair_launches_change_nothing(worker, r50):
         d = rel_err_per_sample(out["paired"], out["single"]).max()
         print("batch %d: paired vs single launches max rel diff %.3e" % (batch, d))
         assert d <= 5e-3
+
+
+def test_resnet50_max_pool_with_its_1x1_changes_nothing(worker, r50):
+    """The max pool and the first bottleneck's 1x1 reduce as one launch or as two: the pooled values are
+    exact either way and the 64-deep products are added in the same order, so the logits are the same bits."""
+    case, x, ref = r50
+    ctx = worker.ctx
+    one = ctx.model_define_resnet(50, 224, 224)
+    ctx.set_fusion_pool(0)
+    try:
+        two = ctx.model_define_resnet(50, 224, 224)
+    finally:
+        ctx.set_fusion_pool(1)
+    for batch in (16, 2):
+        n = 16 if batch == 16 else 4
+        pool = [l for l in ctx.plan(one, batch) if l["kind"] == 3]
+        assert len(pool) == 1 and pool[0]["fused_op"] == 2 and pool[0]["name"] == "maxpool3x3_s2+1x1"
+        assert [l["fused_op"] for l in ctx.plan(two, batch) if l["kind"] == 3] == [-1]
+        assert len(ctx.plan(two, batch)) == len(ctx.plan(one, batch)) + 1
+        out = {}
+        for name, mid in (("one", one), ("two", two)):
+            worker.load(mid, case.blob)
+            out[name] = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, n, batch)])
+            ctx.unload_weights(mid)
+        assert rel_err_per_sample(out["one"], ref[:n]).max() <= TOL
+        assert np.array_equal(out["one"], out["two"])
+    assert not [l for l in ctx.plan(one, 1) if l["kind"] == 3 and l["fused_op"] >= 0]   # too few workgroups at batch 1
 
 
 def test_resnet50_panel_numbering_changes_nothing(worker, r50):
