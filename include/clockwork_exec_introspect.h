@@ -99,6 +99,14 @@ int32_t cw_set_fusion_third(cw_ctx *ctx, int32_t on);
  * plans them as two launches for models defined afterwards (also off with cw_set_fusion(0)),
  * on != 0 restores the default. */
 int32_t cw_set_fusion_pool(cw_ctx *ctx, int32_t on);
+/* A depthwise 3x3 convolution without a residual whose only reader is the 1x1 stride-1 convolution right
+ * behind it (a depthwise-separable block) is planned as ONE launch with that convolution for 32 or 64
+ * channels into 64 or 128 when the batch gives it enough workgroups and
+ * the model has no CONCAT: the depthwise result goes through LDS to the matrix cores and is never
+ * stored; cw_launch_info.op_index of that launch is the 1x1, fused_op the depthwise convolution.
+ * on == 0 plans them as two launches for models defined afterwards (also off with
+ * cw_set_fusion(0)), on != 0 restores the default. */
+int32_t cw_set_fusion_dw(cw_ctx *ctx, int32_t on);
 /* Two consecutive convolutions of the plan that read the same tensor and do not depend on each
  * other (the first 1x1 of a ResNet block and the projection shortcut beside it) are planned as
  * one launch whose first workgroups compute the one and the rest the other: one dispatch and one

@@ -107,6 +107,7 @@ SIGNATURES = {
     "cw_set_panels": (c_int32, [c_void_p, c_int32]),
     "cw_set_fusion_third": (c_int32, [c_void_p, c_int32]),
     "cw_set_fusion_pool": (c_int32, [c_void_p, c_int32]),
+    "cw_set_fusion_dw": (c_int32, [c_void_p, c_int32]),
     "cw_set_fc_softmax": (c_int32, [c_void_p, c_int32]),
     "cw_set_winograd": (c_int32, [c_void_p, c_int32]),
     "cw_set_resident": (c_int32, [c_void_p, c_int32]),
@@ -345,6 +346,9 @@ class Context:
 
     def set_fusion_pool(self, on):
         self._check(lib().cw_set_fusion_pool(self._h, int(on)))
+
+    def set_fusion_dw(self, on):
+        self._check(lib().cw_set_fusion_dw(self._h, int(on)))
 
     def set_panels(self, on):
         self._check(lib().cw_set_panels(self._h, int(on)))

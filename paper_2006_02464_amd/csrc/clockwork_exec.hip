@@ -277,6 +277,14 @@ hipError_t issue(cw_ctx *c, const ModelRt *m, const Bases &s, const Launch &l, h
             a.x = resolve(c, m, s, l.x);
             a.w = resolve(c, m, s, l.w);
             a.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias));
+            if (l.dw_fused) {   // with the 1x1 convolution over its result: res and y are that convolution's
+                ConvArgs cv = l.conv;
+                cv.w = resolve(c, m, s, l.w2);
+                cv.bias = reinterpret_cast<const float *>(resolve(c, m, s, l.bias2));
+                cv.res = resolve(c, m, s, l.res);
+                cv.y = resolve(c, m, s, l.y);
+                return launch_dwconv_conv(dt, a, cv, st);
+            }
             a.res = resolve(c, m, s, l.res);
             a.y = resolve(c, m, s, l.y);
             return launch_dwconv(dt, a, st);
@@ -650,6 +658,12 @@ int32_t cw_set_fusion_third(cw_ctx *c, int32_t on) {
 int32_t cw_set_fusion_pool(cw_ctx *c, int32_t on) {
     if (!c) return CW_ERR_INVALID;
     c->ov.fuse_pool = on != 0;
+    return CW_OK;
+}
+
+int32_t cw_set_fusion_dw(cw_ctx *c, int32_t on) {
+    if (!c) return CW_ERR_INVALID;
+    c->ov.fuse_dw = on != 0;
     return CW_OK;
 }
 

@@ -289,6 +289,11 @@ hipError_t launch_maxpool_conv(DType dt, const PoolArgs &a, const ConvArgs &c, i
 hipError_t launch_fc(DType dt, const FcArgs &a, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_dwconv(DType dt, const DwArgs &a, hipStream_t s);
+// A depthwise 3x3 convolution over c channels (no residual) and the 1x1 stride-1 convolution c -> n that reads it, in
+// one launch (channel counts of dwconv_conv_ok); cv = the 1x1's arguments (its x is not read).
+hipError_t launch_dwconv_conv(DType dt, const DwArgs &a, const ConvArgs &cv, hipStream_t s);
+bool dwconv_conv_ok(int c, int n);
+int dwconv_conv_bm(int c, long long M);   // output pixels per workgroup of that launch
 hipError_t launch_copy_channels(const CopyArgs &a, hipStream_t s);   // 2-byte elements, C % 8 == 0
 hipError_t launch_resident(DType dt, const ResidentArgs &a, hipStream_t s);   // + the epoch bump behind it
 // Host-side check of one program layer against what the resident kernel assumes (shapes, sizes,

@@ -477,6 +477,32 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             pool_conv[j] = k; in_pool[k] = j; pool_bm[j] = 64;
         }
     }
+    // Depthwise + 1x1 (a depthwise-separable block): a depthwise 3x3 convolution without a residual whose only
+    // reader is the 1x1 stride-1 convolution right behind it is computed inside that convolution's launch, from
+    // LDS, for the channel counts the kernel has and where the launch has enough workgroups; models with a
+    // CONCAT keep them apart (their tensors may be channel ranges of wider ones).
+    std::vector<int> dw_into(n_ops, -1), dw_first(n_ops, -1);
+    if (ov.fuse && ov.fuse_dw && !resident && ov.tile < 0 && ov.split_k <= 0) {
+        bool has_concat = false;
+        std::vector<int> uses(n_ops, 0);
+        for (int i = 0; i < n_ops; ++i) {
+            has_concat |= m.ops[i].op == CW_OP_CONCAT;
+            if (m.ops[i].input_from >= 0) ++uses[m.ops[i].input_from];
+            if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0) ++uses[m.ops[i].residual_from];
+        }
+        for (int i = 1; !has_concat && i + 1 < n_ops; ++i) {
+            const cw_op &od = m.ops[i];
+            if (od.op != CW_OP_CONV || od.groups <= 1 || od.kh != 3 || od.kw != 3 || od.residual_from >= 0 || od.input_from < 0 || uses[i] != 1) continue;
+            const int k = i + 1;
+            const cw_op &oc = m.ops[k];
+            if (oc.op != CW_OP_CONV || oc.groups > 1 || oc.input_from != i || oc.residual_from == i) continue;
+            if (oc.kh != 1 || oc.kw != 1 || oc.stride != 1 || oc.pad != 0 || oc.cin != od.cout || !dwconv_conv_ok(od.cout, oc.cout)) continue;
+            if (fuse_into[k] >= 0 || fused_first[k] >= 0 || in_third[k] >= 0 || in_pool[k] >= 0) continue;
+            const int64_t M = (int64_t)batch * m.shapes[i].h * m.shapes[i].w;
+            if (M * 16 >= ((int64_t)1 << 31) || (M + 63) / 64 < 96) continue;
+            dw_into[i] = k; dw_first[k] = i;
+        }
+    }
     // Order in which the ops are planned and launched: op order, except that a convolution j which
     // reads the same tensor as an earlier convolution i and depends on nothing after i (a ResNet
     // block's projection shortcut, i = the block's first 1x1) moves to right behind i, where the two
@@ -489,11 +515,11 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
             for (int i = 1; i < n_ops; ++i) {
                 const cw_op &a = m.ops[i];
                 if (a.op != CW_OP_CONV || a.groups > 1 || a.input_from < 0 || a.cin % 64 != 0 || fuse_into[i] >= 0 || fused_first[i] >= 0 || moved[i]) continue;
-                if (in_third[i] >= 0 || in_pool[i] >= 0) continue;
+                if (in_third[i] >= 0 || in_pool[i] >= 0 || dw_first[i] >= 0) continue;
                 if (m.winograd && wino_eligible(a, i)) continue;
                 for (int j = i + 1; j < n_ops && j <= i + 3; ++j) {
                     const cw_op &b = m.ops[j];
-                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j] || in_third[j] >= 0 || in_pool[j] >= 0) continue;
+                    if (b.op != CW_OP_CONV || b.groups > 1 || b.input_from != a.input_from || fuse_into[j] >= 0 || fused_first[j] >= 0 || moved[j] || in_third[j] >= 0 || in_pool[j] >= 0 || dw_first[j] >= 0) continue;
                     if (b.residual_from >= i || (m.winograd && wino_eligible(b, j))) continue;
                     partner[i] = j; moved[j] = 1;
                     break;
@@ -512,7 +538,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
     // fused launch reads its inputs when that launch runs.
     std::vector<int> last_use(n_ops, -1);
     for (int i = 0; i < n_ops; ++i) {
-        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : (in_third[i] >= 0 ? in_third[i] : (in_pool[i] >= 0 ? in_pool[i] : i))];
+        const int at = pos[fuse_into[i] >= 0 ? fuse_into[i] : (in_third[i] >= 0 ? in_third[i] : (in_pool[i] >= 0 ? in_pool[i] : (dw_into[i] >= 0 ? dw_into[i] : i)))];
         if (m.ops[i].input_from >= 0) last_use[m.ops[i].input_from] = std::max(last_use[m.ops[i].input_from], at);
         if ((m.ops[i].op == CW_OP_CONV || m.ops[i].op == CW_OP_CONCAT) && m.ops[i].residual_from >= 0)
             last_use[m.ops[i].residual_from] = std::max(last_use[m.ops[i].residual_from], at);
@@ -625,6 +651,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 if (fuse_into[i] >= 0) break;  // computed inside the launch of op fuse_into[i]; its output is never stored
                 if (in_third[i] >= 0) break;   // computed, and its output placed, by the fused launch of op in_third[i]
                 if (in_pool[i] >= 0) break;    // likewise by the max-pool launch of op in_pool[i]
+                if (dw_into[i] >= 0) break;    // a depthwise convolution computed inside the launch of the 1x1 behind it; never stored
                 if (fused_first[i] >= 0) {
                     const int f = fused_first[i];
                     const cw_op &o1 = m.ops[f];
@@ -701,6 +728,44 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                     break;
                 }
                 place_output(i, (size_t)batch * os.h * os.w * os.c * esz);
+                if (dw_first[i] >= 0) {   // the depthwise convolution in front of this 1x1, and the 1x1, as one launch
+                    const int f = dw_first[i];
+                    const cw_op &od = m.ops[f];
+                    const OpShape &sd = m.shapes[f];
+                    const OpShape &sin = m.shapes[od.input_from];
+                    const WeightSlot &wsd = m.wslots[m.op_wslot[f]];
+                    Launch l{};
+                    l.kind = K_DWCONV;
+                    l.op_index = i;
+                    l.dw_fused = true;
+                    l.dw = DwArgs{nullptr, nullptr, nullptr, nullptr, nullptr, batch, sin.h, sin.w, od.cin, sd.h, sd.w, od.kh, od.kw, od.stride, od.pad,
+                                  od.relu, p.op_ld[od.input_from], od.cout};
+                    ConvArgs &a = l.conv;
+                    a.B = batch; a.H = sd.h; a.W = sd.w; a.Cin = o.cin; a.Ho = os.h; a.Wo = os.w; a.Cout = o.cout;
+                    a.kh = 1; a.kw = 1; a.kwp = 1; a.khp = 1; a.stride = 1;
+                    conv_set_pad(a, 0, 0);
+                    conv_set_ld(a, o.cin, p.op_ld[i]);
+                    a.M = batch * os.h * os.w;
+                    a.K = o.cin;
+                    a.relu = o.relu;
+                    a.split_k = 1; a.ktiles_per_split = 1;
+                    l.x = p.op_out[od.input_from];
+                    l.w = Ref{SP_WEIGHTS, wsd.packed_w_off};
+                    l.bias = Ref{SP_WEIGHTS, wsd.packed_b_off};
+                    l.w2 = Ref{SP_WEIGHTS, ws.packed_w_off};
+                    l.bias2 = Ref{SP_WEIGHTS, ws.packed_b_off};
+                    l.y = p.op_out[i];
+                    if (o.residual_from >= 0) l.res = p.op_out[o.residual_from];
+                    const int64_t out_b = (int64_t)batch * os.h * os.w * os.c * esz;
+                    l.info.fused_op = f;
+                    l.info.gemm_m = a.M; l.info.gemm_n = a.Cout; l.info.gemm_k = a.K;
+                    l.info.flops = 2 * (int64_t)a.M * od.cout * od.kh * od.kw + 2 * (int64_t)a.M * a.Cout * a.K;
+                    l.info.bytes = (int64_t)batch * sin.h * sin.w * sin.c * esz + (int64_t)od.cout * od.kh * od.kw * esz + od.cout * 4 +
+                                   (int64_t)o.cout * o.cin * esz + o.cout * 4 + out_b + (o.residual_from >= 0 ? out_b : 0);
+                    snprintf(l.info.name, sizeof l.info.name, "dwconv%dx%d_s%d+1x1", od.kh, od.kw, od.stride);
+                    p.launches.push_back(l);
+                    break;
+                }
                 if (o.groups > 1) {   // depthwise: its own kernel
                     Launch l{};
                     l.kind = K_DWCONV;
@@ -1111,7 +1176,15 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
                 else { g = dim3((l.fc.Out + 15) / 16, (l.fc.B + 15) / 16); b = 512; }
                 break;
             case K_SOFTMAX: g = dim3(l.sm.B); b = 256; break;
-            case K_DWCONV: g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256)); b = 256; break;
+            case K_DWCONV:
+                if (l.dw_fused) {
+                    const long long M = (long long)l.dw.B * l.dw.Ho * l.dw.Wo;
+                    const int bm = dwconv_conv_bm(l.dw.C, M);
+                    g = dim3((unsigned)((M + bm - 1) / bm));
+                }
+                else g = dim3((unsigned)(((size_t)l.dw.B * l.dw.Ho * l.dw.Wo * (l.dw.C / 8) + 255) / 256));
+                b = 256;
+                break;
             case K_COPY_CHANNELS: g = dim3((unsigned)(((size_t)l.copy.pixels * (l.copy.C / 8) + 255) / 256)); b = 256; break;
             case K_RESIDENT: g = dim3(kResPartitions * kResGroupsPerPartition); b = 256; break;
             case K_WINO_INPUT:
@@ -1120,7 +1193,7 @@ int32_t plan_build(const Model &m, int32_t batch, const PlanOverride &ov, Plan *
         l.info.op_index = l.op_index;
         const bool fc_sm = l.kind == K_FC && l.probs.space == SP_SLOT_PROBS;   // fused_op = the FC, set where the softmax joined it
         const bool pool_conv1x1 = l.kind == K_MAXPOOL && l.pool_bm > 0;       // fused_op = the 1x1 convolution over the pooled tile
-        if (l.fused_bm <= 0) { if (!fc_sm && !pool_conv1x1) l.info.fused_op = -1; l.info.proj_op = -1; l.info.next_op = -1; }
+        if (l.fused_bm <= 0) { if (!fc_sm && !pool_conv1x1 && !l.dw_fused) l.info.fused_op = -1; l.info.proj_op = -1; l.info.next_op = -1; }
         l.info.pair_op = l.pair_op;
         l.info.kind = l.kind;
         if (l.kind != K_CONV) { l.info.conv_tile = -1; l.info.wave_groups = 1; }

@@ -45,6 +45,9 @@ struct Launch {
     // (conv = that convolution's arguments, w / bias its weights, y2 its output; pool_bm pooled pixels per workgroup)
     int32_t pool_bm = 0;
     Ref y2;
+    // K_DWCONV with dw_fused: the launch computes the depthwise convolution info.fused_op (dw = its arguments, w / bias its
+    // weights; its result is never stored) and the 1x1 convolution op_index over it (conv, w2 / bias2, res, y)
+    bool dw_fused = false;
     // A pair launch (pair_op >= 0): a second, independent convolution over the same input tensor runs
     // in this launch's first workgroups; its arguments and tensors:
     int32_t pair_op = -1;
@@ -107,6 +110,7 @@ struct PlanOverride {
                             // not in a launch that also computes a projection shortcut
     bool fc_softmax = false; // FC and softmax as one launch (batch <= 16, at most 1024 classes)
     bool fuse_pool = true;   // a 3x3 max pool over 64 channels and the 1x1 convolution 64 -> 64 or 128 that reads it as one launch
+    bool fuse_dw = true;     // a depthwise 3x3 convolution and the 1x1 convolution that reads it as one launch (small channel counts)
     bool panels = false;   // tile numbering in channel panels where that moves fewer bytes into the XCDs' L2s
     std::vector<TunedShape> table;  // rows that take precedence over the built-in table
 };

@@ -277,6 +277,32 @@ def test_max_pool_with_the_1x1_behind_it(ctx):
     assert [l["fused_op"] for l in ctx.plan(m18, 16) if l["kind"] == 3] == [-1]
 
 
+def test_depthwise_with_the_1x1_behind_it(ctx):
+    """MobileNet's first two depthwise-separable blocks (32 and 64 channels) are one launch each where the launch has
+    96 workgroups of 64 pixels; the 128-channel ones and everything behind them stay two launches."""
+    from oracle import topology as T
+    ops = [tuple(o) for o in T.mobilenet()]
+    m = ctx.model_define(ops, 3, 224, 224)
+    assert [len(ctx.plan(m, b)) for b in (1, 4, 16)] == [30, 29, 29]
+    for b, n in ((1, 1), (4, 2), (16, 2)):
+        plan = ctx.plan(m, b)
+        both = [l for l in plan if l["kind"] == 7 and l["fused_op"] >= 0]
+        assert len(both) == n
+        for l in both:
+            dw, pw = ops[l["fused_op"]], ops[l["op_index"]]
+            assert l["fused_op"] == l["op_index"] - 1 and dw[11] == dw[1] == dw[2] and dw[3] == 3 and pw[3] == 1 and pw[1] == dw[2] and dw[2] in (32, 64)
+            assert l["grid_x"] == -(-l["gemm_m"] // 64) and l["grid_x"] >= 96 and l["block"] == 256 and l["gemm_k"] == dw[2] and l["gemm_n"] == pw[2]
+            assert l["flops"] == 2 * l["gemm_m"] * dw[2] * 9 + 2 * l["gemm_m"] * pw[2] * pw[1]
+        hit = {l["op_index"] for l in plan} | {l["fused_op"] for l in plan if l["fused_op"] >= 0} | {l["pair_op"] for l in plan if l["pair_op"] >= 0}
+        assert hit == set(range(len(ops)))
+    ctx.set_fusion_dw(0)
+    try:
+        m2 = ctx.model_define(ops, 3, 224, 224)
+        assert [len(ctx.plan(m2, b)) for b in (1, 4, 16)] == [31, 31, 31]
+    finally:
+        ctx.set_fusion_dw(1)
+
+
 def test_weight_pages():
     """The weight pool is paged (paper section 5.1): page counts per model, the limits, the free count."""
     c = cw.Context(device=-1, weight_pool_bytes=1 << 30)          # default page: 16 MiB

@@ -28,7 +28,7 @@ FAMILIES = {
 
 
 @pytest.mark.parametrize("family", sorted(FAMILIES))
-@pytest.mark.parametrize("dtype,batch", [("fp16", 3), ("bf16", 16)])
+@pytest.mark.parametrize("dtype,batch", [("fp16", 3), ("bf16", 16), ("fp16", 16)])
 def test_family_every_layer(worker, family, dtype, batch):
     make, hw = FAMILIES[family]
     case = Case(make(), hw, seed=21, dtype=dtype, dist="normal")
@@ -98,6 +98,36 @@ def test_models_with_tuned_shapes_at_224(worker, name):
             name, batch, len(ctx.plan(mid, batch)), err.max(), int((N.argmax(got) == N.argmax(ref)).sum())))
         assert np.isfinite(got).all() and err.max() <= TOL
     ctx.unload_weights(mid)
+
+
+def test_mobilenet_depthwise_with_its_1x1_or_apart(worker):
+    """The depthwise 3x3 convolutions over 32 and 64 channels inside the launch of the 1x1 behind them, or as
+    launches of their own: the depthwise values are the same bits either way; the 1x1 adds its products up in
+    another order than the stand-alone kernel that takes K = 32, so the plans agree to rounding."""
+    case = Case(T.mobilenet(), 224, seed=0, dist="normal")
+    ctx = worker.ctx
+    fused = ctx.model_define(case.ops, 3, 224, 224)
+    ctx.set_fusion_dw(0)
+    try:
+        apart = ctx.model_define(case.ops, 3, 224, 224)
+    finally:
+        ctx.set_fusion_dw(1)
+    x = case.images(0, 8)
+    ref = case.oracle(x)["logits"]
+    for batch, n_fused in ((4, 2), (1, 1)):
+        pl = ctx.plan(fused, batch)
+        both = [l for l in pl if l["kind"] == 7 and l["fused_op"] >= 0]
+        assert len(both) == n_fused and all(l["fused_op"] == l["op_index"] - 1 and l["name"].endswith("+1x1") for l in both)
+        assert len(ctx.plan(apart, batch)) == len(pl) + n_fused and not [l for l in ctx.plan(apart, batch) if l["fused_op"] >= 0]
+        out = {}
+        for name, mid in (("fused", fused), ("apart", apart)):
+            worker.load(mid, case.blob)
+            out[name] = np.concatenate([worker.infer(mid, x[i:i + batch])[1] for i in range(0, 8, batch)])
+            ctx.unload_weights(mid)
+        assert rel_err_per_sample(out["fused"], ref).max() <= TOL
+        d = rel_err_per_sample(out["fused"], out["apart"]).max()
+        print("mobilenet b%d: fused vs apart max rel diff %.3e" % (batch, d))
+        assert d <= 2e-3
 
 
 def test_depthwise_shapes_off_the_mobilenet_path(worker):

@@ -44,7 +44,7 @@ def check_all_ops(worker, case, mid, batch, x, teacher=True):
     wi = 0
     plan = worker.ctx.plan(mid, batch)
     # the first layer of a fused launch, and a projection computed inside one, are never stored
-    unstored = ({l["fused_op"] for l in plan if l["kind"] == 1 and l["fused_op"] >= 0} |
+    unstored = ({l["fused_op"] for l in plan if l["kind"] in (1, 7) and l["fused_op"] >= 0} |
                 {l["proj_op"] for l in plan if l["kind"] == 1 and l["proj_op"] >= 0})
     for i, (o, (c, h, w)) in enumerate(zip(case.ops, shapes)):
         if o.op in (T.FC, T.SOFTMAX):

@@ -53,7 +53,7 @@ def check_every_launch(worker, case, mid, batch, x):
     """Teacher-forced comparison of every stored op output of the plan of (mid, batch).
 
     A plain convolution launch: oracle conv (+ shortcut, ReLU) over the GPU's own input tensors,
-    rounded once to the storage type.  A fused launch (op f, then the 1x1 op j over its output):
+    rounded once to the storage type.  A fused launch (op f, a convolution or a depthwise one, then the 1x1 op j over its output):
     the oracle rounds op f's result to the storage type, as the kernel does on its way through
     LDS, applies op j, adds the shortcut (read back from the GPU, or, where the projection runs
     inside the launch, computed by the oracle from the GPU's tensor and not rounded, as in the
@@ -63,7 +63,8 @@ def check_every_launch(worker, case, mid, batch, x):
     ops = case.ops
     shapes = T.shapes(ops, case.hw, case.hw)
     plan = ctx.plan(mid, batch)
-    fused = {l["op_index"]: (l["fused_op"], l["proj_op"]) for l in plan if l["fused_op"] >= 0 and l["kind"] == 1}
+    # kind 1: a convolution and the 1x1 behind it; kind 7: a depthwise convolution and the 1x1 behind it
+    fused = {l["op_index"]: (l["fused_op"], l["proj_op"]) for l in plan if l["fused_op"] >= 0 and l["kind"] in (1, 7)}
     unstored = {f for f, _ in fused.values()} | {d for _, d in fused.values() if d >= 0}
     widx, k = {}, 0
     for i, o in enumerate(ops):
@@ -107,18 +108,13 @@ def check_every_launch(worker, case, mid, batch, x):
         gpu[i] = got
         if o.op == T.CONV and i in fused:
             f, d = fused[i]
-            p = conv(ops[f], widx[f], tensor(ops[f].input_from))
-            if ops[f].relu:
-                p = N.relu(p)
-            p = gen.quantize(p, case.dtype)
+            p = gen.quantize(act(ops[f], conv(ops[f], widx[f], tensor(ops[f].input_from))), case.dtype)
             t = conv(o, widx[i], p)
             if d >= 0:
                 t = N.add(t, conv(ops[d], widx[d], tensor(ops[d].input_from)))
-            else:
+            elif o.residual_from >= 0:
                 t = N.add(t, tensor(o.residual_from))
-            if o.relu:
-                t = N.relu(t)
-            t = gen.quantize(t, case.dtype)
+            t = gen.quantize(act(o, t), case.dtype)
             scale = np.abs(t).max()
             diff = np.abs(got - t)
             # an element of the intermediate on a rounding boundary may land one storage ulp away
