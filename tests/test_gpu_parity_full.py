@@ -155,8 +155,9 @@ def _head(case, feat, logits, probs):
 
 
 def _report(key, value):
-    """Measured parity figures go to gpurun_out/parity_report.json when that folder exists."""
-    out = os.path.join(ROOT, "gpurun_out")
+    """Measured parity figures go to parity_report.json in the run's output folder (CW_REPORT_DIR, else the
+    folder of that purpose at the repository root) when it exists."""
+    out = os.environ.get("CW_REPORT_DIR", os.path.join(ROOT, "gpurun_out"))
     if not os.path.isdir(out):
         return
     path = os.path.join(out, "parity_report.json")
